@@ -1,0 +1,180 @@
+"""Integer bookkeeping of the GQLA caches, written out independently of the library.
+TEST INFRASTRUCTURE ONLY (same rule as gqla_oracle.py: tests, smoke and the benchmark's
+CPU-baseline leg may import it; the product path may not).
+
+The paper does not model paging (Sec. 5.1 "Limitations", item (i)); what is fixed by it are the
+per-token element counts of the two caches (Sec. 4.2.1 and 4.2.2: r_kv + d_R and 2 g d_h + d_R).
+The page formats below are this library's documented formats; the functions here restate the
+documentation, element by element, so that the library's own address arithmetic can be checked
+against a second implementation.
+
+Latent page  (P tokens):   row-major  [P][r_kv + d_R]  =  c_kv | k_R   per token.
+Expanded page (P tokens, g_c groups), three planes of 8-element vectors:
+    K_C : [g_c][d_h/8][P][8]     8 consecutive dims of one token are contiguous
+    V   : [g_c][P/8][d_h][8]     8 consecutive tokens of one dim are contiguous
+    k_R : [d_R/8][P][8]
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# ---- sizes (Sec. 4.2.1, 4.2.2) ---------------------------------------------------------
+def latent_elems_per_token(r_kv, d_r):
+    return r_kv + d_r
+
+
+def expanded_elems_per_token(g, d_h, d_r):
+    return 2 * g * d_h + d_r
+
+
+def pages_needed(L, P):
+    return -(-int(L) // P)
+
+
+# ---- logical token -> physical slot ----------------------------------------------------
+def phys_token(page_row, t, P):
+    """(page id, slot) of logical token t of a sequence whose page-table row is page_row."""
+    return int(page_row[t // P]), t % P
+
+
+def contiguous_page(b, p, max_pages):
+    """Page id used when no page table is given: sequence b owns pages b*max_pages ..."""
+    return b * max_pages + p
+
+
+# ---- element offsets inside the pools ---------------------------------------------------
+def latent_offset(page, slot, col, P, r_kv, d_r):
+    """col in [0, r_kv) addresses c_kv, col in [r_kv, r_kv + d_r) addresses k_R."""
+    return (page * P + slot) * (r_kv + d_r) + col
+
+
+def expanded_page_elems(P, g_c, d_h, d_r):
+    return P * (2 * g_c * d_h + d_r)
+
+
+def expanded_k_offset(page, j, slot, d, P, g_c, d_h, d_r):
+    base = page * expanded_page_elems(P, g_c, d_h, d_r)
+    return base + ((j * (d_h // 8) + d // 8) * P + slot) * 8 + d % 8
+
+
+def expanded_v_offset(page, j, slot, d, P, g_c, d_h, d_r):
+    base = page * expanded_page_elems(P, g_c, d_h, d_r) + g_c * P * d_h
+    return base + ((j * (P // 8) + slot // 8) * d_h + d) * 8 + slot % 8
+
+
+def expanded_kr_offset(page, slot, d, P, g_c, d_h, d_r):
+    base = page * expanded_page_elems(P, g_c, d_h, d_r) + 2 * g_c * P * d_h
+    return base + ((d // 8) * P + slot) * 8 + d % 8
+
+
+# ---- whole-pool packers (vectorised restatements of the offsets above) ---------------------
+def pack_latent_pool(seq_rows, table, num_pages, P, width, fill=np.nan):
+    """seq_rows[b] = [L_b, width] array.  Returns pool [num_pages, P, width]; unused slots = fill."""
+    pool = np.full((num_pages, P, width), fill, dtype=np.float32)
+    for b, rows in enumerate(seq_rows):
+        L = rows.shape[0]
+        t = np.arange(L)
+        pool[table[b][t // P], t % P] = rows
+    return pool
+
+
+def pack_expanded_pool(KC_seqs, V_seqs, kR_seqs, table, num_pages, P, fill=np.nan):
+    """KC_seqs[b], V_seqs[b] = [L_b, g_c, d_h]; kR_seqs[b] = [L_b, d_r].
+    Returns a flat fp32 pool of num_pages * expanded_page_elems elements; unused slots = fill."""
+    L0, g_c, d_h = KC_seqs[0].shape
+    d_r = kR_seqs[0].shape[1]
+    pe = expanded_page_elems(P, g_c, d_h, d_r)
+    pool = np.full((num_pages * pe,), fill, dtype=np.float32)
+    for b in range(len(KC_seqs)):
+        L = KC_seqs[b].shape[0]
+        t = np.arange(L)
+        page = np.asarray(table[b])[t // P].astype(np.int64)
+        slot = (t % P).astype(np.int64)
+        base = page * pe
+        d = np.arange(d_h, dtype=np.int64)
+        for j in range(g_c):
+            ko = base[:, None] + ((j * (d_h // 8) + d[None, :] // 8) * P + slot[:, None]) * 8 + d[None, :] % 8
+            pool[ko] = KC_seqs[b][:, j, :]
+            vo = (base[:, None] + g_c * P * d_h
+                  + ((j * (P // 8) + slot[:, None] // 8) * d_h + d[None, :]) * 8 + slot[:, None] % 8)
+            pool[vo] = V_seqs[b][:, j, :]
+        dr = np.arange(d_r, dtype=np.int64)
+        ro = base[:, None] + 2 * g_c * P * d_h + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8
+        pool[ro] = kR_seqs[b]
+    return pool
+
+
+def unpack_expanded_seq(pool, page_row, L, P, g_c, d_h, d_r):
+    """Inverse of pack_expanded_pool for one sequence: (KC [L,g_c,d_h], V [L,g_c,d_h], kR [L,d_r])."""
+    pe = expanded_page_elems(P, g_c, d_h, d_r)
+    t = np.arange(int(L))
+    page = np.asarray(page_row)[t // P].astype(np.int64)
+    slot = (t % P).astype(np.int64)
+    base = page * pe
+    d = np.arange(d_h, dtype=np.int64)
+    KC = np.empty((int(L), g_c, d_h), pool.dtype)
+    V = np.empty((int(L), g_c, d_h), pool.dtype)
+    for j in range(g_c):
+        KC[:, j, :] = pool[base[:, None] + ((j * (d_h // 8) + d[None, :] // 8) * P + slot[:, None]) * 8 + d[None, :] % 8]
+        V[:, j, :] = pool[base[:, None] + g_c * P * d_h
+                          + ((j * (P // 8) + slot[:, None] // 8) * d_h + d[None, :]) * 8 + slot[:, None] % 8]
+    dr = np.arange(d_r, dtype=np.int64)
+    kR = pool[base[:, None] + 2 * g_c * P * d_h + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8]
+    return KC, V, kR
+
+
+# ---- split plan ---------------------------------------------------------------------------
+PATH_ABSORB = 0
+PATH_GQA = 1
+
+
+def plan_slots(num_cus, path, h_q, g, s_q):
+    """How many chunks the device works on at once under the documented launch shapes:
+    absorb  one 4-wave workgroup per CU covers 128 query rows  -> num_cus / ceil(h_q*s_q / 128)
+    gqa     8 waves per CU, one wave per (chunk, group, 32-row block) -> num_cus*8 / (g * ceil(G*s_q / 32))"""
+    if path == PATH_ABSORB:
+        rb = -(-(h_q * s_q) // 128)
+        return max(1, num_cus // rb)
+    rb = -(-((h_q // g) * s_q) // 32)
+    return max(1, (num_cus * 8) // (g * rb))
+
+
+def plan_overhead_pages(path):
+    return 4 if path == PATH_ABSORB else 2
+
+
+def plan_chunk_pages(lens, P, num_cus, path, h_q, g, s_q):
+    """Chunk size (in pages): the cp in 1..max_b npages_b minimising
+    ceil(n_chunks(cp) / slots) * (cp + overhead), n_chunks(cp) = sum_b ceil(npages_b / cp);
+    ties go to the larger cp."""
+    npages = [pages_needed(L, P) for L in lens]
+    slots = plan_slots(num_cus, path, h_q, g, s_q)
+    ovh = plan_overhead_pages(path)
+    best_cp, best_cost = 1, None
+    for cp in range(1, max(npages) + 1):
+        n_chunks = sum(-(-n // cp) for n in npages)
+        cost = -(-n_chunks // slots) * (cp + ovh)
+        if best_cost is None or cost <= best_cost:
+            best_cp, best_cost = cp, cost
+    return best_cp
+
+
+def plan_chunks(lens, P, chunk_pages):
+    """Chunk list in slot order (sequence-major).  Sequence b is cut into n_b = ceil(npages_b / chunk_pages)
+    chunks of ceil(npages_b / n_b) pages (the last one shorter); a chunk is (b, tok_begin, tok_end)
+    with tok_end clipped to L_b.  Also returns first_slot[b]."""
+    chunks, first = [], []
+    for b, L in enumerate(lens):
+        L = int(L)
+        n_pages = pages_needed(L, P)
+        n_b = -(-n_pages // chunk_pages)
+        per = -(-n_pages // n_b)
+        first.append(len(chunks))
+        k = 0
+        while k * per < n_pages:
+            lo = k * per * P
+            hi = min((k + 1) * per * P, L)
+            chunks.append((b, lo, hi))
+            k += 1
+    return chunks, first
