@@ -1,0 +1,176 @@
+/*
+ * gqla.h -- C ABI of the GQLA decode-attention library for AMD MI355X (gfx950).
+ *
+ * GQLA (Group-Query Latent Attention, paper Sec. 3.1) keeps one latent c_kv (r_kv elements) and one
+ * shared RoPE key k_R (d_r elements) per cached token and indexes the up-projections W_UK, W_UV by
+ * g KV groups.  The same weights give two algebraically equivalent decode paths:
+ *
+ *   MQA-absorb path (Sec. 3.1, "MQA-absorb path" equation):
+ *       q_hat[i] = W_UK[j(i)] q_C[i];   logits = (q_hat[i].c_s + q_R[i].k_R,s) / sqrt(d_h + d_r);
+ *       o_hat[i] = sum_s softmax_s(logits) c_s;   o[i] = W_UV[j(i)]^T o_hat[i]
+ *   GQA path (Sec. 3.1, "GQA path" equation), over the expanded cache K_C = W_UK^T c, V = W_UV^T c:
+ *       logits = (q_C[i].K_C[s, j(i)] + q_R[i].k_R,s) / sqrt(d_h + d_r);   o[i] = sum_s softmax_s(logits) V[s, j(i)]
+ *
+ * with head i routed to group j(i) = i / (h_q / g) (0-based form of the paper's ceil(i/(h_q/g));
+ * heads j*G .. j*G+G-1 share group j, G = h_q / g).
+ *
+ * Conventions
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".  Structs passed by
+ *     pointer (gqla_shape, gqla_cache) live in HOST memory and are read before the call returns.
+ *   - Nothing here allocates, frees or synchronises device memory: the caller owns every buffer,
+ *     including the workspace, and passes the hipStream_t (as void*) the kernels are enqueued on.
+ *   - Every entry point validates its arguments on the host before launching anything and returns
+ *     a gqla_status; no exceptions, no abort, nothing printed.  On any status other than GQLA_OK no
+ *     kernel was launched by that call.  On GQLA_OK outputs are fully overwritten (asynchronously,
+ *     in stream order).
+ *   - s_q step tokens per sequence (1 = plain decode, 2 = one multi-token-prediction head).  The
+ *     cached length L_b INCLUDES the s_q step tokens as its last rows; query t (0-based) sits at
+ *     position L_b - s_q + t and attends to cached rows s <= L_b - s_q + t (causal inside the step).
+ *   - dtype GQLA_BF16: caches, queries, weights, q_hat and out are bf16; all accumulation, softmax
+ *     and the split partials are fp32; QK^T and PV run on bf16 MFMA.  Shape limits of the MFMA
+ *     kernels: d_h = 128, d_r = 64, r_kv = 512, page_size a multiple of 64 (<= 1024).
+ *     dtype GQLA_F32: everything fp32 on the vector ALU; d_h, d_r, r_kv, page_size multiples of 8.
+ *
+ * Tensor layouts (row-major, last index fastest)
+ *   q_c   [B][s_q][h_q][d_h]      q_r  [B][s_q][h_q][d_r]     q_hat [B][s_q][h_q][r_kv]
+ *   w_uk, w_uv  [g][r_kv][d_h]    (the transpose of the paper's d_h x r_kv head slice)
+ *   out   [B][s_q][h_q][d_h]      lse  [B][s_q][h_q]  (fp32, natural log of the softmax denominator)
+ *
+ * Cache pools (gqla_cache.pool): pages of page_size (P) tokens, back to back.
+ *   latent page    [P][r_kv + d_r]           per token: c_kv | k_R           (Sec. 4.2.1: r_kv + d_r elements)
+ *   expanded page, g_c groups (Sec. 4.2.2: 2 g d_h + d_r elements per token), three planes of
+ *   8-element vectors so that every 16-byte vector is already an MFMA operand fragment:
+ *       K_C : [g_c][d_h/8][P][8]     element (j, slot s, dim d) at ((j*(d_h/8) + d/8)*P + s)*8 + d%8
+ *       V   : [g_c][P/8][d_h][8]     element (j, s, d) at g_c*P*d_h + ((j*(P/8) + s/8)*d_h + d)*8 + s%8
+ *       k_R : [d_r/8][P][8]          element (s, d)    at 2*g_c*P*d_h + ((d/8)*P + s)*8 + d%8
+ *   Logical token t of sequence b lives in page  page_table[b*max_pages + t/P]  (or b*max_pages + t/P
+ *   when page_table is NULL) at slot t % P.  Slots at or beyond L_b are never used by a decode call
+ *   (whatever bits they hold) and never written by gqla_expand_cache.
+ */
+#ifndef GQLA_H
+#define GQLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GQLA_OK = 0,
+  GQLA_ERR_NULL = 1,       /* a required pointer is NULL                                  */
+  GQLA_ERR_SHAPE = 2,      /* dimensions unsupported or inconsistent (g does not divide h_q, ...) */
+  GQLA_ERR_DTYPE = 3,      /* dtype not GQLA_F32 / GQLA_BF16                               */
+  GQLA_ERR_ALIGN = 4,      /* a data pointer is not 16-byte aligned                         */
+  GQLA_ERR_SEQLEN = 5,     /* some L_b < s_q, or L_b exceeds max_pages * page_size          */
+  GQLA_ERR_PAGE = 6,       /* page_size / max_pages / num_pages inconsistent                */
+  GQLA_ERR_WORKSPACE = 7,  /* workspace too small, or it does not hold this plan's table    */
+  GQLA_ERR_DEVICE = 8,     /* a HIP call (copy or launch) failed                            */
+  GQLA_ERR_PLAN = 9        /* plan was built for another shape / path                       */
+} gqla_status;
+
+typedef enum { GQLA_F32 = 0, GQLA_BF16 = 1 } gqla_dtype;
+typedef enum { GQLA_PATH_ABSORB = 0, GQLA_PATH_GQA = 1 } gqla_path;
+
+typedef struct {
+  int32_t batch;   /* B   sequences in the step                              */
+  int32_t h_q;     /*     query heads                                        */
+  int32_t g;       /*     KV groups (divides h_q)                            */
+  int32_t d_h;     /*     per-head content dim (value dim equals it)         */
+  int32_t r_kv;    /*     latent rank                                        */
+  int32_t d_r;     /*     decoupled-RoPE dim                                 */
+  int32_t s_q;     /*     step tokens per sequence, 1 or 2                   */
+  int32_t dtype;   /*     gqla_dtype                                         */
+  float scale;     /*     softmax scale; 0 selects 1/sqrt(d_h + d_r) (Sec. 3.1) */
+} gqla_shape;
+
+typedef struct {
+  void* pool;                 /* device: num_pages pages in the format of the cache kind        */
+  const int32_t* seq_lens;    /* device int32[batch]: L_b; read by gqla_expand_cache only       */
+  const int32_t* page_table;  /* device int32[batch*max_pages], or NULL for the identity map    */
+  int32_t page_size;          /* P, tokens per page                                            */
+  int32_t max_pages;          /* row stride of page_table; every L_b <= max_pages * page_size  */
+  int32_t num_pages;          /* pages in the pool; kernels skip (never dereference) ids outside [0, num_pages) */
+  int32_t groups;             /* expanded cache: g_c groups stored per page; latent cache: ignored */
+} gqla_cache;
+
+/* ---- split plan (integer bookkeeping; the paper does not model paging or splitting, Sec. 5.1 (i)) ----
+ *
+ * A decode call cuts every sequence into chunks of whole pages, runs flash-decoding per chunk and merges
+ * the chunk partials with a log-sum-exp combine.  The plan is a HOST object holding the chunk table.
+ * Rule (all integer, reproduced bit for bit by the tests' independent implementation):
+ *   npages_b = ceil(L_b / P);   slots = number of chunks the device works on at once:
+ *       absorb: max(1, num_cus / ceil(h_q*s_q / 128))          gqa: max(1, num_cus*8 / (g * ceil(G*s_q / 32)))
+ *   chunk_pages = the cp in 1..max_b npages_b minimising  ceil(sum_b ceil(npages_b/cp) / slots) * (cp + ovh),
+ *       ovh = 4 (absorb) or 2 (gqa) pages of per-chunk fixed cost; ties go to the larger cp;
+ *   sequence b gets n_b = ceil(npages_b / chunk_pages) chunks of ceil(npages_b / n_b) pages (last one shorter);
+ *   chunk k of b covers tokens [k*per_b*P, min((k+1)*per_b*P, L_b)) and owns partial slot first_slot[b] + k.
+ */
+typedef struct gqla_plan gqla_plan;
+
+/* seq_lens_host: host int32[batch].  num_cus: compute units to plan for (256 on MI355X).  chunk_pages_override:
+ * 0 = use the rule above, > 0 = force that chunk size (testing / tuning).  *out receives the plan. */
+gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_host, int32_t page_size,
+                             int32_t num_cus, int32_t path, int32_t chunk_pages_override, gqla_plan** out);
+void gqla_plan_destroy(gqla_plan* plan);
+int32_t gqla_plan_num_chunks(const gqla_plan* plan);
+int32_t gqla_plan_chunk_pages(const gqla_plan* plan);
+/* Copies up to *n chunk triples (b, tok_begin, tok_end) in slot order to triples (host int32[3 * *n]) and the
+ * per-sequence first slots to first_slot (host int32[batch], may be NULL); sets *n to the chunk count. */
+gqla_status gqla_plan_export(const gqla_plan* plan, int32_t* triples, int32_t* first_slot, int32_t* n);
+/* Bytes of device workspace a decode call with this plan needs: the chunk table, then fp32 partial outputs
+ * [chunks][s_q*h_q][d_h] and partial log-sum-exps [chunks][s_q*h_q]. */
+size_t gqla_plan_workspace_bytes(const gqla_plan* plan);
+/* Enqueues the copy of the plan's chunk table into the head of ws (device, 16-byte aligned, at least
+ * gqla_plan_workspace_bytes).  Must precede, in stream order, every decode call that uses (plan, ws).  The plan
+ * must stay alive until that copy has executed. */
+gqla_status gqla_plan_upload(gqla_plan* plan, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- the decode paths --------------------------------------------------------------------------------- */
+
+/* Query absorption, first line of the MQA-absorb equation (Sec. 3.1): q_hat[b,t,i,:] = W_UK[j(i)] q_c[b,t,i,:]
+ * (an r_kv-vector per head).  q_r is not touched (it passes through to gqla_decode_absorb). */
+gqla_status gqla_absorb_query(const gqla_shape* shape, const void* q_c, const void* w_uk, void* q_hat,
+                              void* stream);
+
+/* MQA-absorb decode (Sec. 3.1, MQA-absorb equation, lines 2-6): split-L flash-decoding of all h_q*s_q rows
+ * over the latent cache, each chunk's latent-space output projected through W_UV[j(i)], then the log-sum-exp
+ * combine.  plan: built with GQLA_PATH_ABSORB for this shape and the lengths in the cache, uploaded into ws.
+ * lse may be NULL. */
+gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, const void* q_hat,
+                               const void* q_r, const gqla_cache* latent, const void* w_uv, void* out,
+                               float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Cache switch latent -> expanded (Sec. 3.1, "Two equivalent decoding paths": the one-shot expand; K_C = W_UK^T c,
+ * V = W_UV^T c per group, k_R copied).  Expands groups [group_begin, group_begin + group_count) of every token
+ * t < L_b (L_b read from latent->seq_lens on the device) into `expanded`, whose pages hold
+ * expanded->groups == group_count groups and which must use the same page_size, max_pages and page ids
+ * (page_table content) as `latent`.  A slice with group_count < g is one rank's share of head-axis
+ * tensor parallelism. */
+gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
+                              const void* w_uv, int32_t group_begin, int32_t group_count,
+                              const gqla_cache* expanded, void* stream);
+
+/* GQA-path decode (Sec. 3.1, GQA-path equation) over an expanded cache holding expanded->groups == shape->g
+ * groups (for a tensor-parallel slice pass a shape with h_q and g already divided).  plan: built with
+ * GQLA_PATH_GQA, uploaded into ws.  lse may be NULL. */
+gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
+                            const gqla_cache* expanded, void* out, float* lse, void* ws, size_t ws_bytes,
+                            void* stream);
+
+/* ---- sizes and diagnostics ------------------------------------------------------------------------------ */
+/* Elements per token of the two caches (Sec. 4.2.1: r_kv + d_r;  Sec. 4.2.2: 2 g d_h + d_r). */
+int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r);
+int64_t gqla_expanded_elems_per_token(int32_t groups, int32_t d_h, int32_t d_r);
+/* Element offsets inside a pool (the formulas in the header comment), for callers that fill caches themselves. */
+int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page_size, int32_t r_kv, int32_t d_r);
+int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
+int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
+int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
+const char* gqla_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GQLA_H */

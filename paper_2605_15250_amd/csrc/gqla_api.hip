@@ -1,0 +1,390 @@
+// Host side of the GQLA library: argument validation, the integer split plan, workspace layout and the
+// extern "C" entry points declared in gqla.h.  No device memory is allocated here.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "gqla_internal.h"
+
+using namespace gqla;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+gqla_status check_shape(const gqla_shape* s) {
+  if (!s) return GQLA_ERR_NULL;
+  if (s->dtype != GQLA_F32 && s->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (s->batch < 0 || s->h_q <= 0 || s->g <= 0 || s->h_q % s->g != 0) return GQLA_ERR_SHAPE;
+  if (s->s_q != 1 && s->s_q != 2) return GQLA_ERR_SHAPE;
+  if (s->d_h <= 0 || s->r_kv <= 0 || s->d_r <= 0) return GQLA_ERR_SHAPE;
+  if (!(s->scale >= 0.f) || std::isinf(s->scale)) return GQLA_ERR_SHAPE;
+  if (s->dtype == GQLA_BF16) {
+    if (s->d_h != 128 || s->d_r != 64 || s->r_kv != 512) return GQLA_ERR_SHAPE;
+  } else {
+    if (s->d_h % 8 || s->d_r % 8 || s->r_kv % 8 || s->d_h > 512 || s->r_kv > 512) return GQLA_ERR_SHAPE;
+  }
+  return GQLA_OK;
+}
+
+gqla_status check_page_size(const gqla_shape* s, int32_t page_size) {
+  if (page_size <= 0) return GQLA_ERR_PAGE;
+  if (s->dtype == GQLA_BF16) {
+    if (page_size % 64 || page_size > 1024) return GQLA_ERR_PAGE;
+  } else if (page_size % 8) {
+    return GQLA_ERR_PAGE;
+  }
+  return GQLA_OK;
+}
+
+float resolved_scale(const gqla_shape* s) {
+  return s->scale > 0.f ? s->scale : 1.0f / std::sqrt((float)(s->d_h + s->d_r));
+}
+
+bool same_shape(const gqla_shape& a, const gqla_shape& b) {
+  return a.batch == b.batch && a.h_q == b.h_q && a.g == b.g && a.d_h == b.d_h && a.r_kv == b.r_kv &&
+         a.d_r == b.d_r && a.s_q == b.s_q && a.dtype == b.dtype;
+}
+
+gqla_status check_cache(const gqla_shape* s, const gqla_cache* c, int32_t page_size, int32_t max_len) {
+  if (!c || !c->pool) return GQLA_ERR_NULL;
+  if (!aligned16(c->pool) || (c->page_table && (reinterpret_cast<uintptr_t>(c->page_table) & 3u))) return GQLA_ERR_ALIGN;
+  if (c->page_size != page_size || c->max_pages <= 0 || c->num_pages <= 0) return GQLA_ERR_PAGE;
+  if ((int64_t)c->max_pages * c->page_size < max_len) return GQLA_ERR_SEQLEN;
+  if (!c->page_table && (int64_t)c->num_pages < (int64_t)s->batch * c->max_pages) return GQLA_ERR_PAGE;
+  return GQLA_OK;
+}
+
+int32_t plan_slots(const gqla_shape& s, int32_t num_cus, int32_t path) {
+  if (path == GQLA_PATH_ABSORB) {
+    const int32_t rb = (int32_t)ceil_div((int64_t)s.h_q * s.s_q, 128);
+    return std::max(1, num_cus / rb);
+  }
+  const int32_t rb = (int32_t)ceil_div((int64_t)(s.h_q / s.g) * s.s_q, 32);
+  return std::max<int64_t>(1, (int64_t)num_cus * 8 / ((int64_t)s.g * rb));
+}
+
+WsLayout make_layout(const gqla_plan& p) {
+  WsLayout w;
+  const size_t n = p.chunks.size();
+  const size_t M = (size_t)p.shape.s_q * p.shape.h_q;
+  w.table_off = 0;
+  w.first_slot_off = align_up(n * sizeof(ChunkEntry), 16);
+  w.part_o_off = align_up(w.first_slot_off + (p.shape.batch + 1) * sizeof(int32_t), 256);
+  size_t po;
+  if (p.path == GQLA_PATH_GQA) po = n * M * p.shape.d_h * 4;
+  else po = n * M * p.shape.r_kv * (p.shape.dtype == GQLA_BF16 ? 2 : 4);
+  w.part_lse_off = align_up(w.part_o_off + po, 256);
+  w.total = align_up(w.part_lse_off + n * M * 4, 256);
+  return w;
+}
+
+gqla_status check_decode_common(const gqla_shape* shape, const gqla_plan* plan, int32_t path, const gqla_cache* cache,
+                                const void* qa, const void* qr, const void* out, const float* lse, const void* ws,
+                                size_t ws_bytes) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!plan || !qa || !qr || !out || !ws) return GQLA_ERR_NULL;
+  if (!same_shape(plan->shape, *shape) || plan->path != path) return GQLA_ERR_PLAN;
+  if (!aligned16(qa) || !aligned16(qr) || !aligned16(out) || !aligned16(ws) || (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)))
+    return GQLA_ERR_ALIGN;
+  int32_t max_len = 0;
+  for (int32_t L : plan->lens) max_len = std::max(max_len, L);
+  st = check_cache(shape, cache, plan->page_size, max_len);
+  if (st != GQLA_OK) return st;
+  if (ws_bytes < plan->ws.total || plan->uploaded_ws != ws) return GQLA_ERR_WORKSPACE;
+  return GQLA_OK;
+}
+
+CacheView view_of(const gqla_cache* c) {
+  CacheView v;
+  v.pool = c->pool;
+  v.page_table = c->page_table;
+  v.page_size = c->page_size;
+  v.max_pages = c->max_pages;
+  v.num_pages = c->num_pages;
+  v.groups = c->groups;
+  return v;
+}
+
+DecodeArgs decode_args(const gqla_shape* s, const gqla_plan* plan, const void* qa, const void* qr, const gqla_cache* c,
+                       void* ws) {
+  DecodeArgs a;
+  a.q_a = qa;
+  a.q_r = qr;
+  a.cache = view_of(c);
+  a.chunks = reinterpret_cast<const ChunkEntry*>(static_cast<char*>(ws) + plan->ws.table_off);
+  a.n_chunks = (int32_t)plan->chunks.size();
+  a.part_o = static_cast<char*>(ws) + plan->ws.part_o_off;
+  a.part_lse = reinterpret_cast<float*>(static_cast<char*>(ws) + plan->ws.part_lse_off);
+  a.B = s->batch;
+  a.h_q = s->h_q;
+  a.g = s->g;
+  a.G = s->h_q / s->g;
+  a.d_h = s->d_h;
+  a.r_kv = s->r_kv;
+  a.d_r = s->d_r;
+  a.s_q = s->s_q;
+  a.M = s->s_q * s->h_q;
+  a.scale_log2e = resolved_scale(s) * 1.4426950408889634f;
+  return a;
+}
+
+CombineArgs combine_args(const gqla_shape* s, const gqla_plan* plan, void* ws, const void* w_uv, void* out, float* lse) {
+  CombineArgs c;
+  c.part_o = static_cast<char*>(ws) + plan->ws.part_o_off;
+  c.part_lse = reinterpret_cast<const float*>(static_cast<char*>(ws) + plan->ws.part_lse_off);
+  c.first_slot = reinterpret_cast<const int32_t*>(static_cast<char*>(ws) + plan->ws.first_slot_off);
+  c.w_uv = w_uv;
+  c.out = out;
+  c.lse = lse;
+  c.B = s->batch;
+  c.h_q = s->h_q;
+  c.g = s->g;
+  c.G = s->h_q / s->g;
+  c.d_h = s->d_h;
+  c.r_kv = s->r_kv;
+  c.s_q = s->s_q;
+  c.M = s->s_q * s->h_q;
+  return c;
+}
+
+}  // namespace
+
+extern "C" {
+
+gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_host, int32_t page_size, int32_t num_cus,
+                             int32_t path, int32_t chunk_pages_override, gqla_plan** out) {
+  if (!out) return GQLA_ERR_NULL;
+  *out = nullptr;
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!seq_lens_host && shape->batch > 0) return GQLA_ERR_NULL;
+  if (path != GQLA_PATH_ABSORB && path != GQLA_PATH_GQA) return GQLA_ERR_PLAN;
+  if (num_cus <= 0 || chunk_pages_override < 0) return GQLA_ERR_SHAPE;
+  st = check_page_size(shape, page_size);
+  if (st != GQLA_OK) return st;
+  if (path == GQLA_PATH_GQA && shape->dtype == GQLA_BF16 && (int64_t)(shape->h_q / shape->g) * shape->s_q > 32 * 64)
+    return GQLA_ERR_SHAPE;
+  for (int32_t b = 0; b < shape->batch; ++b)
+    if (seq_lens_host[b] < shape->s_q) return GQLA_ERR_SEQLEN;
+
+  gqla_plan* p = new (std::nothrow) gqla_plan();
+  if (!p) return GQLA_ERR_DEVICE;
+  p->shape = *shape;
+  p->path = path;
+  p->page_size = page_size;
+  p->num_cus = num_cus;
+  p->uploaded_ws = nullptr;
+  p->lens.assign(seq_lens_host, seq_lens_host + shape->batch);
+
+  std::vector<int32_t> npages(shape->batch);
+  int32_t max_np = 1;
+  for (int32_t b = 0; b < shape->batch; ++b) {
+    npages[b] = (int32_t)ceil_div(p->lens[b], page_size);
+    max_np = std::max(max_np, npages[b]);
+  }
+  int32_t cp = chunk_pages_override;
+  if (cp == 0) {
+    const int64_t slots = plan_slots(*shape, num_cus, path);
+    const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : 2;
+    int64_t best = -1;
+    cp = 1;
+    for (int32_t c = 1; c <= max_np; ++c) {
+      int64_t n = 0;
+      for (int32_t b = 0; b < shape->batch; ++b) n += ceil_div(npages[b], c);
+      const int64_t cost = ceil_div(n, slots) * (c + ovh);
+      if (best < 0 || cost <= best) {
+        best = cost;
+        cp = c;
+      }
+    }
+  }
+  p->chunk_pages = cp;
+  p->first_slot.resize(shape->batch + 1);
+  for (int32_t b = 0; b < shape->batch; ++b) {
+    p->first_slot[b] = (int32_t)p->chunks.size();
+    const int32_t n_b = (int32_t)ceil_div(npages[b], cp);
+    const int32_t per = (int32_t)ceil_div(npages[b], n_b);
+    for (int32_t k = 0; (int64_t)k * per < npages[b]; ++k) {
+      ChunkEntry e;
+      e.b = b;
+      e.tok_begin = k * per * page_size;
+      e.tok_end = (int32_t)std::min<int64_t>((int64_t)(k + 1) * per * page_size, p->lens[b]);
+      e.L = p->lens[b];
+      p->chunks.push_back(e);
+    }
+  }
+  p->first_slot[shape->batch] = (int32_t)p->chunks.size();
+  p->ws = make_layout(*p);
+  *out = p;
+  return GQLA_OK;
+}
+
+void gqla_plan_destroy(gqla_plan* plan) { delete plan; }
+
+int32_t gqla_plan_num_chunks(const gqla_plan* plan) { return plan ? (int32_t)plan->chunks.size() : 0; }
+int32_t gqla_plan_chunk_pages(const gqla_plan* plan) { return plan ? plan->chunk_pages : 0; }
+
+gqla_status gqla_plan_export(const gqla_plan* plan, int32_t* triples, int32_t* first_slot, int32_t* n) {
+  if (!plan || !n) return GQLA_ERR_NULL;
+  const int32_t have = (int32_t)plan->chunks.size();
+  if (triples) {
+    const int32_t m = std::min(*n, have);
+    for (int32_t k = 0; k < m; ++k) {
+      triples[3 * k] = plan->chunks[k].b;
+      triples[3 * k + 1] = plan->chunks[k].tok_begin;
+      triples[3 * k + 2] = plan->chunks[k].tok_end;
+    }
+  }
+  if (first_slot)
+    for (int32_t b = 0; b < plan->shape.batch; ++b) first_slot[b] = plan->first_slot[b];
+  *n = have;
+  return GQLA_OK;
+}
+
+size_t gqla_plan_workspace_bytes(const gqla_plan* plan) { return plan ? plan->ws.total : 0; }
+
+gqla_status gqla_plan_upload(gqla_plan* plan, void* ws, size_t ws_bytes, void* stream) {
+  if (!plan || !ws) return GQLA_ERR_NULL;
+  if (!aligned16(ws)) return GQLA_ERR_ALIGN;
+  if (ws_bytes < plan->ws.total) return GQLA_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  if (!plan->chunks.empty()) {
+    if (hipMemcpyAsync(base + plan->ws.table_off, plan->chunks.data(), plan->chunks.size() * sizeof(ChunkEntry),
+                       hipMemcpyHostToDevice, s) != hipSuccess)
+      return GQLA_ERR_DEVICE;
+  }
+  if (hipMemcpyAsync(base + plan->ws.first_slot_off, plan->first_slot.data(), plan->first_slot.size() * sizeof(int32_t),
+                     hipMemcpyHostToDevice, s) != hipSuccess)
+    return GQLA_ERR_DEVICE;
+  plan->uploaded_ws = ws;
+  return GQLA_OK;
+}
+
+gqla_status gqla_absorb_query(const gqla_shape* shape, const void* q_c, const void* w_uk, void* q_hat, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!q_c || !w_uk || !q_hat) return GQLA_ERR_NULL;
+  if (!aligned16(q_c) || !aligned16(w_uk) || !aligned16(q_hat)) return GQLA_ERR_ALIGN;
+  if (shape->batch == 0) return GQLA_OK;
+  AbsorbQueryArgs a;
+  a.q_c = q_c;
+  a.w_uk = w_uk;
+  a.q_hat = q_hat;
+  a.rows = shape->batch * shape->s_q;
+  a.h_q = shape->h_q;
+  a.g = shape->g;
+  a.G = shape->h_q / shape->g;
+  a.d_h = shape->d_h;
+  a.r_kv = shape->r_kv;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = shape->dtype == GQLA_BF16 ? launch_absorb_query_bf16(a, s) : launch_absorb_query_f32(a, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, const void* q_hat, const void* q_r,
+                               const gqla_cache* latent, const void* w_uv, void* out, float* lse, void* ws,
+                               size_t ws_bytes, void* stream) {
+  gqla_status st = check_decode_common(shape, plan, GQLA_PATH_ABSORB, latent, q_hat, q_r, out, lse, ws, ws_bytes);
+  if (st != GQLA_OK) return st;
+  if (!w_uv) return GQLA_ERR_NULL;
+  if (!aligned16(w_uv)) return GQLA_ERR_ALIGN;
+  if (shape->batch == 0) return GQLA_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const DecodeArgs a = decode_args(shape, plan, q_hat, q_r, latent, ws);
+  const CombineArgs c = combine_args(shape, plan, ws, w_uv, out, lse);
+  hipError_t e;
+  if (shape->dtype == GQLA_BF16) {
+    e = launch_decode_absorb_bf16(a, s);
+    if (e == hipSuccess) e = launch_combine_project_bf16(c, s);
+  } else {
+    e = launch_decode_absorb_f32(a, s);
+    if (e == hipSuccess) e = launch_combine_project_f32(c, s);
+  }
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                              int32_t group_begin, int32_t group_count, const gqla_cache* expanded, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
+  if (!aligned16(w_uk) || !aligned16(w_uv) || !aligned16(latent->pool) || !aligned16(expanded->pool)) return GQLA_ERR_ALIGN;
+  if (group_begin < 0 || group_count <= 0 || group_begin + group_count > shape->g || expanded->groups != group_count)
+    return GQLA_ERR_SHAPE;
+  st = check_page_size(shape, latent->page_size);
+  if (st != GQLA_OK) return st;
+  if (latent->page_size != expanded->page_size || latent->max_pages != expanded->max_pages || latent->max_pages <= 0 ||
+      latent->num_pages <= 0 || expanded->num_pages <= 0)
+    return GQLA_ERR_PAGE;
+  if (!latent->page_table && (int64_t)latent->num_pages < (int64_t)shape->batch * latent->max_pages) return GQLA_ERR_PAGE;
+  if (!expanded->page_table && (int64_t)expanded->num_pages < (int64_t)shape->batch * expanded->max_pages) return GQLA_ERR_PAGE;
+  if (shape->batch == 0) return GQLA_OK;
+  ExpandArgs a;
+  a.latent = view_of(latent);
+  a.expanded = view_of(expanded);
+  a.seq_lens = latent->seq_lens;
+  a.w_uk = w_uk;
+  a.w_uv = w_uv;
+  a.B = shape->batch;
+  a.g = shape->g;
+  a.d_h = shape->d_h;
+  a.r_kv = shape->r_kv;
+  a.d_r = shape->d_r;
+  a.group_begin = group_begin;
+  a.group_count = group_count;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, s) : launch_expand_f32(a, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
+                            const gqla_cache* expanded, void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  gqla_status st = check_decode_common(shape, plan, GQLA_PATH_GQA, expanded, q_c, q_r, out, lse, ws, ws_bytes);
+  if (st != GQLA_OK) return st;
+  if (expanded->groups != shape->g) return GQLA_ERR_SHAPE;
+  if (shape->batch == 0) return GQLA_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded, ws);
+  const CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
+  hipError_t e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
+  if (e == hipSuccess) e = launch_combine_f32(c, shape->dtype == GQLA_BF16, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r) { return (int64_t)r_kv + d_r; }
+int64_t gqla_expanded_elems_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + d_r; }
+int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page_size, int32_t r_kv, int32_t d_r) {
+  return (page * page_size + slot) * ((int64_t)r_kv + d_r) + col;
+}
+int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_r) {
+  return page * P * (2ll * groups * d_h + d_r) + (((int64_t)j * (d_h / 8) + d / 8) * P + slot) * 8 + d % 8;
+}
+int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_r) {
+  return page * P * (2ll * groups * d_h + d_r) + (int64_t)groups * P * d_h + (((int64_t)j * (P / 8) + slot / 8) * d_h + d) * 8 + slot % 8;
+}
+int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_r) {
+  return page * P * (2ll * groups * d_h + d_r) + 2ll * groups * P * d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8;
+}
+
+const char* gqla_status_string(int32_t status) {
+  switch (status) {
+    case GQLA_OK: return "ok";
+    case GQLA_ERR_NULL: return "null pointer";
+    case GQLA_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case GQLA_ERR_DTYPE: return "unsupported dtype";
+    case GQLA_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case GQLA_ERR_SEQLEN: return "sequence length out of range";
+    case GQLA_ERR_PAGE: return "inconsistent page geometry";
+    case GQLA_ERR_WORKSPACE: return "workspace too small or plan table not uploaded into it";
+    case GQLA_ERR_DEVICE: return "HIP call failed";
+    case GQLA_ERR_PLAN: return "plan does not match shape or path";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

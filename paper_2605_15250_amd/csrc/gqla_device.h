@@ -1,0 +1,75 @@
+// Device-side helpers shared by the gfx950 kernels: MFMA fragment types, wave64 half swaps,
+// cache address arithmetic.  Lane layouts used throughout (wave64, v_mfma_f32_32x32x16_bf16):
+//   A fragment  lane l holds A[m = l % 32][k = 8*(l / 32) + 0..7]
+//   B fragment  lane l holds B[k = 8*(l / 32) + 0..7][n = l % 32]
+//   C fragment  lane l, register i holds C[m = 8*(i / 4) + 4*(l / 32) + i % 4][n = l % 32]
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gqla_internal.h"
+
+namespace gqla {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+
+#define GQLA_NEG_INF (-__builtin_inff())
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Two floats -> packed bf16 pair (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
+}
+
+// Exchange between the two 32-lane halves: returns {lower-half view, upper-half view}:
+//   r[0] = lanes 0..31 keep x, lanes 32..63 receive y of lane-32;   r[1] = lanes 0..31 receive x of lane+32, lanes 32..63 keep y.
+__device__ __forceinline__ void half_swap(uint32_t x, uint32_t y, uint32_t& r0, uint32_t& r1) {
+  auto r = __builtin_amdgcn_permlane32_swap(x, y, false, false);
+  r0 = r[0];
+  r1 = r[1];
+}
+
+// max / sum of a value over the two lanes (l, l ^ 32).
+__device__ __forceinline__ float pair_max(float v) {
+  uint32_t a, b;
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  half_swap(u, u, a, b);
+  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+__device__ __forceinline__ float pair_sum(float v) {
+  uint32_t a, b;
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  half_swap(u, u, a, b);
+  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Page id of logical page p of sequence b, or -1 when the table entry is outside the pool.
+__device__ __forceinline__ int32_t page_of(const CacheView& c, int32_t b, int32_t p) {
+  int32_t pg = c.page_table ? c.page_table[(int64_t)b * c.max_pages + p] : b * c.max_pages + p;
+  return ((uint32_t)pg < (uint32_t)c.num_pages) ? pg : -1;
+}
+
+}  // namespace gqla

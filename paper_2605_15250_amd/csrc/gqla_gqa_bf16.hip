@@ -1,0 +1,196 @@
+// GQA-path split-L decode over the expanded cache, bf16 MFMA (paper Sec. 3.1, GQA-path equation).
+//
+// One wave per (chunk, 32-row block, group).  The expanded page stores K_C, V and k_R as 16-byte vectors
+// that are already MFMA operand fragments, so every cache byte goes HBM -> VGPR once, with no LDS staging:
+//   S^T[token][row] = K[token][dim] * Q^T[dim][row]        A = cache vectors, B = queries held in registers
+//   O^T[dim][row]  += V^T[dim][token] * P^T[token][row]    A = cache vectors, B = probabilities from S^T
+// S^T and O^T keep one query row per lane (row = lane % 32), so the online-softmax state is per lane and the
+// only cross-lane traffic is between the two half-waves.  All heads of a group (G * s_q rows) share each
+// loaded vector through the MFMA.  The path is bound by HBM bandwidth (intensity 19-39 FLOP/byte, Sec. 4.2.2).
+#include "gqla_device.h"
+
+namespace gqla {
+
+namespace {
+
+template <int DH, int DR>
+__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks) {
+  constexpr int KS_C = DH / 16;  // k-steps over the content dims
+  constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
+  constexpr int MT = DH / 32;    // 32-dim tiles of the output
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 8 + (threadIdx.x >> 6);
+  if (item >= n_items) return;
+  const int j = item % a.g;
+  const int rb = (item / a.g) % row_blocks;
+  const int chunk = item / (a.g * row_blocks);
+  const ChunkEntry ce = a.chunks[chunk];
+  const int n = lane & 31, h = lane >> 5;
+
+  // query row of this lane: rho in [0, G*s_q), rho = t*G + head-in-group
+  const int rho = rb * 32 + n;
+  const bool row_ok = rho < a.G * a.s_q;
+  const int t = row_ok ? rho / a.G : 0;
+  const int head = j * a.G + (row_ok ? rho % a.G : 0);
+  const int64_t qrow = (int64_t)(ce.b * a.s_q + t) * a.h_q + head;
+  const int vis_end = row_ok ? min(ce.tok_end, ce.L - a.s_q + t + 1) : 0;  // tokens this row may see in the chunk
+  const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);             // below this every real row sees every token
+
+  bf16x8 qc[KS_C], qr[KS_R];
+  {
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const __bf16* pc = (const __bf16*)a.q_a + qrow * DH + h * 8;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS_C; ++ks) qc[ks] = row_ok ? *(const bf16x8*)(pc + ks * 16) : zero;
+#pragma unroll
+    for (int ks = 0; ks < KS_R; ++ks) qr[ks] = row_ok ? *(const bf16x8*)(pr + ks * 16) : zero;
+  }
+
+  const int P = a.cache.page_size;
+  const int gc = a.cache.groups;
+  const int64_t page_elems = (int64_t)P * (2 * gc * DH + DR);
+  const __bf16* pool = (const __bf16*)a.cache.pool;
+
+  bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
+  bool k_ok = true, v_ok = true;
+
+  auto load_k = [&](int tok) {
+    const int32_t pg = page_of(a.cache, ce.b, tok / P);
+    k_ok = pg >= 0;
+    const __bf16* base = pool + (int64_t)(k_ok ? pg : 0) * page_elems;
+    const int slot = tok % P + n;
+    const __bf16* kb = base + (int64_t)j * DH * P + ((int64_t)h * P + slot) * 8;
+    const __bf16* rbp = base + (int64_t)2 * gc * DH * P + ((int64_t)h * P + slot) * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS_C; ++ks) kf[ks] = *(const bf16x8*)(kb + (int64_t)ks * 16 * P);
+#pragma unroll
+    for (int ks = 0; ks < KS_R; ++ks) rf[ks] = *(const bf16x8*)(rbp + (int64_t)ks * 16 * P);
+  };
+  auto load_v = [&](int tok) {
+    const int32_t pg = page_of(a.cache, ce.b, tok / P);
+    v_ok = pg >= 0;
+    const __bf16* base = pool + (int64_t)(v_ok ? pg : 0) * page_elems + (int64_t)gc * DH * P + (int64_t)j * DH * P;
+    const int tb = (tok % P) / 8 + h;  // 8-token block of this lane for k-step 0; k-step 1 is two blocks further
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+        vf[mt][kk] = *(const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 8);
+  };
+
+  f32x16 o[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
+  float m_run = GQLA_NEG_INF, l_run = 0.f;
+
+  load_k(ce.tok_begin);
+  load_v(ce.tok_begin);
+  for (int tok = ce.tok_begin; tok < ce.tok_end; tok += 32) {
+    f32x16 s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS_C; ++ks) s = mfma32(kf[ks], qc[ks], s);
+#pragma unroll
+    for (int ks = 0; ks < KS_R; ++ks) s = mfma32(rf[ks], qr[ks], s);
+    const bool tile_k_ok = k_ok;
+    const bool has_next = tok + 32 < ce.tok_end;
+    if (has_next) load_k(tok + 32);
+
+    // online softmax, base-2 domain; register i of lane (n, h) is token tok + 8*(i/4) + 4*h + i%4
+    float sv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sv[i] = s[i] * a.scale_log2e;
+    const bool need_mask = (tok + 32 > unmasked_end) || !tile_k_ok || !row_ok;
+    if (need_mask) {
+      const int lim = tile_k_ok ? vis_end : 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int tk = tok + 8 * (i >> 2) + 4 * h + (i & 3);
+        if (tk >= lim) sv[i] = GQLA_NEG_INF;
+      }
+    }
+    float tmax = sv[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sv[i]);
+    tmax = pair_max(tmax);
+    const float m_new = fmaxf(m_run, tmax);
+    const float m_use = (m_new == GQLA_NEG_INF) ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_use);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      sv[i] = fast_exp2(sv[i] - m_use);
+      psum += sv[i];
+    }
+    l_run = l_run * alpha + psum;  // per-lane partial sum; the two half-waves are added at the end
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
+
+    // P^T fragments: k-step kk covers tokens tok + 16*kk .. +15, lane half h needs tokens 8h .. 8h+7 of them
+    bf16x8 pf[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const uint32_t x0 = pack_bf16(sv[8 * kk + 0], sv[8 * kk + 1]), x1 = pack_bf16(sv[8 * kk + 2], sv[8 * kk + 3]);
+      const uint32_t y0 = pack_bf16(sv[8 * kk + 4], sv[8 * kk + 5]), y1 = pack_bf16(sv[8 * kk + 6], sv[8 * kk + 7]);
+      u32x4 w;
+      uint32_t r0, r1;
+      half_swap(x0, y0, r0, r1);
+      w[0] = r0;
+      w[2] = r1;
+      half_swap(x1, y1, r0, r1);
+      w[1] = r0;
+      w[3] = r1;
+      pf[kk] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    // values of tokens outside the chunk may hold any bits (NaN included): zero them so that 0 * v stays 0
+    if (tok + 32 > ce.tok_end || !v_ok) {
+      const int lim = v_ok ? ce.tok_end : 0;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (tok + 16 * kk + 8 * h + e >= lim) vf[mt][kk][e] = (__bf16)0.f;
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) o[mt] = mfma32(vf[mt][kk], pf[kk], o[mt]);
+    if (has_next) load_v(tok + 32);
+  }
+
+  const float l_tot = pair_sum(l_run);
+  if (!row_ok) return;
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  const int64_t prow = (int64_t)chunk * a.M + (int64_t)t * a.h_q + head;
+  float* po = (float*)a.part_o + prow * DH;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v = {o[mt][4 * q] * inv, o[mt][4 * q + 1] * inv, o[mt][4 * q + 2] * inv, o[mt][4 * q + 3] * inv};
+      *(f32x4*)(po + mt * 32 + 8 * q + 4 * h) = v;
+    }
+  if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_run + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+}
+
+}  // namespace
+
+hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
+  const int row_blocks = (a.G * a.s_q + 31) / 32;
+  const int n_items = a.n_chunks * row_blocks * a.g;
+  const int blocks = (n_items + 7) / 8;
+  decode_gqa_bf16_kernel<128, 64><<<blocks, 512, 0, s>>>(a, n_items, row_blocks);
+  return hipGetLastError();
+}
+
+}  // namespace gqla

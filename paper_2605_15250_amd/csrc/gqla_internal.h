@@ -1,0 +1,97 @@
+// Internal declarations shared by the host entry points and the HIP kernels of the GQLA library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "gqla.h"
+
+namespace gqla {
+
+// One row of the chunk table that a decode kernel reads (16 bytes).
+struct ChunkEntry {
+  int32_t b;          // sequence
+  int32_t tok_begin;  // first cached token of the chunk (multiple of page_size)
+  int32_t tok_end;    // one past the last token, clipped to L_b
+  int32_t L;          // L_b, for the in-step causal mask
+};
+
+// Device-side view of a cache pool.
+struct CacheView {
+  const void* pool;
+  const int32_t* page_table;  // may be null: identity map b*max_pages + p
+  int32_t page_size, max_pages, num_pages, groups;
+};
+
+// Arguments common to both decode kernels.
+struct DecodeArgs {
+  const void* q_a;  // q_c (GQA path) or q_hat (absorb path)
+  const void* q_r;
+  CacheView cache;
+  const ChunkEntry* chunks;
+  int32_t n_chunks;
+  void* part_o;      // GQA: fp32 [chunks][M][d_h];  absorb bf16: bf16 [chunks][M][r_kv];  absorb f32: fp32 [chunks][M][r_kv]
+  float* part_lse;   // fp32 [chunks][M], natural log
+  int32_t B, h_q, g, G, d_h, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i
+  float scale_log2e;                             // softmax scale times log2(e)
+};
+
+// Arguments of the combine (and, for the absorb path, combine + W_UV projection) kernels.
+struct CombineArgs {
+  const void* part_o;
+  const float* part_lse;
+  const int32_t* first_slot;  // int32[B + 1]
+  const void* w_uv;           // absorb path only
+  void* out;                  // [B][s_q][h_q][d_h]
+  float* lse;                 // optional [B][s_q][h_q]
+  int32_t B, h_q, g, G, d_h, r_kv, s_q, M;
+};
+
+struct ExpandArgs {
+  CacheView latent;
+  CacheView expanded;
+  const int32_t* seq_lens;
+  const void* w_uk;
+  const void* w_uv;
+  int32_t B, g, d_h, r_kv, d_r, group_begin, group_count;
+};
+
+struct AbsorbQueryArgs {
+  const void* q_c;
+  const void* w_uk;
+  void* q_hat;
+  int32_t rows;  // B * s_q
+  int32_t h_q, g, G, d_h, r_kv;
+};
+
+// Workspace layout (byte offsets) derived from a plan.
+struct WsLayout {
+  size_t table_off, first_slot_off, part_o_off, part_lse_off, total;
+};
+
+// Kernel launchers (each returns the hipError_t of its launch).
+hipError_t launch_absorb_query_f32(const AbsorbQueryArgs&, hipStream_t);
+hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs&, hipStream_t);
+hipError_t launch_decode_gqa_f32(const DecodeArgs&, hipStream_t);
+hipError_t launch_decode_gqa_bf16(const DecodeArgs&, hipStream_t);
+hipError_t launch_decode_absorb_f32(const DecodeArgs&, hipStream_t);
+hipError_t launch_decode_absorb_bf16(const DecodeArgs&, hipStream_t);
+hipError_t launch_combine_f32(const CombineArgs&, bool out_bf16, hipStream_t);           // partials in d_h space
+hipError_t launch_combine_project_f32(const CombineArgs&, hipStream_t);                  // fp32 latent partials, fp32 out
+hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);                 // bf16 latent partials, bf16 out
+hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
+hipError_t launch_expand_bf16(const ExpandArgs&, hipStream_t);
+
+}  // namespace gqla
+
+// The opaque plan of the public header.
+struct gqla_plan {
+  gqla_shape shape;
+  int32_t path, page_size, num_cus, chunk_pages;
+  std::vector<int32_t> lens;
+  std::vector<gqla::ChunkEntry> chunks;
+  std::vector<int32_t> first_slot;  // B + 1 entries
+  gqla::WsLayout ws;
+  const void* uploaded_ws;          // workspace the table was last uploaded into (host-side bookkeeping)
+};

@@ -1,0 +1,125 @@
+"""Device-side plumbing around the binding: moves seeded host arrays into HBM in the library's documented
+formats, owns plans and workspaces, and calls the entry points.  No arithmetic of the method happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+NUM_CUS = 256
+
+
+def torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def lib_dtype(dtype: str) -> int:
+    return B.GQLA_BF16 if dtype == "bf16" else B.GQLA_F32
+
+
+def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """Host fp32 array (already holding storage-representable values) -> device tensor of the storage type."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    return t.to(torch_dtype(dtype)).cuda()
+
+
+def build_latent_pool(cfg, lens, table, num_pages, row_fn, fill=float("nan")) -> torch.Tensor:
+    """Latent pool [num_pages, P, r_kv + d_r] on the device; row_fn(b, L_b) returns sequence b's rows.
+    Slots no token owns hold `fill` (NaN by default: a decode that touched them would show)."""
+    P, W = cfg.page_size, cfg.r_kv + cfg.d_r
+    pool = torch.full((num_pages, P, W), fill, dtype=torch_dtype(cfg.dtype), device="cuda")
+    flat = pool.view(num_pages * P, W)
+    for b in range(len(lens)):
+        L = int(lens[b])
+        rows = torch.from_numpy(row_fn(b, L)).to(torch_dtype(cfg.dtype))
+        t = np.arange(L)
+        idx = torch.from_numpy(table[b][t // P].astype(np.int64) * P + t % P).cuda()
+        flat[idx] = rows.cuda()
+    return pool
+
+
+class Decoder:
+    """Holds the device-resident state of one configuration and runs the four entry points on it."""
+
+    def __init__(self, cfg, lens, table, num_pages, groups=None, group_begin=0, use_page_table=True,
+                 chunk_pages_absorb=0, chunk_pages_gqa=0):
+        self.cfg = cfg
+        self.lens = np.ascontiguousarray(lens, dtype=np.int32)
+        self.table = np.ascontiguousarray(table, dtype=np.int32)
+        self.num_pages = int(num_pages)
+        self.max_pages = self.table.shape[1]
+        self.groups = cfg.g if groups is None else groups       # groups held by the expanded cache (TP slice if < g)
+        self.group_begin = group_begin
+        self.shape = B.make_shape(cfg.B, cfg.h_q, cfg.g, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q, lib_dtype(cfg.dtype))
+        G = cfg.h_q // cfg.g
+        # shape seen by the GQA decode: for a slice, only the heads and groups of the slice
+        self.shape_gqa = B.make_shape(cfg.B, G * self.groups, self.groups, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q,
+                                      lib_dtype(cfg.dtype), 0.0)
+        self.d_lens = torch.from_numpy(self.lens).cuda()
+        self.d_table = torch.from_numpy(self.table).cuda() if use_page_table else None
+        self.plan_a = B.gqla_plan_create(self.shape, self.lens, cfg.page_size, NUM_CUS, B.GQLA_PATH_ABSORB, chunk_pages_absorb)
+        self.plan_g = B.gqla_plan_create(self.shape_gqa, self.lens, cfg.page_size, NUM_CUS, B.GQLA_PATH_GQA, chunk_pages_gqa)
+        self.ws_a = torch.empty(B.gqla_plan_workspace_bytes(self.plan_a), dtype=torch.uint8, device="cuda")
+        self.ws_g = torch.empty(B.gqla_plan_workspace_bytes(self.plan_g), dtype=torch.uint8, device="cuda")
+        B.gqla_plan_upload(self.plan_a, self.ws_a)
+        B.gqla_plan_upload(self.plan_g, self.ws_g)
+        self.latent_pool = None
+        self.expanded_pool = None
+
+    def close(self):
+        for p in (self.plan_a, self.plan_g):
+            if p:
+                B.gqla_plan_destroy(p)
+        self.plan_a = self.plan_g = None
+
+    # -- caches -------------------------------------------------------------------------------------------
+    def latent_cache(self):
+        return B.make_cache(self.latent_pool, self.d_lens, self.d_table, self.cfg.page_size, self.max_pages, self.num_pages, 0)
+
+    def expanded_cache(self):
+        return B.make_cache(self.expanded_pool, self.d_lens, self.d_table, self.cfg.page_size, self.max_pages,
+                            self.num_pages, self.groups)
+
+    def expanded_page_elems(self):
+        c = self.cfg
+        return c.page_size * (2 * self.groups * c.d_h + c.d_r)
+
+    def alloc_expanded(self, fill=float("nan")):
+        self.expanded_pool = torch.full((self.num_pages * self.expanded_page_elems(),), fill,
+                                        dtype=torch_dtype(self.cfg.dtype), device="cuda")
+        return self.expanded_pool
+
+    # -- entry points ---------------------------------------------------------------------------------------
+    def absorb_query(self, q_c, w_uk, q_hat=None):
+        c = self.cfg
+        if q_hat is None:
+            q_hat = torch.empty((c.B, c.s_q, c.h_q, c.r_kv), dtype=torch_dtype(c.dtype), device="cuda")
+        B.gqla_absorb_query(self.shape, q_c, w_uk, q_hat)
+        return q_hat
+
+    def decode_absorb(self, q_hat, q_r, w_uv, out=None, lse=None):
+        c = self.cfg
+        if out is None:
+            out = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch_dtype(c.dtype), device="cuda")
+        if lse is None:
+            lse = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
+        B.gqla_decode_absorb(self.shape, self.plan_a, q_hat, q_r, self.latent_cache(), w_uv, out, lse, self.ws_a)
+        return out, lse
+
+    def expand(self, w_uk, w_uv):
+        if self.expanded_pool is None:
+            self.alloc_expanded()
+        B.gqla_expand_cache(self.shape, self.latent_cache(), w_uk, w_uv, self.group_begin, self.groups, self.expanded_cache())
+        return self.expanded_pool
+
+    def decode_gqa(self, q_c, q_r, out=None, lse=None):
+        """q_c, q_r: [B, s_q, heads of the slice, d] contiguous."""
+        c = self.cfg
+        hq = (c.h_q // c.g) * self.groups
+        if out is None:
+            out = torch.empty((c.B, c.s_q, hq, c.d_h), dtype=torch_dtype(c.dtype), device="cuda")
+        if lse is None:
+            lse = torch.empty((c.B, c.s_q, hq), dtype=torch.float32, device="cuda")
+        B.gqla_decode_gqa(self.shape_gqa, self.plan_g, q_c, q_r, self.expanded_cache(), out, lse, self.ws_g)
+        return out, lse

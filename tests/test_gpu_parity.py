@@ -1,0 +1,230 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by element, on the
+same seeded input bits.  bf16 bar: max abs 2e-2 and relative L2 1e-2; fp32 bar: max abs 1e-4, relative L2 1e-5
+(the fp32 kernels accumulate a few hundred fp32 products of O(1) values)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import gqla_oracle as O
+from oracle import layout as Lay
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-5)}
+
+
+def rel_l2(a, ref):
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def check(name, got, ref, dtype, scale_abs=1.0):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert np.isfinite(got).all(), name + ": non-finite output"
+    ma, rl = TOL[dtype]
+    err = float(np.max(np.abs(got - ref)))
+    r = rel_l2(got, ref)
+    print("%-34s max_abs %.3e  rel_l2 %.3e" % (name, err, r), flush=True)
+    assert err <= ma * scale_abs, "%s: max abs %.3e" % (name, err)
+    assert r <= rl, "%s: rel l2 %.3e" % (name, r)
+
+
+def host(t):
+    return t.float().cpu().numpy()
+
+
+class Case:
+    """Host copies of everything plus the device-side Decoder."""
+
+    def __init__(self, cfg, lens=None, groups=None, group_begin=0, use_page_table=True, chunk_pages=(0, 0)):
+        from paper_2605_15250_amd.harness import Decoder, to_device, build_latent_pool
+        self.cfg = cfg
+        self.lens = S.seq_lens(cfg) if lens is None else np.asarray(lens, np.int32)
+        cfg_t = cfg.with_(L=0) if lens is not None else cfg
+        self.table, self.num_pages = S.page_table(cfg_t, self.lens)
+        self.w_uk, self.w_uv = S.weights(cfg)
+        self.q_c, self.q_r = S.queries(cfg)
+        self.rows = [S.sequence_rows(cfg, b, self.lens[b]) for b in range(cfg.B)]
+        self.dec = Decoder(cfg, self.lens, self.table, self.num_pages, groups=groups, group_begin=group_begin,
+                           use_page_table=use_page_table, chunk_pages_absorb=chunk_pages[0], chunk_pages_gqa=chunk_pages[1])
+        self.dec.latent_pool = build_latent_pool(cfg, self.lens, self.table, self.num_pages, lambda b, L: self.rows[b])
+        self.d_w_uk = to_device(self.w_uk, cfg.dtype)
+        self.d_w_uv = to_device(self.w_uv, cfg.dtype)
+        self.d_q_c = to_device(self.q_c, cfg.dtype)
+        self.d_q_r = to_device(self.q_r, cfg.dtype)
+        self.to_device = to_device
+
+    def c(self, b):
+        return self.rows[b][:, : self.cfg.r_kv]
+
+    def kR(self, b):
+        return self.rows[b][:, self.cfg.r_kv:]
+
+    def close(self):
+        self.dec.close()
+
+
+def run_absorb_path(case, seqs=None):
+    cfg = case.cfg
+    seqs = range(cfg.B) if seqs is None else seqs
+    # a1: query absorption
+    q_hat = case.dec.absorb_query(case.d_q_c, case.d_w_uk)
+    torch.cuda.synchronize()
+    q_hat_h = host(q_hat)
+    ref_qh = np.stack([O.absorb_query(case.q_c[b], case.w_uk) for b in range(cfg.B)])
+    check("absorb_query", q_hat_h, ref_qh, cfg.dtype, scale_abs=4.0)   # |q_hat| ~ sqrt(d_h) * N(0, 1/r_kv) * ... O(1); bf16 ulp at 4
+    # a2-a4 in isolation: the oracle consumes exactly the q_hat bits the GPU consumes
+    out, lse = case.dec.decode_absorb(q_hat, case.d_q_r, case.d_w_uv)
+    torch.cuda.synchronize()
+    out_h, lse_h = host(out), host(lse)
+    ref_o = np.zeros_like(out_h, dtype=np.float64)
+    ref_l = np.zeros_like(lse_h, dtype=np.float64)
+    for b in seqs:
+        ref_o[b], ref_l[b] = O.decode_absorb(q_hat_h[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv)
+    sel = list(seqs)
+    check("decode_absorb (isolated)", out_h[sel], ref_o[sel], cfg.dtype)
+    check("decode_absorb lse", lse_h[sel], ref_l[sel], cfg.dtype)
+    # chained against the unrounded oracle
+    ref_c = np.stack([O.decode_absorb(ref_qh[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv)[0] for b in seqs])
+    check("absorb path (chained)", out_h[sel], ref_c, cfg.dtype)
+    return out_h
+
+
+def run_gqa_path(case, seqs=None):
+    cfg = case.cfg
+    dec = case.dec
+    seqs = range(cfg.B) if seqs is None else seqs
+    sel = list(seqs)
+    G = cfg.h_q // cfg.g
+    j0, gc = dec.group_begin, dec.groups
+    heads = slice(j0 * G, (j0 + gc) * G)
+    # a5: expansion on the GPU into a NaN-filled pool
+    dec.alloc_expanded()
+    pool = dec.expand(case.d_w_uk, case.d_w_uv)
+    torch.cuda.synchronize()
+    pool_h = host(pool)
+    exp_ref = {}
+    for b in seqs:
+        KC, V = O.expand_latent(case.c(b), case.w_uk[j0:j0 + gc], case.w_uv[j0:j0 + gc])
+        exp_ref[b] = (KC, V)
+        k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], case.lens[b], cfg.page_size, gc, cfg.d_h, cfg.d_r)
+        check("expand K_C seq %d" % b, k2, KC, cfg.dtype, scale_abs=2.0)
+        check("expand V seq %d" % b, v2, V, cfg.dtype, scale_abs=2.0)
+        assert np.array_equal(r2, case.kR(b)), "k_R must be copied bit for bit"
+    # slots no token owns were never written: still NaN, and their count is exact
+    per_tok = 2 * gc * cfg.d_h + cfg.d_r
+    assert int(np.isnan(pool_h).sum()) == pool_h.size - int(case.lens.sum()) * per_tok
+    # a6 in isolation: both sides consume the oracle's expansion rounded to the storage type
+    q_c_s = np.ascontiguousarray(case.q_c[:, :, heads, :])
+    q_r_s = np.ascontiguousarray(case.q_r[:, :, heads, :])
+    d_q_c, d_q_r = case.to_device(q_c_s, cfg.dtype), case.to_device(q_r_s, cfg.dtype)
+    KCq, Vq = {}, {}
+    KC_all, V_all, kR_all = [], [], []
+    for b in range(cfg.B):
+        if b in exp_ref:
+            KC, V = exp_ref[b]
+        else:
+            KC, V = O.expand_latent(case.c(b), case.w_uk[j0:j0 + gc], case.w_uv[j0:j0 + gc])
+        KCq[b], Vq[b] = S.quantize(KC, cfg.dtype), S.quantize(V, cfg.dtype)
+        KC_all.append(KCq[b]); V_all.append(Vq[b]); kR_all.append(case.kR(b))
+    iso_pool = Lay.pack_expanded_pool(KC_all, V_all, kR_all, case.table, case.num_pages, cfg.page_size)
+    gpu_pool = dec.expanded_pool
+    dec.expanded_pool = case.to_device(iso_pool, cfg.dtype)
+    out, lse = dec.decode_gqa(d_q_c, d_q_r)
+    torch.cuda.synchronize()
+    out_h, lse_h = host(out), host(lse)
+    ref_o = np.zeros_like(out_h, dtype=np.float64)
+    ref_l = np.zeros_like(lse_h, dtype=np.float64)
+    for b in seqs:
+        ref_o[b], ref_l[b] = O.decode_gqa(q_c_s[b], q_r_s[b], KCq[b], Vq[b], case.kR(b))
+    check("decode_gqa (isolated)", out_h[sel], ref_o[sel], cfg.dtype)
+    check("decode_gqa lse", lse_h[sel], ref_l[sel], cfg.dtype)
+    # chained: GPU expansion -> GPU decode against the unrounded oracle
+    dec.expanded_pool = gpu_pool
+    out2, _ = dec.decode_gqa(d_q_c, d_q_r)
+    torch.cuda.synchronize()
+    out2_h = host(out2)
+    ref_c = np.stack([O.decode_gqa(q_c_s[b], q_r_s[b], exp_ref[b][0], exp_ref[b][1], case.kR(b))[0] for b in seqs])
+    check("gqa path (chained)", out2_h[sel], ref_c, cfg.dtype)
+    return out2_h
+
+
+# ---- C0: the tiny fp32 configuration, everything checked, including the brute-force per-head attention ---------
+def test_c0_fp32_both_paths():
+    cfg = S.CONFIGS["C0"]
+    case = Case(cfg)
+    try:
+        oa = run_absorb_path(case)
+        og = run_gqa_path(case)
+        brute = O.decode_mha_bruteforce(case.q_c[0], case.q_r[0], case.c(0), case.kR(0), case.w_uk, case.w_uv)
+        check("absorb vs brute-force MHA", oa[0], brute, "f32")
+        check("gqa vs brute-force MHA", og[0], brute, "f32")
+    finally:
+        case.close()
+
+
+@pytest.mark.parametrize("s_q,lens,paged,cp", [
+    (1, [64], False, (0, 0)),
+    (2, [40, 7, 2], True, (0, 0)),          # L == s_q, ragged tails, permuted pages
+    (2, [100, 33], True, (2, 3)),           # forced multi-page chunks
+])
+def test_fp32_small_shapes(s_q, lens, paged, cp):
+    cfg = S.CONFIGS["C0"].with_(B=len(lens), s_q=s_q, L=0, paged=paged, page_size=8, seed=77)
+    case = Case(cfg, lens=lens, chunk_pages=cp)
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
+# ---- bf16 MFMA kernels at the paper's head dims, small batch: several tiles, ragged tails, permuted pages ----------
+@pytest.mark.parametrize("h_q,g,s_q,lens,paged,cp", [
+    (128, 8, 1, [300, 64, 129], True, (0, 0)),
+    (128, 8, 2, [257, 2, 1000, 65], True, (0, 0)),       # L == s_q, a chunk whose only token is hidden from row 0
+    (128, 8, 2, [1500, 700], True, (4, 5)),              # multi-page chunks with a ragged last chunk
+    (32, 8, 1, [513, 100], False, (3, 2)),               # LLaMA-3-8B-converted heads: G = 4 (padded MFMA rows)
+    (128, 8, 2, [640], False, (0, 0)),                   # contiguous cache, no page table
+])
+def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
+    cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
+    case = Case(cfg, lens=lens, use_page_table=paged, chunk_pages=cp)
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
+def test_bf16_single_group_slice():
+    """One rank's share of 8-way head-axis tensor parallelism: 16 heads, one group, 320 elements per token."""
+    cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=909)
+    case = Case(cfg, lens=[700, 130], groups=1, group_begin=5)
+    try:
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
+def test_page_permutation_is_bit_identical():
+    """Same logical data under an identity and a permuted page table, same plan: identical output bits."""
+    lens = [400, 90]
+    outs = []
+    for paged in (False, True):
+        cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=paged, seed=31337)
+        case = Case(cfg, lens=lens, use_page_table=True)
+        try:
+            q_hat = case.dec.absorb_query(case.d_q_c, case.d_w_uk)
+            oa, la = case.dec.decode_absorb(q_hat, case.d_q_r, case.d_w_uv)
+            case.dec.alloc_expanded()
+            case.dec.expand(case.d_w_uk, case.d_w_uv)
+            og, lg = case.dec.decode_gqa(case.d_q_c, case.d_q_r)
+            torch.cuda.synchronize()
+            outs.append([x.clone().cpu() for x in (oa, la, og, lg)])
+        finally:
+            case.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))

@@ -1,0 +1,150 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its host
+logic (split plan, offsets, argument validation) agrees with the oracle's independent bookkeeping."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import layout as Lay
+from paper_2605_15250_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gqla.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(gqla_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(B.gqla_shape) == 36
+    assert C.sizeof(B.gqla_cache) == 40
+
+
+@pytest.mark.parametrize("path,opath", [(B.GQLA_PATH_ABSORB, Lay.PATH_ABSORB), (B.GQLA_PATH_GQA, Lay.PATH_GQA)])
+@pytest.mark.parametrize("lens,h_q,g,s_q", [
+    ([8192] * 64, 128, 8, 1), ([8192] * 64, 128, 8, 2), ([4096] * 32, 32, 8, 1), ([8192] * 64, 16, 1, 2),
+    (list(range(1024, 32768, 499)), 128, 8, 2), ([1, 2, 63, 64, 65, 4097], 128, 8, 1), ([2], 128, 8, 2),
+])
+def test_plan_is_bit_exact_against_oracle_rule(path, opath, lens, h_q, g, s_q):
+    sh = B.make_shape(len(lens), h_q, g, 128, 512, 64, s_q, B.GQLA_BF16)
+    if min(lens) < s_q:
+        with pytest.raises(B.GqlaError) as e:
+            B.gqla_plan_create(sh, lens, 64, 256, path)
+        assert e.value.status == B.GQLA_ERR_SEQLEN
+        return
+    p = B.gqla_plan_create(sh, lens, 64, 256, path)
+    try:
+        cp = Lay.plan_chunk_pages(lens, 64, 256, opath, h_q, g, s_q)
+        chunks, first = Lay.plan_chunks(lens, 64, cp)
+        triples, first_lib = B.gqla_plan_export(p, len(lens))
+        assert B.gqla_plan_chunk_pages(p) == cp
+        assert B.gqla_plan_num_chunks(p) == len(chunks)
+        assert triples.tolist() == [list(c) for c in chunks]
+        assert first_lib.tolist() == first
+        assert B.gqla_plan_workspace_bytes(p) > 0
+    finally:
+        B.gqla_plan_destroy(p)
+
+
+def test_plan_override_and_random_lengths():
+    r = np.random.default_rng(0)
+    for _ in range(20):
+        B_ = int(r.integers(1, 40))
+        lens = r.integers(2, 5000, size=B_).tolist()
+        cp = int(r.integers(1, 9))
+        sh = B.make_shape(B_, 8, 2, 16, 32, 8, 2, B.GQLA_F32)
+        p = B.gqla_plan_create(sh, lens, 16, 256, B.GQLA_PATH_GQA, cp)
+        chunks, first = Lay.plan_chunks(lens, 16, cp)
+        triples, first_lib = B.gqla_plan_export(p, B_)
+        assert triples.tolist() == [list(c) for c in chunks] and first_lib.tolist() == first
+        B.gqla_plan_destroy(p)
+
+
+def test_offsets_match_oracle_layout():
+    r = np.random.default_rng(1)
+    for P, gc, d_h, d_r in ((64, 8, 128, 64), (16, 2, 16, 8), (128, 1, 128, 64)):
+        for _ in range(200):
+            page, j, slot = int(r.integers(0, 1000)), int(r.integers(0, gc)), int(r.integers(0, P))
+            d, dr = int(r.integers(0, d_h)), int(r.integers(0, d_r))
+            assert B.gqla_expanded_k_offset(page, j, slot, d, P, gc, d_h, d_r) == Lay.expanded_k_offset(page, j, slot, d, P, gc, d_h, d_r)
+            assert B.gqla_expanded_v_offset(page, j, slot, d, P, gc, d_h, d_r) == Lay.expanded_v_offset(page, j, slot, d, P, gc, d_h, d_r)
+            assert B.gqla_expanded_kr_offset(page, slot, dr, P, gc, d_h, d_r) == Lay.expanded_kr_offset(page, slot, dr, P, gc, d_h, d_r)
+            assert B.gqla_latent_offset(page, slot, d, P, 512, d_r) == Lay.latent_offset(page, slot, d, P, 512, d_r)
+    assert B.gqla_latent_elems_per_token(512, 64) == 576
+    assert B.gqla_expanded_elems_per_token(8, 128, 64) == 2112
+    assert B.gqla_expanded_elems_per_token(4, 128, 64) * 2 == 2176
+    # large pools do not overflow 32 bits: page 600000 of a g = 8 pool
+    assert B.gqla_expanded_k_offset(600000, 0, 0, 0, 64, 8, 128, 64) == 600000 * 64 * 2112
+
+
+def _expect(status, fn, *args, **kw):
+    with pytest.raises(B.GqlaError) as e:
+        fn(*args, **kw)
+    assert e.value.status == status, (e.value.status, status)
+
+
+def test_argument_validation_happens_on_the_host():
+    """Every rejected call returns before touching a device (this container has none)."""
+    ok = B.make_shape(2, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
+    lens = [100, 200]
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 10, 4, 128, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, 0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 128, 8, 128, 512, 64, 3, B.GQLA_BF16), lens, 64, 256, 0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 128, 8, 96, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, 0)
+    _expect(B.GQLA_ERR_DTYPE, B.gqla_plan_create, B.make_shape(2, 128, 8, 128, 512, 64, 1, 7), lens, 64, 256, 0)
+    _expect(B.GQLA_ERR_PAGE, B.gqla_plan_create, ok, lens, 48, 256, 0)
+    _expect(B.GQLA_ERR_PLAN, B.gqla_plan_create, ok, lens, 64, 256, 5)
+    _expect(B.GQLA_ERR_SEQLEN, B.gqla_plan_create, ok, [100, 0], 64, 256, 0)
+    # fake but aligned "device" addresses: validation never dereferences them
+    A = 0x10000
+    _expect(B.GQLA_ERR_NULL, B.gqla_absorb_query, ok, None, A, A, stream=0)
+    _expect(B.GQLA_ERR_ALIGN, B.gqla_absorb_query, ok, A + 2, A, A, stream=0)
+    plan_a = B.gqla_plan_create(ok, lens, 64, 256, B.GQLA_PATH_ABSORB)
+    plan_g = B.gqla_plan_create(ok, lens, 64, 256, B.GQLA_PATH_GQA)
+    try:
+        big = 1 << 30
+        cache = B.make_cache(A, A, None, 64, 4, 8, 0)
+        # table not uploaded into this workspace
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_decode_absorb, ok, plan_a, A, A, cache, A, A, None, A, big, stream=0)
+        # wrong path for the plan
+        _expect(B.GQLA_ERR_PLAN, B.gqla_decode_absorb, ok, plan_g, A, A, cache, A, A, None, A, big, stream=0)
+        # plan built for another shape
+        other = B.make_shape(2, 128, 8, 128, 512, 64, 2, B.GQLA_BF16)
+        _expect(B.GQLA_ERR_PLAN, B.gqla_decode_gqa, other, plan_g, A, A, cache, A, None, A, big, stream=0)
+        # cache too short for the planned lengths (max_pages * page_size < 200)
+        short = B.make_cache(A, A, None, 64, 2, 8, 8)
+        _expect(B.GQLA_ERR_SEQLEN, B.gqla_decode_gqa, ok, plan_g, A, A, short, A, None, A, big, stream=0)
+        # identity page map needs batch * max_pages pages
+        small = B.make_cache(A, A, None, 64, 4, 7, 8)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_decode_gqa, ok, plan_g, A, A, small, A, None, A, big, stream=0)
+        # page size differs from the plan's
+        _expect(B.GQLA_ERR_PAGE, B.gqla_decode_gqa, ok, plan_g, A, A, B.make_cache(A, A, None, 128, 4, 8, 8), A, None, A, big, stream=0)
+        # workspace too small for the upload
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_plan_upload, plan_g, A, 16, stream=0)
+        # expand: group range and geometry
+        lat = B.make_cache(A, A, None, 64, 4, 8, 0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache, ok, lat, A, A, 6, 3, B.make_cache(A, A, None, 64, 4, 8, 3), stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, B.make_cache(A, A, None, 64, 4, 8, 4), stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, B.make_cache(A, A, None, 64, 5, 8, 8), stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_expand_cache, ok, B.make_cache(A, None, None, 64, 4, 8, 0), A, A, 0, 8,
+                B.make_cache(A, A, None, 64, 4, 8, 8), stream=0)
+    finally:
+        B.gqla_plan_destroy(plan_a)
+        B.gqla_plan_destroy(plan_g)
+    assert B.status_string(B.GQLA_OK) == "ok"
+
+
+def test_empty_batch_is_ok_without_launch():
+    sh = B.make_shape(0, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
+    A = 0x10000
+    B.gqla_absorb_query(sh, A, A, A, stream=0)      # returns GQLA_OK, launches nothing
+    p = B.gqla_plan_create(sh, [], 64, 256, B.GQLA_PATH_GQA)
+    assert B.gqla_plan_num_chunks(p) == 0
+    B.gqla_plan_destroy(p)
