@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the GQLA decode-attention hot path on one MI355X.
+
+One step = one pass of the whole path at the paper's canonical shape (h_q=128, g=8, d_h=128, r_kv=512, d_R=64),
+B=64 sequences of L=8192 cached tokens, on seeded synthetic data already resident in HBM:
+    absorb leg (s_q=1):  gqla_absorb_query -> gqla_decode_absorb   (split-L flash-decode over the latent cache, combine, W_UV)
+    GQA leg   (s_q=2):   gqla_expand_cache -> gqla_decode_gqa      (latent -> per-group cache, grouped decode, combine)
+Prints ONE JSON line.  `value` = decoded step tokens per second of the whole step (B*1 + B*2 tokens per step);
+the per-call figures, their roofline fractions and the oracle's CPU rate on a bounded sample ride along."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
+    ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
+    ap.add_argument("--cpu-seqs", type=int, default=6, help="sequences per leg in the oracle's bounded sample (0 = skip)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no sharding or collectives exist in it); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth_inputs as S
+    from paper_2605_15250_amd import binding as B
+    from paper_2605_15250_amd.harness import Decoder, build_latent_pool, to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()  # fails loudly if libgqla.so is missing: there is no fallback path
+    torch.cuda.set_device(0)
+
+    legs = {}
+    for key, path in (("C2", "absorb"), ("C3", "gqa")):
+        cfg = S.CONFIGS[key]
+        if args.batch:
+            cfg = cfg.with_(B=args.batch)
+        if args.ctx:
+            cfg = cfg.with_(L=args.ctx)
+        lens = S.seq_lens(cfg)
+        table, num_pages = S.page_table(cfg, lens)
+        dec = Decoder(cfg, lens, table, num_pages, use_page_table=False)   # contiguous cache, identity page map
+        dec.latent_pool = build_latent_pool(cfg, lens, table, num_pages, lambda b, L, cfg=cfg: S.sequence_rows(cfg, b, L), fill=0.0)
+        w_uk, w_uv = S.weights(cfg)
+        q_c, q_r = S.queries(cfg)
+        legs[path] = dict(cfg=cfg, lens=lens, table=table, dec=dec, w_uk=w_uk, w_uv=w_uv, q_c=q_c, q_r=q_r,
+                          d_w_uk=to_device(w_uk, cfg.dtype), d_w_uv=to_device(w_uv, cfg.dtype),
+                          d_q_c=to_device(q_c, cfg.dtype), d_q_r=to_device(q_r, cfg.dtype))
+    A, Gq = legs["absorb"], legs["gqa"]
+    ca, cg = A["cfg"], Gq["cfg"]
+    A["q_hat"] = torch.empty((ca.B, ca.s_q, ca.h_q, ca.r_kv), dtype=torch.bfloat16, device="cuda")
+    A["out"] = torch.empty((ca.B, ca.s_q, ca.h_q, ca.d_h), dtype=torch.bfloat16, device="cuda")
+    A["lse"] = torch.empty((ca.B, ca.s_q, ca.h_q), dtype=torch.float32, device="cuda")
+    Gq["out"] = torch.empty((cg.B, cg.s_q, cg.h_q, cg.d_h), dtype=torch.bfloat16, device="cuda")
+    Gq["lse"] = torch.empty((cg.B, cg.s_q, cg.h_q), dtype=torch.float32, device="cuda")
+    Gq["dec"].alloc_expanded(fill=0.0)
+
+    names = ["absorb_query", "decode_absorb", "expand_cache", "decode_gqa"]
+
+    def step(events=None):
+        def rec(i):
+            if events is not None:
+                events[i].record()
+        rec(0)
+        A["dec"].absorb_query(A["d_q_c"], A["d_w_uk"], A["q_hat"])
+        rec(1)
+        A["dec"].decode_absorb(A["q_hat"], A["d_q_r"], A["d_w_uv"], A["out"], A["lse"])
+        rec(2)
+        Gq["dec"].expand(Gq["d_w_uk"], Gq["d_w_uv"])
+        rec(3)
+        Gq["dec"].decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
+        rec(4)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)])) for i, n in enumerate(names)}
+
+    # ---- accounting: the paper's closed forms (Sec. 4.2.1 / 4.2.2) ----------------------------------------------
+    La, Lg = int(A["lens"].sum()), int(Gq["lens"].sum())
+    bytes_absorb = 2 * La * (ca.r_kv + ca.d_r)
+    flops_absorb = 2 * La * ca.h_q * ca.s_q * (2 * ca.r_kv + ca.d_r)
+    bytes_gqa = 2 * Lg * (2 * cg.g * cg.d_h + cg.d_r)
+    flops_gqa = 2 * Lg * cg.h_q * cg.s_q * (2 * cg.d_h + cg.d_r)
+    bytes_expand = bytes_gqa + 2 * Lg * (cg.r_kv + cg.d_r)
+    flops_expand = 2 * Lg * cg.r_kv * 2 * cg.g * cg.d_h
+
+    def roof(name, bound, nbytes, flops):
+        t = call_ms[name] * 1e-3
+        gbs, tf = nbytes / t / 1e9, flops / t / 1e12
+        intensity = flops / nbytes
+        attainable_tf = min(intensity * HBM_PEAK_GBS / 1e3, MFMA_BF16_PEAK_TFLOPS)
+        r = {"call": name, "ms": call_ms[name], "GB/s": gbs, "TFLOP/s": tf, "frac_hbm_peak": gbs / HBM_PEAK_GBS,
+             "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "frac_of_min_roof": tf / attainable_tf,
+             "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
+        if bound == "hbm":
+            r.update({"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS})
+        else:
+            r.update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": tf / MFMA_BF16_PEAK_TFLOPS})
+        r["traffic"] = None
+        return r
+
+    roofs = [roof("decode_absorb", "mfma", bytes_absorb, flops_absorb),
+             roof("decode_gqa", "hbm", bytes_gqa, flops_gqa),
+             roof("expand_cache", "mfma", bytes_expand, flops_expand)]
+    dominant = max(roofs, key=lambda r: r["ms"])
+    tokens_per_step = ca.B * ca.s_q + cg.B * cg.s_q
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- the oracle on a bounded sample of the same workload, and a parity spot check ---------------------------------
+    cpu = None
+    parity = None
+    if args.cpu_seqs > 0:
+        from oracle import gqla_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        nb = min(args.cpu_seqs, ca.B)
+        out_a = A["out"].float().cpu().numpy()
+        out_g = Gq["out"].float().cpu().numpy()
+        ref_a, ref_g = [], []
+        rows_a = [S.sequence_rows(ca, b, A["lens"][b]) for b in range(nb)]
+        rows_g = [S.sequence_rows(cg, b, Gq["lens"][b]) for b in range(nb)]
+        tc0 = time.perf_counter()
+        for b in range(nb):
+            c, kR = rows_a[b][:, :ca.r_kv], rows_a[b][:, ca.r_kv:]
+            qh = O.absorb_query(A["q_c"][b], A["w_uk"])
+            ref_a.append(O.decode_absorb(qh, A["q_r"][b], c, kR, A["w_uv"])[0])
+            c, kR = rows_g[b][:, :cg.r_kv], rows_g[b][:, cg.r_kv:]
+            KC, V = O.expand_latent(c, Gq["w_uk"], Gq["w_uv"])
+            ref_g.append(O.decode_gqa(Gq["q_c"][b], Gq["q_r"][b], KC, V, kR)[0])
+        tc1 = time.perf_counter()
+        cpu = {"value": nb * (ca.s_q + cg.s_q) / (tc1 - tc0), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": "first %d of %d sequences of each leg (absorb s_q=1 and expand+GQA s_q=2 at L=%d), numpy fp64, %.1f s"
+                         % (nb, ca.B, ca.L, tc1 - tc0)}
+        ref_a, ref_g = np.stack(ref_a), np.stack(ref_g)
+
+        def errs(got, ref):
+            return {"max_abs": float(np.max(np.abs(got - ref))), "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+        parity = {"absorb_vs_oracle": errs(out_a[:nb], ref_a), "gqa_vs_oracle": errs(out_g[:nb], ref_g),
+                  "tolerance": {"max_abs": 2e-2, "rel_l2": 1e-2}}
+
+    wl = "canonical (h_q=128,g=8,d_h=128,r_kv=512,d_R=64) B=%d L=%d: configs[2] absorb s_q=1 + configs[3] expand+GQA s_q=2" % (ca.B, ca.L)
+    line = {
+        "metric": "decode attn tokens/s + % roofline (MFMA absorb, HBM GB/s GQA) on 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl, "batch": ca.B, "context": ca.L, "tokens_per_step": tokens_per_step,
+                   "page_size": ca.page_size, "cache": "contiguous"},
+        "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["call"]},
+        "rooflines": roofs,
+        "calls_ms": call_ms,
+        "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / ((call_ms["absorb_query"] + call_ms["decode_absorb"]) * 1e-3),
+                  "gqa_decode_tokens_per_s": cg.B * cg.s_q / (call_ms["decode_gqa"] * 1e-3)},
+        "cpu_baseline": cpu,
+        "parity": parity,
+    }
+    print(json.dumps(line))
+    for leg in legs.values():
+        leg["dec"].close()
+
+
+if __name__ == "__main__":
+    main()
