@@ -31,6 +31,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
     ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
+    ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
     ap.add_argument("--cpu-seqs", type=int, default=6, help="sequences per leg in the oracle's bounded sample (0 = skip)")
     return ap.parse_args()
 
@@ -79,18 +80,24 @@ def main():
 
     names = ["absorb_query", "decode_absorb", "expand_cache", "decode_gqa"]
 
+    run_legs = set(args.legs.split(","))
+
     def step(events=None):
         def rec(i):
             if events is not None:
                 events[i].record()
         rec(0)
-        A["dec"].absorb_query(A["d_q_c"], A["d_w_uk"], A["q_hat"])
+        if "absorb" in run_legs:
+            A["dec"].absorb_query(A["d_q_c"], A["d_w_uk"], A["q_hat"])
         rec(1)
-        A["dec"].decode_absorb(A["q_hat"], A["d_q_r"], A["d_w_uv"], A["out"], A["lse"])
+        if "absorb" in run_legs:
+            A["dec"].decode_absorb(A["q_hat"], A["d_q_r"], A["d_w_uv"], A["out"], A["lse"])
         rec(2)
-        Gq["dec"].expand(Gq["d_w_uk"], Gq["d_w_uv"])
+        if "gqa" in run_legs:
+            Gq["dec"].expand(Gq["d_w_uk"], Gq["d_w_uv"])
         rec(3)
-        Gq["dec"].decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
+        if "gqa" in run_legs:
+            Gq["dec"].decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
         rec(4)
 
     for _ in range(args.warmup):
@@ -116,7 +123,7 @@ def main():
     flops_expand = 2 * Lg * cg.r_kv * 2 * cg.g * cg.d_h
 
     def roof(name, bound, nbytes, flops):
-        t = call_ms[name] * 1e-3
+        t = max(call_ms[name], 1e-6) * 1e-3
         gbs, tf = nbytes / t / 1e9, flops / t / 1e12
         intensity = flops / nbytes
         attainable_tf = min(intensity * HBM_PEAK_GBS / 1e3, MFMA_BF16_PEAK_TFLOPS)
@@ -184,8 +191,8 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["call"]},
         "rooflines": roofs,
         "calls_ms": call_ms,
-        "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / ((call_ms["absorb_query"] + call_ms["decode_absorb"]) * 1e-3),
-                  "gqa_decode_tokens_per_s": cg.B * cg.s_q / (call_ms["decode_gqa"] * 1e-3)},
+        "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / (max(call_ms["absorb_query"] + call_ms["decode_absorb"], 1e-6) * 1e-3),
+                  "gqa_decode_tokens_per_s": cg.B * cg.s_q / (max(call_ms["decode_gqa"], 1e-6) * 1e-3)},
         "cpu_baseline": cpu,
         "parity": parity,
     }

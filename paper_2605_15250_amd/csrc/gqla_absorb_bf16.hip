@@ -24,14 +24,18 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 template <int RKV, int DR>
 __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, int row_blocks, int n_chunks_padded) {
   constexpr int W = RKV + DR;        // elements per latent row
-  constexpr int RC = W / 8;          // 16-byte chunks per row
+  constexpr int ROWB = W * 2;        // bytes per latent row
+  constexpr int NP = W / 64;         // 128-byte panels per latent row
+  constexpr int PANEL = kTile * 128; // bytes per panel
   constexpr int KS = W / 16;         // k-steps of the key contraction
   constexpr int DT = RKV / 32;       // 32-wide tiles of the latent output
-  constexpr int TILE_BYTES = kTile * W * 2;
+  constexpr int TILE_BYTES = kTile * ROWB;
+  static_assert(W % 64 == 0 && RKV % 64 == 0, "latent row must be a whole number of 128-byte panels");
+  static_assert((32 + 16 + 8 + 4) * 128 + 128 + PANEL * (RKV / 64 - 1) < 65536, "value-fragment offsets must fit the 16-bit LDS immediate");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  // blockIdx -> (chunk, row block): the row blocks of one chunk get consecutive-by-8 ids so that they run on the
-  // same XCD (ids are dealt round-robin over the 8 XCDs) and share the chunk's cache lines in that XCD's L2.
+  // blockIdx -> (chunk, row block): the row blocks of one chunk get ids that are equal modulo 8 so that they run on
+  // the same XCD (ids are dealt round-robin over the 8 XCDs) and share the chunk's cache lines in that XCD's L2.
   int chunk, rbk;
   {
     const int id = blockIdx.x;
@@ -51,16 +55,16 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);
   const bool wave_active = rbk * kRowsPerBlock + wave * 32 < a.M;
 
+  // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step
   bf16x8 qf[KS];
   {
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int64_t qrow = (int64_t)ce.b * a.M + rho;
+    const int64_t qrow = (int64_t)ce.b * a.M + min(rho, a.M - 1);
     const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8;
     const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < RKV / 16; ++ks) qf[ks] = row_ok ? *(const bf16x8*)(ph + ks * 16) : zero;
+    for (int ks = 0; ks < RKV / 16; ++ks) qf[ks] = *(const bf16x8*)(ph + ks * 16);
 #pragma unroll
-    for (int ks = 0; ks < DR / 16; ++ks) qf[RKV / 16 + ks] = row_ok ? *(const bf16x8*)(pr + ks * 16) : zero;
+    for (int ks = 0; ks < DR / 16; ++ks) qf[RKV / 16 + ks] = *(const bf16x8*)(pr + ks * 16);
   }
 
   const int P = a.cache.page_size;
@@ -68,9 +72,24 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   auto issue_tile = [&](int tok, char* buf) {
     const int32_t pg = page_of(a.cache, ce.b, tok / P);
     const int valid = pg >= 0 ? min(kTile, ce.tok_end - tok) : 0;
-    const char* g = pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * (W * 2);
-    stage_rows<RC>(buf, g, W * 2, kTile, valid, wave, 4, lane);
+    const char* g = pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * ROWB;
+    stage_panels<kTile, NP, 4, ROWB>(buf, g, valid, wave, lane);
   };
+
+  // Per-lane LDS byte offsets inside a tile (panel layout of gqla_lds.h; everything else is a compile-time offset):
+  //  key fragments     row 32*mt + n, chunk 2*ks + h with ks = 4*a4 + b: panel a4, in-panel chunk 2*b + h
+  //                    -> four bases (b = 0..3), plus a4*PANEL + 32*mt*128.
+  //  value fragments   (transposed reads) this lane addresses row R0 + 4*h + e (and 8 rows further for the second read),
+  //                    4 columns at 32*dt + 16*g1 + 4*q: panel dt/2, in-panel chunk 4*(dt & 1) + cl, cl = 2*g1 + q/2.
+  //                    With R0 a multiple of 16, swz = 2*h + e/2 for the first read and 4 + that for the second, so the
+  //                    chunk lands at 4*(dt & 1) + (cl ^ swz) resp. 4*(1 - (dt & 1)) + (cl ^ swz): one base per lane.
+  uint32_t kbase[4], vbase;
+  {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) kbase[b] = n * 128 + (((2 * b + h) ^ lds_swz(n)) << 4);
+    const int i16 = lane & 15, e = i16 >> 2, q = i16 & 3, g1 = (lane >> 4) & 1;
+    vbase = (4 * h + e) * 128 + (((2 * g1 + (q >> 1)) ^ (2 * h + (e >> 1))) << 4) + (q & 1) * 8;
+  }
 
   f32x16 o[DT];
 #pragma unroll
@@ -90,67 +109,108 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 
     if (!wave_active) continue;  // waves without query rows only help staging (uniform per wave)
     const bool tile_ok = page_of(a.cache, ce.b, tok / P) >= 0;
-
-    // ---- S^T = Kt * Qhat^T : two 32-token tiles ----
-    f32x16 s[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[mt][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) s[mt] = mfma32(row_frag<RC>(buf, 32 * mt + n, 2 * ks + h), qf[ks], s[mt]);
-    }
-
-    // ---- online softmax (base 2); register i of s[mt] is token tok + 32*mt + 8*(i/4) + 4*h + i%4 ----
     const bool need_mask = (tok + kTile > unmasked_end) || !row_ok || !tile_ok;
     const int lim = tile_ok ? vis_end : 0;
-    float tmax = GQLA_NEG_INF;
+
+#pragma unroll 1
+    for (int mt = 0; mt < 2; ++mt) {  // two 32-token halves of the tile, each: S^T, softmax, O^T update
+      // ---- S^T[token][row] = Kt * Qhat^T ----
+      // These MFMAs accumulate in ordinary VGPRs (written as inline assembly) because all 256 accumulation
+      // registers hold O^T; the compiler's own MFMA selection would put S^T there as well and spill.
+      f32x16 s, s_odd;  // two accumulation chains (even / odd k-steps) so that consecutive MFMAs are independent
+      bf16x8 f[2][4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+      for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b] + (32 * mt * 128));
+#pragma unroll
+      for (int a4 = 0; a4 < KS / 4; ++a4) {
+        if (a4 + 1 < KS / 4) {
+#pragma unroll
+          for (int b = 0; b < 4; ++b) f[(a4 + 1) & 1][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 1) * PANEL + 32 * mt * 128));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
+          else if (a4 == 0 && b == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s_odd) : "v"(f[0][1]), "v"(qf[1]));
+          else if (b & 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s_odd) : "v"(f[a4 & 1][b]), "v"(qf[4 * a4 + b]));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 & 1][b]), "v"(qf[4 * a4 + b]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // first batch of value fragments: issued now, consumed after the softmax
+      i16x4 r[2][4][2];
+      auto load_v = [&](int slot, int u, int p4) {  // output tiles dt = 4*p4 .. 4*p4 + 3 of k-step u
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const int dt = 4 * p4 + d;
+          const int off = (dt >> 1) * PANEL + (32 * mt + 16 * u) * 128;
+          r[slot][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 64 * (dt & 1))));
+          r[slot][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 8 * 128 + 64 * (1 - (dt & 1)))));
+        }
+      };
+      load_v(0, 0, 0);
+      // the matrix pipeline's result is not interlocked against vector-ALU reads: wait out its 8 passes
+      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s), "+v"(s_odd));
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] += s_odd[i];
+
+      // ---- online softmax (base 2); register i is token tok + 32*mt + 8*(i/4) + 4*h + i%4 ----
+      float tmax = GQLA_NEG_INF;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float v = s[mt][i] * a.scale_log2e;
+        float v = s[i] * a.scale_log2e;
         if (need_mask && tok + 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3) >= lim) v = GQLA_NEG_INF;
-        s[mt][i] = v;
+        s[i] = v;
         tmax = fmaxf(tmax, v);
       }
-    tmax = pair_max(tmax);
-    if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRescaleThreshold) != 0) {
-      const float m_new = fmaxf(m_ref, tmax);
-      const float alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
-      m_ref = m_new;
-      l_run *= alpha;
-      if (it > 0) {
+      tmax = pair_max(tmax);
+      if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRescaleThreshold) != 0) {
+        const float m_new = fmaxf(m_ref, tmax);
+        const float alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
+        m_ref = m_new;
+        l_run *= alpha;
+        if (it > 0 || mt > 0) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+          for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+            for (int i = 0; i < 16; ++i) {
+              float x = o[dt][i], tmp;
+              asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1" : "+a"(x), "=&v"(tmp) : "v"(alpha));
+              o[dt][i] = x;
+            }
+        }
       }
-    }
-    const float m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
-    bf16x8 pf[4];  // k-step 2*mt + u: tokens 32*mt + 16*u + {4h..4h+3, 8+4h..8+4h+3}
-    float psum = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+      const float m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
+      bf16x8 pf[2];  // k-step u: tokens 32*mt + 16*u + {4h..4h+3, 8+4h..8+4h+3}
+      float psum = 0.f;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         float p[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          p[e] = fast_exp2(s[mt][8 * u + e] - m_use);
+          p[e] = fast_exp2(s[8 * u + e] - m_use);
           psum += p[e];
         }
         u32x4 w = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-        pf[2 * mt + u] = __builtin_bit_cast(bf16x8, w);
+        pf[u] = __builtin_bit_cast(bf16x8, w);
       }
-    l_run += psum;
+      l_run += psum;
+      __builtin_amdgcn_sched_barrier(0);
 
-    // ---- O^T += C^T * P^T ----
+      // ---- O^T[r][row] += C^T * P^T, value fragments one batch of four tiles ahead ----
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int row_a = 16 * kk + 4 * h;  // rows matching elements 0..3 of pf[kk]; elements 4..7 are 8 rows further
+      for (int bt = 0; bt < 2 * (DT / 4); ++bt) {
+        const int u = bt / (DT / 4), p4 = bt % (DT / 4);
+        if (bt + 1 < 2 * (DT / 4)) load_v((bt + 1) & 1, (bt + 1) / (DT / 4), (bt + 1) % (DT / 4));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[dt] = mfma32(tr_frag<RC>(buf, row_a, row_a + 8, 32 * dt, lane), pf[kk], o[dt]);
+        for (int d = 0; d < 4; ++d) {
+          const i16x4 lo = r[bt & 1][d][0], hi = r[bt & 1][d][1];
+          const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          o[4 * p4 + d] = mfma32(__builtin_bit_cast(bf16x8, fr), pf[u], o[4 * p4 + d]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 
@@ -170,25 +230,29 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 }
 
 // ---- combine + latent-output projection: out = W_UV[j]^T (sum_k w_k o_hat_k)   (MQA-absorb equation, line 6) ----
-// One workgroup of 4 waves per (group j, 128 query rows of that group); W_UV[j] ([r_kv][d_h], 128 KB) is staged in
-// LDS and read transposed: O^T[d][row] = W^T[d][r] * Ohat^T[r][row].
+// One workgroup of 4 waves per (group j, 32 query rows of that group).  W_UV[j] ([r_kv][d_h], 128 KB) is staged in LDS
+// and read transposed; wave w contracts over latent dims [w*RKV/4, (w+1)*RKV/4):
+//   O^T[d][row] += W^T[d][r] * Ohat^T[r][row]     A = transposed LDS fragments, B = the combined chunk partials
+// and the four partial O^T are summed through LDS.
 template <int RKV, int DH>
 __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a, int rows_per_group) {
-  constexpr int RC = DH / 8;
-  constexpr int KS = RKV / 16;
+  constexpr int KSW = RKV / 16 / 4;  // k-steps per wave
   constexpr int MT = DH / 32;
+  static_assert(MT == 4, "one output tile per wave in the final reduction");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 31, h = lane >> 5;
   const int j = blockIdx.y;
-  stage_rows<RC>(smem, (const char*)a.w_uv + (int64_t)j * RKV * DH * 2, DH * 2, RKV, RKV, wave, 4, lane);
+  stage_panels_full<RKV, DH / 64, 4, DH * 2>(smem, (const char*)a.w_uv + (int64_t)j * RKV * DH * 2, wave, lane);
 
   // row of this lane among the rows of group j: x = (b * s_q + t) * G + head-in-group
-  const int x = blockIdx.x * 128 + wave * 32 + n;
+  const int x = blockIdx.x * 32 + n;
   const bool row_ok = x < rows_per_group;
-  const int b = row_ok ? x / (a.s_q * a.G) : 0;
-  const int t = row_ok ? (x / a.G) % a.s_q : 0;
-  const int rho = t * a.h_q + j * a.G + (row_ok ? x % a.G : 0);
+  const int xc = row_ok ? x : 0;
+  const int b = xc / (a.s_q * a.G);
+  const int t = (xc / a.G) % a.s_q;
+  const int rho = t * a.h_q + j * a.G + xc % a.G;
   const int s0 = a.first_slot[b], s1 = a.first_slot[b + 1];
   float m = GQLA_NEG_INF;
   for (int s = s0; s < s1; ++s) m = fmaxf(m, a.part_lse[(int64_t)s * a.M + rho]);
@@ -196,46 +260,69 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
   for (int s = s0; s < s1; ++s) den += __expf(a.part_lse[(int64_t)s * a.M + rho] - m);
   const float inv_den = row_ok ? 1.f / den : 0.f;
 
-  wait_all_memory();
-  __syncthreads();
+  // combined latent output of this lane's row, dims 16*(KSW*wave + ksl) + 8*h + 0..7, fp32
+  float acc[KSW][8];
+#pragma unroll
+  for (int ksl = 0; ksl < KSW; ++ksl)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[ksl][e] = 0.f;
+  const __bf16* po = (const __bf16*)a.part_o + (int64_t)rho * RKV + (KSW * wave) * 16 + h * 8;
+  for (int s = s0; s < s1; ++s) {
+    const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m) * inv_den;
+    u32x4 v[KSW];
+#pragma unroll
+    for (int ksl = 0; ksl < KSW; ++ksl) v[ksl] = *(const u32x4*)(po + (int64_t)s * a.M * RKV + ksl * 16);
+#pragma unroll
+    for (int ksl = 0; ksl < KSW; ++ksl)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[ksl][2 * e] += w * bf16_bits_to_float(v[ksl][e] & 0xffffu);
+        acc[ksl][2 * e + 1] += w * bf16_bits_to_float(v[ksl][e] >> 16);
+      }
+  }
 
+  wait_all_memory();
+  __syncthreads();  // W_UV[j] staged
+
+  const TrNatural tr = make_tr_natural(lane);
   f32x16 o[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
-  const __bf16* po = (const __bf16*)a.part_o;
-  for (int ks = 0; ks < KS; ++ks) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (row_ok) {
-      for (int s = s0; s < s1; ++s) {
-        const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m) * inv_den;
-        if (w > 0.f) {
-          const u32x4 v = *(const u32x4*)(po + ((int64_t)s * a.M + rho) * RKV + ks * 16 + h * 8);
+  const char* wbase = smem + (KSW * wave) * 2048;  // this wave's rows of the staged matrix
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += w * bf16_bits_to_float(v[e] & 0xffffu);
-            acc[2 * e + 1] += w * bf16_bits_to_float(v[e] >> 16);
-          }
-        }
-      }
-    }
-    u32x4 pw = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]), pack_bf16(acc[6], acc[7])};
+  for (int ksl = 0; ksl < KSW; ++ksl) {
+    u32x4 pw = {pack_bf16(acc[ksl][0], acc[ksl][1]), pack_bf16(acc[ksl][2], acc[ksl][3]),
+                pack_bf16(acc[ksl][4], acc[ksl][5]), pack_bf16(acc[ksl][6], acc[ksl][7])};
     const bf16x8 bfrag = __builtin_bit_cast(bf16x8, pw);
-    const int row_a = 16 * ks + 8 * h;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) o[mt] = mfma32(tr_frag<RC>(smem, row_a, row_a + 4, 32 * mt, lane), bfrag, o[mt]);
+    for (int mt = 0; mt < MT; ++mt) o[mt] = mfma32(tr_natural_frag<RKV>(wbase, tr, ksl, mt), bfrag, o[mt]);
   }
-  if (!row_ok) return;
-  __bf16* out = (__bf16*)a.out + ((int64_t)b * a.M + rho) * DH;
+
+  // sum the four waves' partial O^T through LDS: slot [wave][mt][i][lane]
+  __syncthreads();  // everyone is done reading the staged weights
+  float* red = (float*)smem;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      u32x2 v = {pack_bf16(o[mt][4 * q], o[mt][4 * q + 1]), pack_bf16(o[mt][4 * q + 2], o[mt][4 * q + 3])};
-      *(u32x2*)(out + mt * 32 + 8 * q + 4 * h) = v;
-    }
-  if (a.lse && h == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
+    for (int i = 0; i < 16; ++i) red[((wave * MT + mt) * 16 + i) * 64 + lane] = o[mt][i];
+  __syncthreads();
+  float r[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    r[i] = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) r[i] += red[((w * MT + wave) * 16 + i) * 64 + lane];
+  }
+  if (!row_ok) return;
+  __bf16* out = (__bf16*)a.out + ((int64_t)b * a.M + rho) * DH + wave * 32;  // this wave writes dims 32*wave .. +31
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    u32x2 v = {pack_bf16(r[4 * q], r[4 * q + 1]), pack_bf16(r[4 * q + 2], r[4 * q + 3])};
+    *(u32x2*)(out + 8 * q + 4 * h) = v;
+  }
+  if (a.lse && h == 0 && wave == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
 }
 
 }  // namespace
@@ -265,7 +352,7 @@ hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {
     attr_set = true;
   }
   const int rows_per_group = a.B * a.s_q * a.G;
-  combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + 127) / 128, a.g), 256, kLds, s>>>(a, rows_per_group);
+  combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + 31) / 32, a.g), 256, kLds, s>>>(a, rows_per_group);
   return hipGetLastError();
 }
 

@@ -114,28 +114,36 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
   if (lane == 0) a.part_lse[(int64_t)chunk * a.M + rho] = l_run > 0.f ? (m_run + fast_log2(l_run)) * kLn2 : GQLA_NEG_INF;
 }
 
-// Log-sum-exp combine of chunk partials that are already in d_h space.  One workgroup per (b, row).
+// Log-sum-exp combine of chunk partials that are already in d_h space.  32 lanes per (b, row), 4 dims per lane
+// and step; the loads of all chunks are independent.
 template <typename OutT>
-__global__ void combine_kernel(CombineArgs a) {
-  const int rho = blockIdx.x, b = blockIdx.y;
+__global__ void __launch_bounds__(256) combine_kernel(CombineArgs a) {
+  const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);  // row = b * M + rho
+  if (row >= (int64_t)a.B * a.M) return;
+  const int b = (int)(row / a.M), rho = (int)(row % a.M);
   const int s0 = a.first_slot[b], s1 = a.first_slot[b + 1];
   float m = GQLA_NEG_INF;
   for (int s = s0; s < s1; ++s) m = fmaxf(m, a.part_lse[(int64_t)s * a.M + rho]);
   float den = 0.f;
   for (int s = s0; s < s1; ++s) den += __expf(a.part_lse[(int64_t)s * a.M + rho] - m);
-  const float* po = (const float*)a.part_o;
-  for (int d = threadIdx.x; d < a.d_h; d += blockDim.x) {
-    float acc = 0.f;
+  const float inv = 1.f / den;
+  const float* po = (const float*)a.part_o + (int64_t)rho * a.d_h;
+  for (int d = (threadIdx.x & 31) * 4; d < a.d_h; d += 128) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s = s0; s < s1; ++s) {
-      const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m);
-      if (w > 0.f) acc += w * po[((int64_t)s * a.M + rho) * a.d_h + d];
+      const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m) * inv;
+      const f32x4 v = *(const f32x4*)(po + (int64_t)s * a.M * a.d_h + d);
+      if (w > 0.f) acc += w * v;
     }
-    const float v = acc / den;
-    OutT* out = (OutT*)a.out + ((int64_t)b * a.M + rho) * a.d_h + d;
-    if constexpr (sizeof(OutT) == 4) *out = v;
-    else *out = (OutT)v;
+    OutT* out = (OutT*)a.out + row * a.d_h + d;
+    if constexpr (sizeof(OutT) == 4) {
+      *(f32x4*)out = acc;
+    } else {
+      u32x2 pk = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
+      *(u32x2*)out = pk;
+    }
   }
-  if (a.lse && threadIdx.x == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
+  if (a.lse && (threadIdx.x & 31) == 0) a.lse[row] = m + __logf(den);
 }
 
 // fp32 absorb path: combine latent-space partials, then o = W_UV[j]^T o_hat  (MQA-absorb equation, line 6).
@@ -214,8 +222,9 @@ hipError_t launch_decode_absorb_f32(const DecodeArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_combine_f32(const CombineArgs& a, bool out_bf16, hipStream_t s) {
-  if (out_bf16) combine_kernel<__bf16><<<dim3(a.M, a.B), 128, 0, s>>>(a);
-  else combine_kernel<float><<<dim3(a.M, a.B), 128, 0, s>>>(a);
+  const unsigned blocks = (unsigned)(((int64_t)a.B * a.M + 7) / 8);
+  if (out_bf16) combine_kernel<__bf16><<<blocks, 256, 0, s>>>(a);
+  else combine_kernel<float><<<blocks, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 hipError_t launch_combine_project_f32(const CombineArgs& a, hipStream_t s) {

@@ -62,10 +62,11 @@ template <int DH, int RKV, int DR>
 __global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
-  constexpr int RC = DH / 8;
   constexpr int MT = DH / 32;
+  static_assert(MT % 2 == 0, "output tiles are processed in pairs that share a 64-column panel");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 31, h = lane >> 5;
   const int b = blockIdx.y;
   const int L = a.seq_lens[b];
@@ -74,21 +75,25 @@ __global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
   const int P = a.latent.page_size;
   const int gc = a.group_count;
   const int tokw = tok0 + wave * 32;  // first token of this wave (a wave never straddles a page: P % 32 == 0)
-  const bool wave_has = tokw < L;
   int32_t pg_in = -1, pg_out = -1;
-  if (wave_has) {
+  if (tokw < L) {
     pg_in = page_of(a.latent, b, tokw / P);
     pg_out = page_of(a.expanded, b, tokw / P);
   }
-  const bool wave_ok = pg_in >= 0 && pg_out >= 0;
+  const bool wave_ok = pg_in >= 0 && pg_out >= 0;  // wave-uniform
   const int slot0 = tokw % P;
   const bool tok_ok = wave_ok && (tokw + n < L);
 
+  // latent rows of this wave's 32 tokens as fragments (lane = token, 8 consecutive latent dims per k-step); rows past
+  // L_b are read from a clamped address and zeroed (their products are never stored)
   bf16x8 xf[KS];
-  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  const __bf16* in_row = (const __bf16*)a.latent.pool + ((int64_t)(wave_ok ? pg_in : 0) * P + slot0 + n) * W;
+  const int n_ld = tok_ok ? n : 0;
+  const __bf16* in_row = (const __bf16*)a.latent.pool + ((int64_t)(wave_ok ? pg_in : 0) * P + slot0 + n_ld) * W;
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) xf[ks] = tok_ok ? *(const bf16x8*)(in_row + ks * 16 + h * 8) : zero;
+  for (int ks = 0; ks < KS; ++ks) {
+    xf[ks] = *(const bf16x8*)(in_row + ks * 16 + h * 8);
+    if (!tok_ok) xf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
 
   __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (2 * gc * DH + DR);
   // k_R plane: a straight copy, 8 dims (16 bytes) per lane and step
@@ -100,61 +105,71 @@ __global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
     }
   }
 
+  const TrNatural tr = make_tr_natural(lane);
   for (int jj = 0; jj < gc; ++jj) {
+#pragma unroll 1
     for (int kind = 0; kind < 2; ++kind) {
       __syncthreads();  // previous weight matrix no longer read
       const char* wsrc = (const char*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * RKV * DH * 2;
-      stage_rows<RC>(smem, wsrc, DH * 2, RKV, RKV, wave, 8, lane);
+      stage_panels_full<RKV, DH / 64, 8, DH * 2>(smem, wsrc, wave, lane);
       wait_all_memory();
       __syncthreads();
       if (!wave_ok) continue;
-      f32x16 acc[MT];
+#pragma unroll 1
+      for (int mtp = 0; mtp < MT / 2; ++mtp) {  // output tiles 2*mtp, 2*mtp + 1: both in panel mtp
+        const char* panel = smem + mtp * (RKV * 128);
+        f32x16 acc0, acc1;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
-      if (kind == 0) {
+        for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.f;
+        bf16x8 w0 = tr_natural_frag<RKV>(panel, tr, 0, 0), w1 = tr_natural_frag<RKV>(panel, tr, 0, 1);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const int row_a = 16 * ks + 8 * h;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma32(tr_frag<RC>(smem, row_a, row_a + 4, 32 * mt, lane), xf[ks], acc[mt]);
+          const bf16x8 c0 = w0, c1 = w1;
+          if (ks + 1 < KS) {
+            w0 = tr_natural_frag<RKV>(panel, tr, ks + 1, 0);
+            w1 = tr_natural_frag<RKV>(panel, tr, ks + 1, 1);
+          }
+          if (kind == 0) {  // K^T[d][tok] = W_UK^T[d][r] * C^T[r][tok]
+            acc0 = mfma32(c0, xf[ks], acc0);
+            acc1 = mfma32(c1, xf[ks], acc1);
+          } else {          // V[tok][d] = C[tok][r] * W_UV[r][d]
+            acc0 = mfma32(xf[ks], c0, acc0);
+            acc1 = mfma32(xf[ks], c1, acc1);
+          }
         }
-        // lane = token n, registers = dims 32*mt + 8*q + 4*h + 0..3  ->  half of one 8-dim vector of the K plane
-        if (tok_ok) {
-          __bf16* kb = out_page + (int64_t)jj * DH * P + (int64_t)(slot0 + n) * 8 + 4 * h;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
+        if (kind == 0) {
+          // lane = token n, registers = dims 32*mt + 8*q + 4*h + 0..3  ->  half of one 8-dim vector of the K plane
+          if (tok_ok) {
+            __bf16* kb = out_page + (int64_t)jj * DH * P + (int64_t)(slot0 + n) * 8 + 4 * h;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              u32x2 v = {pack_bf16(acc[mt][4 * q], acc[mt][4 * q + 1]), pack_bf16(acc[mt][4 * q + 2], acc[mt][4 * q + 3])};
-              *(u32x2*)(kb + (int64_t)(4 * mt + q) * P * 8) = v;
-            }
-        }
-      } else {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const int row_a = 16 * ks + 8 * h;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma32(xf[ks], tr_frag<RC>(smem, row_a, row_a + 4, 32 * mt, lane), acc[mt]);
-        }
-        // lane = dim 32*mt + n, registers = tokens tokw + 8*q + 4*h + 0..3  ->  half of one 8-token vector of the V plane
-        __bf16* vb = out_page + (int64_t)gc * DH * P + (int64_t)jj * DH * P;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int tk = tokw + 8 * q + 4 * h;  // first of 4 tokens
-            __bf16* dst = vb + ((int64_t)((slot0 >> 3) + q) * DH + mt * 32 + n) * 8 + 4 * h;
-            if (tk + 3 < L) {
-              u32x2 v = {pack_bf16(acc[mt][4 * q], acc[mt][4 * q + 1]), pack_bf16(acc[mt][4 * q + 2], acc[mt][4 * q + 3])};
-              *(u32x2*)dst = v;
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (tk + e < L) dst[e] = (__bf16)acc[mt][4 * q + e];
+              u32x2 v0 = {pack_bf16(acc0[4 * q], acc0[4 * q + 1]), pack_bf16(acc0[4 * q + 2], acc0[4 * q + 3])};
+              u32x2 v1 = {pack_bf16(acc1[4 * q], acc1[4 * q + 1]), pack_bf16(acc1[4 * q + 2], acc1[4 * q + 3])};
+              *(u32x2*)(kb + (int64_t)(8 * mtp + q) * P * 8) = v0;
+              *(u32x2*)(kb + (int64_t)(8 * mtp + 4 + q) * P * 8) = v1;
             }
           }
+        } else {
+          // lane = dim 32*mt + n, registers = tokens tokw + 8*q + 4*h + 0..3  ->  half of one 8-token vector of the V plane
+          __bf16* vb = out_page + (int64_t)gc * DH * P + (int64_t)jj * DH * P;
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const f32x16& acc = half ? acc1 : acc0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int tk = tokw + 8 * q + 4 * h;  // first of 4 tokens
+              __bf16* dst = vb + ((int64_t)((slot0 >> 3) + q) * DH + (2 * mtp + half) * 32 + n) * 8 + 4 * h;
+              if (tk + 3 < L) {
+                u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
+                *(u32x2*)dst = v;
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  if (tk + e < L) dst[e] = (__bf16)acc[4 * q + e];
+              }
+            }
+          }
+        }
       }
     }
   }

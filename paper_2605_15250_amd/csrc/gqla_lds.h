@@ -1,13 +1,15 @@
 // LDS staging of row-major bf16 matrices for MFMA operands on gfx950.
 //
-// A staged matrix is a linear array of rows of ROW_CHUNKS 16-byte chunks; chunk c of row r is stored at chunk
-// position c ^ (r & 7) of that row, which spreads both access patterns below over the LDS banks:
-//   row_frag  lane (m = l % 32, h = l / 32) reads 8 consecutive elements of row m (an A or B fragment whose
-//             contraction index runs along the row)                                   -> ds_read_b128
-//   tr_frag   the contraction index runs DOWN the rows: each lane needs 2 x 4 consecutive rows of one column;
-//             ds_read_b64_tr_b16 transposes 4x4 blocks among 16 lanes: lane 4q+r' of a 16-lane group receives
-//             element r' of the 8-byte vectors addressed by lanes q, 4+q, 8+q, 12+q of the group.
-// Rows are filled with global_load_lds_dwordx4 (HBM/L2 -> LDS without passing through VGPRs).
+// Panel layout.  A staged matrix of R rows and 8*NP 16-byte chunks per row is kept as NP panels of [R][128 bytes]:
+// chunk c of row r lives in panel c / 8 at byte  r*128 + (((c & 7) ^ swz(r)) << 4),  swz(r) = (r >> 1) & 7.
+// The XOR spreads both access patterns below over the LDS banks:
+//   row fragment         lane (m = l % 32, h = l / 32) reads 8 consecutive elements of row m (an MFMA operand whose
+//                        contraction index runs along the row)                                  -> ds_read_b128
+//   transposed fragment  the contraction index runs DOWN the rows: each lane needs 2 x 4 consecutive rows of one
+//                        column.  ds_read_b64_tr_b16 transposes 4x4 blocks among 16 lanes: lane 4q+r' of a 16-lane
+//                        group receives element r' of the 8-byte vectors addressed by lanes q, 4+q, 8+q, 12+q.
+// Panels are filled with global_load_lds_dwordx4 (HBM/L2 -> LDS without passing through VGPRs): one wave
+// instruction moves 8 rows x 128 bytes, i.e. 1 KB that is contiguous in the panel.
 #pragma once
 
 #include "gqla_device.h"
@@ -16,53 +18,109 @@ namespace gqla {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
 
-// Asynchronously stage rows [0, rows_valid) of a row-major global matrix (row stride gstride bytes) and zero
-// rows [rows_valid, rows_total).  Work is spread over n_waves waves; every wave of the workgroup must call it.
-// Completion: s_waitcnt vmcnt(0) lgkmcnt(0) by each wave, then a workgroup barrier.
-template <int ROW_CHUNKS>
-__device__ __forceinline__ void stage_rows(char* lds, const char* g, int64_t gstride, int rows_total, int rows_valid,
-                                           int wave, int n_waves, int lane) {
-  const int n_inst = rows_total * ROW_CHUNKS / 64;
-  for (int it = wave; it < n_inst; it += n_waves) {
-    const int q = it * 64 + lane;
-    const int row = q / ROW_CHUNKS;
-    const int pos = q - row * ROW_CHUNKS;
-    const int c = pos ^ (row & 7);
-    if (row < rows_valid) {
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(g + (int64_t)row * gstride + c * 16), (lds_ptr_t)(lds + it * 1024),
-                                       16, 0, 0);
-    } else {
-      *(u32x4*)(lds + q * 16) = u32x4{0u, 0u, 0u, 0u};
+__device__ __forceinline__ int lds_swz(int row) { return (row >> 1) & 7; }
+
+// Asynchronously stage rows [0, rows_valid) of a row-major global matrix with ROWS rows of NP*128 bytes (row stride
+// GSTRIDE bytes) and zero rows [rows_valid, ROWS).  Every wave of the workgroup (NWAVES of them, NWAVES even and
+// dividing ROWS/8) must call it.  Completion: s_waitcnt vmcnt(0) lgkmcnt(0) by each wave, then a workgroup barrier.
+template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+__device__ __forceinline__ void stage_panels(char* lds, const char* g, int rows_valid, int wave, int lane) {
+  static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
+  constexpr int K = ROWS / 8 / NWAVES;  // instructions per wave and panel
+  const int row0 = 8 * wave + (lane >> 3);
+  const int c = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);  // chunk whose swizzled position is lane & 7
+  const uint32_t lane_off = row0 * GSTRIDE + c * 16;
+#pragma unroll
+  for (int a = 0; a < NP; ++a) {
+#pragma unroll
+    for (int v = 0; v < K; ++v) {
+      const int row = row0 + 8 * NWAVES * v;
+      char* dst = lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024;
+      if (row < rows_valid) {
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(g + (lane_off + (uint32_t)(8 * NWAVES * v * GSTRIDE + a * 128))),
+                                         (lds_ptr_t)dst, 16, 0, 0);
+      } else {
+        *(u32x4*)(dst + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  }
+}
+
+// Same, for a matrix whose ROWS rows are all present (no row test, no zero fill): every instruction is issued by
+// every lane, which is what code that counts outstanding loads with s_waitcnt vmcnt(n) needs.
+template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+__device__ __forceinline__ void stage_panels_full(char* lds, const char* g, int wave, int lane) {
+  static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
+  constexpr int K = ROWS / 8 / NWAVES;
+  const int row0 = 8 * wave + (lane >> 3);
+  const int c = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
+  const uint32_t lane_off = row0 * GSTRIDE + c * 16;
+#pragma unroll
+  for (int a = 0; a < NP; ++a) {
+#pragma unroll
+    for (int v = 0; v < K; ++v) {
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(g + (lane_off + (uint32_t)(8 * NWAVES * v * GSTRIDE + a * 128))),
+                                       (lds_ptr_t)(lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024), 16, 0, 0);
     }
   }
 }
 
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
-// 8 consecutive elements (chunk `chunk`) of row `row`.
-template <int ROW_CHUNKS>
+// 8 consecutive elements (chunk `chunk`) of row `row` of a staged matrix with ROWS rows.
+template <int ROWS>
 __device__ __forceinline__ bf16x8 row_frag(const char* lds, int row, int chunk) {
-  return *(const bf16x8*)(lds + row * (ROW_CHUNKS * 16) + ((chunk ^ (row & 7)) << 4));
+  return *(const bf16x8*)(lds + (chunk >> 3) * (ROWS * 128) + row * 128 + (((chunk & 7) ^ lds_swz(row)) << 4));
 }
 
-// Transposed fragment: lane l of the wave receives column (col0 + l % 32) of rows row_a + 0..3 (elements 0..3)
-// and row_b + 0..3 (elements 4..7), where row_a / row_b are per-lane-half bases supplied by the caller
-// (typically base + 8 * (l / 32) and that + 4, or any other pairing that matches the other MFMA operand).
-// col0 must be a multiple of 32; row_a, row_b multiples of 4.
-template <int ROW_CHUNKS>
+// Transposed fragment: lane l receives column (col0 + l % 32) of rows row_a + 0..3 (elements 0..3) and row_b + 0..3
+// (elements 4..7); row_a, row_b are per-lane-half values supplied by the caller (multiples of 4), col0 a multiple of 32.
+template <int ROWS>
 __device__ __forceinline__ bf16x8 tr_frag(const char* lds, int row_a, int row_b, int col0, int lane) {
   const int i16 = lane & 15;
-  const int e = i16 >> 2, q = i16 & 3;            // this lane ADDRESSES row (+e), columns 4q..4q+3 of its 16-col block
+  const int e = i16 >> 2, q = i16 & 3;  // this lane ADDRESSES row (+e), columns 4q..4q+3 of its 16-column block
   const int col = col0 + ((lane >> 4) & 1) * 16 + 4 * q;
   const int chunk = col >> 3, sub = (col & 7) * 2;
   const int ra = row_a + e, rb = row_b + e;
-  const char* pa = lds + ra * (ROW_CHUNKS * 16) + ((chunk ^ (ra & 7)) << 4) + sub;
-  const char* pb = lds + rb * (ROW_CHUNKS * 16) + ((chunk ^ (rb & 7)) << 4) + sub;
-  i16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)pa);
-  i16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)pb);
-  typedef __attribute__((ext_vector_type(8))) short i16x8;
-  i16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  const char* panel = lds + (chunk >> 3) * (ROWS * 128) + sub;
+  const char* pa = panel + ra * 128 + (((chunk & 7) ^ lds_swz(ra)) << 4);
+  const char* pb = panel + rb * 128 + (((chunk & 7) ^ lds_swz(rb)) << 4);
+  const i16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)pa);
+  const i16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)pb);
+  const i16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Transposed fragments in natural contraction order out of a staged [ROWS][NP*64] matrix: fragment (ks, mt) holds,
+// for column 32*mt + l % 32, rows 16*ks + 8*(l / 32) + 0..7.  The per-lane part of the two read addresses depends only
+// on the parity of mt (the swizzle flips the 64-byte half with the lane half), so four lane offsets cover the
+// whole matrix and everything else is a compile-time offset:  base[read][mt & 1] + (mt >> 1)*ROWS*128 + ks*2048.
+struct TrNatural {
+  uint32_t base[2][2];
+};
+
+__device__ __forceinline__ TrNatural make_tr_natural(int lane) {
+  const int h = lane >> 5, i16 = lane & 15, e = i16 >> 2, q = i16 & 3, g1 = (lane >> 4) & 1;
+  const int cl = 2 * g1 + (q >> 1), sub = (q & 1) * 8;
+  TrNatural t;
+#pragma unroll
+  for (int rd = 0; rd < 2; ++rd) {
+    const int x = 2 * rd + (e >> 1);  // low swizzle bits of row 16*ks + 8*h + e + 4*rd; bit 2 of the swizzle is h
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+      t.base[rd][par] = (8 * h + e + 4 * rd) * 128 + ((4 * (par ^ h) + (cl ^ x)) << 4) + sub;
+  }
+  return t;
+}
+
+template <int ROWS>
+__device__ __forceinline__ bf16x8 tr_natural_frag(const char* lds, const TrNatural& t, int ks, int mt) {
+  const int off = (mt >> 1) * (ROWS * 128) + ks * 2048;
+  const i16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(lds + t.base[0][mt & 1] + off));
+  const i16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(lds + t.base[1][mt & 1] + off));
+  const i16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
   return __builtin_bit_cast(bf16x8, r);
 }
 
