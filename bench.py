@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
     ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
-    ap.add_argument("--cpu-seqs", type=int, default=6, help="sequences per leg in the oracle's bounded sample (0 = skip)")
+    ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences per leg in the oracle's bounded sample (0 = skip)")
     return ap.parse_args()
 
 

@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // ---- S^T[token][row] = Kt * Qhat^T ----
       // These MFMAs accumulate in ordinary VGPRs (written as inline assembly) because all 256 accumulation
       // registers hold O^T; the compiler's own MFMA selection would put S^T there as well and spill.
-      f32x16 s, s_odd;  // two accumulation chains (even / odd k-steps) so that consecutive MFMAs are independent
+      f32x16 s;
       bf16x8 f[2][4];
 #pragma unroll
       for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b] + (32 * mt * 128));
@@ -131,8 +131,6 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
-          else if (a4 == 0 && b == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s_odd) : "v"(f[0][1]), "v"(qf[1]));
-          else if (b & 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s_odd) : "v"(f[a4 & 1][b]), "v"(qf[4 * a4 + b]));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 & 1][b]), "v"(qf[4 * a4 + b]));
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -150,20 +148,19 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       };
       load_v(0, 0, 0);
       // the matrix pipeline's result is not interlocked against vector-ALU reads: wait out its 8 passes
-      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s), "+v"(s_odd));
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] += s_odd[i];
+      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));
 
       // ---- online softmax (base 2); register i is token tok + 32*mt + 8*(i/4) + 4*h + i%4 ----
-      float tmax = GQLA_NEG_INF;
+      // The maximum is taken on the raw logits (the scale is positive) and the scale rides in the exponent's FMA.
+      if (__builtin_amdgcn_ballot_w64(need_mask) != 0) {  // wave-uniform: only tiles at the chunk end, or padding rows
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float v = s[i] * a.scale_log2e;
-        if (need_mask && tok + 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3) >= lim) v = GQLA_NEG_INF;
-        s[i] = v;
-        tmax = fmaxf(tmax, v);
+        for (int i = 0; i < 16; ++i)
+          if (need_mask && tok + 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3) >= lim) s[i] = GQLA_NEG_INF;
       }
-      tmax = pair_max(tmax);
+      float tmax = s[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
+      tmax = pair_max(tmax) * a.scale_log2e;
       if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRescaleThreshold) != 0) {
         const float m_new = fmaxf(m_ref, tmax);
         const float alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
@@ -188,7 +185,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         float p[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          p[e] = fast_exp2(s[8 * u + e] - m_use);
+          p[e] = fast_exp2(__builtin_fmaf(s[8 * u + e], a.scale_log2e, -m_use));
           psum += p[e];
         }
         u32x4 w = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};

@@ -1,0 +1,170 @@
+"""GPU parity at the workload's full sizes, in the launch configuration bench.py times (default plans, 256 CUs).
+
+The oracle cannot redo a whole configuration in seconds, so each test checks
+  * sampled (sequence, group) slices element by element against the oracle (always the shortest and the longest
+    sequence, and for the ragged configuration one whose length is not a multiple of the page size), and
+  * properties that hold at any size over EVERY output: finiteness, and the paper's own invariant that the two
+    decode paths agree (Sec. 3.1) -- here between two independent GPU kernels, within the bf16 tolerance.
+Tolerances as in test_gpu_parity.py: max abs 2e-2, relative L2 1e-2."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import gqla_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 2e-2, 1e-2
+
+
+def rel_l2(a, ref):
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def check(name, got, ref):
+    got = np.asarray(got, np.float64)
+    err = float(np.max(np.abs(got - ref)))
+    r = rel_l2(got, ref)
+    print("%-44s max_abs %.3e  rel_l2 %.3e" % (name, err, r), flush=True)
+    assert np.isfinite(got).all(), name
+    assert err <= MAX_ABS and r <= REL_L2, (name, err, r)
+
+
+class FullCase:
+    def __init__(self, cfg, groups=None, group_begin=0):
+        from paper_2605_15250_amd.harness import Decoder, to_device, build_latent_pool
+        self.cfg = cfg
+        self.lens = S.seq_lens(cfg)
+        self.table, self.num_pages = S.page_table(cfg, self.lens)
+        self.w_uk, self.w_uv = S.weights(cfg)
+        self.q_c, self.q_r = S.queries(cfg)
+        self.dec = Decoder(cfg, self.lens, self.table, self.num_pages, groups=groups, group_begin=group_begin,
+                           use_page_table=cfg.paged)
+        print("building latent pool: %d sequences, %d tokens" % (cfg.B, int(self.lens.sum())), flush=True)
+        self.dec.latent_pool = build_latent_pool(cfg, self.lens, self.table, self.num_pages,
+                                                 lambda b, L: S.sequence_rows(cfg, b, L))
+        self.d = lambda x: to_device(x, cfg.dtype)
+        self.d_w_uk, self.d_w_uv = self.d(self.w_uk), self.d(self.w_uv)
+
+    def rows(self, b):
+        r = S.sequence_rows(self.cfg, b, self.lens[b])
+        return r[:, :self.cfg.r_kv], r[:, self.cfg.r_kv:]
+
+    def sample_sequences(self):
+        picks = {int(np.argmin(self.lens)), int(np.argmax(self.lens))}
+        odd = [b for b in range(self.cfg.B) if self.lens[b] % self.cfg.page_size]
+        if odd:
+            picks.add(odd[len(odd) // 2])
+        return sorted(picks)
+
+    def close(self):
+        self.dec.close()
+
+
+def oracle_group(case, b, j, path):
+    """Oracle output of sequence b restricted to the heads of group j (a self-consistent h_q = G, g = 1 problem)."""
+    cfg = case.cfg
+    G = cfg.h_q // cfg.g
+    hs = slice(j * G, (j + 1) * G)
+    c, kR = case.rows(b)
+    qc, qr = case.q_c[b][:, hs], case.q_r[b][:, hs]
+    wk, wv = case.w_uk[j:j + 1], case.w_uv[j:j + 1]
+    if path == "absorb":
+        return O.decode_absorb(O.absorb_query(qc, wk), qr, c, kR, wv)
+    KC, V = O.expand_latent(c, wk, wv)
+    return O.decode_gqa(qc, qr, KC, V, kR)
+
+
+def run_both_paths(case, groups_to_check):
+    cfg = case.cfg
+    G = cfg.h_q // cfg.g
+    q_hat = case.dec.absorb_query(case.d(case.q_c), case.d_w_uk)
+    out_a, lse_a = case.dec.decode_absorb(q_hat, case.d(case.q_r), case.d_w_uv)
+    case.dec.alloc_expanded()
+    case.dec.expand(case.d_w_uk, case.d_w_uv)
+    out_g, lse_g = case.dec.decode_gqa(case.d(case.q_c), case.d(case.q_r))
+    torch.cuda.synchronize()
+    oa, og = out_a.float().cpu().numpy(), out_g.float().cpu().numpy()
+    la, lg = lse_a.cpu().numpy(), lse_g.cpu().numpy()
+    # properties over every output
+    assert np.isfinite(oa).all() and np.isfinite(og).all() and np.isfinite(la).all() and np.isfinite(lg).all()
+    check("absorb vs gqa path, all outputs", oa, og)
+    assert float(np.max(np.abs(la - lg))) <= 2e-2, "lse of the two paths"
+    # sampled slices against the oracle
+    for b in case.sample_sequences():
+        for j in groups_to_check:
+            hs = slice(j * G, (j + 1) * G)
+            ref_o, ref_l = oracle_group(case, b, j, "absorb")
+            check("absorb  b=%d L=%d group %d" % (b, case.lens[b], j), oa[b][:, hs], ref_o)
+            check("gqa     b=%d L=%d group %d" % (b, case.lens[b], j), og[b][:, hs], ref_o)
+            assert float(np.max(np.abs(la[b][:, hs] - ref_l))) <= 2e-2
+            assert float(np.max(np.abs(lg[b][:, hs] - ref_l))) <= 2e-2
+
+
+def test_c1_llama3_shape_both_paths():
+    case = FullCase(S.CONFIGS["C1"])
+    try:
+        run_both_paths(case, groups_to_check=range(8))     # all 32 heads of the sampled sequences
+    finally:
+        case.close()
+
+
+def test_c2_c3_canonical_both_paths_with_mtp():
+    """configs[2] and configs[3] share shape and weights; the s_q = 2 configuration exercises both paths (row 1 of the
+    step is a plain s_q = 1 decode at length L, row 0 one at length L - 1)."""
+    case = FullCase(S.CONFIGS["C3"])
+    try:
+        run_both_paths(case, groups_to_check=[0, 5])
+    finally:
+        case.close()
+
+
+def test_c2_absorb_sq1():
+    case = FullCase(S.CONFIGS["C2"])
+    try:
+        q_hat = case.dec.absorb_query(case.d(case.q_c), case.d_w_uk)
+        out_a, lse_a = case.dec.decode_absorb(q_hat, case.d(case.q_r), case.d_w_uv)
+        torch.cuda.synchronize()
+        oa = out_a.float().cpu().numpy()
+        assert np.isfinite(oa).all()
+        G = 16
+        for b in (0, 63):
+            for j in (2, 7):
+                ref_o, _ = oracle_group(case, b, j, "absorb")
+                check("absorb  b=%d group %d" % (b, j), oa[b][:, j * G:(j + 1) * G], ref_o)
+    finally:
+        case.close()
+
+
+def test_c3_single_group_slice():
+    """One GPU's share of 8-way head-axis tensor parallelism: group 3 only, 320 cached elements per token."""
+    cfg = S.CONFIGS["C3"]
+    case = FullCase(cfg, groups=1, group_begin=3)
+    try:
+        G = cfg.h_q // cfg.g
+        hs = slice(3 * G, 4 * G)
+        case.dec.alloc_expanded()
+        case.dec.expand(case.d_w_uk, case.d_w_uv)
+        q_c = np.ascontiguousarray(case.q_c[:, :, hs])
+        q_r = np.ascontiguousarray(case.q_r[:, :, hs])
+        out, lse = case.dec.decode_gqa(case.d(q_c), case.d(q_r))
+        torch.cuda.synchronize()
+        og = out.float().cpu().numpy()
+        assert np.isfinite(og).all()
+        for b in (1, 40):
+            ref_o, ref_l = oracle_group(case, b, 3, "gqa")
+            check("slice   b=%d group 3" % b, og[b], ref_o)
+    finally:
+        case.close()
+
+
+def test_c4_ragged_paged_both_paths():
+    case = FullCase(S.CONFIGS["C4"])
+    try:
+        assert case.lens.min() >= 1024 and case.lens.max() <= 32768
+        run_both_paths(case, groups_to_check=[6])
+    finally:
+        case.close()
