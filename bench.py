@@ -22,6 +22,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+CALIB_COPY_BYTES = 1 << 30
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_canonical.json")   # measured with rocprofv3 --pmc, see profiles/
 
 
 def parse_args():
@@ -100,6 +102,14 @@ def main():
             Gq["dec"].decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
         rec(4)
 
+    # one plain device-to-device copy of known size: the calibration kernel for the HBM traffic counters
+    # (FETCH_SIZE / WRITE_SIZE per dispatch are scaled by what they read for this copy)
+    calib_src = torch.empty(CALIB_COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -122,6 +132,11 @@ def main():
     bytes_expand = bytes_gqa + 2 * Lg * (cg.r_kv + cg.d_r)
     flops_expand = 2 * Lg * cg.r_kv * 2 * cg.g * cg.d_h
 
+    traffic = {}
+    if os.path.exists(TRAFFIC_FILE) and not args.batch and not args.ctx:
+        with open(TRAFFIC_FILE) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch", {})
+
     def roof(name, bound, nbytes, flops):
         t = max(call_ms[name], 1e-6) * 1e-3
         gbs, tf = nbytes / t / 1e9, flops / t / 1e12
@@ -135,7 +150,7 @@ def main():
         else:
             r.update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                       "frac": tf / MFMA_BF16_PEAK_TFLOPS})
-        r["traffic"] = None
+        r["traffic"] = traffic.get(name)
         return r
 
     roofs = [roof("decode_absorb", "mfma", bytes_absorb, flops_absorb),

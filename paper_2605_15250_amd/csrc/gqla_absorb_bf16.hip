@@ -118,25 +118,27 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // These MFMAs accumulate in ordinary VGPRs (written as inline assembly) because all 256 accumulation
       // registers hold O^T; the compiler's own MFMA selection would put S^T there as well and spill.
       f32x16 s;
-      bf16x8 f[2][4];
+      bf16x8 f[3][4];  // ring of fragment batches: loads run two batches (8 MFMAs) ahead of their use
 #pragma unroll
       for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b] + (32 * mt * 128));
 #pragma unroll
-      for (int a4 = 0; a4 < KS / 4; ++a4) {
-        if (a4 + 1 < KS / 4) {
+      for (int b = 0; b < 4; ++b) f[1][b] = *(const bf16x8*)(buf + kbase[b] + (PANEL + 32 * mt * 128));
 #pragma unroll
-          for (int b = 0; b < 4; ++b) f[(a4 + 1) & 1][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 1) * PANEL + 32 * mt * 128));
+      for (int a4 = 0; a4 < KS / 4; ++a4) {
+        if (a4 + 2 < KS / 4) {
+#pragma unroll
+          for (int b = 0; b < 4; ++b) f[(a4 + 2) % 3][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 2) * PANEL + 32 * mt * 128));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
-          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 & 1][b]), "v"(qf[4 * a4 + b]));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 % 3][b]), "v"(qf[4 * a4 + b]));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
       // first batch of value fragments: issued now, consumed after the softmax
-      i16x4 r[2][4][2];
+      i16x4 r[3][4][2];
       auto load_v = [&](int slot, int u, int p4) {  // output tiles dt = 4*p4 .. 4*p4 + 3 of k-step u
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
@@ -147,6 +149,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         }
       };
       load_v(0, 0, 0);
+      load_v(1, 0, 1);
       // the matrix pipeline's result is not interlocked against vector-ALU reads: wait out its 8 passes
       asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));
 
@@ -198,11 +201,11 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 #pragma unroll
       for (int bt = 0; bt < 2 * (DT / 4); ++bt) {
         const int u = bt / (DT / 4), p4 = bt % (DT / 4);
-        if (bt + 1 < 2 * (DT / 4)) load_v((bt + 1) & 1, (bt + 1) / (DT / 4), (bt + 1) % (DT / 4));
+        if (bt + 2 < 2 * (DT / 4)) load_v((bt + 2) % 3, (bt + 2) / (DT / 4), (bt + 2) % (DT / 4));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-          const i16x4 lo = r[bt & 1][d][0], hi = r[bt & 1][d][1];
+          const i16x4 lo = r[bt % 3][d][0], hi = r[bt % 3][d][1];
           const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           o[4 * p4 + d] = mfma32(__builtin_bit_cast(bf16x8, fr), pf[u], o[4 * p4 + d]);
         }
