@@ -44,7 +44,8 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     chunk = grp * 8 + rem % 8;
   }
   if (chunk >= a.n_chunks) return;  // whole workgroup leaves together
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction: keep it scalar
   const int n = lane & 31, h = lane >> 5;
   const ChunkEntry ce = a.chunks[chunk];
 
@@ -69,11 +70,17 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 
   const int P = a.cache.page_size;
   const char* pool = (const char*)a.cache.pool;
-  auto issue_tile = [&](int tok, char* buf) {
-    const int32_t pg = page_of(a.cache, ce.b, tok / P);
-    const int valid = pg >= 0 ? min(kTile, ce.tok_end - tok) : 0;
-    const char* g = pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * ROWB;
-    stage_panels<kTile, NP, 4, ROWB>(buf, g, valid, wave, lane);
+  // Tiles are always staged whole: rows past the chunk end still come from the page (allocated memory), an
+  // out-of-pool page id falls back to page 0; such rows are zeroed in LDS before use (see the loop).
+  // Page ids are looked up two tiles ahead and consumed one iteration later, right after the point where every
+  // outstanding load has been waited for anyway, so that the table read never stalls the pipeline.
+  auto raw_page = [&](int tok) -> int32_t {  // table entry (or identity page) of the page holding token `tok`
+    const int p = tok / P;
+    return a.cache.page_table ? a.cache.page_table[(int64_t)ce.b * a.cache.max_pages + p] : ce.b * a.cache.max_pages + p;
+  };
+  auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
+  auto tile_src = [&](int32_t pg, int tok) -> const char* {
+    return pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * ROWB;
   };
 
   // Per-lane LDS byte offsets inside a tile (panel layout of gqla_lds.h; everything else is a compile-time offset):
@@ -84,6 +91,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   //                    With R0 a multiple of 16, swz = 2*h + e/2 for the first read and 4 + that for the second, so the
   //                    chunk lands at 4*(dt & 1) + (cl ^ swz) resp. 4*(1 - (dt & 1)) + (cl ^ swz): one base per lane.
   uint32_t kbase[4], vbase;
+  const uint32_t stage_off = stage_lane_offset<kTile, NP, 4, ROWB>(wave, lane);
   {
 #pragma unroll
     for (int b = 0; b < 4; ++b) kbase[b] = n * 128 + (((2 * b + h) ^ lds_swz(n)) << 4);
@@ -99,16 +107,41 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   float m_ref = GQLA_NEG_INF, l_run = 0.f;
 
   const int n_tiles = (ce.tok_end - ce.tok_begin + kTile - 1) / kTile;
-  issue_tile(ce.tok_begin, smem);
+  int32_t pg_cur = checked(raw_page(ce.tok_begin));
+  int32_t pg_n1 = n_tiles > 1 ? checked(raw_page(ce.tok_begin + kTile)) : -1;
+  int32_t pg_raw = n_tiles > 2 ? raw_page(ce.tok_begin + 2 * kTile) : -1;  // consumed at the top of iteration 1
+  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg_cur, ce.tok_begin), wave, lane);
   for (int it = 0; it < n_tiles; ++it) {
     const int tok = ce.tok_begin + it * kTile;
     const char* buf = smem + (it & 1) * TILE_BYTES;
     wait_all_memory();
     __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
-    if (it + 1 < n_tiles) issue_tile(tok + kTile, smem + ((it + 1) & 1) * TILE_BYTES);
+    // The next tile is staged one LDS-DMA instruction per MFMA batch of the S phase (18 batches, 18 instructions):
+    // issued in one burst, the loads would block this wave for thousands of cycles.
+    if (it > 0) {  // rotate the page-id window; pg_raw was loaded one iteration ago
+      pg_cur = pg_n1;
+      pg_n1 = checked(__builtin_amdgcn_readfirstlane(pg_raw));
+      pg_raw = it + 2 < n_tiles ? raw_page(tok + 2 * kTile) : -1;
+    }
+    const bool stage_next = it + 1 < n_tiles;
+    const char* next_g = tile_src(stage_next ? pg_n1 : 0, tok + kTile);
+    char* next_buf = smem + ((it + 1) & 1) * TILE_BYTES;
+    const bool tile_ok = pg_cur >= 0;
+    const int valid = tile_ok ? min(kTile, ce.tok_end - tok) : 0;
+    if (valid < kTile) {
+      // rows past the chunk end hold whatever the page holds (NaN bits included): zero them so that 0 * v stays 0
+      for (int idx = threadIdx.x; idx < (kTile - valid) * (W / 8); idx += 256) {
+        const int r = valid + idx / (W / 8), c = idx % (W / 8);
+        *(u32x4*)(smem + (it & 1) * TILE_BYTES + (c >> 3) * PANEL + r * 128 + (c & 7) * 16) = u32x4{0u, 0u, 0u, 0u};
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      __syncthreads();
+    }
 
-    if (!wave_active) continue;  // waves without query rows only help staging (uniform per wave)
-    const bool tile_ok = page_of(a.cache, ce.b, tok / P) >= 0;
+    if (!wave_active) {  // waves without query rows only help staging (uniform per wave): their share, in one burst
+      if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      continue;
+    }
     const bool need_mask = (tok + kTile > unmasked_end) || !row_ok || !tile_ok;
     const int lim = tile_ok ? vis_end : 0;
 
@@ -134,6 +167,10 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         for (int b = 0; b < 4; ++b) {
           if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 % 3][b]), "v"(qf[4 * a4 + b]));
+        }
+        if (stage_next && mt == 0) {  // both of the batch's staging steps ride in the first half-tile's S phase
+          stage_panels_step<kTile, NP, 4, ROWB>(next_buf, next_g, wave, stage_off, 2 * a4);
+          stage_panels_step<kTile, NP, 4, ROWB>(next_buf, next_g, wave, stage_off, 2 * a4 + 1);
         }
         __builtin_amdgcn_sched_barrier(0);
       }

@@ -48,23 +48,36 @@ __device__ __forceinline__ void stage_panels(char* lds, const char* g, int rows_
   }
 }
 
-// Same, for a matrix whose ROWS rows are all present (no row test, no zero fill): every instruction is issued by
-// every lane, which is what code that counts outstanding loads with s_waitcnt vmcnt(n) needs.
 template <int ROWS, int NP, int NWAVES, int GSTRIDE>
-__device__ __forceinline__ void stage_panels_full(char* lds, const char* g, int wave, int lane) {
-  static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
-  constexpr int K = ROWS / 8 / NWAVES;
+__device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane) {
   const int row0 = 8 * wave + (lane >> 3);
   const int c = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
-  const uint32_t lane_off = row0 * GSTRIDE + c * 16;
+  return row0 * GSTRIDE + c * 16;
+}
+// g and wave must be wave-uniform; lane_off = stage_lane_offset(wave, lane) is the only per-lane part of the address.
+// The instruction is written as inline assembly on purpose: the compiler then does not know that LDS is being written
+// behind its back, and does not put a "wait for every outstanding load" in front of the next LDS read (it cannot see
+// that the reads go to another buffer).  The caller orders things itself: s_waitcnt vmcnt(0) and a workgroup barrier
+// before the staged tile is read.
+template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+__device__ __forceinline__ void stage_panels_step(char* lds, const char* g, int wave, uint32_t lane_off, int u) {
+  static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
+  constexpr int K = ROWS / 8 / NWAVES;
+  const int a = u / K, v = u % K;
+  const char* base = g + (8 * NWAVES * v * GSTRIDE + a * 128);
+  const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(dst), "v"(lane_off), "s"(base)
+               : "memory");  // M0 is written here; nothing else in these kernels uses it
+}
+
+// Whole matrix (all ROWS rows present), this wave's share in one burst of asm steps.
+template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+__device__ __forceinline__ void stage_panels_full(char* lds, const char* g, int wave, int lane) {
+  const uint32_t lane_off = stage_lane_offset<ROWS, NP, NWAVES, GSTRIDE>(wave, lane);
 #pragma unroll
-  for (int a = 0; a < NP; ++a) {
-#pragma unroll
-    for (int v = 0; v < K; ++v) {
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(g + (lane_off + (uint32_t)(8 * NWAVES * v * GSTRIDE + a * 128))),
-                                       (lds_ptr_t)(lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024), 16, 0, 0);
-    }
-  }
+  for (int u = 0; u < NP * (ROWS / 8 / NWAVES); ++u) stage_panels_step<ROWS, NP, NWAVES, GSTRIDE>(lds, g, wave, lane_off, u);
 }
 
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
