@@ -147,10 +147,16 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
  * t < L_b (L_b read from latent->seq_lens on the device) into `expanded`, whose pages hold
  * expanded->groups == group_count groups and which must use the same page_size, max_pages and page ids
  * (page_table content) as `latent`.  A slice with group_count < g is one rank's share of head-axis
- * tensor parallelism. */
+ * tensor parallelism.  `ws` is device scratch of at least gqla_expand_workspace_bytes(shape, group_count) bytes
+ * (16-byte aligned; it receives the slice's weights reordered for the matrix cores and may be reused or freed
+ * once the call's kernels have run); with dtype GQLA_F32 no scratch is needed and ws may be NULL.
+ * Errors: GQLA_ERR_SHAPE for a group range outside [0, g) or expanded->groups != group_count, GQLA_ERR_PAGE when
+ * the two caches disagree on geometry, GQLA_ERR_WORKSPACE when ws is NULL or too small. */
 gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
                               const void* w_uv, int32_t group_begin, int32_t group_count,
-                              const gqla_cache* expanded, void* stream);
+                              const gqla_cache* expanded, void* ws, size_t ws_bytes, void* stream);
+/* Bytes of scratch gqla_expand_cache needs for a slice of group_count groups (0 for GQLA_F32 or a bad shape). */
+size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count);
 
 /* GQA-path decode (Sec. 3.1, GQA-path equation) over an expanded cache holding expanded->groups == shape->g
  * groups (for a tensor-parallel slice pass a shape with h_q and g already divided).  plan: built with

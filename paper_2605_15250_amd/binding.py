@@ -21,6 +21,7 @@ GQLA_PATH_ABSORB, GQLA_PATH_GQA = 0, 1
 EXPORTS = [
     "gqla_plan_create", "gqla_plan_destroy", "gqla_plan_num_chunks", "gqla_plan_chunk_pages", "gqla_plan_export",
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
+    "gqla_expand_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -72,8 +73,10 @@ def lib():
         L.gqla_absorb_query.restype = i32
         L.gqla_decode_absorb.argtypes = [sp, vp, vp, vp, cp, vp, vp, vp, vp, sz, vp]
         L.gqla_decode_absorb.restype = i32
-        L.gqla_expand_cache.argtypes = [sp, cp, vp, vp, i32, i32, cp, vp]
+        L.gqla_expand_cache.argtypes = [sp, cp, vp, vp, i32, i32, cp, vp, C.c_size_t, vp]
         L.gqla_expand_cache.restype = i32
+        L.gqla_expand_workspace_bytes.argtypes = [sp, i32]
+        L.gqla_expand_workspace_bytes.restype = C.c_size_t
         L.gqla_decode_gqa.argtypes = [sp, vp, vp, vp, cp, vp, vp, vp, sz, vp]
         L.gqla_decode_gqa.restype = i32
         L.gqla_latent_elems_per_token.argtypes = [i32, i32]
@@ -180,9 +183,16 @@ def gqla_decode_absorb(shape, plan, q_hat, q_r, latent: gqla_cache, w_uv, out, l
                                     _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_absorb")
 
 
-def gqla_expand_cache(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded: gqla_cache, stream=None):
+def gqla_expand_workspace_bytes(shape, group_count) -> int:
+    return lib().gqla_expand_workspace_bytes(C.byref(shape), group_count)
+
+
+def gqla_expand_cache(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded: gqla_cache, ws=None,
+                      ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
     _check(lib().gqla_expand_cache(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
-                                   C.byref(expanded), _stream(stream)), "gqla_expand_cache")
+                                   C.byref(expanded), _ptr(ws), ws_bytes, _stream(stream)), "gqla_expand_cache")
 
 
 def gqla_decode_gqa(shape, plan, q_c, q_r, expanded: gqla_cache, out, lse, ws, ws_bytes=None, stream=None):

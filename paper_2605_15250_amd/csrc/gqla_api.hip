@@ -308,8 +308,14 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
+size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count) {
+  if (!shape || check_shape(shape) != GQLA_OK || shape->dtype != GQLA_BF16 || group_count <= 0) return 0;
+  return (size_t)2 * group_count * shape->r_kv * shape->d_h * 2;  // both weight slices in fragment order, bf16
+}
+
 gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
-                              int32_t group_begin, int32_t group_count, const gqla_cache* expanded, void* stream) {
+                              int32_t group_begin, int32_t group_count, const gqla_cache* expanded, void* ws,
+                              size_t ws_bytes, void* stream) {
   gqla_status st = check_shape(shape);
   if (st != GQLA_OK) return st;
   if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
@@ -323,6 +329,10 @@ gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent,
     return GQLA_ERR_PAGE;
   if (!latent->page_table && (int64_t)latent->num_pages < (int64_t)shape->batch * latent->max_pages) return GQLA_ERR_PAGE;
   if (!expanded->page_table && (int64_t)expanded->num_pages < (int64_t)shape->batch * expanded->max_pages) return GQLA_ERR_PAGE;
+  if (shape->dtype == GQLA_BF16) {
+    if (!ws || ws_bytes < gqla_expand_workspace_bytes(shape, group_count)) return GQLA_ERR_WORKSPACE;
+    if (!aligned16(ws)) return GQLA_ERR_ALIGN;
+  }
   if (shape->batch == 0) return GQLA_OK;
   ExpandArgs a;
   a.latent = view_of(latent);
@@ -338,7 +348,7 @@ gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent,
   a.group_begin = group_begin;
   a.group_count = group_count;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, s) : launch_expand_f32(a, s);
+  hipError_t e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, ws, s) : launch_expand_f32(a, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 

@@ -49,21 +49,63 @@ __global__ void __launch_bounds__(256) absorb_query_bf16_kernel(AbsorbQueryArgs 
     }
 }
 
+// MFMAs written out so that the latent fragments can live in the accumulation registers (the compiler's own selection
+// keeps A and B operands in ordinary registers only): c (+)= A * B with one operand in an AGPR quad.  The *_first forms
+// start a sum from zero.  Dependent MFMAs on one accumulator interlock in hardware; before any other instruction reads
+// the results, mfma_results_ready() covers the 16-pass latency of the last one.
+__device__ __forceinline__ void mfma_va(f32x16& c, bf16x8 a_vgpr, bf16x8 b_agpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a_vgpr), "a"(b_agpr));
+}
+__device__ __forceinline__ void mfma_va_first(f32x16& c, bf16x8 a_vgpr, bf16x8 b_agpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a_vgpr), "a"(b_agpr));
+}
+__device__ __forceinline__ void mfma_av(f32x16& c, bf16x8 a_agpr, bf16x8 b_vgpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "a"(a_agpr), "v"(b_vgpr));
+}
+__device__ __forceinline__ void mfma_av_first(f32x16& c, bf16x8 a_agpr, bf16x8 b_vgpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "a"(a_agpr), "v"(b_vgpr));
+}
+__device__ __forceinline__ void mfma_results_ready(f32x16& c0, f32x16& c1, f32x16& c2, f32x16& c3) {
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
+}
+
 // ---- cache expansion -----------------------------------------------------------------------------------------
-// One workgroup of 8 waves per (256-token block, sequence); wave w owns 32 tokens.  Each wave keeps its tokens'
-// latent rows as 32 register fragments (lane = token, 8 consecutive latent dims per k-step) and reuses them for
-// every group and for both K and V, so the latent is read from HBM once.  The weight matrix of one (group, kind)
-// at a time ([r_kv][d_h], 128 KB) is staged in LDS and read transposed:
+// Step 1 (tiny): the weights of the expanded groups are repacked once per call into MFMA fragment order,
+//   packed[(jj*2 + kind)*2 + mtp][ks][e][lane][8]  with  lane (m = l % 32, h = l / 32), element i  =
+//   W_kind[group_begin + jj][r = 16*ks + 8*h + i][d = 64*mtp + 32*e + m],
+// i.e. each 1 KB block is one A fragment of W^T (or, with the same register contents, one B fragment of W), and each
+// (matrix, 64-column half) is one contiguous 64 KB "stage".
+template <int DH, int RKV>
+__global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __bf16* packed) {
+  const int stage = blockIdx.x;  // (jj*2 + kind)*2 + mtp
+  const int mtp = stage & 1, kind = (stage >> 1) & 1, jj = stage >> 2;
+  const __bf16* w = (const __bf16*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * RKV * DH;
+  __bf16* out = packed + (int64_t)stage * (RKV / 16) * 2 * 512;
+  for (int idx = threadIdx.x; idx < (RKV / 16) * 2 * 512; idx += 256) {
+    const int i = idx & 7, lane = (idx >> 3) & 63, e = (idx >> 9) & 1, ks = idx >> 10;
+    const int m = lane & 31, h = lane >> 5;
+    out[idx] = w[(int64_t)(16 * ks + 8 * h + i) * DH + 64 * mtp + 32 * e + m];
+  }
+}
+
+// Step 2: one workgroup of 4 waves per (256-token block, sequence); wave w owns 64 tokens (two 32-token tiles) and,
+// alone on its SIMD, the whole 512-entry register file.  Each wave keeps its tokens' latent rows as 2 x 32 register
+// fragments (lane = token, 8 consecutive latent dims per k-step) and reuses them for every group and for both K and V,
+// so the latent is read from HBM once.  The packed weights stream through LDS one 64 KB stage at a time (LDS-DMA,
+// double buffered, the next stage in flight while the current one is multiplied); every weight fragment read from LDS
+// feeds two MFMAs (one per token tile):
 //   K^T[d][tok] = W_UK^T[d][r] * C^T[r][tok]     A = weight fragment, B = latent fragment
 //   V[tok][d]   = C[tok][r]    * W_UV[r][d]      A = latent fragment, B = weight fragment (same register contents)
 // The two output orientations put 4 consecutive dims (K plane) or 4 consecutive tokens (V plane) of the expanded
-// page's 8-element vectors in one lane.
+// page's 8-element vectors in one lane.  A stage's results are stored while the next stage is being multiplied, so
+// that the end-of-stage wait (which also covers stores on this hardware) finds them long gone.
 template <int DH, int RKV, int DR>
-__global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
+__global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
-  constexpr int MT = DH / 32;
-  static_assert(MT % 2 == 0, "output tiles are processed in pairs that share a 64-column panel");
+  constexpr int STAGE_BYTES = KS * 2 * 1024;  // 64 KB
+  constexpr int DEPTH = 2;                    // weight fragments are fetched this many k-steps ahead
+  static_assert(DH == 128, "two 64-column stages per weight matrix");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -74,7 +116,7 @@ __global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
   if (tok0 >= L) return;  // whole workgroup
   const int P = a.latent.page_size;
   const int gc = a.group_count;
-  const int tokw = tok0 + wave * 32;  // first token of this wave (a wave never straddles a page: P % 32 == 0)
+  const int tokw = tok0 + wave * 64;  // first token of this wave (a wave never straddles a page: P % 64 == 0)
   int32_t pg_in = -1, pg_out = -1;
   if (tokw < L) {
     pg_in = page_of(a.latent, b, tokw / P);
@@ -82,97 +124,145 @@ __global__ void __launch_bounds__(512) expand_bf16_kernel(ExpandArgs a) {
   }
   const bool wave_ok = pg_in >= 0 && pg_out >= 0;  // wave-uniform
   const int slot0 = tokw % P;
-  const bool tok_ok = wave_ok && (tokw + n < L);
 
-  // latent rows of this wave's 32 tokens as fragments (lane = token, 8 consecutive latent dims per k-step); rows past
-  // L_b are read from a clamped address and zeroed (their products are never stored)
-  bf16x8 xf[KS];
-  const int n_ld = tok_ok ? n : 0;
-  const __bf16* in_row = (const __bf16*)a.latent.pool + ((int64_t)(wave_ok ? pg_in : 0) * P + slot0 + n_ld) * W;
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    xf[ks] = *(const bf16x8*)(in_row + ks * 16 + h * 8);
-    if (!tok_ok) xf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-  }
-
+  // latent rows of this wave's 64 tokens as fragments, loaded straight into aligned AGPR quads.  Rows past L_b read a
+  // clamped (valid) address instead: a token is one MFMA column (K) or row (V), so whatever such a lane computes
+  // stays in that token's outputs, and those are never stored.
+  bf16x8 xf[2][KS];
+  const __bf16* in_page = (const __bf16*)a.latent.pool + (int64_t)(wave_ok ? pg_in : 0) * P * W;
   __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (2 * gc * DH + DR);
-  // k_R plane: a straight copy, 8 dims (16 bytes) per lane and step
-  if (tok_ok) {
 #pragma unroll
-    for (int cb = h; cb < DR / 8; cb += 2) {
-      const u32x4 v = *(const u32x4*)(in_row + RKV + cb * 8);
-      *(u32x4*)(out_page + (int64_t)2 * gc * DH * P + ((int64_t)cb * P + slot0 + n) * 8) = v;
-    }
-  }
-
-  const TrNatural tr = make_tr_natural(lane);
-  for (int jj = 0; jj < gc; ++jj) {
-#pragma unroll 1
-    for (int kind = 0; kind < 2; ++kind) {
-      __syncthreads();  // previous weight matrix no longer read
-      const char* wsrc = (const char*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * RKV * DH * 2;
-      stage_panels_full<RKV, DH / 64, 8, DH * 2>(smem, wsrc, wave, lane);
-      wait_all_memory();
-      __syncthreads();
-      if (!wave_ok) continue;
-#pragma unroll 1
-      for (int mtp = 0; mtp < MT / 2; ++mtp) {  // output tiles 2*mtp, 2*mtp + 1: both in panel mtp
-        const char* panel = smem + mtp * (RKV * 128);
-        f32x16 acc0, acc1;
+  for (int nt = 0; nt < 2; ++nt) {
+    const bool tok_ok = wave_ok && (tokw + 32 * nt + n < L);
+    const __bf16* in_row = in_page + (int64_t)(slot0 + (tok_ok ? 32 * nt + n : 0)) * W;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.f;
-        bf16x8 w0 = tr_natural_frag<RKV>(panel, tr, 0, 0), w1 = tr_natural_frag<RKV>(panel, tr, 0, 1);
+    for (int ks = 0; ks < KS; ++ks)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(xf[nt][ks]) : "v"(in_row + ks * 16 + h * 8));
+    // k_R plane: a straight copy, 8 dims (16 bytes) per lane and step
+    if (tok_ok) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 c0 = w0, c1 = w1;
-          if (ks + 1 < KS) {
-            w0 = tr_natural_frag<RKV>(panel, tr, ks + 1, 0);
-            w1 = tr_natural_frag<RKV>(panel, tr, ks + 1, 1);
-          }
-          if (kind == 0) {  // K^T[d][tok] = W_UK^T[d][r] * C^T[r][tok]
-            acc0 = mfma32(c0, xf[ks], acc0);
-            acc1 = mfma32(c1, xf[ks], acc1);
-          } else {          // V[tok][d] = C[tok][r] * W_UV[r][d]
-            acc0 = mfma32(xf[ks], c0, acc0);
-            acc1 = mfma32(xf[ks], c1, acc1);
-          }
-        }
-        if (kind == 0) {
-          // lane = token n, registers = dims 32*mt + 8*q + 4*h + 0..3  ->  half of one 8-dim vector of the K plane
-          if (tok_ok) {
-            __bf16* kb = out_page + (int64_t)jj * DH * P + (int64_t)(slot0 + n) * 8 + 4 * h;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              u32x2 v0 = {pack_bf16(acc0[4 * q], acc0[4 * q + 1]), pack_bf16(acc0[4 * q + 2], acc0[4 * q + 3])};
-              u32x2 v1 = {pack_bf16(acc1[4 * q], acc1[4 * q + 1]), pack_bf16(acc1[4 * q + 2], acc1[4 * q + 3])};
-              *(u32x2*)(kb + (int64_t)(8 * mtp + q) * P * 8) = v0;
-              *(u32x2*)(kb + (int64_t)(8 * mtp + 4 + q) * P * 8) = v1;
-            }
-          }
-        } else {
-          // lane = dim 32*mt + n, registers = tokens tokw + 8*q + 4*h + 0..3  ->  half of one 8-token vector of the V plane
-          __bf16* vb = out_page + (int64_t)gc * DH * P + (int64_t)jj * DH * P;
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            const f32x16& acc = half ? acc1 : acc0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int tk = tokw + 8 * q + 4 * h;  // first of 4 tokens
-              __bf16* dst = vb + ((int64_t)((slot0 >> 3) + q) * DH + (2 * mtp + half) * 32 + n) * 8 + 4 * h;
-              if (tk + 3 < L) {
-                u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
-                *(u32x2*)dst = v;
-              } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                  if (tk + e < L) dst[e] = (__bf16)acc[4 * q + e];
-              }
-            }
-          }
-        }
+      for (int cb = h; cb < DR / 8; cb += 2) {
+        const u32x4 v = *(const u32x4*)(in_row + RKV + cb * 8);
+        *(u32x4*)(out_page + (int64_t)2 * gc * DH * P + ((int64_t)cb * P + slot0 + 32 * nt + n) * 8) = v;
       }
     }
   }
+
+  // LDS-DMA of one stage: 64 instructions of 1 KB, 16 per wave, linear (the packed layout is already fragment order)
+  auto stage_in = [&](int stage, char* buf) {
+    const char* src = (const char*)packed + (int64_t)stage * STAGE_BYTES;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int blk = wave * 16 + u;
+      const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(buf + blk * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(lane * 16), "s"(src + blk * 1024) : "memory");
+    }
+  };
+  // results of the previous stage ([token tile][32-column half]), kept until the next stage's arithmetic is under way
+  f32x16 prev[2][2];
+  // stores address the page through one uniform base and 32-bit offsets (a page is at most a few MB)
+  char* const page_bytes = (char*)out_page;
+  const uint32_t plane = (uint32_t)DH * P;                            // elements of one group's K (or V) plane
+  const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + 4 * h;          // K plane: token slot0 + n (+ 32 per token tile)
+  const uint32_t v_lane = (uint32_t)(slot0 >> 3) * DH * 8 + n * 8 + 4 * h;  // V plane: 8-token block slot0/8 (+ 4 per tile, + q)
+  const bool wave_full = tokw + 64 <= L;                              // no token of this wave lies beyond L_b
+  auto store_prev = [&](int kind, int mtp, int jj) {  // kind and mtp are compile-time at every call site
+    if (jj < 0 || !wave_ok) return;
+    if (kind == 0) {
+      // lane = token, registers = dims 64*mtp + 32*e + 8*q + 4*h + 0..3  ->  half of one 8-dim vector of the K plane
+      const uint32_t base = (uint32_t)jj * plane + (uint32_t)(8 * mtp) * P * 8;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        if (wave_full || tokw + 32 * nt + n < L) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const f32x16& acc = prev[nt][e];
+              u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
+              const uint32_t off = base + (uint32_t)(4 * e + q) * P * 8 + 32 * nt * 8 + k_lane;
+              *(u32x2*)(page_bytes + (size_t)off * 2) = v;
+            }
+        }
+      }
+    } else {
+      // lane = dim 64*mtp + 32*e + n, registers = tokens 32*nt + 8*q + 4*h + 0..3  ->  half of one 8-token vector of the V plane
+      const uint32_t base = (uint32_t)(gc + jj) * plane + (uint32_t)(2 * mtp) * 32 * 8;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const f32x16& acc = prev[nt][e];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t off = base + (uint32_t)(4 * nt + q) * DH * 8 + e * 32 * 8 + v_lane;
+            __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
+            const int tk = tokw + 32 * nt + 8 * q + 4 * h;  // first of 4 tokens
+            if (wave_full || tk + 3 < L) {
+              u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
+              *(u32x2*)dst = v;
+            } else {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (tk + i < L) dst[i] = (__bf16)acc[4 * q + i];
+            }
+          }
+        }
+    }
+  };
+
+  const int n_stages = gc * 4;
+  stage_in(0, smem);
+  wait_all_memory();
+  __syncthreads();
+  for (int jj = 0; jj < gc; ++jj) {
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {  // sub = kind*2 + mtp, compile time: fixes the MFMA operand order
+      const int stage = jj * 4 + sub;
+      const char* buf = smem + (stage & 1) * STAGE_BYTES + lane * 16;
+      if (stage + 1 < n_stages) stage_in(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES);
+      f32x16 acc[2][2];
+      if (wave_ok) {
+        bf16x8 w[DEPTH + 1][2];
+#pragma unroll
+        for (int ks = 0; ks < DEPTH; ++ks) {
+          w[ks][0] = *(const bf16x8*)(buf + (2 * ks) * 1024);
+          w[ks][1] = *(const bf16x8*)(buf + (2 * ks + 1) * 1024);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          if (ks + DEPTH < KS) {
+            w[(ks + DEPTH) % (DEPTH + 1)][0] = *(const bf16x8*)(buf + (2 * (ks + DEPTH)) * 1024);
+            w[(ks + DEPTH) % (DEPTH + 1)][1] = *(const bf16x8*)(buf + (2 * (ks + DEPTH) + 1) * 1024);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const bf16x8 wf = w[ks % (DEPTH + 1)][e];
+              if ((sub >> 1) == 0) {
+                if (ks == 0) mfma_va_first(acc[nt][e], wf, xf[nt][ks]);
+                else mfma_va(acc[nt][e], wf, xf[nt][ks]);
+              } else {
+                if (ks == 0) mfma_av_first(acc[nt][e], xf[nt][ks], wf);
+                else mfma_av(acc[nt][e], xf[nt][ks], wf);
+              }
+            }
+          __builtin_amdgcn_sched_barrier(0);
+          if (ks == 3) store_prev(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj);  // previous stage's results
+        }
+        mfma_results_ready(acc[0][0], acc[0][1], acc[1][0], acc[1][1]);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int e = 0; e < 2; ++e) prev[nt][e] = acc[nt][e];
+      }
+      wait_all_memory();
+      __syncthreads();  // next stage has landed; everyone is done with this stage's buffer
+    }
+  }
+  store_prev(1, 1, gc - 1);
 }
 
 }  // namespace
@@ -184,8 +274,8 @@ hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_expand_bf16(const ExpandArgs& a, hipStream_t s) {
-  constexpr int kLds = 512 * 128 * 2;
+hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
+  constexpr int kLds = 2 * (512 / 16) * 2 * 1024;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64>,
@@ -195,7 +285,10 @@ hipError_t launch_expand_bf16(const ExpandArgs& a, hipStream_t s) {
   }
   const int64_t max_tokens = (int64_t)a.latent.max_pages * a.latent.page_size;
   dim3 grid((unsigned)((max_tokens + 255) / 256), a.B);
-  expand_bf16_kernel<128, 512, 64><<<grid, 512, kLds, s>>>(a);
+  pack_weights_bf16_kernel<128, 512><<<a.group_count * 4, 256, 0, s>>>(a, (__bf16*)ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_bf16_kernel<128, 512, 64><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }
 

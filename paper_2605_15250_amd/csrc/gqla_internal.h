@@ -81,7 +81,7 @@ hipError_t launch_combine_f32(const CombineArgs&, bool out_bf16, hipStream_t);  
 hipError_t launch_combine_project_f32(const CombineArgs&, hipStream_t);                  // fp32 latent partials, fp32 out
 hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);                 // bf16 latent partials, bf16 out
 hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
-hipError_t launch_expand_bf16(const ExpandArgs&, hipStream_t);
+hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*group_count*r_kv*d_h bf16 */, hipStream_t);
 
 }  // namespace gqla
 

@@ -66,6 +66,7 @@ class Decoder:
         B.gqla_plan_upload(self.plan_g, self.ws_g)
         self.latent_pool = None
         self.expanded_pool = None
+        self.ws_e = None                                        # scratch of the expand call
 
     def close(self):
         for p in (self.plan_a, self.plan_g):
@@ -110,7 +111,11 @@ class Decoder:
     def expand(self, w_uk, w_uv):
         if self.expanded_pool is None:
             self.alloc_expanded()
-        B.gqla_expand_cache(self.shape, self.latent_cache(), w_uk, w_uv, self.group_begin, self.groups, self.expanded_cache())
+        if self.ws_e is None:
+            nbytes = B.gqla_expand_workspace_bytes(self.shape, self.groups)
+            self.ws_e = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+        B.gqla_expand_cache(self.shape, self.latent_cache(), w_uk, w_uv, self.group_begin, self.groups,
+                            self.expanded_cache(), self.ws_e)
         return self.expanded_pool
 
     def decode_gqa(self, q_c, q_r, out=None, lse=None):

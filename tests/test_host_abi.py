@@ -135,6 +135,13 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_PAGE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, B.make_cache(A, A, None, 64, 5, 8, 8), stream=0)
         _expect(B.GQLA_ERR_NULL, B.gqla_expand_cache, ok, B.make_cache(A, None, None, 64, 4, 8, 0), A, A, 0, 8,
                 B.make_cache(A, A, None, 64, 4, 8, 8), stream=0)
+        # expand scratch: both weight slices of the expanded groups, bf16; none for fp32
+        assert B.gqla_expand_workspace_bytes(ok, 8) == 2 * 8 * 512 * 128 * 2
+        assert B.gqla_expand_workspace_bytes(ok, 1) == 2 * 512 * 128 * 2
+        assert B.gqla_expand_workspace_bytes(B.make_shape(2, 128, 8, 128, 512, 64, 1, B.GQLA_F32), 8) == 0
+        full = B.make_cache(A, A, None, 64, 4, 8, 8)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, full, None, 0, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, full, A, 2 * 8 * 512 * 128 * 2 - 1, stream=0)
     finally:
         B.gqla_plan_destroy(plan_a)
         B.gqla_plan_destroy(plan_g)
