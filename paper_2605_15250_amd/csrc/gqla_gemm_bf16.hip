@@ -143,71 +143,61 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 #pragma unroll
       for (int cb = h; cb < DR / 8; cb += 2) {
         const u32x4 v = *(const u32x4*)(in_row + RKV + cb * 8);
-        *(u32x4*)(out_page + (int64_t)2 * gc * DH * P + ((int64_t)cb * P + slot0 + 32 * nt + n) * 8) = v;
+        __builtin_nontemporal_store(v, (u32x4*)(out_page + (int64_t)2 * gc * DH * P + ((int64_t)cb * P + slot0 + 32 * nt + n) * 8));
       }
     }
   }
 
   // LDS-DMA of one stage: 64 instructions of 1 KB, 16 per wave, linear (the packed layout is already fragment order)
-  auto stage_in = [&](int stage, char* buf) {
+  auto stage_in_step = [&](int stage, char* buf, int u) {  // u = 0..15
     const char* src = (const char*)packed + (int64_t)stage * STAGE_BYTES;
+    const int blk = wave * 16 + u;
+    const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(buf + blk * 1024);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(lane * 16), "s"(src + blk * 1024) : "memory");
+  };
+  auto stage_in = [&](int stage, char* buf) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int blk = wave * 16 + u;
-      const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(buf + blk * 1024);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(lane * 16), "s"(src + blk * 1024) : "memory");
-    }
+    for (int u = 0; u < 16; ++u) stage_in_step(stage, buf, u);
   };
   // results of the previous stage ([token tile][32-column half]), kept until the next stage's arithmetic is under way
-  f32x16 prev[2][2];
+  f32x16 accs[2][2][2];  // [stage parity][token tile][32-column half]: one set accumulates while the other is stored
   // stores address the page through one uniform base and 32-bit offsets (a page is at most a few MB)
   char* const page_bytes = (char*)out_page;
   const uint32_t plane = (uint32_t)DH * P;                            // elements of one group's K (or V) plane
-  const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + 4 * h;          // K plane: token slot0 + n (+ 32 per token tile)
-  const uint32_t v_lane = (uint32_t)(slot0 >> 3) * DH * 8 + n * 8 + 4 * h;  // V plane: 8-token block slot0/8 (+ 4 per tile, + q)
-  const bool wave_full = tokw + 64 <= L;                              // no token of this wave lies beyond L_b
-  auto store_prev = [&](int kind, int mtp, int jj) {  // kind and mtp are compile-time at every call site
+  const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + (uint32_t)h * P * 8;        // K plane: token slot0 + n, 8-dim block + h
+  const uint32_t v_lane = (uint32_t)((slot0 >> 3) + h) * DH * 8 + n * 8;          // V plane: dim n, 8-token block slot0/8 + h
+  const bool wave_full = tokw + 64 <= L;                                          // no token of this wave lies beyond L_b
+  // One 16-byte store per lane: piece (nt, e, qp) of the previous stage's results; kind, mtp and the piece are compile-time.
+  // A lane holds rows 4h..4h+3 of each 8-row block of its column; the two half-waves trade so that lane (n, h) ends up
+  // with all 8 rows of block 2*qp + h, i.e. one complete vector of the page layout.
+  auto store_prev = [&](int kind, int mtp, int jj, int nt, int e, int qp) {
     if (jj < 0 || !wave_ok) return;
+    const f32x16& acc = accs[(kind * 2 + mtp) & 1][nt][e];
+    const int q0 = 2 * qp;
+    const uint32_t x0 = pack_bf16(acc[4 * q0], acc[4 * q0 + 1]), x1 = pack_bf16(acc[4 * q0 + 2], acc[4 * q0 + 3]);
+    const uint32_t y0 = pack_bf16(acc[4 * q0 + 4], acc[4 * q0 + 5]), y1 = pack_bf16(acc[4 * q0 + 6], acc[4 * q0 + 7]);
+    uint32_t r0, r1, r2, r3;
+    half_swap(x0, y0, r0, r2);
+    half_swap(x1, y1, r1, r3);
+    const u32x4 v = {r0, r1, r2, r3};
     if (kind == 0) {
-      // lane = token, registers = dims 64*mtp + 32*e + 8*q + 4*h + 0..3  ->  half of one 8-dim vector of the K plane
-      const uint32_t base = (uint32_t)jj * plane + (uint32_t)(8 * mtp) * P * 8;
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        if (wave_full || tokw + 32 * nt + n < L) {
-#pragma unroll
-          for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const f32x16& acc = prev[nt][e];
-              u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
-              const uint32_t off = base + (uint32_t)(4 * e + q) * P * 8 + 32 * nt * 8 + k_lane;
-              *(u32x2*)(page_bytes + (size_t)off * 2) = v;
-            }
-        }
+      // lane = token; the vector is dims 64*mtp + 32*e + 8*(2*qp + h) + 0..7 of the K plane
+      if (wave_full || tokw + 32 * nt + n < L) {
+        const uint32_t off = (uint32_t)jj * plane + (uint32_t)(8 * mtp + 4 * e + q0) * P * 8 + 32 * nt * 8 + k_lane;
+        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (size_t)off * 2));
       }
     } else {
-      // lane = dim 64*mtp + 32*e + n, registers = tokens 32*nt + 8*q + 4*h + 0..3  ->  half of one 8-token vector of the V plane
-      const uint32_t base = (uint32_t)(gc + jj) * plane + (uint32_t)(2 * mtp) * 32 * 8;
+      // lane = dim 64*mtp + 32*e + n; the vector is tokens 32*nt + 8*(2*qp + h) + 0..7 of the V plane
+      const uint32_t off = (uint32_t)(gc + jj) * plane + (uint32_t)(4 * nt + q0) * DH * 8 + (2 * mtp + e) * 32 * 8 + v_lane;
+      __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
+      const int tk = tokw + 32 * nt + 8 * (q0 + h);  // first of 8 tokens
+      if (wave_full || tk + 7 < L) {
+        __builtin_nontemporal_store(v, (u32x4*)dst);
+      } else {
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const f32x16& acc = prev[nt][e];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t off = base + (uint32_t)(4 * nt + q) * DH * 8 + e * 32 * 8 + v_lane;
-            __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
-            const int tk = tokw + 32 * nt + 8 * q + 4 * h;  // first of 4 tokens
-            if (wave_full || tk + 3 < L) {
-              u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
-              *(u32x2*)dst = v;
-            } else {
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                if (tk + i < L) dst[i] = (__bf16)acc[4 * q + i];
-            }
-          }
-        }
+        for (int i = 0; i < 8; ++i)
+          if (tk + i < L) ((uint16_t*)dst)[i] = (uint16_t)(v[i >> 1] >> (16 * (i & 1)));
+      }
     }
   };
 
@@ -220,8 +210,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
     for (int sub = 0; sub < 4; ++sub) {  // sub = kind*2 + mtp, compile time: fixes the MFMA operand order
       const int stage = jj * 4 + sub;
       const char* buf = smem + (stage & 1) * STAGE_BYTES + lane * 16;
-      if (stage + 1 < n_stages) stage_in(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES);
-      f32x16 acc[2][2];
+      f32x16 (&acc)[2][2] = accs[sub & 1];
       if (wave_ok) {
         bf16x8 w[DEPTH + 1][2];
 #pragma unroll
@@ -235,6 +224,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
             w[(ks + DEPTH) % (DEPTH + 1)][0] = *(const bf16x8*)(buf + (2 * (ks + DEPTH)) * 1024);
             w[(ks + DEPTH) % (DEPTH + 1)][1] = *(const bf16x8*)(buf + (2 * (ks + DEPTH) + 1) * 1024);
           }
+          if (ks < 16 && stage + 1 < n_stages) stage_in_step(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES, ks);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int nt = 0; nt < 2; ++nt)
@@ -250,19 +240,20 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
               }
             }
           __builtin_amdgcn_sched_barrier(0);
-          if (ks == 3) store_prev(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj);  // previous stage's results
+          // the previous stage's results leave one store at a time, in the shadow of this stage's MFMAs
+          if (ks >= 1 && ks <= 15 && (ks & 1))
+            store_prev(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj, (ks >> 1) >> 2, ((ks >> 1) >> 1) & 1, (ks >> 1) & 1);
         }
         mfma_results_ready(acc[0][0], acc[0][1], acc[1][0], acc[1][1]);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-          for (int e = 0; e < 2; ++e) prev[nt][e] = acc[nt][e];
+      } else if (stage + 1 < n_stages) {
+        stage_in(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES);  // a wave without tokens still stages its share
       }
       wait_all_memory();
       __syncthreads();  // next stage has landed; everyone is done with this stage's buffer
     }
   }
-  store_prev(1, 1, gc - 1);
+#pragma unroll
+  for (int piece = 0; piece < 8; ++piece) store_prev(1, 1, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
 }
 
 }  // namespace
