@@ -5,7 +5,8 @@
 //   S^T[token][row] = K[token][dim] * Q^T[dim][row]        A = cache vectors, B = queries held in registers
 //   O^T[dim][row]  += V^T[dim][token] * P^T[token][row]    A = cache vectors, B = probabilities from S^T
 // S^T and O^T keep one query row per lane (row = lane % 32), so the online-softmax state is per lane and the
-// only cross-lane traffic is between the two half-waves.  All heads of a group (G * s_q rows) share each
+// only cross-lane traffic is between the two half-waves.  Cache vectors are read once, so their loads carry the
+// non-temporal hint.  All heads of a group (G * s_q rows) share each
 // loaded vector through the MFMA.  The path is bound by HBM bandwidth (intensity 19-39 FLOP/byte, Sec. 4.2.2).
 #include "gqla_device.h"
 
@@ -63,9 +64,9 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     const __bf16* kb = base + (int64_t)j * DH * P + ((int64_t)h * P + slot) * 8;
     const __bf16* rbp = base + (int64_t)2 * gc * DH * P + ((int64_t)h * P + slot) * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS_C; ++ks) kf[ks] = *(const bf16x8*)(kb + (int64_t)ks * 16 * P);
+    for (int ks = 0; ks < KS_C; ++ks) kf[ks] = __builtin_nontemporal_load((const bf16x8*)(kb + (int64_t)ks * 16 * P));
 #pragma unroll
-    for (int ks = 0; ks < KS_R; ++ks) rf[ks] = *(const bf16x8*)(rbp + (int64_t)ks * 16 * P);
+    for (int ks = 0; ks < KS_R; ++ks) rf[ks] = __builtin_nontemporal_load((const bf16x8*)(rbp + (int64_t)ks * 16 * P));
   };
   auto load_v = [&](int tok) {
     const int32_t pg = page_of(a.cache, ce.b, tok / P);
@@ -76,7 +77,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
-        vf[mt][kk] = *(const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 8);
+        vf[mt][kk] = __builtin_nontemporal_load((const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 8));
   };
 
   f32x16 o[MT];
