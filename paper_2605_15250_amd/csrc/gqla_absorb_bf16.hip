@@ -17,9 +17,64 @@ namespace gqla {
 
 namespace {
 
-constexpr int kTile = 64;                 // tokens per LDS tile
+constexpr int kTile = 32;                 // tokens per LDS tile
+constexpr int kSlots = 4;                 // tile buffers in the LDS ring
 constexpr int kRowsPerBlock = 128;        // query rows per workgroup
 constexpr float kRescaleThreshold = 8.f;  // log2 units
+
+// ---- O^T accumulators, managed by hand ----
+// O^T (512 x 32 fp32 per wave) fills all 256 accumulation registers: tile dt (32 latent dims x 32 rows) is a[16*dt : 16*dt+15].
+// They are addressed by NAME in inline assembly and never appear as C++ values: the compiler then has nothing to
+// allocate, copy or spill there, and the rest of the kernel gets the 256 ordinary registers to itself.  Every statement
+// below is `asm volatile`, so they keep their program order; the callers keep the hardware's timing rules
+// (results of an MFMA are read by non-MFMA instructions only after its last pass has long retired).
+#define GQLA_A10(p) "a" #p "0", "a" #p "1", "a" #p "2", "a" #p "3", "a" #p "4", "a" #p "5", "a" #p "6", "a" #p "7", "a" #p "8", "a" #p "9"
+#define GQLA_ALL_AGPRS                                                                                                   \
+  "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", GQLA_A10(1), GQLA_A10(2), GQLA_A10(3), GQLA_A10(4),       \
+      GQLA_A10(5), GQLA_A10(6), GQLA_A10(7), GQLA_A10(8), GQLA_A10(9), GQLA_A10(10), GQLA_A10(11), GQLA_A10(12),        \
+      GQLA_A10(13), GQLA_A10(14), GQLA_A10(15), GQLA_A10(16), GQLA_A10(17), GQLA_A10(18), GQLA_A10(19), GQLA_A10(20),  \
+      GQLA_A10(21), GQLA_A10(22), GQLA_A10(23), GQLA_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
+#define GQLA_ACC(D) "a[" #D "*16:" #D "*16+15]"
+#define GQLA_FOR_DT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
+
+__device__ __forceinline__ void acc_zero() {
+  asm volatile(".set gqla_i, 0\n.rept 256\n\tv_accvgpr_write_b32 a[gqla_i], 0\n.set gqla_i, gqla_i+1\n.endr" : : : GQLA_ALL_AGPRS);
+}
+// O^T tile dt += A * B (dt is a compile-time value at every call site: the switch folds away)
+__device__ __forceinline__ void acc_mfma(int dt, bf16x8 a, bf16x8 b) {
+  switch (dt) {
+#define X(D) case D: asm volatile("v_mfma_f32_32x32x16_bf16 " GQLA_ACC(D) ", %0, %1, " GQLA_ACC(D) : : "v"(a), "v"(b)); break;
+    GQLA_FOR_DT(X)
+#undef X
+  }
+}
+// every accumulator of this lane times alpha (one query row per lane, so alpha is per lane)
+__device__ __forceinline__ void acc_scale(float alpha) {
+  float t0, t1;
+  asm volatile(
+      ".set gqla_i, 0\n.rept 128\n"
+      "\tv_accvgpr_read_b32 %0, a[gqla_i]\n\tv_accvgpr_read_b32 %1, a[gqla_i+1]\n"
+      "\tv_mul_f32 %0, %0, %2\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n"
+      "\tv_accvgpr_write_b32 a[gqla_i], %0\n\tv_accvgpr_write_b32 a[gqla_i+1], %1\n"
+      ".set gqla_i, gqla_i+2\n.endr"
+      : "=&v"(t0), "=&v"(t1)
+      : "v"(alpha));
+}
+// tile dt into 16 ordinary registers (first call after the last MFMA: pass wait = true)
+__device__ __forceinline__ void acc_read(int dt, bool wait, float (&x)[16]) {
+  if (wait) asm volatile("s_nop 15\n\ts_nop 7");
+  switch (dt) {
+#define X(D)                                                                                                            \
+  case D:                                                                                                               \
+    asm volatile(".set gqla_i, 0\n.irp r, %0, %1, %2, %3, %4, %5, %6, %7, %8, %9, %10, %11, %12, %13, %14, %15\n"        \
+                 "\tv_accvgpr_read_b32 \\r, a[" #D "*16+gqla_i]\n.set gqla_i, gqla_i+1\n.endr"                           \
+                 : "=v"(x[0]), "=v"(x[1]), "=v"(x[2]), "=v"(x[3]), "=v"(x[4]), "=v"(x[5]), "=v"(x[6]), "=v"(x[7]),      \
+                   "=v"(x[8]), "=v"(x[9]), "=v"(x[10]), "=v"(x[11]), "=v"(x[12]), "=v"(x[13]), "=v"(x[14]), "=v"(x[15])); \
+    break;
+    GQLA_FOR_DT(X)
+#undef X
+  }
+}
 
 template <int RKV, int DR>
 __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, int row_blocks, int n_chunks_padded) {
@@ -31,7 +86,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   constexpr int DT = RKV / 32;       // 32-wide tiles of the latent output
   constexpr int TILE_BYTES = kTile * ROWB;
   static_assert(W % 64 == 0 && RKV % 64 == 0, "latent row must be a whole number of 128-byte panels");
-  static_assert((32 + 16 + 8 + 4) * 128 + 128 + PANEL * (RKV / 64 - 1) < 65536, "value-fragment offsets must fit the 16-bit LDS immediate");
+  static_assert((16 + 8 + 4) * 128 + 128 + PANEL * (RKV / 64 - 1) < 65536, "value-fragment offsets must fit the 16-bit LDS immediate");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   // blockIdx -> (chunk, row block): the row blocks of one chunk get ids that are equal modulo 8 so that they run on
@@ -72,26 +127,20 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const char* pool = (const char*)a.cache.pool;
   // Tiles are always staged whole: rows past the chunk end still come from the page (allocated memory), an
   // out-of-pool page id falls back to page 0; such rows are zeroed in LDS before use (see the loop).
-  // Page ids are looked up two tiles ahead and consumed one iteration later, right after the point where every
-  // outstanding load has been waited for anyway, so that the table read never stalls the pipeline.
-  auto raw_page = [&](int tok) -> int32_t {  // table entry (or identity page) of the page holding token `tok`
-    const int p = tok / P;
-    return a.cache.page_table ? a.cache.page_table[(int64_t)ce.b * a.cache.max_pages + p] : ce.b * a.cache.max_pages + p;
-  };
+  const int32_t* table_row = a.cache.page_table ? a.cache.page_table + (int64_t)ce.b * a.cache.max_pages : nullptr;
   auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
   auto tile_src = [&](int32_t pg, int tok) -> const char* {
     return pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * ROWB;
   };
 
   // Per-lane LDS byte offsets inside a tile (panel layout of gqla_lds.h; everything else is a compile-time offset):
-  //  key fragments     row 32*mt + n, chunk 2*ks + h with ks = 4*a4 + b: panel a4, in-panel chunk 2*b + h
-  //                    -> four bases (b = 0..3), plus a4*PANEL + 32*mt*128.
+  //  key fragments     row n, chunk 2*ks + h with ks = 4*a4 + b: panel a4, in-panel chunk 2*b + h
+  //                    -> four bases (b = 0..3), plus a4*PANEL.
   //  value fragments   (transposed reads) this lane addresses row R0 + 4*h + e (and 8 rows further for the second read),
   //                    4 columns at 32*dt + 16*g1 + 4*q: panel dt/2, in-panel chunk 4*(dt & 1) + cl, cl = 2*g1 + q/2.
   //                    With R0 a multiple of 16, swz = 2*h + e/2 for the first read and 4 + that for the second, so the
   //                    chunk lands at 4*(dt & 1) + (cl ^ swz) resp. 4*(1 - (dt & 1)) + (cl ^ swz): one base per lane.
   uint32_t kbase[4], vbase;
-  const uint32_t stage_off = stage_lane_offset<kTile, NP, 4, ROWB>(wave, lane);
   {
 #pragma unroll
     for (int b = 0; b < 4; ++b) kbase[b] = n * 128 + (((2 * b + h) ^ lds_swz(n)) << 4);
@@ -99,68 +148,99 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     vbase = (4 * h + e) * 128 + (((2 * g1 + (q >> 1)) ^ (2 * h + (e >> 1))) << 4) + (q & 1) * 8;
   }
 
-  f32x16 o[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  static_assert(DT == 16, "O^T fills the 256 accumulation registers exactly");
+  acc_zero();
   float m_ref = GQLA_NEG_INF, l_run = 0.f;
 
+  // Ring of kSlots tile buffers.  Tile it + kAhead is staged (9 LDS-DMA instructions per wave, after the S phase)
+  // while tile `it` is worked on, so every load has about three tile times to land and only a few KB per wave are
+  // ever requested at once.  Loads complete in issue order, so "tile `it` has landed" is a count:
+  // at most the instructions of the tiles staged after it may still be outstanding.  No other vector-memory
+  // instruction is issued inside the loop: page ids come through the scalar cache, one tile ahead of their use.
+  constexpr int kAhead = kSlots - 1;
+  constexpr int kStageSteps = NP * (kTile / 8 / 4);  // LDS-DMA instructions per wave and tile
+  static_assert(kStageSteps == 9, "the wait counts below assume 9 instructions per wave and tile");
   const int n_tiles = (ce.tok_end - ce.tok_begin + kTile - 1) / kTile;
-  int32_t pg_cur = checked(raw_page(ce.tok_begin));
-  int32_t pg_n1 = n_tiles > 1 ? checked(raw_page(ce.tok_begin + kTile)) : -1;
-  int32_t pg_raw = n_tiles > 2 ? raw_page(ce.tok_begin + 2 * kTile) : -1;  // consumed at the top of iteration 1
-  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg_cur, ce.tok_begin), wave, lane);
+  // page ids of tiles it, it+1, it+2 (staged) and it+3 (staged during tile it); the four first lookups go out together
+  // (indices clamped to the chunk's last page, results of tiles that do not exist discarded)
+  int32_t pg0, pg1, pg2, pg3;
+  {
+    const int p_last = (ce.tok_end - 1) / P;
+    int32_t raw[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int p = min((ce.tok_begin + k * kTile) / P, p_last);
+      raw[k] = table_row ? table_row[p] : ce.b * a.cache.max_pages + p;
+    }
+    pg0 = checked(raw[0]);
+    pg1 = n_tiles > 1 ? checked(raw[1]) : -1;
+    pg2 = n_tiles > 2 ? checked(raw[2]) : -1;
+    pg3 = n_tiles > 3 ? checked(raw[3]) : -1;
+  }
+  int32_t pg_raw = 0;  // table entry of tile it + 4, in flight through the scalar cache
+  static_assert(kAhead == 3, "the page-id shift register holds four tiles");
+  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg0, ce.tok_begin), wave, lane);
+  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB>(smem + TILE_BYTES, tile_src(pg1, ce.tok_begin + kTile), wave, lane);
+  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB>(smem + 2 * TILE_BYTES, tile_src(pg2, ce.tok_begin + 2 * kTile), wave, lane);
+#pragma unroll 1
   for (int it = 0; it < n_tiles; ++it) {
     const int tok = ce.tok_begin + it * kTile;
-    const char* buf = smem + (it & 1) * TILE_BYTES;
-    wait_all_memory();
-    __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
-    // The next tile is staged one LDS-DMA instruction per MFMA batch of the S phase (18 batches, 18 instructions):
-    // issued in one burst, the loads would block this wave for thousands of cycles.
-    if (it > 0) {  // rotate the page-id window; pg_raw was loaded one iteration ago
-      pg_cur = pg_n1;
-      pg_n1 = checked(__builtin_amdgcn_readfirstlane(pg_raw));
-      pg_raw = it + 2 < n_tiles ? raw_page(tok + 2 * kTile) : -1;
+    const char* buf = smem + (it & (kSlots - 1)) * TILE_BYTES;
+    {
+      const int behind = min(kAhead - 1, n_tiles - 1 - it);  // tiles staged after this one
+      if (behind >= 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+      else if (behind == 1) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    const bool stage_next = it + 1 < n_tiles;
-    const char* next_g = tile_src(stage_next ? pg_n1 : 0, tok + kTile);
-    char* next_buf = smem + ((it + 1) & 1) * TILE_BYTES;
-    const bool tile_ok = pg_cur >= 0;
+    __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
+    const bool stage_next = it + kAhead < n_tiles;
+    const char* next_g = tile_src(stage_next ? pg3 : 0, tok + kAhead * kTile);
+    char* next_buf = smem + ((it + kAhead) & (kSlots - 1)) * TILE_BYTES;
+    const bool lookup = it + kAhead + 1 < n_tiles;
+    if (lookup && table_row)  // scalar load, consumed after the S phase (its wait is written out there)
+      asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pg_raw) : "s"(table_row + (tok + (kAhead + 1) * kTile) / P) : "memory");
+    const bool tile_ok = pg0 >= 0;
     const int valid = tile_ok ? min(kTile, ce.tok_end - tok) : 0;
     if (valid < kTile) {
       // rows past the chunk end hold whatever the page holds (NaN bits included): zero them so that 0 * v stays 0
       for (int idx = threadIdx.x; idx < (kTile - valid) * (W / 8); idx += 256) {
         const int r = valid + idx / (W / 8), c = idx % (W / 8);
-        *(u32x4*)(smem + (it & 1) * TILE_BYTES + (c >> 3) * PANEL + r * 128 + (c & 7) * 16) = u32x4{0u, 0u, 0u, 0u};
+        *(u32x4*)(smem + (it & (kSlots - 1)) * TILE_BYTES + (c >> 3) * PANEL + r * 128 + (c & 7) * 16) = u32x4{0u, 0u, 0u, 0u};
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
       __syncthreads();
     }
 
+    auto shift_pages = [&]() {  // the entry looked up above belongs to tile it + kAhead + 1
+      if (lookup && table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pg_raw) : : "memory");
+      pg0 = pg1;
+      pg1 = pg2;
+      pg2 = pg3;
+      pg3 = lookup ? checked(table_row ? pg_raw : ce.b * a.cache.max_pages + (tok + (kAhead + 1) * kTile) / P) : -1;
+    };
     if (!wave_active) {  // waves without query rows only help staging (uniform per wave): their share, in one burst
       if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      shift_pages();
       continue;
     }
-    const bool need_mask = (tok + kTile > unmasked_end) || !row_ok || !tile_ok;
-    const int lim = tile_ok ? vis_end : 0;
+    {
+      const bool need_mask = (tok + kTile > unmasked_end) || !row_ok || !tile_ok;
+      const int lim = tile_ok ? vis_end : 0;
 
-#pragma unroll 1
-    for (int mt = 0; mt < 2; ++mt) {  // two 32-token halves of the tile, each: S^T, softmax, O^T update
       // ---- S^T[token][row] = Kt * Qhat^T ----
       // These MFMAs accumulate in ordinary VGPRs (written as inline assembly) because all 256 accumulation
       // registers hold O^T; the compiler's own MFMA selection would put S^T there as well and spill.
       f32x16 s;
       bf16x8 f[3][4];  // ring of fragment batches: loads run two batches (8 MFMAs) ahead of their use
 #pragma unroll
-      for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b] + (32 * mt * 128));
+      for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b]);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) f[1][b] = *(const bf16x8*)(buf + kbase[b] + (PANEL + 32 * mt * 128));
+      for (int b = 0; b < 4; ++b) f[1][b] = *(const bf16x8*)(buf + kbase[b] + PANEL);
 #pragma unroll
       for (int a4 = 0; a4 < KS / 4; ++a4) {
         if (a4 + 2 < KS / 4) {
 #pragma unroll
-          for (int b = 0; b < 4; ++b) f[(a4 + 2) % 3][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 2) * PANEL + 32 * mt * 128));
+          for (int b = 0; b < 4; ++b) f[(a4 + 2) % 3][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 2) * PANEL));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -168,19 +248,19 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
           if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 % 3][b]), "v"(qf[4 * a4 + b]));
         }
-        if (stage_next && mt == 0) {  // both of the batch's staging steps ride in the first half-tile's S phase
-          stage_panels_step<kTile, NP, 4, ROWB>(next_buf, next_g, wave, stage_off, 2 * a4);
-          stage_panels_step<kTile, NP, 4, ROWB>(next_buf, next_g, wave, stage_off, 2 * a4 + 1);
-        }
         __builtin_amdgcn_sched_barrier(0);
       }
-      // first batch of value fragments: issued now, consumed after the softmax
+      // Tile it + kAhead is requested here, in one burst: at this point no LDS read of this wave is outstanding.
+      // (An LDS-DMA instruction issued while reads are in flight holds the wave, and with it the MFMA stream, until
+      // they have returned.)
+      if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      // first batches of value fragments: issued now, consumed after the softmax
       i16x4 r[3][4][2];
       auto load_v = [&](int slot, int u, int p4) {  // output tiles dt = 4*p4 .. 4*p4 + 3 of k-step u
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const int dt = 4 * p4 + d;
-          const int off = (dt >> 1) * PANEL + (32 * mt + 16 * u) * 128;
+          const int off = (dt >> 1) * PANEL + (16 * u) * 128;
           r[slot][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 64 * (dt & 1))));
           r[slot][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 8 * 128 + 64 * (1 - (dt & 1)))));
         }
@@ -190,12 +270,12 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // the matrix pipeline's result is not interlocked against vector-ALU reads: wait out its 8 passes
       asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));
 
-      // ---- online softmax (base 2); register i is token tok + 32*mt + 8*(i/4) + 4*h + i%4 ----
+      // ---- online softmax (base 2); register i is token tok + 8*(i/4) + 4*h + i%4 ----
       // The maximum is taken on the raw logits (the scale is positive) and the scale rides in the exponent's FMA.
       if (__builtin_amdgcn_ballot_w64(need_mask) != 0) {  // wave-uniform: only tiles at the chunk end, or padding rows
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          if (need_mask && tok + 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3) >= lim) s[i] = GQLA_NEG_INF;
+          if (need_mask && tok + 8 * (i >> 2) + 4 * h + (i & 3) >= lim) s[i] = GQLA_NEG_INF;
       }
       float tmax = s[0];
 #pragma unroll
@@ -206,19 +286,10 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         const float alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
         m_ref = m_new;
         l_run *= alpha;
-        if (it > 0 || mt > 0) {
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              float x = o[dt][i], tmp;
-              asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1" : "+a"(x), "=&v"(tmp) : "v"(alpha));
-              o[dt][i] = x;
-            }
-        }
+        if (it > 0) acc_scale(alpha);
       }
       const float m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
-      bf16x8 pf[2];  // k-step u: tokens 32*mt + 16*u + {4h..4h+3, 8+4h..8+4h+3}
+      bf16x8 pf[2];  // k-step u: tokens 16*u + {4h..4h+3, 8+4h..8+4h+3}
       float psum = 0.f;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -244,11 +315,12 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         for (int d = 0; d < 4; ++d) {
           const i16x4 lo = r[bt % 3][d][0], hi = r[bt % 3][d][1];
           const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          o[4 * p4 + d] = mfma32(__builtin_bit_cast(bf16x8, fr), pf[u], o[4 * p4 + d]);
+          acc_mfma(4 * p4 + d, __builtin_bit_cast(bf16x8, fr), pf[u]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    shift_pages();
   }
 
   const float l_tot = pair_sum(l_run);
@@ -257,12 +329,15 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const int64_t prow = (int64_t)chunk * a.M + rho;
   __bf16* po = (__bf16*)a.part_o + prow * RKV;
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt) {
+    float x[16];
+    acc_read(dt, dt == 0, x);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      u32x2 v = {pack_bf16(o[dt][4 * q] * inv, o[dt][4 * q + 1] * inv), pack_bf16(o[dt][4 * q + 2] * inv, o[dt][4 * q + 3] * inv)};
+      u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
       *(u32x2*)(po + dt * 32 + 8 * q + 4 * h) = v;
     }
+  }
   if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
 }
 
@@ -365,7 +440,7 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
 }  // namespace
 
 hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
-  constexpr int kLds = 2 * kTile * (512 + 64) * 2;
+  constexpr int kLds = kSlots * kTile * (512 + 64) * 2;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)decode_absorb_bf16_kernel<512, 64>,
