@@ -129,8 +129,8 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   // out-of-pool page id falls back to page 0; such rows are zeroed in LDS before use (see the loop).
   const int32_t* table_row = a.cache.page_table ? a.cache.page_table + (int64_t)ce.b * a.cache.max_pages : nullptr;
   auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
-  auto tile_src = [&](int32_t pg, int tok) -> const char* {
-    return pool + ((int64_t)(pg >= 0 ? pg : 0) * P + tok % P) * ROWB;
+  auto tile_src = [&](int32_t pg, int slot) -> const char* {  // first row of a tile: page pg (or page 0), slot `slot`
+    return pool + ((int64_t)(pg >= 0 ? pg : 0) * P + slot) * ROWB;
   };
 
   // Per-lane LDS byte offsets inside a tile (panel layout of gqla_lds.h; everything else is a compile-time offset):
@@ -169,7 +169,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     int32_t raw[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const int p = min((ce.tok_begin + k * kTile) / P, p_last);
+      const int p = min(ce.tok_begin / P + (k * kTile) / P, p_last);
       raw[k] = table_row ? table_row[p] : ce.b * a.cache.max_pages + p;
     }
     pg0 = checked(raw[0]);
@@ -178,10 +178,15 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     pg3 = n_tiles > 3 ? checked(raw[3]) : -1;
   }
   int32_t pg_raw = 0;  // table entry of tile it + 4, in flight through the scalar cache
+  // Chunks start on a page boundary and pages hold a whole number of tiles: (page index, slot) of the tiles ahead are
+  // advanced by addition, and the table is consulted once per page.
+  const int p_first = ce.tok_begin / P;
+  int st_slot = (kAhead * kTile) % P;                                       // slot of tile it + 3 in its page
+  int lk_slot = ((kAhead + 1) * kTile) % P, lk_p = p_first + ((kAhead + 1) * kTile) / P;  // tile it + 4
   static_assert(kAhead == 3, "the page-id shift register holds four tiles");
-  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg0, ce.tok_begin), wave, lane);
-  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB>(smem + TILE_BYTES, tile_src(pg1, ce.tok_begin + kTile), wave, lane);
-  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB>(smem + 2 * TILE_BYTES, tile_src(pg2, ce.tok_begin + 2 * kTile), wave, lane);
+  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg0, 0), wave, lane);
+  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB>(smem + TILE_BYTES, tile_src(pg1, kTile % P), wave, lane);
+  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB>(smem + 2 * TILE_BYTES, tile_src(pg2, (2 * kTile) % P), wave, lane);
 #pragma unroll 1
   for (int it = 0; it < n_tiles; ++it) {
     const int tok = ce.tok_begin + it * kTile;
@@ -194,11 +199,12 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     }
     __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
     const bool stage_next = it + kAhead < n_tiles;
-    const char* next_g = tile_src(stage_next ? pg3 : 0, tok + kAhead * kTile);
+    const char* next_g = tile_src(stage_next ? pg3 : 0, st_slot);
     char* next_buf = smem + ((it + kAhead) & (kSlots - 1)) * TILE_BYTES;
     const bool lookup = it + kAhead + 1 < n_tiles;
-    if (lookup && table_row)  // scalar load, consumed after the S phase (its wait is written out there)
-      asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pg_raw) : "s"(table_row + (tok + (kAhead + 1) * kTile) / P) : "memory");
+    const bool new_page = lookup && lk_slot == 0;
+    if (new_page && table_row)  // scalar load, consumed at the end of the tile (its wait is written out there)
+      asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pg_raw) : "s"(table_row + lk_p) : "memory");
     const bool tile_ok = pg0 >= 0;
     const int valid = tile_ok ? min(kTile, ce.tok_end - tok) : 0;
     if (valid < kTile) {
@@ -211,12 +217,19 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       __syncthreads();
     }
 
-    auto shift_pages = [&]() {  // the entry looked up above belongs to tile it + kAhead + 1
-      if (lookup && table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pg_raw) : : "memory");
+    auto shift_pages = [&]() {  // tile it+1 becomes current; the page of tile it + 4 joins the window
+      if (new_page && table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pg_raw) : : "memory");
       pg0 = pg1;
       pg1 = pg2;
       pg2 = pg3;
-      pg3 = lookup ? checked(table_row ? pg_raw : ce.b * a.cache.max_pages + (tok + (kAhead + 1) * kTile) / P) : -1;
+      if (new_page) pg3 = checked(table_row ? pg_raw : ce.b * a.cache.max_pages + lk_p);
+      if (!lookup) pg3 = -1;
+      st_slot = lk_slot;
+      lk_slot += kTile;
+      if (lk_slot == P) {
+        lk_slot = 0;
+        ++lk_p;
+      }
     };
     if (!wave_active) {  // waves without query rows only help staging (uniform per wave): their share, in one burst
       if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
