@@ -199,6 +199,22 @@ def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
         case.close()
 
 
+@pytest.mark.parametrize("cp", [(0, 0), (1, 1)])
+def test_bf16_length_sweep(cp):
+    """Every length from s_q to s_q + 160 in one batch: one to six tiles per chunk in the absorb kernel's tile ring
+    (fewer tiles than ring slots included), every tail length, lengths on and next to page boundaries; with one-page
+    chunks every chunk has at most two tiles and most sequences are split."""
+    s_q = 2
+    lens = list(range(s_q, s_q + 161))
+    cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=32, g=8, s_q=s_q, L=0, paged=True, seed=777)
+    case = Case(cfg, lens=lens, chunk_pages=cp)
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
 def test_bf16_single_group_slice():
     """One rank's share of 8-way head-axis tensor parallelism: 16 heads, one group, 320 elements per token."""
     cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=909)
