@@ -302,20 +302,23 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         if (it > 0) acc_scale(alpha);
       }
       const float m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
-      bf16x8 pf[2];  // k-step u: tokens 16*u + {4h..4h+3, 8+4h..8+4h+3}
-      float psum = 0.f;
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        float p[8];
+      // P^T fragments, k-step u: tokens 16*u + {4h..4h+3, 8+4h..8+4h+3}.  Only the first is finished before the
+      // O^T update starts; the exponentials of the second ride in the shadow of the first k-step's MFMAs (one
+      // exponential, its FMA and its add fit behind one MFMA of the same wave).
+      bf16x8 pf[2];
+      float p1[8];
+      u32x4 w1;
+      {
+        float p[8], psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          p[e] = fast_exp2(__builtin_fmaf(s[8 * u + e], a.scale_log2e, -m_use));
+          p[e] = fast_exp2(__builtin_fmaf(s[e], a.scale_log2e, -m_use));
           psum += p[e];
         }
         u32x4 w = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-        pf[u] = __builtin_bit_cast(bf16x8, w);
+        pf[0] = __builtin_bit_cast(bf16x8, w);
+        l_run += psum;
       }
-      l_run += psum;
       __builtin_amdgcn_sched_barrier(0);
 
       // ---- O^T[r][row] += C^T * P^T, value fragments one batch of four tiles ahead ----
@@ -323,12 +326,23 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       for (int bt = 0; bt < 2 * (DT / 4); ++bt) {
         const int u = bt / (DT / 4), p4 = bt % (DT / 4);
         if (bt + 2 < 2 * (DT / 4)) load_v((bt + 2) % 3, (bt + 2) / (DT / 4), (bt + 2) % (DT / 4));
+        if (bt == DT / 4) pf[1] = __builtin_bit_cast(bf16x8, w1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const i16x4 lo = r[bt % 3][d][0], hi = r[bt % 3][d][1];
           const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           acc_mfma(4 * p4 + d, __builtin_bit_cast(bf16x8, fr), pf[u]);
+          if (u == 0) {  // second k-step's probabilities, one piece per MFMA
+            const int idx = 4 * bt + d;
+            if (idx < 8) {
+              p1[idx] = fast_exp2(__builtin_fmaf(s[8 + idx], a.scale_log2e, -m_use));
+              l_run += p1[idx];
+            } else if (idx < 12) {
+              w1[idx - 8] = pack_bf16(p1[2 * (idx - 8)], p1[2 * (idx - 8) + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
