@@ -35,6 +35,7 @@ def parse_args():
     ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
     ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences per leg in the oracle's bounded sample (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the ceiling probes and the single-group slice timing")
     return ap.parse_args()
 
 
@@ -127,6 +128,52 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)])) for i, n in enumerate(names)}
 
+    # ---- outside the timed step: measured ceilings of this chip, and one rank's share of 8-way head-axis TP ----------
+    measured = None
+    tp_slice = None
+    full_run = run_legs >= {"absorb", "gqa"} and "noexpand" not in run_legs
+    if full_run and not args.no_extras:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e-3
+        num_cus = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        pool = Gq["dec"].expanded_pool
+        unit = 16 * 1024 * 8 * num_cus
+        nbytes = pool.numel() * pool.element_size() // unit * unit
+        t_rd = timed(lambda: B.gqla_probe_stream_read(pool, nbytes, sink, num_cus), 5)
+        iters = 100000
+        t_mf = timed(lambda: B.gqla_probe_mfma_bf16(sink, iters, num_cus), 3)
+        measured = {"hbm_stream_read_GBs": nbytes / t_rd / 1e9, "mfma_bf16_TFLOPs": B.gqla_probe_mfma_flops(iters, num_cus) / t_mf / 1e12,
+                    "how": "gqla_probe_stream_read over %.2f GB (16-byte loads, %d workgroups); gqla_probe_mfma_bf16: register-resident "
+                           "32x32x16 bf16 MFMAs with random operand bits, %.0f ms sustained" % (nbytes / 1e9, 8 * num_cus, t_mf * 1e3)}
+        # single-group slice of the GQA leg (configs[3]): 16 heads, one group, 320 cached elements per token
+        G = cg.h_q // cg.g
+        j0 = 3
+        sl = Decoder(cg, Gq["lens"], Gq["table"], Gq["dec"].num_pages, groups=1, group_begin=j0, use_page_table=False)
+        sl.latent_pool = Gq["dec"].latent_pool
+        sl.alloc_expanded(fill=0.0)
+        q_c_s = to_device(np.ascontiguousarray(Gq["q_c"][:, :, j0 * G:(j0 + 1) * G]), cg.dtype)
+        q_r_s = to_device(np.ascontiguousarray(Gq["q_r"][:, :, j0 * G:(j0 + 1) * G]), cg.dtype)
+        out_s = torch.empty((cg.B, cg.s_q, G, cg.d_h), dtype=torch.bfloat16, device="cuda")
+        lse_s = torch.empty((cg.B, cg.s_q, G), dtype=torch.float32, device="cuda")
+        t_ex = timed(lambda: sl.expand(Gq["d_w_uk"], Gq["d_w_uv"]), 5)
+        t_dec = timed(lambda: sl.decode_gqa(q_c_s, q_r_s, out_s, lse_s), 10)
+        Lsum = int(Gq["lens"].sum())
+        sl_bytes = 2 * Lsum * (2 * cg.d_h + cg.d_r)
+        tp_slice = {"groups": 1, "heads": G, "cache_elems_per_token": 2 * cg.d_h + cg.d_r, "decode_gqa_ms": t_dec * 1e3,
+                    "GB/s": sl_bytes / t_dec / 1e9, "frac_hbm_peak": sl_bytes / t_dec / 1e9 / HBM_PEAK_GBS,
+                    "tokens_per_s": cg.B * cg.s_q / t_dec, "expand_cache_ms": t_ex * 1e3}
+        sl.latent_pool = None
+        sl.close()
+
     # ---- accounting: the paper's closed forms (Sec. 4.2.1 / 4.2.2) ----------------------------------------------
     La, Lg = int(A["lens"].sum()), int(Gq["lens"].sum())
     bytes_absorb = 2 * La * (ca.r_kv + ca.d_r)
@@ -155,6 +202,8 @@ def main():
             r.update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                       "frac": tf / MFMA_BF16_PEAK_TFLOPS})
         r["traffic"] = traffic.get(name)
+        if measured:
+            r["frac_of_measured"] = {"hbm_stream_read": gbs / measured["hbm_stream_read_GBs"], "mfma_bf16": tf / measured["mfma_bf16_TFLOPs"]}
         return r
 
     roofs = []
@@ -213,6 +262,8 @@ def main():
                    "page_size": ca.page_size, "cache": "contiguous"},
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["call"]},
         "rooflines": roofs,
+        "measured_peaks": measured,
+        "tp_slice": tp_slice,
         "calls_ms": call_ms,
         "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / (max(call_ms["absorb_query"] + call_ms["decode_absorb"], 1e-6) * 1e-3),
                   "gqa_decode_tokens_per_s": cg.B * cg.s_q / (max(call_ms["decode_gqa"], 1e-6) * 1e-3)},

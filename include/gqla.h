@@ -174,6 +174,18 @@ int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page
 int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
+
+/* Ceiling probes (measurement only; they compute nothing of the method).  The caller times them with events on
+ * `stream` and derives  bytes / t  resp.  gqla_probe_mfma_flops(iters, num_cus) / t.
+ *   gqla_probe_stream_read: every byte of src[0, bytes) is read once with 16-byte loads by 8 * num_cus workgroups;
+ *     bytes must be a multiple of 16 * 1024 * 8 * num_cus (GQLA_ERR_SHAPE otherwise).  `sink` is 4 bytes of device
+ *     memory that is (practically) never written.
+ *   gqla_probe_mfma_bf16: num_cus workgroups of 4 waves issue 4 * iters independent-accumulator
+ *     v_mfma_f32_32x32x16_bf16 each, operands resident in registers with random sign and mantissa bits. */
+gqla_status gqla_probe_stream_read(const void* src, size_t bytes, void* sink, int32_t num_cus, void* stream);
+gqla_status gqla_probe_mfma_bf16(void* sink, int32_t iters, int32_t num_cus, void* stream);
+double gqla_probe_mfma_flops(int32_t iters, int32_t num_cus);
+
 const char* gqla_status_string(int32_t status);
 
 #ifdef __cplusplus

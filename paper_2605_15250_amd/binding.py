@@ -21,7 +21,7 @@ GQLA_PATH_ABSORB, GQLA_PATH_GQA = 0, 1
 EXPORTS = [
     "gqla_plan_create", "gqla_plan_destroy", "gqla_plan_num_chunks", "gqla_plan_chunk_pages", "gqla_plan_export",
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
-    "gqla_expand_workspace_bytes",
+    "gqla_expand_workspace_bytes", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -75,6 +75,12 @@ def lib():
         L.gqla_decode_absorb.restype = i32
         L.gqla_expand_cache.argtypes = [sp, cp, vp, vp, i32, i32, cp, vp, C.c_size_t, vp]
         L.gqla_expand_cache.restype = i32
+        L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
+        L.gqla_probe_stream_read.restype = i32
+        L.gqla_probe_mfma_bf16.argtypes = [vp, i32, i32, vp]
+        L.gqla_probe_mfma_bf16.restype = i32
+        L.gqla_probe_mfma_flops.argtypes = [i32, i32]
+        L.gqla_probe_mfma_flops.restype = C.c_double
         L.gqla_expand_workspace_bytes.argtypes = [sp, i32]
         L.gqla_expand_workspace_bytes.restype = C.c_size_t
         L.gqla_decode_gqa.argtypes = [sp, vp, vp, vp, cp, vp, vp, vp, sz, vp]
@@ -181,6 +187,18 @@ def gqla_decode_absorb(shape, plan, q_hat, q_r, latent: gqla_cache, w_uv, out, l
     nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
     _check(lib().gqla_decode_absorb(C.byref(shape), plan, _ptr(q_hat), _ptr(q_r), C.byref(latent), _ptr(w_uv), _ptr(out),
                                     _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_absorb")
+
+
+def gqla_probe_stream_read(src, nbytes, sink, num_cus, stream=None):
+    _check(lib().gqla_probe_stream_read(_ptr(src), nbytes, _ptr(sink), num_cus, _stream(stream)), "gqla_probe_stream_read")
+
+
+def gqla_probe_mfma_bf16(sink, iters, num_cus, stream=None):
+    _check(lib().gqla_probe_mfma_bf16(_ptr(sink), iters, num_cus, _stream(stream)), "gqla_probe_mfma_bf16")
+
+
+def gqla_probe_mfma_flops(iters, num_cus) -> float:
+    return lib().gqla_probe_mfma_flops(iters, num_cus)
 
 
 def gqla_expand_workspace_bytes(shape, group_count) -> int:

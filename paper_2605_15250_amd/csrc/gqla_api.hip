@@ -381,6 +381,25 @@ int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t P
   return page * P * (2ll * groups * d_h + d_r) + 2ll * groups * P * d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8;
 }
 
+gqla_status gqla_probe_stream_read(const void* src, size_t bytes, void* sink, int32_t num_cus, void* stream) {
+  if (!src || !sink) return GQLA_ERR_NULL;
+  if (!aligned16(src)) return GQLA_ERR_ALIGN;
+  if (num_cus <= 0 || bytes == 0 || bytes % ((size_t)16 * 1024 * 8 * num_cus)) return GQLA_ERR_SHAPE;
+  const hipError_t e = launch_probe_stream_read(src, bytes, static_cast<uint32_t*>(sink), 8 * num_cus, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_probe_mfma_bf16(void* sink, int32_t iters, int32_t num_cus, void* stream) {
+  if (!sink) return GQLA_ERR_NULL;
+  if (num_cus <= 0 || iters <= 0) return GQLA_ERR_SHAPE;
+  const hipError_t e = launch_probe_mfma(static_cast<uint32_t*>(sink), iters, num_cus, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+double gqla_probe_mfma_flops(int32_t iters, int32_t num_cus) {
+  return (double)num_cus * 4.0 /* waves */ * 4.0 /* MFMAs per iteration */ * (double)iters * 32768.0;  // 2 * 32 * 32 * 16 each
+}
+
 const char* gqla_status_string(int32_t status) {
   switch (status) {
     case GQLA_OK: return "ok";

@@ -9,6 +9,7 @@
 // non-temporal hint.  All heads of a group (G * s_q rows) share each
 // loaded vector through the MFMA.  The path is bound by HBM bandwidth (intensity 19-39 FLOP/byte, Sec. 4.2.2).
 #include "gqla_device.h"
+#include "gqla_lds.h"
 
 namespace gqla {
 
@@ -20,7 +21,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
   constexpr int MT = DH / 32;    // 32-dim tiles of the output
   const int lane = threadIdx.x & 63;
-  const int item = blockIdx.x * 8 + (threadIdx.x >> 6);
+  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * 8 + (threadIdx.x >> 6));  // wave-uniform: keep it scalar
   if (item >= n_items) return;
   const int j = item % a.g;
   const int rb = (item / a.g) % row_blocks;
@@ -56,8 +57,22 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
   bool k_ok = true, v_ok = true;
 
-  auto load_k = [&](int tok) {
-    const int32_t pg = page_of(a.cache, ce.b, tok / P);
+  // The shared RoPE key of a tile is the same for every group.  When the 8 waves of a workgroup are the 8 (or a
+  // multiple of 8) groups of one (chunk, row block), the tile's k_R (4 KB) is brought into LDS once per workgroup --
+  // one 1 KB LDS-DMA instruction by each of waves 0..3 -- and every wave takes its fragments from there, instead of
+  // every wave pulling the same lines through the vector memory path (a fifth of all its load instructions).
+  __shared__ __attribute__((aligned(16))) char kr_lds[2][KS_R * 1024];
+  const bool share_kr = (a.g % 8) == 0;  // kernel-uniform
+  const int wave = item & 7;             // position in the workgroup (scalar)
+  auto stage_kr = [&](int tok, int32_t pg, int buf) {
+    if (wave < KS_R) {
+      const __bf16* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_elems + (int64_t)2 * gc * DH * P + ((int64_t)(2 * wave) * P + tok % P) * 8;
+      const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(kr_lds[buf] + wave * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"((h * P + n) * 16), "s"(src));
+    }
+  };
+
+  auto load_k = [&](int tok, int32_t pg) {
     k_ok = pg >= 0;
     const __bf16* base = pool + (int64_t)(k_ok ? pg : 0) * page_elems;
     const int slot = tok % P + n;
@@ -65,11 +80,12 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     const __bf16* rbp = base + (int64_t)2 * gc * DH * P + ((int64_t)h * P + slot) * 8;
 #pragma unroll
     for (int ks = 0; ks < KS_C; ++ks) kf[ks] = __builtin_nontemporal_load((const bf16x8*)(kb + (int64_t)ks * 16 * P));
+    if (!share_kr) {
 #pragma unroll
-    for (int ks = 0; ks < KS_R; ++ks) rf[ks] = __builtin_nontemporal_load((const bf16x8*)(rbp + (int64_t)ks * 16 * P));
+      for (int ks = 0; ks < KS_R; ++ks) rf[ks] = __builtin_nontemporal_load((const bf16x8*)(rbp + (int64_t)ks * 16 * P));
+    }
   };
-  auto load_v = [&](int tok) {
-    const int32_t pg = page_of(a.cache, ce.b, tok / P);
+  auto load_v = [&](int tok, int32_t pg) {
     v_ok = pg >= 0;
     const __bf16* base = pool + (int64_t)(v_ok ? pg : 0) * page_elems + (int64_t)gc * DH * P + (int64_t)j * DH * P;
     const int tb = (tok % P) / 8 + h;  // 8-token block of this lane for k-step 0; k-step 1 is two blocks further
@@ -87,19 +103,50 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
   float m_run = GQLA_NEG_INF, l_run = 0.f;
 
-  load_k(ce.tok_begin);
-  load_v(ce.tok_begin);
+  // Page ids travel through the scalar cache, looked up one tile ahead of the loads that need them: a vector load of
+  // the table entry would have to be waited for with vmcnt(0), i.e. behind every cache load still in flight.
+  const int32_t* table_row = a.cache.page_table ? a.cache.page_table + (int64_t)ce.b * a.cache.max_pages : nullptr;
+  auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
+  auto lookup_start = [&](int tok, int32_t& raw) {  // asynchronous; lookup_done() must precede any use of raw
+    if (table_row) asm volatile("s_load_dword %0, %1, 0x0" : "=s"(raw) : "s"(table_row + tok / P));
+    else raw = ce.b * a.cache.max_pages + tok / P;
+  };
+  auto lookup_done = [&](int32_t& raw) {
+    if (table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(raw));
+  };
+  int32_t pg_raw = 0;
+  lookup_start(ce.tok_begin, pg_raw);
+  lookup_done(pg_raw);
+  int32_t pg_next = checked(pg_raw);
+  if (share_kr) stage_kr(ce.tok_begin, pg_next, 0);
+  load_k(ce.tok_begin, pg_next);
+  load_v(ce.tok_begin, pg_next);
+  if (ce.tok_begin + 32 < ce.tok_end) lookup_start(ce.tok_begin + 32, pg_raw);
   for (int tok = ce.tok_begin; tok < ce.tok_end; tok += 32) {
     f32x16 s;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS_C; ++ks) s = mfma32(kf[ks], qc[ks], s);
+    if (share_kr) {
+      // this tile's k_R was requested before the 16 cache loads that followed it (loads complete in issue order)
+      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      __syncthreads();
+      const char* kr = kr_lds[((tok - ce.tok_begin) >> 5) & 1] + lane * 16;
+#pragma unroll
+      for (int ks = 0; ks < KS_R; ++ks) rf[ks] = *(const bf16x8*)(kr + ks * 1024);
+    }
 #pragma unroll
     for (int ks = 0; ks < KS_R; ++ks) s = mfma32(rf[ks], qr[ks], s);
     const bool tile_k_ok = k_ok;
     const bool has_next = tok + 32 < ce.tok_end;
-    if (has_next) load_k(tok + 32);
+    if (has_next) {
+      lookup_done(pg_raw);
+      pg_next = checked(pg_raw);
+      if (share_kr) stage_kr(tok + 32, pg_next, (((tok - ce.tok_begin) >> 5) + 1) & 1);
+      load_k(tok + 32, pg_next);
+      if (tok + 64 < ce.tok_end) lookup_start(tok + 64, pg_raw);
+    }
 
     // online softmax, base-2 domain; register i of lane (n, h) is token tok + 8*(i/4) + 4*h + i%4
     float sv[16];
@@ -166,7 +213,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) o[mt] = mfma32(vf[mt][kk], pf[kk], o[mt]);
-    if (has_next) load_v(tok + 32);
+    if (has_next) load_v(tok + 32, pg_next);
   }
 
   const float l_tot = pair_sum(l_run);

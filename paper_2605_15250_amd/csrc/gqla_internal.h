@@ -83,6 +83,9 @@ hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);        
 hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*group_count*r_kv*d_h bf16 */, hipStream_t);
 
+hipError_t launch_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t);
+hipError_t launch_probe_mfma(uint32_t* sink, int iters, int blocks, hipStream_t);
+
 }  // namespace gqla
 
 // The opaque plan of the public header.
