@@ -191,13 +191,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   for (int it = 0; it < n_tiles; ++it) {
     const int tok = ce.tok_begin + it * kTile;
     const char* buf = smem + (it & (kSlots - 1)) * TILE_BYTES;
-    {
-      const int behind = min(kAhead - 1, n_tiles - 1 - it);  // tiles staged after this one
-      if (behind >= 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
-      else if (behind == 1) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
+    // everything that does not need the tile goes before the wait for it
     const bool stage_next = it + kAhead < n_tiles;
     const char* next_g = tile_src(stage_next ? pg3 : 0, st_slot);
     char* next_buf = smem + ((it + kAhead) & (kSlots - 1)) * TILE_BYTES;
@@ -205,6 +199,13 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     const bool new_page = lookup && lk_slot == 0;
     if (new_page && table_row)  // scalar load, consumed at the end of the tile (its wait is written out there)
       asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pg_raw) : "s"(table_row + lk_p) : "memory");
+    {
+      const int behind = min(kAhead - 1, n_tiles - 1 - it);  // tiles staged after this one
+      if (behind >= 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+      else if (behind == 1) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();  // tile `it` has landed for every wave; every wave is done reading tile it-1
     const bool tile_ok = pg0 >= 0;
     const int valid = tile_ok ? min(kTile, ce.tok_end - tok) : 0;
     if (valid < kTile) {
