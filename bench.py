@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
     ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences per leg in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip the ceiling probes and the single-group slice timing")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time both decode paths and the expansion on the other bf16 workload shapes (C1, C3, C4); "
+                         "adds about a minute; their parity is covered by tests/, here they are timed on device-generated N(0,1) latents")
     return ap.parse_args()
 
 
@@ -174,6 +177,47 @@ def main():
         sl.latent_pool = None
         sl.close()
 
+    other = None
+    if args.all_configs:
+        def timed2(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e-3
+        other = []
+        for key in ("C1", "C3", "C4"):
+            c = S.CONFIGS[key]
+            lens_k = S.seq_lens(c)
+            table_k, np_k = S.page_table(c, lens_k)
+            dk = Decoder(c, lens_k, table_k, np_k, use_page_table=c.paged)
+            dk.latent_pool = torch.empty(np_k * c.page_size * (c.r_kv + c.d_r), dtype=torch.bfloat16, device="cuda").normal_()
+            wk, wv = S.weights(c)
+            qc_k, qr_k = S.queries(c)
+            d_wk, d_wv, d_qc, d_qr = (to_device(x, c.dtype) for x in (wk, wv, qc_k, qr_k))
+            o_k = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch.bfloat16, device="cuda")
+            l_k = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
+            qh_k = dk.absorb_query(d_qc, d_wk)
+            t_a = timed2(lambda: dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k), 5)
+            dk.alloc_expanded(fill=0.0)
+            t_e = timed2(lambda: dk.expand(d_wk, d_wv), 2)
+            t_g = timed2(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 5)
+            Ls = int(lens_k.sum())
+            b_a, f_a = 2 * Ls * (c.r_kv + c.d_r), 2 * Ls * c.h_q * c.s_q * (2 * c.r_kv + c.d_r)
+            b_g, f_e = 2 * Ls * (2 * c.g * c.d_h + c.d_r), 2 * Ls * c.r_kv * 2 * c.g * c.d_h
+            other.append({"config": key, "batch": c.B, "h_q": c.h_q, "s_q": c.s_q, "cached_tokens": Ls, "paged": bool(c.paged),
+                          "decode_absorb": {"ms": t_a * 1e3, "GB/s": b_a / t_a / 1e9, "TFLOP/s": f_a / t_a / 1e12,
+                                            "frac_hbm_peak": b_a / t_a / 1e9 / HBM_PEAK_GBS, "frac_mfma_peak": f_a / t_a / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+                          "decode_gqa": {"ms": t_g * 1e3, "GB/s": b_g / t_g / 1e9, "frac_hbm_peak": b_g / t_g / 1e9 / HBM_PEAK_GBS},
+                          "expand_cache": {"ms": t_e * 1e3, "TFLOP/s": f_e / t_e / 1e12, "frac_mfma_peak": f_e / t_e / 1e12 / MFMA_BF16_PEAK_TFLOPS}})
+            dk.close()
+            del dk, o_k, l_k, qh_k
+            torch.cuda.empty_cache()
+
     # ---- accounting: the paper's closed forms (Sec. 4.2.1 / 4.2.2) ----------------------------------------------
     La, Lg = int(A["lens"].sum()), int(Gq["lens"].sum())
     bytes_absorb = 2 * La * (ca.r_kv + ca.d_r)
@@ -264,6 +308,7 @@ def main():
         "rooflines": roofs,
         "measured_peaks": measured,
         "tp_slice": tp_slice,
+        "other_configs": other,
         "calls_ms": call_ms,
         "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / (max(call_ms["absorb_query"] + call_ms["decode_absorb"], 1e-6) * 1e-3),
                   "gqa_decode_tokens_per_s": cg.B * cg.s_q / (max(call_ms["decode_gqa"], 1e-6) * 1e-3)},
