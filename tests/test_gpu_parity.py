@@ -215,6 +215,20 @@ def test_bf16_length_sweep(cp):
         case.close()
 
 
+@pytest.mark.parametrize("page_size,lens", [
+    (1024, [1500, 70, 1024]),     # the largest page the MFMA kernels take; a sequence that ends exactly on a page boundary
+    (192, [500, 193, 64]),        # a page size that is a multiple of 64 but not a power of two
+])
+def test_bf16_page_sizes(page_size, lens):
+    cfg = S.CONFIGS["C3"].with_(B=len(lens), L=0, paged=True, page_size=page_size, seed=5150 + page_size)
+    case = Case(cfg, lens=lens)
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
 def test_bf16_single_group_slice():
     """One rank's share of 8-way head-axis tensor parallelism: 16 heads, one group, 320 elements per token."""
     cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=909)
