@@ -43,10 +43,41 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
+# Kernels listed here keep data in accumulation registers that they address by name in inline assembly; the
+# compiler knows those registers only as clobbered, so it must never park values of its own there.  It does so
+# (v_accvgpr_write / _read / _mov outside the assembly blocks) only when it runs out of ordinary registers: the build
+# checks the generated assembly and refuses such a kernel instead of shipping silent corruption.
+NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"]}
+
+
+def _check_named_agprs(src: str, kernels, extra) -> None:
+    asm_path = os.path.join(BUILD, os.path.splitext(src)[0] + ".s")
+    cmd = [_hipcc(), *FLAGS, *extra, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm_path]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stderr))
+    current, in_asm = None, False
+    with open(asm_path) as fh:
+        for line in fh:
+            t = line.strip()
+            if t.endswith(":") and not t.startswith(".") and not t.startswith(";"):
+                current = next((k for k in kernels if k in t), None)
+            elif ";;#ASMSTART" in t:
+                in_asm = True
+            elif ";;#ASMEND" in t:
+                in_asm = False
+            elif current and not in_asm and t.startswith("v_accvgpr_"):
+                raise RuntimeError("%s: the compiler uses accumulation registers of its own in %s (%s); "
+                                   "lower the kernel's VGPR pressure" % (src, current, t))
+
+
 def build(extra_flags=(), jobs: int = 5) -> str:
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
+        checks = [ex.submit(_check_named_agprs, src, ks, list(extra_flags)) for src, ks in NAMED_AGPR_SOURCES.items()]
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+        for c in checks:
+            c.result()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

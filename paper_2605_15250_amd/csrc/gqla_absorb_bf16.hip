@@ -28,12 +28,6 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 // allocate, copy or spill there, and the rest of the kernel gets the 256 ordinary registers to itself.  Every statement
 // below is `asm volatile`, so they keep their program order; the callers keep the hardware's timing rules
 // (results of an MFMA are read by non-MFMA instructions only after its last pass has long retired).
-#define GQLA_A10(p) "a" #p "0", "a" #p "1", "a" #p "2", "a" #p "3", "a" #p "4", "a" #p "5", "a" #p "6", "a" #p "7", "a" #p "8", "a" #p "9"
-#define GQLA_ALL_AGPRS                                                                                                   \
-  "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", GQLA_A10(1), GQLA_A10(2), GQLA_A10(3), GQLA_A10(4),       \
-      GQLA_A10(5), GQLA_A10(6), GQLA_A10(7), GQLA_A10(8), GQLA_A10(9), GQLA_A10(10), GQLA_A10(11), GQLA_A10(12),        \
-      GQLA_A10(13), GQLA_A10(14), GQLA_A10(15), GQLA_A10(16), GQLA_A10(17), GQLA_A10(18), GQLA_A10(19), GQLA_A10(20),  \
-      GQLA_A10(21), GQLA_A10(22), GQLA_A10(23), GQLA_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
 #define GQLA_ACC(D) "a[" #D "*16:" #D "*16+15]"
 #define GQLA_FOR_DT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
 

@@ -10,6 +10,15 @@
 
 #include "gqla_internal.h"
 
+// Names of all 256 accumulation registers, for the clobber list of kernels that address them by name in inline
+// assembly (the compiler then counts them as used and keeps its own values out of them).
+#define GQLA_A10(p) "a" #p "0", "a" #p "1", "a" #p "2", "a" #p "3", "a" #p "4", "a" #p "5", "a" #p "6", "a" #p "7", "a" #p "8", "a" #p "9"
+#define GQLA_ALL_AGPRS                                                                                                   \
+  "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", GQLA_A10(1), GQLA_A10(2), GQLA_A10(3), GQLA_A10(4),       \
+      GQLA_A10(5), GQLA_A10(6), GQLA_A10(7), GQLA_A10(8), GQLA_A10(9), GQLA_A10(10), GQLA_A10(11), GQLA_A10(12),        \
+      GQLA_A10(13), GQLA_A10(14), GQLA_A10(15), GQLA_A10(16), GQLA_A10(17), GQLA_A10(18), GQLA_A10(19), GQLA_A10(20),  \
+      GQLA_A10(21), GQLA_A10(22), GQLA_A10(23), GQLA_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
+
 namespace gqla {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
