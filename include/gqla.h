@@ -27,7 +27,8 @@
  *     cached length L_b INCLUDES the s_q step tokens as its last rows; query t (0-based) sits at
  *     position L_b - s_q + t and attends to cached rows s <= L_b - s_q + t (causal inside the step).
  *   - dtype GQLA_BF16: caches, queries, weights, q_hat and out are bf16; all accumulation, softmax
- *     and the split partials are fp32; QK^T and PV run on bf16 MFMA.  Shape limits of the MFMA
+ *     and the log-sum-exps are fp32 (split partials: fp32 on the GQA path, bf16 in latent space on the absorb
+ *     path); QK^T and PV run on bf16 MFMA.  Shape limits of the MFMA
  *     kernels: d_h = 128, d_r = 64, r_kv = 512, page_size a multiple of 64 (<= 1024).
  *     dtype GQLA_F32: everything fp32 on the vector ALU; d_h, d_r, r_kv, page_size multiples of 8.
  *
@@ -119,8 +120,9 @@ int32_t gqla_plan_chunk_pages(const gqla_plan* plan);
 /* Copies up to *n chunk triples (b, tok_begin, tok_end) in slot order to triples (host int32[3 * *n]) and the
  * per-sequence first slots to first_slot (host int32[batch], may be NULL); sets *n to the chunk count. */
 gqla_status gqla_plan_export(const gqla_plan* plan, int32_t* triples, int32_t* first_slot, int32_t* n);
-/* Bytes of device workspace a decode call with this plan needs: the chunk table, then fp32 partial outputs
- * [chunks][s_q*h_q][d_h] and partial log-sum-exps [chunks][s_q*h_q]. */
+/* Bytes of device workspace a decode call with this plan needs: the chunk table, then the partial outputs
+ * (GQA path: fp32 [chunks][s_q*h_q][d_h]; absorb path: [chunks][s_q*h_q][r_kv], bf16 for GQLA_BF16, fp32 for
+ * GQLA_F32) and the fp32 partial log-sum-exps [chunks][s_q*h_q]. */
 size_t gqla_plan_workspace_bytes(const gqla_plan* plan);
 /* Enqueues the copy of the plan's chunk table into the head of ws (device, 16-byte aligned, at least
  * gqla_plan_workspace_bytes).  Must precede, in stream order, every decode call that uses (plan, ws).  The plan

@@ -1,15 +1,17 @@
 // MQA-absorb split-L decode over the latent cache, bf16 MFMA (paper Sec. 3.1, MQA-absorb equation, lines 2-5).
 //
 // One workgroup of 4 waves per (chunk, block of 128 query rows); wave w owns rows 32w..32w+31 of the block.
-// A 64-token latent tile [64][r_kv + d_r] is staged once into LDS (double buffered, global_load_lds) and serves
-// every row of the block twice: row-wise as the key operand [c | k_R] and transposed (ds_read_b64_tr_b16) as
-// the value operand c:
+// A 32-token latent tile [32][r_kv + d_r] is staged once into LDS (global_load_lds into a ring of four tile
+// buffers, three tiles ahead of its use) and serves every row of the block twice: row-wise as the key operand
+// [c | k_R] and transposed (ds_read_b64_tr_b16) as the value operand c:
 //   S^T[token][row]  = Kt[token][576] * Qhat^T[576][row]      A = LDS row fragments,   B = queries in registers
 //   O^T[r][row]     += C^T[r][token]  * P^T[token][row]       A = LDS transposed frags, B = probabilities
-// O^T (512 x 32 fp32 per wave) lives in 256 accumulator registers; the softmax reference maximum is only moved
-// (and O^T rescaled) when a row's maximum grows by more than 2^8, so that rescaling is rare.
+// O^T (512 x 32 fp32 per wave) lives in the 256 accumulation registers, addressed by name (see acc_* below); the
+// softmax reference maximum is only moved (and O^T rescaled) when a row's maximum grows by more than 2^8, so that
+// rescaling is rare.
 // Each chunk's normalised latent-space output is written as bf16 with its log-sum-exp; the combine kernel merges
-// chunks and applies W_UV.  Intensity h_q s_q (2 r_kv + d_r) / (r_kv + d_r) (Sec. 4.2.1): MFMA-bound for 256 rows.
+// chunks and applies W_UV.  Intensity h_q s_q (2 r_kv + d_r) / (r_kv + d_r) (Sec. 4.2.1): 242 FLOP/byte for 128 rows,
+// 484 for 256 (s_q = 2), against a ridge of about 310 on this chip.
 #include "gqla_device.h"
 #include "gqla_lds.h"
 
