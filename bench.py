@@ -296,6 +296,19 @@ def main():
         parity = {"absorb_vs_oracle": errs(out_a[:nb], ref_a), "gqa_vs_oracle": errs(out_g[:nb], ref_g),
                   "tolerance": {"max_abs": 2e-2, "rel_l2": 1e-2}}
 
+    # ---- the paper's path-selection model (Sec. 4.2.3) evaluated with this chip's measured ceilings --------------------
+    path_model = None
+    if measured:
+        path_model = {"rates": "measured_peaks (this run)"}
+        for leg, c, Ltot in (("absorb_leg_s_q1", ca, La), ("gqa_leg_s_q2", cg, Lg)):
+            est = B.gqla_estimate_paths(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ltot,
+                                        measured["hbm_stream_read_GBs"] * 1e9, measured["mfma_bf16_TFLOPs"] * 1e12)
+            path_model[leg] = {"model_absorb_us": est["absorb_seconds"] * 1e6, "model_gqa_us": est["gqa_seconds"] * 1e6,
+                               "model_faster_path": "gqa" if est["faster_path"] == B.GQLA_PATH_GQA else "absorb",
+                               "ridge": est["ridge"], "absorb_intensity": est["absorb_intensity"], "gqa_intensity": est["gqa_intensity"]}
+        path_model["absorb_leg_s_q1"]["measured_absorb_us"] = call_ms["decode_absorb"] * 1e3
+        path_model["gqa_leg_s_q2"]["measured_gqa_us"] = call_ms["decode_gqa"] * 1e3
+
     wl = "canonical (h_q=128,g=8,d_h=128,r_kv=512,d_R=64) B=%d L=%d: configs[2] absorb s_q=1 + configs[3] expand+GQA s_q=2" % (ca.B, ca.L)
     line = {
         "metric": "decode attn tokens/s + % roofline (MFMA absorb, HBM GB/s GQA) on 1 MI355X",
@@ -307,6 +320,7 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["call"]},
         "rooflines": roofs,
         "measured_peaks": measured,
+        "path_model": path_model,
         "tp_slice": tp_slice,
         "other_configs": other,
         "calls_ms": call_ms,

@@ -177,6 +177,22 @@ int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d,
 int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 
+/* Path selection (Sec. 4: "the runtime selects the path that matches the target hardware").  The paper's Roofline
+ * model of one decode step over `cached_tokens` tokens (summed over the batch): the absorb path moves
+ * 2(r_kv + d_r) bytes and performs 2 h_q s_q (2 r_kv + d_r) FLOPs per cached token (Sec. 4.2.1), the GQA path
+ * 2(2 g d_h + d_r) bytes and 2 h_q s_q (2 d_h + d_r) FLOPs (Sec. 4.2.2); the predicted time of a path is
+ * max(bytes / hbm_bytes_per_s, flops / mfma_flops_per_s) (Sec. 4.2.3).  Element size: 2 bytes for GQLA_BF16, 4 for
+ * GQLA_F32.  Pure host arithmetic; the two rates are whatever the caller trusts (published peaks, or the rates the
+ * probes below measure).  faster_path is the gqla_path with the smaller predicted time (absorb on a tie). */
+typedef struct {
+  double absorb_bytes, absorb_flops, absorb_intensity, absorb_seconds;
+  double gqa_bytes, gqa_flops, gqa_intensity, gqa_seconds;
+  double ridge;          /* mfma_flops_per_s / hbm_bytes_per_s (Sec. 4.1) */
+  int32_t faster_path;   /* gqla_path */
+} gqla_path_estimate;
+gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, double hbm_bytes_per_s,
+                                double mfma_flops_per_s, gqla_path_estimate* out);
+
 /* Ceiling probes (measurement only; they compute nothing of the method).  The caller times them with events on
  * `stream` and derives  bytes / t  resp.  gqla_probe_mfma_flops(iters, num_cus) / t.
  *   gqla_probe_stream_read: every byte of src[0, bytes) is read once with 16-byte loads by 8 * num_cus workgroups;

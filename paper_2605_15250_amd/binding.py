@@ -21,7 +21,7 @@ GQLA_PATH_ABSORB, GQLA_PATH_GQA = 0, 1
 EXPORTS = [
     "gqla_plan_create", "gqla_plan_destroy", "gqla_plan_num_chunks", "gqla_plan_chunk_pages", "gqla_plan_export",
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
-    "gqla_expand_workspace_bytes", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops",
+    "gqla_expand_workspace_bytes", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -41,6 +41,12 @@ class gqla_shape(C.Structure):
 class gqla_cache(C.Structure):
     _fields_ = [("pool", C.c_void_p), ("seq_lens", C.c_void_p), ("page_table", C.c_void_p), ("page_size", C.c_int32),
                 ("max_pages", C.c_int32), ("num_pages", C.c_int32), ("groups", C.c_int32)]
+
+
+class gqla_path_estimate(C.Structure):
+    _fields_ = [("absorb_bytes", C.c_double), ("absorb_flops", C.c_double), ("absorb_intensity", C.c_double),
+                ("absorb_seconds", C.c_double), ("gqa_bytes", C.c_double), ("gqa_flops", C.c_double),
+                ("gqa_intensity", C.c_double), ("gqa_seconds", C.c_double), ("ridge", C.c_double), ("faster_path", C.c_int32)]
 
 
 _lib = None
@@ -75,6 +81,8 @@ def lib():
         L.gqla_decode_absorb.restype = i32
         L.gqla_expand_cache.argtypes = [sp, cp, vp, vp, i32, i32, cp, vp, C.c_size_t, vp]
         L.gqla_expand_cache.restype = i32
+        L.gqla_estimate_paths.argtypes = [sp, i64, C.c_double, C.c_double, C.POINTER(gqla_path_estimate)]
+        L.gqla_estimate_paths.restype = i32
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
         L.gqla_probe_stream_read.restype = i32
         L.gqla_probe_mfma_bf16.argtypes = [vp, i32, i32, vp]
@@ -187,6 +195,13 @@ def gqla_decode_absorb(shape, plan, q_hat, q_r, latent: gqla_cache, w_uv, out, l
     nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
     _check(lib().gqla_decode_absorb(C.byref(shape), plan, _ptr(q_hat), _ptr(q_r), C.byref(latent), _ptr(w_uv), _ptr(out),
                                     _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_absorb")
+
+
+def gqla_estimate_paths(shape, cached_tokens, hbm_bytes_per_s, mfma_flops_per_s) -> dict:
+    est = gqla_path_estimate()
+    _check(lib().gqla_estimate_paths(C.byref(shape), int(cached_tokens), float(hbm_bytes_per_s), float(mfma_flops_per_s),
+                                     C.byref(est)), "gqla_estimate_paths")
+    return {name: getattr(est, name) for name, _ in gqla_path_estimate._fields_}
 
 
 def gqla_probe_stream_read(src, nbytes, sink, num_cus, stream=None):

@@ -381,6 +381,29 @@ int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t P
   return page * P * (2ll * groups * d_h + d_r) + 2ll * groups * P * d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8;
 }
 
+gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, double hbm_bytes_per_s,
+                                double mfma_flops_per_s, gqla_path_estimate* out) {
+  if (!out) return GQLA_ERR_NULL;
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (cached_tokens < 0 || !(hbm_bytes_per_s > 0.0) || !(mfma_flops_per_s > 0.0)) return GQLA_ERR_SHAPE;
+  const double L = (double)cached_tokens, elem = shape->dtype == GQLA_BF16 ? 2.0 : 4.0;
+  const double rows = (double)shape->h_q * shape->s_q;
+  out->absorb_bytes = L * elem * (shape->r_kv + shape->d_r);
+  out->absorb_flops = 2.0 * L * rows * (2.0 * shape->r_kv + shape->d_r);
+  out->absorb_intensity = rows * (2.0 * shape->r_kv + shape->d_r) / (elem / 2.0 * (shape->r_kv + shape->d_r));
+  out->gqa_bytes = L * elem * (2.0 * shape->g * shape->d_h + shape->d_r);
+  out->gqa_flops = 2.0 * L * rows * (2.0 * shape->d_h + shape->d_r);
+  out->gqa_intensity = rows * (2.0 * shape->d_h + shape->d_r) / (elem / 2.0 * (2.0 * shape->g * shape->d_h + shape->d_r));
+  const double ta_m = out->absorb_bytes / hbm_bytes_per_s, ta_c = out->absorb_flops / mfma_flops_per_s;
+  const double tg_m = out->gqa_bytes / hbm_bytes_per_s, tg_c = out->gqa_flops / mfma_flops_per_s;
+  out->absorb_seconds = ta_m > ta_c ? ta_m : ta_c;
+  out->gqa_seconds = tg_m > tg_c ? tg_m : tg_c;
+  out->ridge = mfma_flops_per_s / hbm_bytes_per_s;
+  out->faster_path = out->gqa_seconds < out->absorb_seconds ? GQLA_PATH_GQA : GQLA_PATH_ABSORB;
+  return GQLA_OK;
+}
+
 gqla_status gqla_probe_stream_read(const void* src, size_t bytes, void* sink, int32_t num_cus, void* stream) {
   if (!src || !sink) return GQLA_ERR_NULL;
   if (!aligned16(src)) return GQLA_ERR_ALIGN;

@@ -155,3 +155,38 @@ def test_empty_batch_is_ok_without_launch():
     p = B.gqla_plan_create(sh, [], 64, 256, B.GQLA_PATH_GQA)
     assert B.gqla_plan_num_chunks(p) == 0
     B.gqla_plan_destroy(p)
+
+
+def test_path_estimate_matches_the_papers_model():
+    """gqla_estimate_paths against the oracle's transcription of Sec. 4.2 and against the paper's own Table 2
+    (H100: 989 TFLOP/s, 3.35 TB/s; H20: 148 TFLOP/s, 4.0 TB/s; canonical shape, L = 8192, B = 1)."""
+    from oracle import roofline as R
+    L = 8192
+    for (peak, bw, g, s_q, want_path) in [
+        (989e12, 3.35e12, 8, 1, B.GQLA_PATH_ABSORB),   # H100: absorb 2.82 us (memory) beats GQA 10.3 us
+        (989e12, 3.35e12, 8, 2, B.GQLA_PATH_ABSORB),
+        (148e12, 4.0e12, 8, 1, B.GQLA_PATH_GQA),       # H20: GQA 8.65 us beats absorb 15.42 us (compute)
+        (148e12, 4.0e12, 8, 2, B.GQLA_PATH_GQA),
+        (148e12, 4.0e12, 4, 1, B.GQLA_PATH_GQA),
+        (2500e12, 8.0e12, 8, 1, B.GQLA_PATH_ABSORB),   # MI355X published peaks
+    ]:
+        sh = B.make_shape(1, 128, g, 128, 512, 64, s_q, B.GQLA_BF16)
+        est = B.gqla_estimate_paths(sh, L, bw, peak)
+        oa = R.operating_point(R.absorb_bytes(L, 512, 64), R.absorb_flops(L, 128, s_q, 512, 64), s_q, peak, bw)
+        og = R.operating_point(R.gqa_bytes(L, g, 128, 64), R.gqa_flops(L, 128, s_q, 128, 64), s_q, peak, bw)
+        assert est["absorb_bytes"] == R.absorb_bytes(L, 512, 64) and est["gqa_bytes"] == R.gqa_bytes(L, g, 128, 64)
+        assert est["absorb_flops"] == R.absorb_flops(L, 128, s_q, 512, 64) and est["gqa_flops"] == R.gqa_flops(L, 128, s_q, 128, 64)
+        assert abs(est["absorb_seconds"] - oa["step_s"]) <= 1e-15 and abs(est["gqa_seconds"] - og["step_s"]) <= 1e-15
+        assert abs(est["absorb_intensity"] - R.absorb_intensity(128, s_q, 512, 64)) < 1e-9
+        assert abs(est["gqa_intensity"] - R.gqa_intensity(128, g, s_q, 128, 64)) < 1e-9
+        assert abs(est["ridge"] - R.ridge(peak, bw)) < 1e-9
+        assert est["faster_path"] == want_path
+    # the printed values of Table 2 (microseconds, rounded as printed)
+    h20 = B.gqla_estimate_paths(B.make_shape(1, 128, 8, 128, 512, 64, 1, B.GQLA_BF16), L, 4.0e12, 148e12)
+    assert abs(h20["absorb_seconds"] * 1e6 - 15.42) < 0.01 and abs(h20["gqa_seconds"] * 1e6 - 8.65) < 0.01
+    h100 = B.gqla_estimate_paths(B.make_shape(1, 128, 8, 128, 512, 64, 1, B.GQLA_BF16), L, 3.35e12, 989e12)
+    assert abs(h100["absorb_seconds"] * 1e6 - 2.82) < 0.01
+    # argument checks
+    sh = B.make_shape(1, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_estimate_paths, sh, -1, 1.0, 1.0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_estimate_paths, sh, 10, 0.0, 1.0)
