@@ -390,12 +390,11 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
   const int t = (xc / a.G) % a.s_q;
   const int rho = t * a.h_q + j * a.G + xc % a.G;
   const int s0 = a.first_slot[b], s1 = a.first_slot[b + 1];
-  float m = GQLA_NEG_INF;
-  for (int s = s0; s < s1; ++s) m = fmaxf(m, a.part_lse[(int64_t)s * a.M + rho]);
-  float den = 0.f;
-  for (int s = s0; s < s1; ++s) den += __expf(a.part_lse[(int64_t)s * a.M + rho] - m);
-  const float inv_den = row_ok ? 1.f / den : 0.f;
-
+  // Log-sum-exp merge of the row's chunk partials in ONE pass, kNB chunks at a time so that their loads (log-sum-exps
+  // and latent vectors) are in flight together; the running maximum moves as in an online softmax.  (Three passes
+  // with one dependent load per chunk each cost three memory latencies per chunk.)
+  constexpr int kNB = 4;
+  float m = GQLA_NEG_INF, den = 0.f;
   // combined latent output of this lane's row, dims 16*(KSW*wave + ksl) + 8*h + 0..7, fp32
   float acc[KSW][8];
 #pragma unroll
@@ -403,19 +402,48 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[ksl][e] = 0.f;
   const __bf16* po = (const __bf16*)a.part_o + (int64_t)rho * RKV + (KSW * wave) * 16 + h * 8;
-  for (int s = s0; s < s1; ++s) {
-    const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m) * inv_den;
-    u32x4 v[KSW];
+  for (int sb = s0; sb < s1; sb += kNB) {
+    float l[kNB];
+    u32x4 v[kNB][KSW];
 #pragma unroll
-    for (int ksl = 0; ksl < KSW; ++ksl) v[ksl] = *(const u32x4*)(po + (int64_t)s * a.M * RKV + ksl * 16);
+    for (int k = 0; k < kNB; ++k) {
+      const int sc = min(sb + k, s1 - 1);  // clamped: a chunk beyond the range is loaded again and given weight 0
+      l[k] = a.part_lse[(int64_t)sc * a.M + rho];
+#pragma unroll
+      for (int ksl = 0; ksl < KSW; ++ksl) v[k][ksl] = *(const u32x4*)(po + (int64_t)sc * a.M * RKV + ksl * 16);
+    }
+    float m_new = m;
+#pragma unroll
+    for (int k = 0; k < kNB; ++k) {
+      if (sb + k >= s1) l[k] = GQLA_NEG_INF;
+      m_new = fmaxf(m_new, l[k]);
+    }
+    const float m_use = (m_new == GQLA_NEG_INF) ? 0.f : m_new;
+    const float rescale = __expf(m - m_use);  // 0 on the first batch (m = -inf), where den and acc are 0 anyway
+    den *= rescale;
 #pragma unroll
     for (int ksl = 0; ksl < KSW; ++ksl)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[ksl][2 * e] += w * bf16_bits_to_float(v[ksl][e] & 0xffffu);
-        acc[ksl][2 * e + 1] += w * bf16_bits_to_float(v[ksl][e] >> 16);
-      }
+      for (int e = 0; e < 8; ++e) acc[ksl][e] *= rescale;
+    m = m_new;
+#pragma unroll
+    for (int k = 0; k < kNB; ++k) {
+      const float w = __expf(l[k] - m_use);
+      den += w;
+#pragma unroll
+      for (int ksl = 0; ksl < KSW; ++ksl)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[ksl][2 * e] += w * bf16_bits_to_float(v[k][ksl][e] & 0xffffu);
+          acc[ksl][2 * e + 1] += w * bf16_bits_to_float(v[k][ksl][e] >> 16);
+        }
+    }
   }
+  const float inv_den = (row_ok && den > 0.f) ? 1.f / den : 0.f;
+#pragma unroll
+  for (int ksl = 0; ksl < KSW; ++ksl)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[ksl][e] *= inv_den;
 
   wait_all_memory();
   __syncthreads();  // W_UV[j] staged

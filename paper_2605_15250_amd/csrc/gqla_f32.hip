@@ -114,27 +114,51 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
   if (lane == 0) a.part_lse[(int64_t)chunk * a.M + rho] = l_run > 0.f ? (m_run + fast_log2(l_run)) * kLn2 : GQLA_NEG_INF;
 }
 
-// Log-sum-exp combine of chunk partials that are already in d_h space.  32 lanes per (b, row), 4 dims per lane
-// and step; the loads of all chunks are independent.
+// Log-sum-exp combine of chunk partials that are already in d_h space.  32 lanes per (b, row), 4 dims per lane and
+// step.  One pass over the chunks, kNB at a time so that their loads are in flight together; the running maximum
+// moves as in an online softmax (three passes with one dependent load per chunk each would cost three memory
+// latencies per chunk).
 template <typename OutT>
 __global__ void __launch_bounds__(256) combine_kernel(CombineArgs a) {
+  constexpr int kNB = 4;
   const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);  // row = b * M + rho
   if (row >= (int64_t)a.B * a.M) return;
   const int b = (int)(row / a.M), rho = (int)(row % a.M);
   const int s0 = a.first_slot[b], s1 = a.first_slot[b + 1];
-  float m = GQLA_NEG_INF;
-  for (int s = s0; s < s1; ++s) m = fmaxf(m, a.part_lse[(int64_t)s * a.M + rho]);
-  float den = 0.f;
-  for (int s = s0; s < s1; ++s) den += __expf(a.part_lse[(int64_t)s * a.M + rho] - m);
-  const float inv = 1.f / den;
   const float* po = (const float*)a.part_o + (int64_t)rho * a.d_h;
+  float m = GQLA_NEG_INF, den = 0.f;
   for (int d = (threadIdx.x & 31) * 4; d < a.d_h; d += 128) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = s0; s < s1; ++s) {
-      const float w = __expf(a.part_lse[(int64_t)s * a.M + rho] - m) * inv;
-      const f32x4 v = *(const f32x4*)(po + (int64_t)s * a.M * a.d_h + d);
-      if (w > 0.f) acc += w * v;
+    m = GQLA_NEG_INF;
+    den = 0.f;
+    for (int sb = s0; sb < s1; sb += kNB) {
+      float l[kNB];
+      f32x4 v[kNB];
+#pragma unroll
+      for (int k = 0; k < kNB; ++k) {
+        const int sc = min(sb + k, s1 - 1);  // clamped: a chunk beyond the range is loaded again and given weight 0
+        l[k] = a.part_lse[(int64_t)sc * a.M + rho];
+        v[k] = *(const f32x4*)(po + (int64_t)sc * a.M * a.d_h + d);
+      }
+      float m_new = m;
+#pragma unroll
+      for (int k = 0; k < kNB; ++k) {
+        if (sb + k >= s1) l[k] = GQLA_NEG_INF;
+        m_new = fmaxf(m_new, l[k]);
+      }
+      const float m_use = (m_new == GQLA_NEG_INF) ? 0.f : m_new;
+      const float rescale = __expf(m - m_use);  // 0 on the first batch (m = -inf), where den and acc are 0 anyway
+      den *= rescale;
+      acc *= rescale;
+      m = m_new;
+#pragma unroll
+      for (int k = 0; k < kNB; ++k) {
+        const float w = __expf(l[k] - m_use);
+        den += w;
+        if (w > 0.f) acc += w * v[k];  // a chunk without visible tokens may hold anything
+      }
     }
+    acc *= 1.f / den;
     OutT* out = (OutT*)a.out + row * a.d_h + d;
     if constexpr (sizeof(OutT) == 4) {
       *(f32x4*)out = acc;
