@@ -73,7 +73,7 @@ __device__ __forceinline__ void acc_read(int dt, bool wait, float (&x)[16]) {
 }
 
 template <int RKV, int DR>
-__global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, int row_blocks, int n_chunks_padded) {
+__global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, int row_blocks) {
   constexpr int W = RKV + DR;        // elements per latent row
   constexpr int ROWB = W * 2;        // bytes per latent row
   constexpr int NP = W / 64;         // 128-byte panels per latent row
@@ -502,7 +502,7 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   }
   const int row_blocks = (a.M + kRowsPerBlock - 1) / kRowsPerBlock;
   const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
-  decode_absorb_bf16_kernel<512, 64><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks, chunks_padded);
+  decode_absorb_bf16_kernel<512, 64><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks);
   return hipGetLastError();
 }
 

@@ -16,12 +16,13 @@ namespace gqla {
 namespace {
 
 template <int DH, int DR>
-__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks) {
+__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg) {
   constexpr int KS_C = DH / 16;  // k-steps over the content dims
   constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
   constexpr int MT = DH / 32;    // 32-dim tiles of the output
   const int lane = threadIdx.x & 63;
-  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * 8 + (threadIdx.x >> 6));  // wave-uniform: keep it scalar
+  const int wpb = __builtin_amdgcn_readfirstlane(blockDim.x >> 6);  // waves per workgroup: 8, or the number of groups when that is 2 or 4
+  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));  // wave-uniform: keep it scalar
   if (item >= n_items) return;
   const int j = item % a.g;
   const int rb = (item / a.g) % row_blocks;
@@ -57,21 +58,21 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
   bool k_ok = true, v_ok = true;
 
-  // The shared RoPE key of a tile is the same for every group.  When the 8 waves of a workgroup are the 8 (or a
-  // multiple of 8) groups of one (chunk, row block), the tile's k_R (4 KB) is brought into LDS once per workgroup --
-  // one 1 KB LDS-DMA instruction by each of waves 0..3 -- and every wave takes its fragments from there, instead of
-  // every wave pulling the same lines through the vector memory path (a fifth of all its load instructions).
+  // The shared RoPE key of a tile is the same for every group.  When all waves of a workgroup are groups of one
+  // (chunk, row block) -- 8 waves for g a multiple of 8, g waves for g = 2 or 4 -- the tile's k_R (4 KB) is brought
+  // into LDS once per workgroup, as four 1 KB LDS-DMA instructions dealt over the waves, and every wave takes its
+  // fragments from there, instead of every wave pulling the same lines through the vector memory path (a fifth of
+  // all its load instructions).
   __shared__ __attribute__((aligned(16))) char kr_lds[2][KS_R * 1024];
-  const bool share_kr = (a.g % 8) == 0;  // kernel-uniform
-  const int wave = item & 7;             // position in the workgroup (scalar)
+  const bool share_kr = share_kr_arg != 0;                                  // kernel-uniform
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);        // position in the workgroup (scalar)
   auto stage_kr = [&](int tok, int32_t pg, int buf) {
-    if (wave < KS_R) {
-      const __bf16* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_elems + (int64_t)2 * gc * DH * P + ((int64_t)(2 * wave) * P + tok % P) * 8;
-      const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(kr_lds[buf] + wave * 1024);
+    for (int ks = wave; ks < KS_R; ks += wpb) {  // k-step ks: dims 16*ks .. 16*ks + 15
+      const __bf16* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_elems + (int64_t)2 * gc * DH * P + ((int64_t)(2 * ks) * P + tok % P) * 8;
+      const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)(kr_lds[buf] + ks * 1024));
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"((h * P + n) * 16), "s"(src));
     }
   };
-
   auto load_k = [&](int tok, int32_t pg) {
     k_ok = pg >= 0;
     const __bf16* base = pool + (int64_t)(k_ok ? pg : 0) * page_elems;
@@ -236,8 +237,12 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
 hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
   const int row_blocks = (a.G * a.s_q + 31) / 32;
   const int n_items = a.n_chunks * row_blocks * a.g;
-  const int blocks = (n_items + 7) / 8;
-  decode_gqa_bf16_kernel<128, 64><<<blocks, 512, 0, s>>>(a, n_items, row_blocks);
+  // all waves of a workgroup are groups of one (chunk, row block) when the group count is a multiple of the waves per
+  // workgroup: then they share the tile's k_R through LDS (and run in step, one barrier per tile)
+  const bool team = a.g % 8 == 0 || a.g == 4 || a.g == 2;
+  const int wpb = (a.g == 4 || a.g == 2) ? a.g : 8;
+  const int blocks = (n_items + wpb - 1) / wpb;
+  decode_gqa_bf16_kernel<128, 64><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -188,6 +188,9 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (128, 8, 2, [1500, 700], True, (4, 5)),              # multi-page chunks with a ragged last chunk
     (32, 8, 1, [513, 100], False, (3, 2)),               # LLaMA-3-8B-converted heads: G = 4 (padded MFMA rows)
     (128, 8, 2, [640], False, (0, 0)),                   # contiguous cache, no page table
+    (64, 4, 1, [900, 333], True, (0, 0)),                # g = 4 (2176 bytes per token, Sec. 4.2.3): 4-wave workgroups
+    (32, 2, 2, [450, 64], True, (2, 2)),                 # g = 2: 2-wave workgroups, each wave stages two k_R slabs
+    (48, 3, 1, [300], True, (0, 0)),                     # g = 3: no k_R sharing (direct loads)
 ])
 def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
