@@ -191,6 +191,7 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (64, 4, 1, [900, 333], True, (0, 0)),                # g = 4 (2176 bytes per token, Sec. 4.2.3): 4-wave workgroups
     (32, 2, 2, [450, 64], True, (2, 2)),                 # g = 2: 2-wave workgroups, each wave stages two k_R slabs
     (48, 3, 1, [300], True, (0, 0)),                     # g = 3: no k_R sharing (direct loads)
+    (128, 8, 1, [20000], True, (0, 0)),                  # one long sequence: the plan cuts it into a few hundred chunks
 ])
 def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
