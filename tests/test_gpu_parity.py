@@ -233,6 +233,30 @@ def test_bf16_page_sizes(page_size, lens):
         case.close()
 
 
+def test_bf16_growing_logits(monkeypatch):
+    """Logits that keep growing along the sequence and reach far beyond the usual range: the reference maximum of the
+    absorb kernel's online softmax has to move many times (it only moves in steps of more than 2^8), and both kernels
+    must keep their exponentials in range.  The RoPE key of a cached token (which enters the logits only, so the outputs
+    stay O(1)) is scaled by a factor that rises from 1 to 8 with the position, so late tokens dominate; the oracle sees
+    exactly the same rows."""
+    real_rows = S.sequence_rows
+
+    def growing_rows(cfg, b, L_b):
+        rows = real_rows(cfg, b, L_b).astype(np.float64)
+        ramp = 1.0 + 7.0 * np.arange(int(L_b), dtype=np.float64) / max(int(L_b) - 1, 1)
+        rows[:, cfg.r_kv:] *= ramp[:, None]
+        return S.quantize(rows.astype(np.float32), cfg.dtype)
+
+    monkeypatch.setattr(S, "sequence_rows", growing_rows)
+    cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=8128)
+    case = Case(cfg, lens=[1500, 333])
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
 def test_bf16_single_group_slice():
     """One rank's share of 8-way head-axis tensor parallelism: 16 heads, one group, 320 elements per token."""
     cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=909)
