@@ -70,7 +70,8 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     for (int ks = wave; ks < KS_R; ks += wpb) {  // k-step ks: dims 16*ks .. 16*ks + 15
       const __bf16* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_elems + (int64_t)2 * gc * DH * P + ((int64_t)(2 * ks) * P + tok % P) * 8;
       const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)(kr_lds[buf] + ks * 1024));
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"((h * P + n) * 16), "s"(src));
+      // ("memory": the cache loads that follow must stay behind this request, the counted wait relies on it)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"((h * P + n) * 16), "s"(src) : "memory");
     }
   };
   auto load_k = [&](int tok, int32_t pg) {
