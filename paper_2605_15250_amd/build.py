@@ -43,11 +43,13 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-# Kernels listed here keep data in accumulation registers that they address by name in inline assembly; the
-# compiler knows those registers only as clobbered, so it must never park values of its own there.  It does so
-# (v_accvgpr_write / _read / _mov outside the assembly blocks) only when it runs out of ordinary registers: the build
-# checks the generated assembly and refuses such a kernel instead of shipping silent corruption.
-NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"]}
+# Kernels listed here keep data in accumulation registers behind the compiler's back: the absorb decode addresses
+# them by name in inline assembly (the compiler knows them only as clobbered, so it must never park values of its own
+# there), the expansion loads them asynchronously from inline assembly (a compiler-made copy before the wait would copy
+# stale data).  The compiler touches accumulation registers itself (v_accvgpr_write / _read / _mov outside the assembly
+# blocks) only when it runs out of ordinary registers: the build checks the generated assembly and refuses such a
+# kernel instead of shipping silent corruption.
+NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"], "gqla_gemm_bf16.hip": ["expand_bf16_kernel"]}
 
 
 def _check_named_agprs(src: str, kernels, extra) -> None:
