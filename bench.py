@@ -180,7 +180,8 @@ def main():
     other = None
     if args.all_configs:
         def timed2(fn, reps):
-            fn()
+            for _ in range(3):
+                fn()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
@@ -202,10 +203,10 @@ def main():
             o_k = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch.bfloat16, device="cuda")
             l_k = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
             qh_k = dk.absorb_query(d_qc, d_wk)
-            t_a = timed2(lambda: dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k), 5)
+            t_a = timed2(lambda: dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k), 20)
             dk.alloc_expanded(fill=0.0)
-            t_e = timed2(lambda: dk.expand(d_wk, d_wv), 2)
-            t_g = timed2(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 5)
+            t_e = timed2(lambda: dk.expand(d_wk, d_wv), 5)
+            t_g = timed2(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 20)
             Ls = int(lens_k.sum())
             b_a, f_a = 2 * Ls * (c.r_kv + c.d_r), 2 * Ls * c.h_q * c.s_q * (2 * c.r_kv + c.d_r)
             b_g, f_e = 2 * Ls * (2 * c.g * c.d_h + c.d_r), 2 * Ls * c.r_kv * 2 * c.g * c.d_h

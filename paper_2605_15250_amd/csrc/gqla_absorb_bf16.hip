@@ -72,7 +72,13 @@ __device__ __forceinline__ void acc_read(int dt, bool wait, float (&x)[16]) {
   }
 }
 
-template <int RKV, int DR>
+// SPLIT = 1: the layout above.  SPLIT = 4 (at most 32 query rows per sequence, e.g. one rank's heads under tensor
+// parallelism): the four waves share the one block of 32 rows instead of three of them having no rows.  A wave of
+// the team contracts a quarter of the key dimension (k-step `part` of each 4-step panel), the team sums its partial
+// S^T through LDS (every wave adds them in the same order, so all hold the same bits), each wave runs the same
+// softmax and then updates its own RKV/4 slice of O^T.  With so few rows the kernel is bound by the rate at which
+// tiles stream into LDS (measured: 64 rows gain nothing from two-wave teams, so those keep SPLIT = 1).
+template <int RKV, int DR, int SPLIT>
 __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, int row_blocks) {
   constexpr int W = RKV + DR;        // elements per latent row
   constexpr int ROWB = W * 2;        // bytes per latent row
@@ -81,6 +87,10 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   constexpr int KS = W / 16;         // k-steps of the key contraction
   constexpr int DT = RKV / 32;       // 32-wide tiles of the latent output
   constexpr int TILE_BYTES = kTile * ROWB;
+  constexpr int RPB = kRowsPerBlock / SPLIT;  // query rows per workgroup
+  constexpr int KB = 4 / SPLIT;               // k-steps of every 4-step panel that one wave contracts
+  constexpr int DTW = DT / SPLIT;             // output tiles per wave
+  static_assert(SPLIT == 1 || SPLIT == 4, "one wave or the whole workgroup per 32 rows");
   static_assert(W % 64 == 0 && RKV % 64 == 0, "latent row must be a whole number of 128-byte panels");
   static_assert((16 + 8 + 4) * 128 + 128 + PANEL * (RKV / 64 - 1) < 65536, "value-fragment offsets must fit the 16-bit LDS immediate");
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -100,24 +110,38 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const int n = lane & 31, h = lane >> 5;
   const ChunkEntry ce = a.chunks[chunk];
 
-  const int rho = rbk * kRowsPerBlock + wave * 32 + n;  // row = t * h_q + i
+  const int part = wave & (SPLIT - 1), team = wave / SPLIT;  // this wave's share of its 32 rows' work; which 32 rows
+  const int rho = rbk * RPB + team * 32 + n;                 // row = t * h_q + i
   const bool row_ok = rho < a.M;
   const int t = row_ok ? rho / a.h_q : 0;
   const int vis_end = row_ok ? min(ce.tok_end, ce.L - a.s_q + t + 1) : 0;
   const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);
-  const bool wave_active = rbk * kRowsPerBlock + wave * 32 < a.M;
+  // With SPLIT > 1 the launcher sends a single row block whose every team has rows (all waves meet at the team's
+  // exchange barrier, so none may skip a tile).
+  const bool wave_active = SPLIT > 1 || rbk * RPB + team * 32 < a.M;
 
-  // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step
-  bf16x8 qf[KS];
+  // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step; this wave's
+  // k-steps are 4*a4 + part*KB + b
+  bf16x8 qf[KS / SPLIT];
   {
     const int64_t qrow = (int64_t)ce.b * a.M + min(rho, a.M - 1);
-    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8;
-    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
+    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8 + part * KB * 16;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8 + part * KB * 16;
 #pragma unroll
-    for (int ks = 0; ks < RKV / 16; ++ks) qf[ks] = *(const bf16x8*)(ph + ks * 16);
+    for (int a4 = 0; a4 < KS / 4; ++a4)
 #pragma unroll
-    for (int ks = 0; ks < DR / 16; ++ks) qf[RKV / 16 + ks] = *(const bf16x8*)(pr + ks * 16);
+      for (int b = 0; b < KB; ++b)
+        qf[a4 * KB + b] = *(const bf16x8*)((a4 < RKV / 64 ? ph + a4 * 64 : pr + (a4 - RKV / 64) * 64) + b * 16);
   }
+
+  // The query loads are made to complete here, before any tile is requested.  Otherwise the compiler, which counts
+  // only the loads it issued itself, keeps "wait for the query loads" counts in front of the loop's first MFMAs; on
+  // the hardware counter those waits would also cover the tile requests in flight and drain the ring on every tile.
+#pragma unroll
+  for (int k = 0; k < KS / SPLIT; k += 9)
+    asm volatile("" : "+v"(qf[k]), "+v"(qf[k + 1]), "+v"(qf[k + 2]), "+v"(qf[k + 3]), "+v"(qf[k + 4]), "+v"(qf[k + 5]),
+                      "+v"(qf[k + 6]), "+v"(qf[k + 7]), "+v"(qf[k + 8]));
+  static_assert((KS / SPLIT) % 9 == 0, "query fragments are touched nine at a time");
 
   const int P = a.cache.page_size;
   const char* pool = (const char*)a.cache.pool;
@@ -136,12 +160,13 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   //                    4 columns at 32*dt + 16*g1 + 4*q: panel dt/2, in-panel chunk 4*(dt & 1) + cl, cl = 2*g1 + q/2.
   //                    With R0 a multiple of 16, swz = 2*h + e/2 for the first read and 4 + that for the second, so the
   //                    chunk lands at 4*(dt & 1) + (cl ^ swz) resp. 4*(1 - (dt & 1)) + (cl ^ swz): one base per lane.
-  uint32_t kbase[4], vbase;
+  uint32_t kbase[KB], vbase;
   {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) kbase[b] = n * 128 + (((2 * b + h) ^ lds_swz(n)) << 4);
+    for (int b = 0; b < KB; ++b) kbase[b] = n * 128 + (((2 * (part * KB + b) + h) ^ lds_swz(n)) << 4);
     const int i16 = lane & 15, e = i16 >> 2, q = i16 & 3, g1 = (lane >> 4) & 1;
     vbase = (4 * h + e) * 128 + (((2 * g1 + (q >> 1)) ^ (2 * h + (e >> 1))) << 4) + (q & 1) * 8;
+    vbase += part * (DTW / 2) * PANEL;  // this wave's output tiles are part*DTW .. part*DTW + DTW-1
   }
 
   static_assert(DT == 16, "O^T fills the 256 accumulation registers exactly");
@@ -241,29 +266,53 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // These MFMAs accumulate in ordinary VGPRs (written as inline assembly) because all 256 accumulation
       // registers hold O^T; the compiler's own MFMA selection would put S^T there as well and spill.
       f32x16 s;
-      bf16x8 f[3][4];  // ring of fragment batches: loads run two batches (8 MFMAs) ahead of their use
+      // With few query rows the kernel is bound by how many bytes it keeps in flight, not by its MFMAs: the request
+      // for tile it + kAhead goes out first (no LDS read is outstanding here either).
+      if constexpr (SPLIT > 1) {
+        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      }
+      if constexpr (SPLIT == 1) {
+        bf16x8 f[3][4];  // ring of fragment batches: loads run two batches (8 MFMAs) ahead of their use
 #pragma unroll
-      for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b]);
+        for (int b = 0; b < 4; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b]);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) f[1][b] = *(const bf16x8*)(buf + kbase[b] + PANEL);
+        for (int b = 0; b < 4; ++b) f[1][b] = *(const bf16x8*)(buf + kbase[b] + PANEL);
 #pragma unroll
-      for (int a4 = 0; a4 < KS / 4; ++a4) {
-        if (a4 + 2 < KS / 4) {
+        for (int a4 = 0; a4 < KS / 4; ++a4) {
+          if (a4 + 2 < KS / 4) {
 #pragma unroll
-          for (int b = 0; b < 4; ++b) f[(a4 + 2) % 3][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 2) * PANEL));
+            for (int b = 0; b < 4; ++b) f[(a4 + 2) % 3][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 2) * PANEL));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(f[0][0]), "v"(qf[0]));  // result registers must not overlap the operands
+            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 % 3][b]), "v"(qf[4 * a4 + b]));
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
+      } else {
+        bf16x8 f[KS / 4][KB];  // this wave's share is short: every fragment is requested up front
+#pragma unroll
+        for (int a4 = 0; a4 < KS / 4; ++a4)
+#pragma unroll
+          for (int b = 0; b < KB; ++b) f[a4][b] = *(const bf16x8*)(buf + kbase[b] + a4 * PANEL);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s) : "v"(f[0][0]), "v"(qf[0]));
-          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 % 3][b]), "v"(qf[4 * a4 + b]));
-        }
+        for (int a4 = 0; a4 < KS / 4; ++a4)
+#pragma unroll
+          for (int b = 0; b < KB; ++b) {
+            if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(f[0][0]), "v"(qf[0]));  // result registers must not overlap the operands
+            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4][b]), "v"(qf[a4 * KB + b]));
+          }
         __builtin_amdgcn_sched_barrier(0);
       }
       // Tile it + kAhead is requested here, in one burst: at this point no LDS read of this wave is outstanding.
       // (An LDS-DMA instruction issued while reads are in flight holds the wave, and with it the MFMA stream, until
       // they have returned.)
-      if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      if constexpr (SPLIT == 1) {
+        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      }
       // first batches of value fragments: issued now, consumed after the softmax
       i16x4 r[3][4][2];
       auto load_v = [&](int slot, int u, int p4) {  // output tiles dt = 4*p4 .. 4*p4 + 3 of k-step u
@@ -275,10 +324,28 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
           r[slot][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 8 * 128 + 64 * (1 - (dt & 1)))));
         }
       };
+      constexpr int NBT = 2 * (DTW / 4);  // batches of four value fragments: k-step bt / (DTW/4), tiles 4*(bt % (DTW/4)) ..
       load_v(0, 0, 0);
-      load_v(1, 0, 1);
+      load_v(1, 1 / (DTW / 4), 1 % (DTW / 4));
       // the matrix pipeline's result is not interlocked against vector-ALU reads: wait out its 8 passes
       asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));
+      if constexpr (SPLIT > 1) {
+        // team sum of the partial S^T: [wave][quarter][lane] 16-byte slots behind the tile ring
+        char* ex = smem + kSlots * TILE_BYTES;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *(f32x4*)(ex + wave * 4096 + q * 1024 + lane * 16) = f32x4{s[4 * q], s[4 * q + 1], s[4 * q + 2], s[4 * q + 3]};
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+        __syncthreads();  // the next write to these slots comes after the next tile's barrier, which follows these reads
+#pragma unroll
+        for (int w = 0; w < SPLIT; ++w)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4 x = *(const f32x4*)(ex + (team * SPLIT + w) * 4096 + q * 1024 + lane * 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[4 * q + e] = (w == 0) ? x[e] : s[4 * q + e] + x[e];
+          }
+      }
 
       // ---- online softmax (base 2); register i is token tok + 8*(i/4) + 4*h + i%4 ----
       // The maximum is taken on the raw logits (the scale is positive) and the scale rides in the exponent's FMA.
@@ -305,6 +372,16 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       bf16x8 pf[2];
       float p1[8];
       u32x4 w1;
+      if constexpr (SPLIT > 1) {  // too few MFMAs per k-step to hide exponentials behind: both halves now
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          p1[e] = fast_exp2(__builtin_fmaf(s[8 + e], a.scale_log2e, -m_use));
+          psum += p1[e];
+        }
+        w1 = u32x4{pack_bf16(p1[0], p1[1]), pack_bf16(p1[2], p1[3]), pack_bf16(p1[4], p1[5]), pack_bf16(p1[6], p1[7])};
+        l_run += psum;
+      }
       {
         float p[8], psum = 0.f;
 #pragma unroll
@@ -316,21 +393,26 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
         pf[0] = __builtin_bit_cast(bf16x8, w);
         l_run += psum;
       }
+      // An MFMA may read a register as an operand no sooner than two wait states after a vector-ALU instruction wrote
+      // it.  The compiler keeps that distance for its own MFMAs but does not look inside inline assembly, so the
+      // distance between the last pack of the probabilities and the first O^T update is made here.
+      if constexpr (SPLIT > 1) asm volatile("s_nop 1" : "+v"(pf[0]), "+v"(w1));
+      else asm volatile("s_nop 1" : "+v"(pf[0]));
       __builtin_amdgcn_sched_barrier(0);
 
       // ---- O^T[r][row] += C^T * P^T, value fragments one batch of four tiles ahead ----
 #pragma unroll
-      for (int bt = 0; bt < 2 * (DT / 4); ++bt) {
-        const int u = bt / (DT / 4), p4 = bt % (DT / 4);
-        if (bt + 2 < 2 * (DT / 4)) load_v((bt + 2) % 3, (bt + 2) / (DT / 4), (bt + 2) % (DT / 4));
-        if (bt == DT / 4) pf[1] = __builtin_bit_cast(bf16x8, w1);
+      for (int bt = 0; bt < NBT; ++bt) {
+        const int u = bt / (DTW / 4), p4 = bt % (DTW / 4);
+        if (bt + 2 < NBT) load_v((bt + 2) % 3, (bt + 2) / (DTW / 4), (bt + 2) % (DTW / 4));
+        if (bt == DTW / 4) pf[1] = __builtin_bit_cast(bf16x8, w1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const i16x4 lo = r[bt % 3][d][0], hi = r[bt % 3][d][1];
           const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           acc_mfma(4 * p4 + d, __builtin_bit_cast(bf16x8, fr), pf[u]);
-          if (u == 0) {  // second k-step's probabilities, one piece per MFMA
+          if (SPLIT == 1 && u == 0) {  // second k-step's probabilities, one piece per MFMA
             const int idx = 4 * bt + d;
             if (idx < 8) {
               p1[idx] = fast_exp2(__builtin_fmaf(s[8 + idx], a.scale_log2e, -m_use));
@@ -353,16 +435,16 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const int64_t prow = (int64_t)chunk * a.M + rho;
   __bf16* po = (__bf16*)a.part_o + prow * RKV;
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) {
+  for (int dt = 0; dt < DTW; ++dt) {
     float x[16];
     acc_read(dt, dt == 0, x);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
-      *(u32x2*)(po + dt * 32 + 8 * q + 4 * h) = v;
+      *(u32x2*)(po + (part * DTW + dt) * 32 + 8 * q + 4 * h) = v;
     }
   }
-  if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+  if (h == 0 && part == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
 }
 
 // ---- combine + latent-output projection: out = W_UV[j]^T (sum_k w_k o_hat_k)   (MQA-absorb equation, line 6) ----
@@ -491,19 +573,27 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
 
 }  // namespace
 
-hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
-  constexpr int kLds = kSlots * kTile * (512 + 64) * 2;
+template <int SPLIT>
+static hipError_t launch_decode_absorb_split(const DecodeArgs& a, hipStream_t s) {
+  // tile ring, plus the team exchange (4 KB per wave) when waves share rows
+  constexpr int kLds = kSlots * kTile * (512 + 64) * 2 + (SPLIT > 1 ? 4 * 4096 : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)decode_absorb_bf16_kernel<512, 64>,
+    hipError_t e = hipFuncSetAttribute((const void*)decode_absorb_bf16_kernel<512, 64, SPLIT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int row_blocks = (a.M + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int row_blocks = (a.M + kRowsPerBlock / SPLIT - 1) / (kRowsPerBlock / SPLIT);
   const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
-  decode_absorb_bf16_kernel<512, 64><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks);
+  decode_absorb_bf16_kernel<512, 64, SPLIT><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks);
   return hipGetLastError();
+}
+
+hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
+  // at most 32 query rows: the four waves share them, so that none is left without work (a single row block)
+  if (a.M <= 32) return launch_decode_absorb_split<4>(a, s);
+  return launch_decode_absorb_split<1>(a, s);
 }
 
 hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {

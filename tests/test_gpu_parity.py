@@ -192,6 +192,10 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (32, 2, 2, [450, 64], True, (2, 2)),                 # g = 2: 2-wave workgroups, each wave stages two k_R slabs
     (48, 3, 1, [300], True, (0, 0)),                     # g = 3: no k_R sharing (direct loads)
     (128, 8, 1, [20000], True, (0, 0)),                  # one long sequence: the plan cuts it into a few hundred chunks
+    (16, 8, 1, [777, 40], True, (0, 0)),                 # one rank's heads under 8-way head parallelism: 16 query rows,
+                                                         # four waves share them in the absorb kernel (half its rows padding)
+    (16, 4, 2, [2, 300, 1029], True, (1, 2)),            # 32 rows shared by four waves, L == s_q, ragged chunks
+    (8, 8, 1, [130, 64], False, (0, 0)),                 # G = 1 (multi-head limit of the grouping): 8 rows
 ])
 def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
@@ -233,7 +237,8 @@ def test_bf16_page_sizes(page_size, lens):
         case.close()
 
 
-def test_bf16_growing_logits(monkeypatch):
+@pytest.mark.parametrize("h_q", [128, 32, 16])   # absorb kernel: one, two and four waves per 32 query rows
+def test_bf16_growing_logits(monkeypatch, h_q):
     """Logits that keep growing along the sequence and reach far beyond the usual range: the reference maximum of the
     absorb kernel's online softmax has to move many times (it only moves in steps of more than 2^8), and both kernels
     must keep their exponentials in range.  The RoPE key of a cached token (which enters the logits only, so the outputs
@@ -248,7 +253,7 @@ def test_bf16_growing_logits(monkeypatch):
         return S.quantize(rows.astype(np.float32), cfg.dtype)
 
     monkeypatch.setattr(S, "sequence_rows", growing_rows)
-    cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=8128)
+    cfg = S.CONFIGS["C3"].with_(B=2, h_q=h_q, L=0, paged=True, seed=8128)
     case = Case(cfg, lens=[1500, 333])
     try:
         run_absorb_path(case)
