@@ -29,8 +29,8 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_canonical.json")   # 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=0, help="override B (debugging only; changes the workload name)")
     ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
