@@ -144,17 +144,24 @@ def plan_overhead_pages(path):
     return 4 if path == PATH_ABSORB else 2
 
 
+def plan_merge_cost(path):
+    """Sixteenths of a page time that each chunk partial of the longest sequence adds to the combine."""
+    return 4 if path == PATH_ABSORB else 1
+
+
 def plan_chunk_pages(lens, P, num_cus, path, h_q, g, s_q):
     """Chunk size (in pages): the cp in 1..max_b npages_b minimising
-    ceil(n_chunks(cp) / slots) * (cp + overhead), n_chunks(cp) = sum_b ceil(npages_b / cp);
-    ties go to the larger cp."""
+    16 * ceil(n_chunks(cp) / slots) * (cp + overhead) + merge * ceil(max_b npages_b / cp),
+    n_chunks(cp) = sum_b ceil(npages_b / cp); ties go to the larger cp."""
     npages = [pages_needed(L, P) for L in lens]
     slots = plan_slots(num_cus, path, h_q, g, s_q)
     ovh = plan_overhead_pages(path)
+    longest = max(npages)
     best_cp, best_cost = 1, None
-    for cp in range(1, max(npages) + 1):
+    for cp in range(1, longest + 1):
         n_chunks = sum(-(-n // cp) for n in npages)
-        cost = -(-n_chunks // slots) * (cp + ovh)
+        rounds = -(-n_chunks // slots)
+        cost = 16 * rounds * (cp + ovh) + plan_merge_cost(path) * (-(-longest // cp))
         if best_cost is None or cost <= best_cost:
             best_cp, best_cost = cp, cost
     return best_cp

@@ -189,13 +189,16 @@ gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_ho
   int32_t cp = chunk_pages_override;
   if (cp == 0) {
     const int64_t slots = plan_slots(*shape, num_cus, path);
+    // Cost in sixteenths of the time one page takes: rounds of chunks on the device, each a chunk plus its fixed cost,
+    // then the combine, whose time is set by the longest chain of chunk partials it merges for one sequence.
     const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : 2;
+    const int64_t merge = path == GQLA_PATH_ABSORB ? 4 : 1;
     int64_t best = -1;
     cp = 1;
     for (int32_t c = 1; c <= max_np; ++c) {
       int64_t n = 0;
       for (int32_t b = 0; b < shape->batch; ++b) n += ceil_div(npages[b], c);
-      const int64_t cost = ceil_div(n, slots) * (c + ovh);
+      const int64_t cost = 16 * ceil_div(n, slots) * (c + ovh) + merge * ceil_div(max_np, c);
       if (best < 0 || cost <= best) {
         best = cost;
         cp = c;

@@ -240,8 +240,10 @@ hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
   const int n_items = a.n_chunks * row_blocks * a.g;
   // all waves of a workgroup are groups of one (chunk, row block) when the group count is a multiple of the waves per
   // workgroup: then they share the tile's k_R through LDS (and run in step, one barrier per tile)
+  // With 2 or 4 groups the workgroup also takes all row blocks of the chunk when that keeps it within 8 waves: they
+  // stream the same cache vectors in step, so all but the first request for a line is served by the cache hierarchy.
   const bool team = a.g % 8 == 0 || a.g == 4 || a.g == 2;
-  const int wpb = (a.g == 4 || a.g == 2) ? a.g : 8;
+  const int wpb = (a.g == 4 || a.g == 2) ? (a.g * row_blocks <= 8 ? a.g * row_blocks : a.g) : 8;
   const int blocks = (n_items + wpb - 1) / wpb;
   decode_gqa_bf16_kernel<128, 64><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0);
   return hipGetLastError();

@@ -196,6 +196,8 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
                                                          # four waves share them in the absorb kernel (half its rows padding)
     (16, 4, 2, [2, 300, 1029], True, (1, 2)),            # 32 rows shared by four waves, L == s_q, ragged chunks
     (8, 8, 1, [130, 64], False, (0, 0)),                 # G = 1 (multi-head limit of the grouping): 8 rows
+    (128, 4, 2, [700, 65], True, (0, 0)),                # (g, s_q) = (4, 2) at 128 heads: G = 32, 64 rows per group
+    (128, 4, 1, [321], False, (0, 0)),                   # (g, s_q) = (4, 1), the 2176-byte-per-token operating point
 ])
 def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
