@@ -88,7 +88,7 @@ typedef struct {
 
 typedef struct {
   void* pool;                 /* device: num_pages pages in the format of the cache kind        */
-  const int32_t* seq_lens;    /* device int32[batch]: L_b; read by gqla_expand_cache only       */
+  const int32_t* seq_lens;    /* device int32[batch]: L_b; read by the cache-update calls only  */
   const int32_t* page_table;  /* device int32[batch*max_pages], or NULL for the identity map    */
   int32_t page_size;          /* P, tokens per page                                            */
   int32_t max_pages;          /* row stride of page_table; every L_b <= max_pages * page_size  */
@@ -161,6 +161,25 @@ gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent,
                               const gqla_cache* expanded, void* ws, size_t ws_bytes, void* stream);
 /* Bytes of scratch gqla_expand_cache needs for a slice of group_count groups (0 for GQLA_F32 or a bad shape). */
 size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count);
+
+/* ---- the per-step cache updates around the two decode paths (Sec. 3.1: each step caches the new token's c_kv and
+ * shared RoPE key; the GQA path's K_C, V of that token follow from the same latent) ----
+ *
+ * gqla_append_latent writes the step's rows into the latent cache: rows is device memory [B][s_q][r_kv + d_r]
+ * (c_kv | k_R per token, the cache's element type); row t of sequence b goes to logical position L_b - s_q + t, with
+ * L_b read from latent->seq_lens on the device, i.e. the lengths already count the step's tokens, as the decode calls
+ * expect them.  A sequence with L_b < s_q only receives the rows that have a position >= 0.  Nothing else is written.
+ *
+ * gqla_expand_cache_tail is gqla_expand_cache restricted to the last tail_tokens positions of every sequence
+ * (L_b - tail_tokens .. L_b - 1, clipped at 0): after gqla_append_latent with s_q = tail_tokens it brings an
+ * expanded cache that was complete before the step up to date, at a cost that does not grow with the context.
+ * Arguments, geometry rules, scratch and errors as for gqla_expand_cache; tail_tokens must be in [1, page_size]
+ * (GQLA_ERR_SHAPE otherwise).  Both calls only enqueue work on `stream`. */
+gqla_status gqla_append_latent(const gqla_shape* shape, const void* rows, const gqla_cache* latent, void* stream);
+gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
+                                   const void* w_uv, int32_t group_begin, int32_t group_count,
+                                   const gqla_cache* expanded, int32_t tail_tokens, void* ws, size_t ws_bytes,
+                                   void* stream);
 
 /* GQA-path decode (Sec. 3.1, GQA-path equation) over an expanded cache holding expanded->groups == shape->g
  * groups (for a tensor-parallel slice pass a shape with h_q and g already divided).  plan: built with

@@ -21,7 +21,7 @@ GQLA_PATH_ABSORB, GQLA_PATH_GQA = 0, 1
 EXPORTS = [
     "gqla_plan_create", "gqla_plan_destroy", "gqla_plan_num_chunks", "gqla_plan_chunk_pages", "gqla_plan_export",
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
-    "gqla_expand_workspace_bytes", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths",
+    "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -81,6 +81,10 @@ def lib():
         L.gqla_decode_absorb.restype = i32
         L.gqla_expand_cache.argtypes = [sp, cp, vp, vp, i32, i32, cp, vp, C.c_size_t, vp]
         L.gqla_expand_cache.restype = i32
+        L.gqla_expand_cache_tail.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, vp, C.c_size_t, vp]
+        L.gqla_expand_cache_tail.restype = i32
+        L.gqla_append_latent.argtypes = [sp, vp, cp, vp]
+        L.gqla_append_latent.restype = i32
         L.gqla_estimate_paths.argtypes = [sp, i64, C.c_double, C.c_double, C.POINTER(gqla_path_estimate)]
         L.gqla_estimate_paths.restype = i32
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
@@ -226,6 +230,19 @@ def gqla_expand_cache(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_
         ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
     _check(lib().gqla_expand_cache(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
                                    C.byref(expanded), _ptr(ws), ws_bytes, _stream(stream)), "gqla_expand_cache")
+
+
+def gqla_expand_cache_tail(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded: gqla_cache,
+                           tail_tokens, ws=None, ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().gqla_expand_cache_tail(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
+                                        C.byref(expanded), tail_tokens, _ptr(ws), ws_bytes, _stream(stream)),
+           "gqla_expand_cache_tail")
+
+
+def gqla_append_latent(shape, rows, latent: gqla_cache, stream=None):
+    _check(lib().gqla_append_latent(C.byref(shape), _ptr(rows), C.byref(latent), _stream(stream)), "gqla_append_latent")
 
 
 def gqla_decode_gqa(shape, plan, q_c, q_r, expanded: gqla_cache, out, lse, ws, ws_bytes=None, stream=None):

@@ -316,9 +316,11 @@ size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count)
   return (size_t)2 * group_count * shape->r_kv * shape->d_h * 2;  // both weight slices in fragment order, bf16
 }
 
-gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
-                              int32_t group_begin, int32_t group_count, const gqla_cache* expanded, void* ws,
-                              size_t ws_bytes, void* stream) {
+namespace {
+// tail = 0: every token of every sequence; tail > 0: the last `tail` positions only
+gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                        int32_t group_begin, int32_t group_count, const gqla_cache* expanded, int32_t tail, void* ws,
+                        size_t ws_bytes, void* stream) {
   gqla_status st = check_shape(shape);
   if (st != GQLA_OK) return st;
   if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
@@ -350,8 +352,46 @@ gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent,
   a.d_r = shape->d_r;
   a.group_begin = group_begin;
   a.group_count = group_count;
+  a.tail = tail;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, ws, s) : launch_expand_f32(a, s);
+  hipError_t e;
+  if (tail > 0) e = shape->dtype == GQLA_BF16 ? launch_expand_tail_bf16(a, ws, s) : launch_expand_tail_f32(a, s);
+  else e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, ws, s) : launch_expand_f32(a, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+}  // namespace
+
+gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                              int32_t group_begin, int32_t group_count, const gqla_cache* expanded, void* ws,
+                              size_t ws_bytes, void* stream) {
+  return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, 0, ws, ws_bytes, stream);
+}
+
+gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                                   int32_t group_begin, int32_t group_count, const gqla_cache* expanded,
+                                   int32_t tail_tokens, void* ws, size_t ws_bytes, void* stream) {
+  if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
+  return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, ws, ws_bytes, stream);
+}
+
+gqla_status gqla_append_latent(const gqla_shape* shape, const void* rows, const gqla_cache* latent, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!rows || !latent || !latent->pool || !latent->seq_lens) return GQLA_ERR_NULL;
+  if (!aligned16(rows) || !aligned16(latent->pool)) return GQLA_ERR_ALIGN;
+  st = check_page_size(shape, latent->page_size);
+  if (st != GQLA_OK) return st;
+  if (latent->max_pages <= 0 || latent->num_pages <= 0) return GQLA_ERR_PAGE;
+  if (!latent->page_table && (int64_t)latent->num_pages < (int64_t)shape->batch * latent->max_pages) return GQLA_ERR_PAGE;
+  if (shape->batch == 0) return GQLA_OK;
+  AppendArgs a;
+  a.rows = rows;
+  a.latent = view_of(latent);
+  a.seq_lens = latent->seq_lens;
+  a.B = shape->batch;
+  a.s_q = shape->s_q;
+  a.row_bytes = (shape->r_kv + shape->d_r) * (shape->dtype == GQLA_BF16 ? 2 : 4);
+  const hipError_t e = launch_append_latent(a, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 

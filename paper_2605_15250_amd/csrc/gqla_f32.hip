@@ -231,8 +231,61 @@ __global__ void expand_f32_kernel(ExpandArgs a) {
   }
 }
 
+// Cache switch for the last a.tail positions of every sequence, fp32: one workgroup per (tail token, sequence).
+__global__ void expand_tail_f32_kernel(ExpandArgs a) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  const int L = a.seq_lens[b];
+  const int pos = L - a.tail + t;
+  if (pos < 0) return;
+  const int P = a.latent.page_size;
+  const int32_t pg_in = page_of(a.latent, b, pos / P);
+  const int32_t pg_out = page_of(a.expanded, b, pos / P);
+  if (pg_in < 0 || pg_out < 0) return;
+  const int W = a.r_kv + a.d_r;
+  const int gc = a.group_count;
+  const int slot = pos % P;
+  const float* c = (const float*)a.latent.pool + ((int64_t)pg_in * P + slot) * W;
+  float* out = (float*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * a.d_h + a.d_r);
+  const int per_tok = 2 * gc * a.d_h + a.d_r;
+  for (int e = threadIdx.x; e < per_tok; e += blockDim.x) {
+    if (e < 2 * gc * a.d_h) {
+      const int kind = e / (gc * a.d_h), jj = (e / a.d_h) % gc, d = e % a.d_h;
+      const float* w = (const float*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * a.r_kv * a.d_h;
+      float acc = 0.f;
+      for (int r = 0; r < a.r_kv; ++r) acc += w[(int64_t)r * a.d_h + d] * c[r];
+      if (kind == 0) out[((int64_t)(jj * (a.d_h / 8) + d / 8) * P + slot) * 8 + d % 8] = acc;
+      else out[(int64_t)gc * P * a.d_h + ((int64_t)(jj * (P / 8) + slot / 8) * a.d_h + d) * 8 + slot % 8] = acc;
+    } else {
+      const int d = e - 2 * gc * a.d_h;
+      out[(int64_t)2 * gc * P * a.d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8] = c[a.r_kv + d];
+    }
+  }
+}
+
+// The step's latent rows into their cache slots (any element type: rows are copied as 16-byte vectors).
+// One workgroup per (step token, sequence).
+__global__ void append_latent_kernel(AppendArgs a) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  const int pos = a.seq_lens[b] - a.s_q + t;
+  if (pos < 0) return;
+  const int P = a.latent.page_size;
+  const int32_t pg = page_of(a.latent, b, pos / P);
+  if (pg < 0) return;
+  const u32x4* src = (const u32x4*)((const char*)a.rows + ((int64_t)b * a.s_q + t) * a.row_bytes);
+  u32x4* dst = (u32x4*)((char*)a.latent.pool + ((int64_t)pg * P + pos % P) * a.row_bytes);
+  for (int i = threadIdx.x; i < a.row_bytes / 16; i += blockDim.x) dst[i] = src[i];
+}
+
 }  // namespace
 
+hipError_t launch_expand_tail_f32(const ExpandArgs& a, hipStream_t s) {
+  expand_tail_f32_kernel<<<dim3(a.tail, a.B), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+hipError_t launch_append_latent(const AppendArgs& a, hipStream_t s) {
+  append_latent_kernel<<<dim3(a.s_q, a.B), 128, 0, s>>>(a);
+  return hipGetLastError();
+}
 hipError_t launch_absorb_query_f32(const AbsorbQueryArgs& a, hipStream_t s) {
   absorb_query_f32_kernel<<<dim3(a.h_q, a.rows), 64, 0, s>>>(a);
   return hipGetLastError();

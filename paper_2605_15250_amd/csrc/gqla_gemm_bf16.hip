@@ -75,16 +75,29 @@ __device__ __forceinline__ void mfma_results_ready(f32x16& c0, f32x16& c1, f32x1
 //   W_kind[group_begin + jj][r = 16*ks + 8*h + i][d = 64*mtp + 32*e + m],
 // i.e. each 1 KB block is one A fragment of W^T (or, with the same register contents, one B fragment of W), and each
 // (matrix, 64-column half) is one contiguous 64 KB "stage".
+// One workgroup per (stage, 4 k-steps): a [64 latent dims][64 columns] tile of W goes through LDS, read with whole
+// 16-byte vectors along the rows and written as whole fragments.
 template <int DH, int RKV>
 __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __bf16* packed) {
+  constexpr int KS = RKV / 16;
+  __shared__ __attribute__((aligned(16))) __bf16 tile[64][64 + 8];  // rows padded by one vector: column reads spread over the banks
   const int stage = blockIdx.x;  // (jj*2 + kind)*2 + mtp
+  const int kq = blockIdx.y;     // k-steps 4*kq .. 4*kq + 3
   const int mtp = stage & 1, kind = (stage >> 1) & 1, jj = stage >> 2;
-  const __bf16* w = (const __bf16*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * RKV * DH;
-  __bf16* out = packed + (int64_t)stage * (RKV / 16) * 2 * 512;
-  for (int idx = threadIdx.x; idx < (RKV / 16) * 2 * 512; idx += 256) {
-    const int i = idx & 7, lane = (idx >> 3) & 63, e = (idx >> 9) & 1, ks = idx >> 10;
+  const __bf16* w = (const __bf16*)(kind ? a.w_uv : a.w_uk) + ((int64_t)(a.group_begin + jj) * RKV + 64 * kq) * DH + 64 * mtp;
+  for (int v = threadIdx.x; v < 512; v += 256) {
+    const int r = v >> 3, c = (v & 7) * 8;
+    *(u32x4*)&tile[r][c] = *(const u32x4*)(w + (int64_t)r * DH + c);
+  }
+  __syncthreads();
+  __bf16* out = packed + (int64_t)stage * KS * 2 * 512 + (int64_t)(4 * kq) * 2 * 512;
+  for (int v = threadIdx.x; v < 512; v += 256) {
+    const int lane = v & 63, e = (v >> 6) & 1, ksl = v >> 7;
     const int m = lane & 31, h = lane >> 5;
-    out[idx] = w[(int64_t)(16 * ks + 8 * h + i) * DH + 64 * mtp + 32 * e + m];
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = tile[16 * ksl + 8 * h + i][32 * e + m];
+    *(bf16x8*)(out + (ksl * 2 + e) * 512 + lane * 8) = o;
   }
 }
 
@@ -256,12 +269,87 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   for (int piece = 0; piece < 8; ++piece) store_prev(1, 1, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
 }
 
+// ---- cache expansion of the last a.tail positions of every sequence (the step's new tokens) ------------------------
+// The B * tail tokens form one list (index = b * tail + t) cut into 32-token tiles; a workgroup is one packed weight
+// stage (64 output columns of one group's W_UK or W_UV, see pack_weights_bf16_kernel) times 64 tokens, wave w taking
+// the 32-column half w & 1 and the token tile w >> 1:
+//   K^T[d][tok] = W_UK^T[d][r] * C^T[r][tok]   and   V^T[d][tok] = W_UV^T[d][r] * C^T[r][tok]
+//   A = packed weight fragment straight from global memory (1 KB, contiguous), B = the tokens' latent rows, gathered
+//   (lane = token, 8 consecutive latent dims per k-step).
+// Tokens of a tile belong to different sequences and pages, so results go out as 8-byte (K plane: 4 consecutive dims
+// of one token) and 2-byte (V plane: one token's element of an 8-token vector) stores; with a few hundred tokens per
+// step that is a few hundred KB.  The first stage's workgroups also copy the tokens' k_R.
+template <int DH, int RKV, int DR>
+__global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, const __bf16* packed) {
+  constexpr int W = RKV + DR;
+  constexpr int KS = RKV / 16;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int stage = blockIdx.x;  // (jj*2 + kind)*2 + mtp
+  const int mtp = stage & 1, kind = (stage >> 1) & 1, jj = stage >> 2;
+  const int e = wave & 1;
+  const int idx = blockIdx.y * 64 + (wave >> 1) * 32 + n;  // this lane's token in the list
+  const int P = a.latent.page_size;
+  const int gc = a.group_count;
+  bool ok = idx < a.B * a.tail;
+  int b = 0, pos = 0;
+  if (ok) {
+    b = idx / a.tail;
+    pos = a.seq_lens[b] - a.tail + idx % a.tail;
+    ok = pos >= 0;
+  }
+  int32_t pg_in = -1, pg_out = -1;
+  if (ok) {
+    pg_in = page_of(a.latent, b, pos / P);
+    pg_out = page_of(a.expanded, b, pos / P);
+    ok = pg_in >= 0 && pg_out >= 0;
+  }
+  const int slot = ok ? pos % P : 0;
+  // a lane without a token reads row 0 of page 0 (valid memory); its MFMA column is never stored
+  const __bf16* row = (const __bf16*)a.latent.pool + ((int64_t)(ok ? pg_in : 0) * P + slot) * W;
+  const __bf16* wf = packed + (int64_t)stage * KS * 2 * 512 + e * 512 + lane * 8;
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll 8
+  for (int ks = 0; ks < KS; ++ks)
+    acc = mfma32(*(const bf16x8*)(wf + (int64_t)ks * 1024), *(const bf16x8*)(row + ks * 16 + h * 8), acc);
+  if (!ok) return;
+  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * DH + DR);
+  const int d0 = 64 * mtp + 32 * e;  // register i holds dim d0 + 8*(i/4) + 4*h + i%4 of this lane's token
+  if (kind == 0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const u32x2 v = {pack_bf16(acc[4 * q], acc[4 * q + 1]), pack_bf16(acc[4 * q + 2], acc[4 * q + 3])};
+      *(u32x2*)(out_page + ((int64_t)(jj * (DH / 8) + d0 / 8 + q) * P + slot) * 8 + 4 * h) = v;
+    }
+  } else {
+    __bf16* vp = out_page + (int64_t)gc * P * DH + ((int64_t)(jj * (P / 8) + slot / 8) * DH) * 8 + slot % 8;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vp[(int64_t)(d0 + 8 * (i >> 2) + 4 * h + (i & 3)) * 8] = (__bf16)acc[i];
+  }
+  if (stage == 0 && e == 0) {  // k_R of this token: dims 8*c .. 8*c + 7 for c = h, h + 2, ...
+    __bf16* rp = out_page + (int64_t)2 * gc * P * DH;
+#pragma unroll
+    for (int c = h; c < DR / 8; c += 2) *(u32x4*)(rp + ((int64_t)c * P + slot) * 8) = *(const u32x4*)(row + RKV + c * 8);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   const int rows_per_group = a.rows * a.G;
   dim3 grid((rows_per_group + 31) / 32, (512 / 128 + 3) / 4, a.g);
   absorb_query_bf16_kernel<128, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_tail_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
+  const int tokens = a.B * a.tail;
+  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_tail_bf16_kernel<128, 512, 64><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }
 
@@ -276,7 +364,7 @@ hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
   }
   const int64_t max_tokens = (int64_t)a.latent.max_pages * a.latent.page_size;
   dim3 grid((unsigned)((max_tokens + 255) / 256), a.B);
-  pack_weights_bf16_kernel<128, 512><<<a.group_count * 4, 256, 0, s>>>(a, (__bf16*)ws);
+  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   expand_bf16_kernel<128, 512, 64><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);

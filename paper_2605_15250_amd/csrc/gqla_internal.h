@@ -55,6 +55,14 @@ struct ExpandArgs {
   const void* w_uk;
   const void* w_uv;
   int32_t B, g, d_h, r_kv, d_r, group_begin, group_count;
+  int32_t tail;  // tail variants only: positions L_b - tail .. L_b - 1 of every sequence
+};
+
+struct AppendArgs {
+  const void* rows;  // [B][s_q][row_bytes]
+  CacheView latent;
+  const int32_t* seq_lens;
+  int32_t B, s_q, row_bytes;
 };
 
 struct AbsorbQueryArgs {
@@ -82,6 +90,9 @@ hipError_t launch_combine_project_f32(const CombineArgs&, hipStream_t);         
 hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);                 // bf16 latent partials, bf16 out
 hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*group_count*r_kv*d_h bf16 */, hipStream_t);
+hipError_t launch_expand_tail_f32(const ExpandArgs&, hipStream_t);
+hipError_t launch_expand_tail_bf16(const ExpandArgs&, void* ws /* as above */, hipStream_t);
+hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t);
 hipError_t launch_probe_mfma(uint32_t* sink, int iters, int blocks, hipStream_t);

@@ -118,6 +118,18 @@ class Decoder:
                             self.expanded_cache(), self.ws_e)
         return self.expanded_pool
 
+    def expand_tail(self, w_uk, w_uv, tail_tokens):
+        if self.ws_e is None:
+            nbytes = B.gqla_expand_workspace_bytes(self.shape, self.groups)
+            self.ws_e = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+        B.gqla_expand_cache_tail(self.shape, self.latent_cache(), w_uk, w_uv, self.group_begin, self.groups,
+                                 self.expanded_cache(), tail_tokens, self.ws_e)
+        return self.expanded_pool
+
+    def append_latent(self, rows):
+        """rows: [B, s_q, r_kv + d_r] contiguous, the cache's element type."""
+        B.gqla_append_latent(self.shape, rows, self.latent_cache())
+
     def decode_gqa(self, q_c, q_r, out=None, lse=None):
         """q_c, q_r: [B, s_q, heads of the slice, d] contiguous."""
         c = self.cfg

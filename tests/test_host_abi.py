@@ -142,6 +142,16 @@ def test_argument_validation_happens_on_the_host():
         full = B.make_cache(A, A, None, 64, 4, 8, 8)
         _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, full, None, 0, stream=0)
         _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache, ok, lat, A, A, 0, 8, full, A, 2 * 8 * 512 * 128 * 2 - 1, stream=0)
+        # the per-step cache updates: the tail expansion takes the same checks plus 1 <= tail_tokens <= page_size
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 0, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 65, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 6, 3, B.make_cache(A, A, None, 64, 4, 8, 3), 1, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 2, None, 0, stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_append_latent, ok, None, lat, stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_append_latent, ok, A, B.make_cache(A, None, None, 64, 4, 8, 0), stream=0)
+        _expect(B.GQLA_ERR_ALIGN, B.gqla_append_latent, ok, A + 4, lat, stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_append_latent, ok, A, B.make_cache(A, A, None, 48, 4, 8, 0), stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_append_latent, ok, A, B.make_cache(A, A, None, 64, 4, 7, 0), stream=0)
     finally:
         B.gqla_plan_destroy(plan_a)
         B.gqla_plan_destroy(plan_g)
@@ -152,6 +162,9 @@ def test_empty_batch_is_ok_without_launch():
     sh = B.make_shape(0, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
     A = 0x10000
     B.gqla_absorb_query(sh, A, A, A, stream=0)      # returns GQLA_OK, launches nothing
+    lat = B.make_cache(A, A, None, 64, 4, 8, 0)
+    B.gqla_append_latent(sh, A, lat, stream=0)
+    B.gqla_expand_cache_tail(sh, lat, A, A, 0, 8, B.make_cache(A, A, None, 64, 4, 8, 8), 1, A, 1 << 24, stream=0)
     p = B.gqla_plan_create(sh, [], 64, 256, B.GQLA_PATH_GQA)
     assert B.gqla_plan_num_chunks(p) == 0
     B.gqla_plan_destroy(p)
