@@ -98,6 +98,15 @@ def test_plan_known_cases():
     # canonical uniform cases: one chunk per compute unit
     assert Lay.plan_chunk_pages([8192] * 64, 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 32
     assert Lay.plan_chunk_pages([4096] * 32, 64, 256, Lay.PATH_GQA, 32, 8, 1) == 8
+    # one 8192-token sequence (128 pages) on 256 compute units, costs by hand in sixteenths of a page time
+    # (16 * rounds * (cp + overhead) + merge * chunks of the sequence):
+    #   absorb (overhead 4, merge 4): cp 5 -> 16*9 + 4*26 = 248, cp 6 -> 16*10 + 4*22 = 248, cp 7 -> 16*11 + 4*19 = 252,
+    #   cp 4 -> 16*8 + 4*32 = 256; the tie goes to the larger chunk
+    assert Lay.plan_chunk_pages([8192], 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 6
+    #   gqa (overhead 2, merge 1): cp 2 -> 64 + 64 = 128, cp 3 -> 80 + 43 = 123, cp 4 -> 96 + 32 = 128
+    assert Lay.plan_chunk_pages([8192], 64, 256, Lay.PATH_GQA, 128, 8, 1) == 3
+    # without the merge term both would be cut into one-page chunks: a longer chain of partials costs more than it saves
+    assert Lay.plan_chunk_pages([65536], 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 16   # 16*20 + 4*64 = 576 < cp 8: 16*12 + 4*128 = 704
     chunks, first = Lay.plan_chunks([130, 64], 64, 2)
     assert chunks == [(0, 0, 128), (0, 128, 130), (1, 0, 64)] and first == [0, 2]
     chunks, _ = Lay.plan_chunks([64 * 5], 64, 2)              # 5 pages, cp 2 -> 3 chunks of 2,2,1
