@@ -120,29 +120,6 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   // exchange barrier, so none may skip a tile).
   const bool wave_active = SPLIT > 1 || rbk * RPB + team * 32 < a.M;
 
-  // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step; this wave's
-  // k-steps are 4*a4 + part*KB + b
-  bf16x8 qf[KS / SPLIT];
-  {
-    const int64_t qrow = (int64_t)ce.b * a.M + min(rho, a.M - 1);
-    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8 + part * KB * 16;
-    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8 + part * KB * 16;
-#pragma unroll
-    for (int a4 = 0; a4 < KS / 4; ++a4)
-#pragma unroll
-      for (int b = 0; b < KB; ++b)
-        qf[a4 * KB + b] = *(const bf16x8*)((a4 < RKV / 64 ? ph + a4 * 64 : pr + (a4 - RKV / 64) * 64) + b * 16);
-  }
-
-  // The query loads are made to complete here, before any tile is requested.  Otherwise the compiler, which counts
-  // only the loads it issued itself, keeps "wait for the query loads" counts in front of the loop's first MFMAs; on
-  // the hardware counter those waits would also cover the tile requests in flight and drain the ring on every tile.
-#pragma unroll
-  for (int k = 0; k < KS / SPLIT; k += 9)
-    asm volatile("" : "+v"(qf[k]), "+v"(qf[k + 1]), "+v"(qf[k + 2]), "+v"(qf[k + 3]), "+v"(qf[k + 4]), "+v"(qf[k + 5]),
-                      "+v"(qf[k + 6]), "+v"(qf[k + 7]), "+v"(qf[k + 8]));
-  static_assert((KS / SPLIT) % 9 == 0, "query fragments are touched nine at a time");
-
   const int P = a.cache.page_size;
   const char* pool = (const char*)a.cache.pool;
   // Tiles are always staged whole: rows past the chunk end still come from the page (allocated memory), an
@@ -188,10 +165,16 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   {
     const int p_last = (ce.tok_end - 1) / P;
     int32_t raw[4];
+    if (table_row) {  // four scalar loads in flight together, one wait
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int p = min(ce.tok_begin / P + (k * kTile) / P, p_last);
-      raw[k] = table_row ? table_row[p] : ce.b * a.cache.max_pages + p;
+      for (int k = 0; k < 4; ++k) {
+        const int p = __builtin_amdgcn_readfirstlane(min(ce.tok_begin / P + (k * kTile) / P, p_last));
+        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(raw[k]) : "s"(table_row + p) : "memory");
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(raw[0]), "+s"(raw[1]), "+s"(raw[2]), "+s"(raw[3]) : : "memory");
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) raw[k] = ce.b * a.cache.max_pages + min(ce.tok_begin / P + (k * kTile) / P, p_last);
     }
     pg0 = checked(raw[0]);
     pg1 = n_tiles > 1 ? checked(raw[1]) : -1;
@@ -208,6 +191,32 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg0, 0), wave, lane);
   if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB>(smem + TILE_BYTES, tile_src(pg1, kTile % P), wave, lane);
   if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB>(smem + 2 * TILE_BYTES, tile_src(pg2, (2 * kTile) % P), wave, lane);
+
+  // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step; this wave's
+  // k-steps are 4*a4 + part*KB + b
+  bf16x8 qf[KS / SPLIT];
+  {
+    const int64_t qrow = (int64_t)ce.b * a.M + min(rho, a.M - 1);
+    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8 + part * KB * 16;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8 + part * KB * 16;
+#pragma unroll
+    for (int a4 = 0; a4 < KS / 4; ++a4)
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+        qf[a4 * KB + b] = *(const bf16x8*)((a4 < RKV / 64 ? ph + a4 * 64 : pr + (a4 - RKV / 64) * 64) + b * 16);
+  }
+
+  // The query loads go out behind the first tile requests (one memory latency for both) and are made to complete
+  // here, before the loop.  Otherwise the compiler, which counts only the loads it issued itself, keeps "wait for
+  // the query loads" counts in front of the loop's first MFMAs; on the hardware counter those waits would also
+  // cover the tile requests in flight and drain the ring on every tile.  (The wait that the compiler places here
+  // covers the three tiles requested above as well; the loop's own counted waits then pass at once for them.)
+#pragma unroll
+  for (int k = 0; k < KS / SPLIT; k += 9)
+    asm volatile("" : "+v"(qf[k]), "+v"(qf[k + 1]), "+v"(qf[k + 2]), "+v"(qf[k + 3]), "+v"(qf[k + 4]), "+v"(qf[k + 5]),
+                      "+v"(qf[k + 6]), "+v"(qf[k + 7]), "+v"(qf[k + 8]));
+  static_assert((KS / SPLIT) % 9 == 0, "query fragments are touched nine at a time");
+
 #pragma unroll 1
   for (int it = 0; it < n_tiles; ++it) {
     const int tok = ce.tok_begin + it * kTile;

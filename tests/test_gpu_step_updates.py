@@ -83,9 +83,10 @@ def test_append_then_tail_expand_then_decode(key, lens, page_size, s_q):
 
 
 def test_tail_expand_of_a_group_slice():
-    """One rank's share under head-axis tensor parallelism: 2 of 8 groups, 3 tail tokens."""
-    cfg = S.CONFIGS["C3"].with_(B=3, L=0, paged=True, seed=1618)
-    case = Case(cfg, lens=[200, 3, 70], groups=2, group_begin=5)
+    """One rank's share under head-axis tensor parallelism: 2 of 8 groups, 3 tail tokens; one sequence is shorter than
+    the tail (its positions below 0 do not exist and nothing is written for them)."""
+    cfg = S.CONFIGS["C3"].with_(B=4, L=0, paged=True, seed=1618)
+    case = Case(cfg, lens=[200, 3, 70, 2], groups=2, group_begin=5)
     dec = case.dec
     try:
         tail, gc, j0 = 3, 2, 5
@@ -94,14 +95,15 @@ def test_tail_expand_of_a_group_slice():
         dec.expand_tail(case.d_w_uk, case.d_w_uv, tail)
         torch.cuda.synchronize()
         pool_h = host(dec.expanded_pool)
-        assert int(np.isnan(pool_h).sum()) == pool_h.size - cfg.B * tail * per_tok
+        assert int(np.isnan(pool_h).sum()) == pool_h.size - int(np.minimum(case.lens, tail).sum()) * per_tok
         for b in range(cfg.B):
             L = int(case.lens[b])
             KC, V = O.expand_latent(case.c(b), case.w_uk[j0:j0 + gc], case.w_uv[j0:j0 + gc])
             k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], L, cfg.page_size, gc, cfg.d_h, cfg.d_r)
-            assert np.isnan(k2[:L - tail]).all() and np.isnan(v2[:L - tail]).all() and np.isnan(r2[:L - tail]).all()
-            check("K_C tail seq %d" % b, k2[L - tail:], KC[L - tail:], cfg.dtype, scale_abs=2.0)
-            check("V tail seq %d" % b, v2[L - tail:], V[L - tail:], cfg.dtype, scale_abs=2.0)
-            assert np.array_equal(r2[L - tail:], case.kR(b)[L - tail:])
+            lo = max(L - tail, 0)
+            assert np.isnan(k2[:lo]).all() and np.isnan(v2[:lo]).all() and np.isnan(r2[:lo]).all()
+            check("K_C tail seq %d" % b, k2[lo:], KC[lo:], cfg.dtype, scale_abs=2.0)
+            check("V tail seq %d" % b, v2[lo:], V[lo:], cfg.dtype, scale_abs=2.0)
+            assert np.array_equal(r2[lo:], case.kR(b)[lo:])
     finally:
         case.close()
