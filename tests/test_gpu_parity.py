@@ -209,6 +209,35 @@ def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
         case.close()
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        g = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 16]))
+        G = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 32]))
+        if g * G > 128:
+            continue
+        s_q = int(rng.integers(1, 3))
+        page_size = int(rng.choice([64, 128]))
+        lens = [int(x) for x in rng.integers(s_q, 700, size=int(rng.integers(1, 4)))]
+        cases.append((g * G, g, s_q, page_size, lens, bool(rng.integers(0, 2)), (int(rng.integers(0, 4)), int(rng.integers(0, 4)))))
+    return cases
+
+
+@pytest.mark.parametrize("h_q,g,s_q,page_size,lens,paged,cp", _random_cases(12, 20260515))
+def test_bf16_random_shapes(h_q, g, s_q, page_size, lens, paged, cp):
+    """Seeded random draws over what the bf16 kernels accept: group counts with and without k_R sharing, 1 to 32 heads
+    per group (1 to 64 rows per group, 1 to 256 query rows per sequence), both page sizes, ragged lengths, forced
+    chunk sizes, permuted or identity page tables."""
+    cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, page_size=page_size, seed=9000 + h_q + g)
+    case = Case(cfg, lens=lens, use_page_table=paged, chunk_pages=cp)
+    try:
+        run_absorb_path(case)
+        run_gqa_path(case)
+    finally:
+        case.close()
+
+
 @pytest.mark.parametrize("cp", [(0, 0), (1, 1)])
 def test_bf16_length_sweep(cp):
     """Every length from s_q to s_q + 160 in one batch: one to six tiles per chunk in the absorb kernel's tile ring
