@@ -73,7 +73,8 @@ __device__ __forceinline__ void acc_read(int dt, bool wait, float (&x)[16]) {
 }
 
 // SPLIT = 1: the layout above.  SPLIT = 4 (at most 32 query rows per sequence, e.g. one rank's heads under tensor
-// parallelism): the four waves share the one block of 32 rows instead of three of them having no rows.  A wave of
+// parallelism; or so few chunks that one workgroup per 32 rows still fits the chip in one round): the four waves
+// share a block of 32 rows instead of owning 32 rows each.  A wave of
 // the team contracts a quarter of the key dimension (k-step `part` of each 4-step panel), the team sums its partial
 // S^T through LDS (every wave adds them in the same order, so all hold the same bits), each wave runs the same
 // softmax and then updates its own RKV/4 slice of O^T.  With so few rows the kernel is bound by the rate at which
@@ -116,8 +117,8 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   const int t = row_ok ? rho / a.h_q : 0;
   const int vis_end = row_ok ? min(ce.tok_end, ce.L - a.s_q + t + 1) : 0;
   const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);
-  // With SPLIT > 1 the launcher sends a single row block whose every team has rows (all waves meet at the team's
-  // exchange barrier, so none may skip a tile).
+  // With SPLIT > 1 a workgroup is one team, and the launcher only makes row blocks that have rows (all waves meet
+  // at the team's exchange barrier, so none may skip a tile).
   const bool wave_active = SPLIT > 1 || rbk * RPB + team * 32 < a.M;
 
   const int P = a.cache.page_size;
@@ -600,8 +601,12 @@ static hipError_t launch_decode_absorb_split(const DecodeArgs& a, hipStream_t s)
 }
 
 hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
-  // at most 32 query rows: the four waves share them, so that none is left without work (a single row block)
-  if (a.M <= 32) return launch_decode_absorb_split<4>(a, s);
+  // At most 32 query rows: the four waves share them, so that none is left without work.  More rows but few chunks
+  // (small batches): one workgroup per (chunk, 32 rows) with the four waves sharing its rows, as long as all of them
+  // still run at once -- four times the workgroups, each with a shorter tile (the tiles' re-reads hit the L2, and
+  // with so few chunks the chip is nowhere near its memory rate).
+  const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
+  if (a.M <= 32 || chunks_padded * ((a.M + 31) / 32) <= a.num_cus) return launch_decode_absorb_split<4>(a, s);
   return launch_decode_absorb_split<1>(a, s);
 }
 

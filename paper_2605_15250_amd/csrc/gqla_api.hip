@@ -128,6 +128,7 @@ DecodeArgs decode_args(const gqla_shape* s, const gqla_plan* plan, const void* q
   a.d_r = s->d_r;
   a.s_q = s->s_q;
   a.M = s->s_q * s->h_q;
+  a.num_cus = plan->num_cus;
   a.scale_log2e = resolved_scale(s) * 1.4426950408889634f;
   return a;
 }

@@ -34,6 +34,7 @@ struct DecodeArgs {
   void* part_o;      // GQA: fp32 [chunks][M][d_h];  absorb bf16: bf16 [chunks][M][r_kv];  absorb f32: fp32 [chunks][M][r_kv]
   float* part_lse;   // fp32 [chunks][M], natural log
   int32_t B, h_q, g, G, d_h, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i
+  int32_t num_cus;                               // compute units the plan was made for (launch-shape choices only)
   float scale_log2e;                             // softmax scale times log2(e)
 };
 

@@ -43,7 +43,7 @@ class Decoder:
     """Holds the device-resident state of one configuration and runs the four entry points on it."""
 
     def __init__(self, cfg, lens, table, num_pages, groups=None, group_begin=0, use_page_table=True,
-                 chunk_pages_absorb=0, chunk_pages_gqa=0):
+                 chunk_pages_absorb=0, chunk_pages_gqa=0, num_cus=NUM_CUS):
         self.cfg = cfg
         self.lens = np.ascontiguousarray(lens, dtype=np.int32)
         self.table = np.ascontiguousarray(table, dtype=np.int32)
@@ -58,8 +58,8 @@ class Decoder:
                                       lib_dtype(cfg.dtype), 0.0)
         self.d_lens = torch.from_numpy(self.lens).cuda()
         self.d_table = torch.from_numpy(self.table).cuda() if use_page_table else None
-        self.plan_a = B.gqla_plan_create(self.shape, self.lens, cfg.page_size, NUM_CUS, B.GQLA_PATH_ABSORB, chunk_pages_absorb)
-        self.plan_g = B.gqla_plan_create(self.shape_gqa, self.lens, cfg.page_size, NUM_CUS, B.GQLA_PATH_GQA, chunk_pages_gqa)
+        self.plan_a = B.gqla_plan_create(self.shape, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_ABSORB, chunk_pages_absorb)
+        self.plan_g = B.gqla_plan_create(self.shape_gqa, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_GQA, chunk_pages_gqa)
         self.ws_a = torch.empty(B.gqla_plan_workspace_bytes(self.plan_a), dtype=torch.uint8, device="cuda")
         self.ws_g = torch.empty(B.gqla_plan_workspace_bytes(self.plan_g), dtype=torch.uint8, device="cuda")
         B.gqla_plan_upload(self.plan_a, self.ws_a)

@@ -39,7 +39,7 @@ def host(t):
 class Case:
     """Host copies of everything plus the device-side Decoder."""
 
-    def __init__(self, cfg, lens=None, groups=None, group_begin=0, use_page_table=True, chunk_pages=(0, 0)):
+    def __init__(self, cfg, lens=None, groups=None, group_begin=0, use_page_table=True, chunk_pages=(0, 0), num_cus=256):
         from paper_2605_15250_amd.harness import Decoder, to_device, build_latent_pool
         self.cfg = cfg
         self.lens = S.seq_lens(cfg) if lens is None else np.asarray(lens, np.int32)
@@ -49,7 +49,8 @@ class Case:
         self.q_c, self.q_r = S.queries(cfg)
         self.rows = [S.sequence_rows(cfg, b, self.lens[b]) for b in range(cfg.B)]
         self.dec = Decoder(cfg, self.lens, self.table, self.num_pages, groups=groups, group_begin=group_begin,
-                           use_page_table=use_page_table, chunk_pages_absorb=chunk_pages[0], chunk_pages_gqa=chunk_pages[1])
+                           use_page_table=use_page_table, chunk_pages_absorb=chunk_pages[0], chunk_pages_gqa=chunk_pages[1],
+                           num_cus=num_cus)
         self.dec.latent_pool = build_latent_pool(cfg, self.lens, self.table, self.num_pages, lambda b, L: self.rows[b])
         self.d_w_uk = to_device(self.w_uk, cfg.dtype)
         self.d_w_uv = to_device(self.w_uv, cfg.dtype)
@@ -199,9 +200,12 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (128, 4, 2, [700, 65], True, (0, 0)),                # (g, s_q) = (4, 2) at 128 heads: G = 32, 64 rows per group
     (128, 4, 1, [321], False, (0, 0)),                   # (g, s_q) = (4, 1), the 2176-byte-per-token operating point
 ])
-def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp):
+@pytest.mark.parametrize("num_cus", [256, 2])   # planned for the whole chip, or for a sliver of it: with few chunks and
+                                                # many compute units the absorb decode gives every 32 query rows a
+                                                # workgroup of their own, otherwise 128 rows share one
+def test_bf16_small_batches(h_q, g, s_q, lens, paged, cp, num_cus):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=4242 + h_q + s_q)
-    case = Case(cfg, lens=lens, use_page_table=paged, chunk_pages=cp)
+    case = Case(cfg, lens=lens, use_page_table=paged, chunk_pages=cp, num_cus=num_cus)
     try:
         run_absorb_path(case)
         run_gqa_path(case)
@@ -268,8 +272,9 @@ def test_bf16_page_sizes(page_size, lens):
         case.close()
 
 
-@pytest.mark.parametrize("h_q", [128, 32, 16])   # absorb kernel: one, two and four waves per 32 query rows
-def test_bf16_growing_logits(monkeypatch, h_q):
+@pytest.mark.parametrize("h_q,num_cus", [(128, 2), (128, 256), (16, 256)])   # absorb kernel: one wave per 32 query
+                                                                              # rows, or four sharing them
+def test_bf16_growing_logits(monkeypatch, h_q, num_cus):
     """Logits that keep growing along the sequence and reach far beyond the usual range: the reference maximum of the
     absorb kernel's online softmax has to move many times (it only moves in steps of more than 2^8), and both kernels
     must keep their exponentials in range.  The RoPE key of a cached token (which enters the logits only, so the outputs
@@ -285,7 +290,7 @@ def test_bf16_growing_logits(monkeypatch, h_q):
 
     monkeypatch.setattr(S, "sequence_rows", growing_rows)
     cfg = S.CONFIGS["C3"].with_(B=2, h_q=h_q, L=0, paged=True, seed=8128)
-    case = Case(cfg, lens=[1500, 333])
+    case = Case(cfg, lens=[1500, 333], num_cus=num_cus)
     try:
         run_absorb_path(case)
         run_gqa_path(case)
