@@ -192,7 +192,8 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (64, 4, 1, [900, 333], True, (0, 0)),                # g = 4 (2176 bytes per token, Sec. 4.2.3): 4-wave workgroups
     (32, 2, 2, [450, 64], True, (2, 2)),                 # g = 2: 2-wave workgroups, each wave stages two k_R slabs
     (48, 3, 1, [300], True, (0, 0)),                     # g = 3: no k_R sharing (direct loads)
-    (128, 8, 1, [20000], True, (0, 0)),                  # one long sequence: the plan cuts it into a few hundred chunks
+    (128, 8, 1, [20000], True, (0, 0)),                  # one long sequence: the plan cuts it into a few dozen chunks
+    (128, 8, 2, [6000, 70], True, (1, 1)),               # forced one-page chunks: 94 partials to merge for one sequence
     (16, 8, 1, [777, 40], True, (0, 0)),                 # one rank's heads under 8-way head parallelism: 16 query rows,
                                                          # four waves share them in the absorb kernel (half its rows padding)
     (16, 4, 2, [2, 300, 1029], True, (1, 2)),            # 32 rows shared by four waves, L == s_q, ragged chunks
