@@ -282,7 +282,10 @@ def main():
                                "absorb_tokens_per_s": Bn * sq_k / t_a, "gqa_tokens_per_s": Bn * sq_k / t_g,
                                "faster_path": "gqa" if t_g < t_a else "absorb",
                                "model_absorb_us": est["absorb_seconds"] * 1e6, "model_gqa_us": est["gqa_seconds"] * 1e6,
-                               "model_faster_path": "gqa" if est["faster_path"] == B.GQLA_PATH_GQA else "absorb"})
+                               "model_faster_path": "gqa" if est["faster_path"] == B.GQLA_PATH_GQA else "absorb",
+                               "calibrated": (lambda ch: {"absorb_us": ch["absorb_seconds"] * 1e6, "gqa_us": ch["gqa_seconds"] * 1e6,
+                                                          "path": "gqa" if ch["faster_path"] == B.GQLA_PATH_GQA else "absorb"})(
+                                   B.gqla_select_path(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls))})
                 dk.close()
                 del dk, o_k, l_k, qh_k
                 torch.cuda.empty_cache()

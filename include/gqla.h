@@ -214,6 +214,20 @@ typedef struct {
 gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, double hbm_bytes_per_s,
                                 double mfma_flops_per_s, gqla_path_estimate* out);
 
+/* The same choice for THIS library's kernels on the MI355X (GQLA_BF16 only; GQLA_ERR_DTYPE otherwise): the paper's
+ * two-roof form with the rates the kernels sustain instead of the chip's peaks, a fixed cost per call, and a floor
+ * that a call's chain of dependent kernels never gets under.  All constants are measurements of this build (the
+ * operating-point and all-config tables under profiles/):
+ *   absorb (query absorption + decode):  max(50 us, 28 us + max(bytes / 5.5 TB/s, flops / 0.95 PFLOP/s))
+ *   gqa    (decode on the expanded cache): max(28 us, 10 us + f * bytes / 6.6 TB/s),
+ *          f = 1 + 0.45 * (ceil(G s_q / 32) - 1): a group's rows beyond 32 stream the cache again, mostly from the caches
+ * with bytes and flops as in gqla_estimate_paths.  faster_path is the path with the smaller time (absorb on a tie). */
+typedef struct {
+  double absorb_seconds, gqa_seconds;
+  int32_t faster_path;   /* gqla_path */
+} gqla_path_choice;
+gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gqla_path_choice* out);
+
 /* Ceiling probes (measurement only; they compute nothing of the method).  The caller times them with events on
  * `stream` and derives  bytes / t  resp.  gqla_probe_mfma_flops(iters, num_cus) / t.
  *   gqla_probe_stream_read: every byte of src[0, bytes) is read once with 16-byte loads by 8 * num_cus workgroups;

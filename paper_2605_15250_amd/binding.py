@@ -21,7 +21,8 @@ GQLA_PATH_ABSORB, GQLA_PATH_GQA = 0, 1
 EXPORTS = [
     "gqla_plan_create", "gqla_plan_destroy", "gqla_plan_num_chunks", "gqla_plan_chunk_pages", "gqla_plan_export",
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
-    "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read", "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths",
+    "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
+    "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -47,6 +48,10 @@ class gqla_path_estimate(C.Structure):
     _fields_ = [("absorb_bytes", C.c_double), ("absorb_flops", C.c_double), ("absorb_intensity", C.c_double),
                 ("absorb_seconds", C.c_double), ("gqa_bytes", C.c_double), ("gqa_flops", C.c_double),
                 ("gqa_intensity", C.c_double), ("gqa_seconds", C.c_double), ("ridge", C.c_double), ("faster_path", C.c_int32)]
+
+
+class gqla_path_choice(C.Structure):
+    _fields_ = [("absorb_seconds", C.c_double), ("gqa_seconds", C.c_double), ("faster_path", C.c_int32)]
 
 
 _lib = None
@@ -87,6 +92,8 @@ def lib():
         L.gqla_append_latent.restype = i32
         L.gqla_estimate_paths.argtypes = [sp, i64, C.c_double, C.c_double, C.POINTER(gqla_path_estimate)]
         L.gqla_estimate_paths.restype = i32
+        L.gqla_select_path.argtypes = [sp, i64, C.POINTER(gqla_path_choice)]
+        L.gqla_select_path.restype = i32
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
         L.gqla_probe_stream_read.restype = i32
         L.gqla_probe_mfma_bf16.argtypes = [vp, i32, i32, vp]
@@ -206,6 +213,12 @@ def gqla_estimate_paths(shape, cached_tokens, hbm_bytes_per_s, mfma_flops_per_s)
     _check(lib().gqla_estimate_paths(C.byref(shape), int(cached_tokens), float(hbm_bytes_per_s), float(mfma_flops_per_s),
                                      C.byref(est)), "gqla_estimate_paths")
     return {name: getattr(est, name) for name, _ in gqla_path_estimate._fields_}
+
+
+def gqla_select_path(shape, cached_tokens) -> dict:
+    ch = gqla_path_choice()
+    _check(lib().gqla_select_path(C.byref(shape), int(cached_tokens), C.byref(ch)), "gqla_select_path")
+    return {name: getattr(ch, name) for name, _ in gqla_path_choice._fields_}
 
 
 def gqla_probe_stream_read(src, nbytes, sink, num_cus, stream=None):

@@ -448,6 +448,24 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
   return GQLA_OK;
 }
 
+gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gqla_path_choice* out) {
+  if (!out) return GQLA_ERR_NULL;
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (cached_tokens < 0) return GQLA_ERR_SHAPE;
+  gqla_path_estimate e;
+  st = gqla_estimate_paths(shape, cached_tokens, 1.0, 1.0, &e);  // only its byte and FLOP counts are used
+  if (st != GQLA_OK) return st;
+  const double row_blocks = (double)(((shape->h_q / shape->g) * shape->s_q + 31) / 32);
+  const double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 0.95e15);
+  const double tg = 10e-6 + (1.0 + 0.45 * (row_blocks - 1.0)) * e.gqa_bytes / 6.6e12;
+  out->absorb_seconds = std::max(50e-6, ta);
+  out->gqa_seconds = std::max(28e-6, tg);
+  out->faster_path = out->gqa_seconds < out->absorb_seconds ? GQLA_PATH_GQA : GQLA_PATH_ABSORB;
+  return GQLA_OK;
+}
+
 gqla_status gqla_probe_stream_read(const void* src, size_t bytes, void* sink, int32_t num_cus, void* stream) {
   if (!src || !sink) return GQLA_ERR_NULL;
   if (!aligned16(src)) return GQLA_ERR_ALIGN;
