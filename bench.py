@@ -23,7 +23,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 CALIB_COPY_BYTES = 1 << 30
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_canonical.json")   # measured with rocprofv3 --pmc, see profiles/
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_canonical_bench.txt")   # measured with rocprofv3 --pmc
+TRAFFIC_ROWS = {"decode_gqa_bf16_kernel": "decode_gqa", "decode_absorb_bf16_kernel": "decode_absorb", "expand_bf16_kernel": "expand_cache"}
 
 
 def parse_args():
@@ -301,8 +302,12 @@ def main():
 
     traffic = {}
     if os.path.exists(TRAFFIC_FILE) and not args.batch and not args.ctx:
+        # rows of the committed summary: kernel, FETCH_SIZE, read MB, WRITE_SIZE, written MB, read/alg
         with open(TRAFFIC_FILE) as fh:
-            traffic = json.load(fh).get("hbm_bytes_per_launch", {})
+            for ln in fh:
+                f = ln.split()
+                if len(f) == 6 and f[0] in TRAFFIC_ROWS:
+                    traffic[TRAFFIC_ROWS[f[0]]] = int(round((float(f[2]) + float(f[4])) * 1e6))
 
     def roof(name, bound, nbytes, flops):
         t = max(call_ms[name], 1e-6) * 1e-3
