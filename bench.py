@@ -134,10 +134,30 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)])) for i, n in enumerate(names)}
 
+    def timed_steady(fn, reps):
+        """Seconds per call over `reps` calls, after at least 40 ms of the same calls: the clock needs some tens of
+        milliseconds of load to settle, and the first calls after an idle gap run up to 15 % slower."""
+        t0 = time.perf_counter()
+        n = 0
+        while n < 3 or time.perf_counter() - t0 < 0.04:
+            fn()
+            n += 1
+            if n % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
     # ---- outside the timed step: measured ceilings of this chip, and one rank's share of 8-way head-axis TP ----------
     measured = None
     tp_slice = None
     step_updates = None
+    fp8_kv = None
     full_run = run_legs >= {"absorb", "gqa"} and "noexpand" not in run_legs
     if full_run and not args.no_extras:
         def timed(fn, reps):
@@ -193,25 +213,21 @@ def main():
         t_app = timed(lambda: gd.append_latent(step_rows), 20)
         t_tail = timed(lambda: gd.expand_tail(Gq["d_w_uk"], Gq["d_w_uv"], cg.s_q), 20)
         step_updates = {"append_latent_ms": t_app * 1e3, "expand_cache_tail_ms": t_tail * 1e3, "tail_tokens": cg.s_q}
-
-    def timed_steady(fn, reps):
-        """Seconds per call over `reps` calls, after at least 40 ms of the same calls: the clock needs some tens of
-        milliseconds of load to settle, and the first calls after an idle gap run up to 15 % slower."""
-        t0 = time.perf_counter()
-        n = 0
-        while n < 3 or time.perf_counter() - t0 < 0.04:
-            fn()
-            n += 1
-            if n % 8 == 0:
-                torch.cuda.synchronize()
+        # the GQA leg over an 8-bit expanded cache (K_C, V as E4M3 codes, k_R in 16 bits): 2176 instead of 4224 bytes
+        # per token; the quantising cache switch is one-shot, like the expansion
+        gd.alloc_expanded_fp8(fill=0)
+        t_q = timed(lambda: gd.quantize_expanded(1.0, 1.0), 5)
+        out8 = torch.empty_like(Gq["out"])
+        t_d8 = timed_steady(lambda: gd.decode_gqa_fp8(Gq["d_q_c"], Gq["d_q_r"], 1.0, 1.0, out8, Gq["lse"]), 20)
+        gd.decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e-3
+        b8 = int(Gq["lens"].sum()) * B.gqla_expanded_fp8_bytes_per_token(cg.g, cg.d_h, cg.d_r)
+        d16 = Gq["out"].float()
+        fp8_kv = {"quantize_expanded_ms": t_q * 1e3, "decode_gqa_fp8_ms": t_d8 * 1e3, "bytes_per_token": b8 // int(Gq["lens"].sum()),
+                  "GB/s": b8 / t_d8 / 1e9, "frac_hbm_peak": b8 / t_d8 / 1e9 / HBM_PEAK_GBS, "tokens_per_s": cg.B * cg.s_q / t_d8,
+                  "rel_l2_vs_16bit_cache": float(torch.linalg.norm(out8.float() - d16) / torch.linalg.norm(d16))}
+        gd.expanded_fp8_pool = None
+        del out8
 
     other = None
     if args.all_configs:
@@ -400,6 +416,7 @@ def main():
         "path_model": path_model,
         "tp_slice": tp_slice,
         "step_updates": step_updates,
+        "fp8_kv": fp8_kv,
         "other_configs": other,
         "operating_points": points,
         "calls_ms": call_ms,

@@ -188,6 +188,31 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
                             const gqla_cache* expanded, void* out, float* lse, void* ws, size_t ws_bytes,
                             void* stream);
 
+/* ---- 8-bit expanded cache for the GQA path --------------------------------------------------------------
+ * The paper names quantised KV caches as complementary to the method and leaves them out of its model (Sec. 2
+ * "Related work"; Sec. 5.1, item (i)); format and scales are this library's.  K_C and V are stored as E4M3 codes of
+ * the OCP 8-bit floating point specification ("FN" variant: bias 7, 3 mantissa bits, subnormals, no infinities,
+ * largest finite value 448), one positive scale per tensor kind:
+ *     code = E4M3(fp32(x) * fp32(1 / scale))   round to nearest, ties to even, magnitudes above 448 saturate
+ *     x'   = value(code) * scale
+ * k_R stays in 16 bits; queries, outputs and the latent cache are GQLA_BF16 (GQLA_ERR_DTYPE otherwise).  A page of P
+ * tokens and g_c groups has P * (2 g_c d_h + 2 d_r) BYTES; every 16-byte vector of the two code planes holds what
+ * one lane of a 32x32x16 matrix instruction consumes in two consecutive k-steps (byte offsets inside the page):
+ *     K8 : [g_c][d_h/16][P][16]      dim d = 32 kp + 16 u + 8 h + i  ->  ((j*(d_h/16) + 2 kp + h)*P + s)*16 + 8 u + i
+ *     V8 : [g_c][P/32][d_h][2][16]   slot s = 32 T + 16 u + 8 h + i  ->  g_c*P*d_h + (((j*(P/32) + T)*d_h + d)*2 + h)*16 + 8 u + i
+ *     k_R: [d_r/8][P][8] 16-bit      2*g_c*P*d_h + (((d/8)*P + s)*8 + d%8)*2
+ * gqla_quantize_expanded converts an expanded cache of the 16-bit format (all groups it holds, every token t < L_b,
+ * L_b read from expanded->seq_lens on the device) into an 8-bit one with the same page geometry and page ids; bytes of
+ * slots no token owns are left as they are.  gqla_decode_gqa_fp8 is gqla_decode_gqa over such a cache (same plan,
+ * workspace and outputs): the codes are widened to bf16 in registers, the scales applied to the content part of the
+ * logits and to the output.  Errors as for the 16-bit calls; scales that are not positive and finite: GQLA_ERR_SHAPE. */
+gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* expanded, const gqla_cache* expanded_fp8,
+                                   float k_scale, float v_scale, void* stream);
+gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
+                                const gqla_cache* expanded_fp8, float k_scale, float v_scale, void* out, float* lse,
+                                void* ws, size_t ws_bytes, void* stream);
+int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r);
+
 /* ---- sizes and diagnostics ------------------------------------------------------------------------------ */
 /* Elements per token of the two caches (Sec. 4.2.1: r_kv + d_r;  Sec. 4.2.2: 2 g d_h + d_r). */
 int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r);

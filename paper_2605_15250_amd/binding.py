@@ -23,6 +23,7 @@ EXPORTS = [
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
+    "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -94,6 +95,12 @@ def lib():
         L.gqla_estimate_paths.restype = i32
         L.gqla_select_path.argtypes = [sp, i64, C.POINTER(gqla_path_choice)]
         L.gqla_select_path.restype = i32
+        L.gqla_quantize_expanded.argtypes = [sp, cp, cp, C.c_float, C.c_float, vp]
+        L.gqla_quantize_expanded.restype = i32
+        L.gqla_decode_gqa_fp8.argtypes = [sp, vp, vp, vp, cp, C.c_float, C.c_float, vp, vp, vp, sz, vp]
+        L.gqla_decode_gqa_fp8.restype = i32
+        L.gqla_expanded_fp8_bytes_per_token.argtypes = [i32, i32, i32]
+        L.gqla_expanded_fp8_bytes_per_token.restype = i64
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
         L.gqla_probe_stream_read.restype = i32
         L.gqla_probe_mfma_bf16.argtypes = [vp, i32, i32, vp]
@@ -262,6 +269,21 @@ def gqla_decode_gqa(shape, plan, q_c, q_r, expanded: gqla_cache, out, lse, ws, w
     nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
     _check(lib().gqla_decode_gqa(C.byref(shape), plan, _ptr(q_c), _ptr(q_r), C.byref(expanded), _ptr(out), _ptr(lse),
                                  _ptr(ws), nbytes, _stream(stream)), "gqla_decode_gqa")
+
+
+def gqla_quantize_expanded(shape, expanded: gqla_cache, expanded_fp8: gqla_cache, k_scale, v_scale, stream=None):
+    _check(lib().gqla_quantize_expanded(C.byref(shape), C.byref(expanded), C.byref(expanded_fp8), float(k_scale), float(v_scale),
+                                        _stream(stream)), "gqla_quantize_expanded")
+
+
+def gqla_decode_gqa_fp8(shape, plan, q_c, q_r, expanded_fp8: gqla_cache, k_scale, v_scale, out, lse, ws, ws_bytes=None, stream=None):
+    nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
+    _check(lib().gqla_decode_gqa_fp8(C.byref(shape), plan, _ptr(q_c), _ptr(q_r), C.byref(expanded_fp8), float(k_scale),
+                                     float(v_scale), _ptr(out), _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_gqa_fp8")
+
+
+def gqla_expanded_fp8_bytes_per_token(groups, d_h, d_r) -> int:
+    return lib().gqla_expanded_fp8_bytes_per_token(groups, d_h, d_r)
 
 
 # ---- sizes ----------------------------------------------------------------------------------------------------------

@@ -410,6 +410,53 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
+gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* expanded, const gqla_cache* expanded_fp8,
+                                   float k_scale, float v_scale, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (!expanded || !expanded_fp8 || !expanded->pool || !expanded_fp8->pool || !expanded->seq_lens) return GQLA_ERR_NULL;
+  if (!aligned16(expanded->pool) || !aligned16(expanded_fp8->pool)) return GQLA_ERR_ALIGN;
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
+  if (expanded->groups <= 0 || expanded->groups > shape->g || expanded->groups != expanded_fp8->groups) return GQLA_ERR_SHAPE;
+  st = check_page_size(shape, expanded->page_size);
+  if (st != GQLA_OK) return st;
+  if (expanded->page_size != expanded_fp8->page_size || expanded->max_pages != expanded_fp8->max_pages ||
+      expanded->max_pages <= 0 || expanded->num_pages <= 0 || expanded_fp8->num_pages <= 0)
+    return GQLA_ERR_PAGE;
+  if (!expanded->page_table && (int64_t)expanded->num_pages < (int64_t)shape->batch * expanded->max_pages) return GQLA_ERR_PAGE;
+  if (!expanded_fp8->page_table && (int64_t)expanded_fp8->num_pages < (int64_t)shape->batch * expanded_fp8->max_pages)
+    return GQLA_ERR_PAGE;
+  if (shape->batch == 0) return GQLA_OK;
+  QuantizeArgs a;
+  a.src = view_of(expanded);
+  a.dst = view_of(expanded_fp8);
+  a.seq_lens = expanded->seq_lens;
+  a.B = shape->batch;
+  a.k_inv_scale = 1.0f / k_scale;
+  a.v_inv_scale = 1.0f / v_scale;
+  const hipError_t e = launch_quantize_expanded(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
+                                const gqla_cache* expanded_fp8, float k_scale, float v_scale, void* out, float* lse,
+                                void* ws, size_t ws_bytes, void* stream) {
+  gqla_status st = check_decode_common(shape, plan, GQLA_PATH_GQA, expanded_fp8, q_c, q_r, out, lse, ws, ws_bytes);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (expanded_fp8->groups != shape->g) return GQLA_ERR_SHAPE;
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
+  if (shape->batch == 0) return GQLA_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded_fp8, ws);
+  const CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
+  hipError_t e = launch_decode_gqa_fp8(a, k_scale, v_scale, s);
+  if (e == hipSuccess) e = launch_combine_f32(c, true, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + 2ll * d_r; }
 int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r) { return (int64_t)r_kv + d_r; }
 int64_t gqla_expanded_elems_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + d_r; }
 int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page_size, int32_t r_kv, int32_t d_r) {

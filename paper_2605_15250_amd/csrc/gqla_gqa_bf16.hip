@@ -15,8 +15,21 @@ namespace gqla {
 
 namespace {
 
-template <int DH, int DR>
-__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg) {
+// FP8 = true: K_C and V are E4M3 codes (16-byte vectors holding one lane's elements of two consecutive k-steps, see
+// the header's format), widened to bf16 in registers right before their MFMAs; the scales enter once per tile (K: on
+// the content part of the logits, before the RoPE part is added) and once per chunk (V: on the normalised output).
+// Half the bytes per token, the same MFMAs.
+__device__ __forceinline__ bf16x8 widen_e4m3(uint32_t w0, uint32_t w1) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+  const u32x4 r = {pack_bf16(a[0], a[1]), pack_bf16(b[0], b[1]), pack_bf16(c[0], c[1]), pack_bf16(d[0], d[1])};
+  return __builtin_bit_cast(bf16x8, r);  // exact: every E4M3 value is a bf16 value
+}
+
+template <int DH, int DR, bool FP8>
+__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg,
+                                                              float k_scale, float v_scale) {
   constexpr int KS_C = DH / 16;  // k-steps over the content dims
   constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
   constexpr int MT = DH / 32;    // 32-dim tiles of the output
@@ -52,10 +65,13 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
 
   const int P = a.cache.page_size;
   const int gc = a.cache.groups;
-  const int64_t page_elems = (int64_t)P * (2 * gc * DH + DR);
-  const __bf16* pool = (const __bf16*)a.cache.pool;
+  constexpr int EB = FP8 ? 1 : 2;                                             // bytes per K_C / V element
+  const int64_t page_bytes = (int64_t)P * (2 * gc * DH * EB + DR * 2);
+  const int64_t kr_plane = (int64_t)2 * gc * DH * P * EB;                      // byte offset of the k_R plane in a page
+  const char* pool = (const char*)a.cache.pool;
 
   bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
+  u32x4 kf8[FP8 ? KS_C / 2 : 1], vf8[FP8 ? MT : 1];                           // raw code vectors (FP8 only)
   bool k_ok = true, v_ok = true;
 
   // The shared RoPE key of a tile is the same for every group.  When all waves of a workgroup are groups of one
@@ -68,7 +84,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);        // position in the workgroup (scalar)
   auto stage_kr = [&](int tok, int32_t pg, int buf) {
     for (int ks = wave; ks < KS_R; ks += wpb) {  // k-step ks: dims 16*ks .. 16*ks + 15
-      const __bf16* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_elems + (int64_t)2 * gc * DH * P + ((int64_t)(2 * ks) * P + tok % P) * 8;
+      const char* src = pool + (int64_t)(pg >= 0 ? pg : 0) * page_bytes + kr_plane + ((int64_t)(2 * ks) * P + tok % P) * 16;
       const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)(kr_lds[buf] + ks * 1024));
       // ("memory": the cache loads that follow must stay behind this request, the counted wait relies on it)
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"((h * P + n) * 16), "s"(src) : "memory");
@@ -76,26 +92,38 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   };
   auto load_k = [&](int tok, int32_t pg) {
     k_ok = pg >= 0;
-    const __bf16* base = pool + (int64_t)(k_ok ? pg : 0) * page_elems;
+    const char* base = pool + (int64_t)(k_ok ? pg : 0) * page_bytes;
     const int slot = tok % P + n;
-    const __bf16* kb = base + (int64_t)j * DH * P + ((int64_t)h * P + slot) * 8;
-    const __bf16* rbp = base + (int64_t)2 * gc * DH * P + ((int64_t)h * P + slot) * 8;
+    const char* kb = base + (int64_t)j * DH * P * EB + ((int64_t)h * P + slot) * 16;   // vector index h (+ 2 per step below)
+    const char* rbp = base + kr_plane + ((int64_t)h * P + slot) * 16;
+    if constexpr (FP8) {
 #pragma unroll
-    for (int ks = 0; ks < KS_C; ++ks) kf[ks] = __builtin_nontemporal_load((const bf16x8*)(kb + (int64_t)ks * 16 * P));
+      for (int kp = 0; kp < KS_C / 2; ++kp) kf8[kp] = __builtin_nontemporal_load((const u32x4*)(kb + (int64_t)kp * 32 * P));
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS_C; ++ks) kf[ks] = __builtin_nontemporal_load((const bf16x8*)(kb + (int64_t)ks * 32 * P));
+    }
     if (!share_kr) {
 #pragma unroll
-      for (int ks = 0; ks < KS_R; ++ks) rf[ks] = __builtin_nontemporal_load((const bf16x8*)(rbp + (int64_t)ks * 16 * P));
+      for (int ks = 0; ks < KS_R; ++ks) rf[ks] = __builtin_nontemporal_load((const bf16x8*)(rbp + (int64_t)ks * 32 * P));
     }
   };
   auto load_v = [&](int tok, int32_t pg) {
     v_ok = pg >= 0;
-    const __bf16* base = pool + (int64_t)(v_ok ? pg : 0) * page_elems + (int64_t)gc * DH * P + (int64_t)j * DH * P;
-    const int tb = (tok % P) / 8 + h;  // 8-token block of this lane for k-step 0; k-step 1 is two blocks further
+    const char* base = pool + (int64_t)(v_ok ? pg : 0) * page_bytes + ((int64_t)gc * DH * P + (int64_t)j * DH * P) * EB;
+    if constexpr (FP8) {
+      const int T = (tok % P) / 32;  // 32-token tile of the page: [T][dim][half] vectors
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
+        vf8[mt] = __builtin_nontemporal_load((const u32x4*)(base + ((((int64_t)T * DH + mt * 32 + n) * 2 + h) * 16)));
+    } else {
+      const int tb = (tok % P) / 8 + h;  // 8-token block of this lane for k-step 0; k-step 1 is two blocks further
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
-        vf[mt][kk] = __builtin_nontemporal_load((const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 8));
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+          vf[mt][kk] = __builtin_nontemporal_load((const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 16));
+    }
   };
 
   f32x16 o[MT];
@@ -128,8 +156,19 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     f32x16 s;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    if constexpr (FP8) {
+#pragma unroll
+      for (int kp = 0; kp < KS_C / 2; ++kp) {
+        kf[2 * kp] = widen_e4m3(kf8[kp][0], kf8[kp][1]);
+        kf[2 * kp + 1] = widen_e4m3(kf8[kp][2], kf8[kp][3]);
+      }
+    }
 #pragma unroll
     for (int ks = 0; ks < KS_C; ++ks) s = mfma32(kf[ks], qc[ks], s);
+    if constexpr (FP8) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] *= k_scale;
+    }
     if (share_kr) {
       // this tile's k_R was requested before the 16 cache loads that followed it (loads complete in issue order)
       asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
@@ -200,6 +239,13 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       pf[kk] = __builtin_bit_cast(bf16x8, w);
     }
 
+    if constexpr (FP8) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        vf[mt][0] = widen_e4m3(vf8[mt][0], vf8[mt][1]);
+        vf[mt][1] = widen_e4m3(vf8[mt][2], vf8[mt][3]);
+      }
+    }
     // values of tokens outside the chunk may hold any bits (NaN included): zero them so that 0 * v stays 0
     if (tok + 32 > ce.tok_end || !v_ok) {
       const int lim = v_ok ? ce.tok_end : 0;
@@ -220,7 +266,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
 
   const float l_tot = pair_sum(l_run);
   if (!row_ok) return;
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * (FP8 ? v_scale : 1.f);
   const int64_t prow = (int64_t)chunk * a.M + (int64_t)t * a.h_q + head;
   float* po = (float*)a.part_o + prow * DH;
 #pragma unroll
@@ -235,17 +281,31 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
 
 }  // namespace
 
-hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
-  const int row_blocks = (a.G * a.s_q + 31) / 32;
-  const int n_items = a.n_chunks * row_blocks * a.g;
+static void gqa_launch_shape(const DecodeArgs& a, int& row_blocks, int& n_items, bool& team, int& wpb, int& blocks) {
+  row_blocks = (a.G * a.s_q + 31) / 32;
+  n_items = a.n_chunks * row_blocks * a.g;
   // all waves of a workgroup are groups of one (chunk, row block) when the group count is a multiple of the waves per
   // workgroup: then they share the tile's k_R through LDS (and run in step, one barrier per tile)
   // With 2 or 4 groups the workgroup also takes all row blocks of the chunk when that keeps it within 8 waves: they
   // stream the same cache vectors in step, so all but the first request for a line is served by the cache hierarchy.
-  const bool team = a.g % 8 == 0 || a.g == 4 || a.g == 2;
-  const int wpb = (a.g == 4 || a.g == 2) ? (a.g * row_blocks <= 8 ? a.g * row_blocks : a.g) : 8;
-  const int blocks = (n_items + wpb - 1) / wpb;
-  decode_gqa_bf16_kernel<128, 64><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0);
+  team = a.g % 8 == 0 || a.g == 4 || a.g == 2;
+  wpb = (a.g == 4 || a.g == 2) ? (a.g * row_blocks <= 8 ? a.g * row_blocks : a.g) : 8;
+  blocks = (n_items + wpb - 1) / wpb;
+}
+
+hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
+  int row_blocks, n_items, wpb, blocks;
+  bool team;
+  gqa_launch_shape(a, row_blocks, n_items, team, wpb, blocks);
+  decode_gqa_bf16_kernel<128, 64, false><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_gqa_fp8(const DecodeArgs& a, float k_scale, float v_scale, hipStream_t s) {
+  int row_blocks, n_items, wpb, blocks;
+  bool team;
+  gqa_launch_shape(a, row_blocks, n_items, team, wpb, blocks);
+  decode_gqa_bf16_kernel<128, 64, true><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
   return hipGetLastError();
 }
 

@@ -59,6 +59,14 @@ struct ExpandArgs {
   int32_t tail;  // tail variants only: positions L_b - tail .. L_b - 1 of every sequence
 };
 
+struct QuantizeArgs {
+  CacheView src;  // 16-bit expanded cache
+  CacheView dst;  // 8-bit expanded cache, same geometry and page ids
+  const int32_t* seq_lens;
+  int32_t B;
+  float k_inv_scale, v_inv_scale;
+};
+
 struct AppendArgs {
   const void* rows;  // [B][s_q][row_bytes]
   CacheView latent;
@@ -94,6 +102,8 @@ hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*g
 hipError_t launch_expand_tail_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_tail_bf16(const ExpandArgs&, void* ws /* as above */, hipStream_t);
 hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
+hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);
+hipError_t launch_decode_gqa_fp8(const DecodeArgs&, float k_scale, float v_scale, hipStream_t);
 
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t);
 hipError_t launch_probe_mfma(uint32_t* sink, int iters, int blocks, hipStream_t);

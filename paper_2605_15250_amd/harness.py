@@ -66,6 +66,7 @@ class Decoder:
         B.gqla_plan_upload(self.plan_g, self.ws_g)
         self.latent_pool = None
         self.expanded_pool = None
+        self.expanded_fp8_pool = None
         self.ws_e = None                                        # scratch of the expand call
 
     def close(self):
@@ -129,6 +130,33 @@ class Decoder:
     def append_latent(self, rows):
         """rows: [B, s_q, r_kv + d_r] contiguous, the cache's element type."""
         B.gqla_append_latent(self.shape, rows, self.latent_cache())
+
+    # -- 8-bit expanded cache ------------------------------------------------------------------------------
+    def fp8_page_bytes(self):
+        c = self.cfg
+        return c.page_size * B.gqla_expanded_fp8_bytes_per_token(self.groups, c.d_h, c.d_r)
+
+    def alloc_expanded_fp8(self, fill=0xAA):
+        self.expanded_fp8_pool = torch.full((self.num_pages * self.fp8_page_bytes(),), fill, dtype=torch.uint8, device="cuda")
+        return self.expanded_fp8_pool
+
+    def expanded_fp8_cache(self):
+        return B.make_cache(self.expanded_fp8_pool, self.d_lens, self.d_table, self.cfg.page_size, self.max_pages,
+                            self.num_pages, self.groups)
+
+    def quantize_expanded(self, k_scale, v_scale):
+        B.gqla_quantize_expanded(self.shape, self.expanded_cache(), self.expanded_fp8_cache(), k_scale, v_scale)
+        return self.expanded_fp8_pool
+
+    def decode_gqa_fp8(self, q_c, q_r, k_scale, v_scale, out=None, lse=None):
+        c = self.cfg
+        heads = self.groups * (c.h_q // c.g)
+        if out is None:
+            out = torch.empty((c.B, c.s_q, heads, c.d_h), dtype=torch_dtype(c.dtype), device="cuda")
+        if lse is None:
+            lse = torch.empty((c.B, c.s_q, heads), dtype=torch.float32, device="cuda")
+        B.gqla_decode_gqa_fp8(self.shape_gqa, self.plan_g, q_c, q_r, self.expanded_fp8_cache(), k_scale, v_scale, out, lse, self.ws_g)
+        return out, lse
 
     def decode_gqa(self, q_c, q_r, out=None, lse=None):
         """q_c, q_r: [B, s_q, heads of the slice, d] contiguous."""

@@ -1,0 +1,100 @@
+"""GPU parity of the 8-bit expanded cache: the quantising cache switch bit for bit against the oracle's quantiser and
+page format, the decode over such a cache against the oracle's GQA-path decode on the dequantised values, and the
+whole chain (expand, quantise, decode) on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import fp8_cache as F8
+from oracle import gqla_oracle as O
+from oracle import layout as Lay
+from test_gpu_parity import Case, check, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_bits(x):
+    """16-bit patterns of fp32 values that are representable in bf16."""
+    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("h_q,g,s_q,lens,paged,scales", [
+    (128, 8, 2, [300, 2, 129, 65], True, (1.0, 1.0)),      # ragged tails inside 16-token code vectors
+    (32, 8, 1, [513, 40], False, (0.37, 2.5)),             # scales that are not powers of two
+    (64, 4, 1, [700], True, (0.02, 0.01)),                 # small scales: part of the values saturate at 448
+])
+def test_fp8_cache_quantise_and_decode(h_q, g, s_q, lens, paged, scales):
+    cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=880 + h_q)
+    case = Case(cfg, lens=lens, use_page_table=paged)
+    dec = case.dec
+    ks, vs = scales
+    try:
+        # the 16-bit expanded cache both sides start from: the oracle's expansion rounded once to bf16
+        KCq, Vq = [], []
+        for b in range(cfg.B):
+            KC, V = O.expand_latent(case.c(b), case.w_uk, case.w_uv)
+            KCq.append(S.quantize(KC, cfg.dtype)); Vq.append(S.quantize(V, cfg.dtype))
+        kR = [case.kR(b) for b in range(cfg.B)]
+        dec.expanded_pool = case.to_device(Lay.pack_expanded_pool(KCq, Vq, kR, case.table, case.num_pages, cfg.page_size, fill=0.0), cfg.dtype)
+        # -- the quantising cache switch, bit for bit (bytes no token owns keep the fill pattern)
+        dec.alloc_expanded_fp8(fill=0xAA)
+        dec.quantize_expanded(ks, vs)
+        torch.cuda.synchronize()
+        kc_codes = [F8.quantize_tensor(x, ks) for x in KCq]
+        v_codes = [F8.quantize_tensor(x, vs) for x in Vq]
+        ref_pool = F8.pack_fp8_pool(kc_codes, v_codes, [_bf16_bits(x) for x in kR], case.table, case.num_pages, cfg.page_size, fill=0xAA)
+        got_pool = dec.expanded_fp8_pool.cpu().numpy()
+        assert got_pool.shape == ref_pool.shape
+        assert np.array_equal(got_pool, ref_pool), "%d of %d bytes differ" % (int((got_pool != ref_pool).sum()), got_pool.size)
+        # -- decode over the oracle-packed 8-bit cache against the oracle on the dequantised values
+        dec.expanded_fp8_pool = torch.from_numpy(ref_pool).cuda()
+        out, lse = dec.decode_gqa_fp8(case.d_q_c, case.d_q_r, ks, vs)
+        torch.cuda.synchronize()
+        ref_o, ref_l, exact = [], [], []
+        for b in range(cfg.B):
+            o, l = O.decode_gqa(case.q_c[b], case.q_r[b], F8.dequantize_e4m3(kc_codes[b]) * ks, F8.dequantize_e4m3(v_codes[b]) * vs, kR[b])
+            ref_o.append(o); ref_l.append(l)
+            exact.append(O.decode_gqa(case.q_c[b], case.q_r[b], KCq[b], Vq[b], kR[b])[0])
+        check("decode_gqa_fp8", host(out), np.stack(ref_o), cfg.dtype)
+        check("decode_gqa_fp8 lse", host(lse), np.stack(ref_l), cfg.dtype)
+        print("8-bit cache vs the 16-bit cache (what the quantisation itself costs): rel_l2 %.3e" % rel_l2(np.stack(ref_o), np.stack(exact)), flush=True)
+    finally:
+        case.close()
+
+
+def test_fp8_chain_on_the_gpu():
+    """expand -> quantise -> decode, all on the GPU, against the oracle's chain (its expansion rounded to bf16, then
+    quantised): the few codes that differ because the GPU's bf16 rounding of an expanded value differs by one unit do
+    not show at the output tolerance."""
+    cfg = S.CONFIGS["C3"].with_(B=2, L=0, paged=True, seed=881)
+    case = Case(cfg, lens=[1000, 257])
+    dec = case.dec
+    try:
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        dec.alloc_expanded_fp8()
+        dec.quantize_expanded(1.0, 1.0)
+        out, _ = dec.decode_gqa_fp8(case.d_q_c, case.d_q_r, 1.0, 1.0)
+        torch.cuda.synchronize()
+        ref = []
+        n_codes = n_diff = 0
+        pool = dec.expanded_fp8_pool.cpu().numpy()
+        for b in range(cfg.B):
+            KC, V = O.expand_latent(case.c(b), case.w_uk, case.w_uv)
+            kc = F8.quantize_tensor(S.quantize(KC, cfg.dtype), 1.0)
+            vv = F8.quantize_tensor(S.quantize(V, cfg.dtype), 1.0)
+            ref.append(O.decode_gqa(case.q_c[b], case.q_r[b], F8.dequantize_e4m3(kc), F8.dequantize_e4m3(vv), case.kR(b))[0])
+            # how many of the GPU's codes differ from the oracle's (sampled tokens)
+            for s in (0, 100, int(case.lens[b]) - 1):
+                page, slot = int(case.table[b][s // cfg.page_size]), s % cfg.page_size
+                for j in range(cfg.g):
+                    for d in range(cfg.d_h):
+                        n_codes += 2
+                        n_diff += int(pool[F8.k8_offset(page, j, slot, d, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r)] != kc[s, j, d])
+                        n_diff += int(pool[F8.v8_offset(page, j, slot, d, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r)] != vv[s, j, d])
+        print("codes that differ between the GPU chain and the oracle chain: %d of %d sampled" % (n_diff, n_codes), flush=True)
+        assert n_diff <= 0.02 * n_codes
+        check("expand -> quantise -> decode_gqa_fp8", host(out), np.stack(ref), cfg.dtype)
+    finally:
+        case.close()
