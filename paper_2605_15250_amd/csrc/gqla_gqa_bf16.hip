@@ -162,7 +162,15 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
         kf[2 * kp] = widen_e4m3(kf8[kp][0], kf8[kp][1]);
         kf[2 * kp + 1] = widen_e4m3(kf8[kp][2], kf8[kp][3]);
       }
+      // the value codes are widened here as well: their registers are then free for the next tile's codes, which are
+      // requested together with the key codes (twice the bytes in flight per wave)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        vf[mt][0] = widen_e4m3(vf8[mt][0], vf8[mt][1]);
+        vf[mt][1] = widen_e4m3(vf8[mt][2], vf8[mt][3]);
+      }
     }
+    const bool tile_v_ok = v_ok;  // v_ok is overwritten by the next tile's request below (FP8)
 #pragma unroll
     for (int ks = 0; ks < KS_C; ++ks) s = mfma32(kf[ks], qc[ks], s);
     if constexpr (FP8) {
@@ -186,6 +194,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       pg_next = checked(pg_raw);
       if (share_kr) stage_kr(tok + 32, pg_next, (((tok - ce.tok_begin) >> 5) + 1) & 1);
       load_k(tok + 32, pg_next);
+      if constexpr (FP8) load_v(tok + 32, pg_next);
       if (tok + 64 < ce.tok_end) lookup_start(tok + 64, pg_raw);
     }
 
@@ -239,16 +248,9 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       pf[kk] = __builtin_bit_cast(bf16x8, w);
     }
 
-    if constexpr (FP8) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        vf[mt][0] = widen_e4m3(vf8[mt][0], vf8[mt][1]);
-        vf[mt][1] = widen_e4m3(vf8[mt][2], vf8[mt][3]);
-      }
-    }
     // values of tokens outside the chunk may hold any bits (NaN included): zero them so that 0 * v stays 0
-    if (tok + 32 > ce.tok_end || !v_ok) {
-      const int lim = v_ok ? ce.tok_end : 0;
+    if (tok + 32 > ce.tok_end || !tile_v_ok) {
+      const int lim = tile_v_ok ? ce.tok_end : 0;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -261,7 +263,9 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) o[mt] = mfma32(vf[mt][kk], pf[kk], o[mt]);
-    if (has_next) load_v(tok + 32, pg_next);
+    if constexpr (!FP8) {
+      if (has_next) load_v(tok + 32, pg_next);
+    }
   }
 
   const float l_tot = pair_sum(l_run);
