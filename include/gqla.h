@@ -211,6 +211,13 @@ gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* ex
 gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
                                 const gqla_cache* expanded_fp8, float k_scale, float v_scale, void* out, float* lse,
                                 void* ws, size_t ws_bytes, void* stream);
+/* gqla_expand_cache_tail whose destination is an 8-bit cache: the step's positions of every sequence, with the codes
+ * that expanding into a 16-bit cache and converting it would give (each result is rounded to bf16 before it is
+ * quantised).  Arguments and errors as for gqla_expand_cache_tail, plus the two scales. */
+gqla_status gqla_expand_cache_tail_fp8(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
+                                       const void* w_uv, int32_t group_begin, int32_t group_count,
+                                       const gqla_cache* expanded_fp8, int32_t tail_tokens, float k_scale, float v_scale,
+                                       void* ws, size_t ws_bytes, void* stream);
 int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r);
 
 /* ---- sizes and diagnostics ------------------------------------------------------------------------------ */

@@ -23,7 +23,7 @@ EXPORTS = [
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
-    "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token",
+    "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -99,6 +99,8 @@ def lib():
         L.gqla_quantize_expanded.restype = i32
         L.gqla_decode_gqa_fp8.argtypes = [sp, vp, vp, vp, cp, C.c_float, C.c_float, vp, vp, vp, sz, vp]
         L.gqla_decode_gqa_fp8.restype = i32
+        L.gqla_expand_cache_tail_fp8.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, C.c_float, C.c_float, vp, C.c_size_t, vp]
+        L.gqla_expand_cache_tail_fp8.restype = i32
         L.gqla_expanded_fp8_bytes_per_token.argtypes = [i32, i32, i32]
         L.gqla_expanded_fp8_bytes_per_token.restype = i64
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
@@ -280,6 +282,15 @@ def gqla_decode_gqa_fp8(shape, plan, q_c, q_r, expanded_fp8: gqla_cache, k_scale
     nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
     _check(lib().gqla_decode_gqa_fp8(C.byref(shape), plan, _ptr(q_c), _ptr(q_r), C.byref(expanded_fp8), float(k_scale),
                                      float(v_scale), _ptr(out), _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_gqa_fp8")
+
+
+def gqla_expand_cache_tail_fp8(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded_fp8: gqla_cache,
+                               tail_tokens, k_scale, v_scale, ws=None, ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().gqla_expand_cache_tail_fp8(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
+                                            C.byref(expanded_fp8), tail_tokens, float(k_scale), float(v_scale), _ptr(ws), ws_bytes,
+                                            _stream(stream)), "gqla_expand_cache_tail_fp8")
 
 
 def gqla_expanded_fp8_bytes_per_token(groups, d_h, d_r) -> int:

@@ -321,7 +321,7 @@ namespace {
 // tail = 0: every token of every sequence; tail > 0: the last `tail` positions only
 gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
                         int32_t group_begin, int32_t group_count, const gqla_cache* expanded, int32_t tail, void* ws,
-                        size_t ws_bytes, void* stream) {
+                        size_t ws_bytes, void* stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f) {
   gqla_status st = check_shape(shape);
   if (st != GQLA_OK) return st;
   if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
@@ -354,9 +354,12 @@ gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const
   a.group_begin = group_begin;
   a.group_count = group_count;
   a.tail = tail;
+  a.k_inv_scale = 1.0f / k_scale;
+  a.v_inv_scale = 1.0f / v_scale;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (tail > 0) e = shape->dtype == GQLA_BF16 ? launch_expand_tail_bf16(a, ws, s) : launch_expand_tail_f32(a, s);
+  if (fp8) e = launch_expand_tail_fp8(a, ws, s);
+  else if (tail > 0) e = shape->dtype == GQLA_BF16 ? launch_expand_tail_bf16(a, ws, s) : launch_expand_tail_f32(a, s);
   else e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, ws, s) : launch_expand_f32(a, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
@@ -373,6 +376,17 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
                                    int32_t tail_tokens, void* ws, size_t ws_bytes, void* stream) {
   if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
   return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, ws, ws_bytes, stream);
+}
+
+gqla_status gqla_expand_cache_tail_fp8(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                                       int32_t group_begin, int32_t group_count, const gqla_cache* expanded_fp8,
+                                       int32_t tail_tokens, float k_scale, float v_scale, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  if (shape && shape->dtype != GQLA_BF16) return check_shape(shape) == GQLA_OK ? GQLA_ERR_DTYPE : check_shape(shape);
+  if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
+  return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded_fp8, tail_tokens, ws, ws_bytes, stream, true,
+                     k_scale, v_scale);
 }
 
 gqla_status gqla_append_latent(const gqla_shape* shape, const void* rows, const gqla_cache* latent, void* stream) {
@@ -442,11 +456,13 @@ gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* ex
 gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
                                 const gqla_cache* expanded_fp8, float k_scale, float v_scale, void* out, float* lse,
                                 void* ws, size_t ws_bytes, void* stream) {
-  gqla_status st = check_decode_common(shape, plan, GQLA_PATH_GQA, expanded_fp8, q_c, q_r, out, lse, ws, ws_bytes);
+  gqla_status st = check_shape(shape);
   if (st != GQLA_OK) return st;
   if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
-  if (expanded_fp8->groups != shape->g) return GQLA_ERR_SHAPE;
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
+  st = check_decode_common(shape, plan, GQLA_PATH_GQA, expanded_fp8, q_c, q_r, out, lse, ws, ws_bytes);
+  if (st != GQLA_OK) return st;
+  if (expanded_fp8->groups != shape->g) return GQLA_ERR_SHAPE;
   if (shape->batch == 0) return GQLA_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded_fp8, ws);

@@ -76,6 +76,17 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
 // Page id of logical page p of sequence b, or -1 when the table entry is outside the pool.
+// Four fp32 values -> four E4M3 codes of x * inv_scale (OCP 8-bit float, "FN" variant), round to nearest even; magnitudes
+// above 448 saturate (the conversion instruction alone would turn them into NaN).  Byte k of the result is value k.
+__device__ __forceinline__ uint32_t quantize_e4m3x4(float a, float b, float c, float d, float inv_scale) {
+  auto q = [&](float x) { return fminf(fmaxf(x * inv_scale, -448.f), 448.f); };
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(q(a), q(b), 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(q(c), q(d), w, true);
+  return (uint32_t)w;
+}
+// the value a float has after one rounding to bf16 (what a 16-bit cache would hold)
+__device__ __forceinline__ float round_to_bf16(float x) { return bf16_bits_to_float(pack_bf16(x, 0.f) & 0xffffu); }
+
 __device__ __forceinline__ int32_t page_of(const CacheView& c, int32_t b, int32_t p) {
   int32_t pg = c.page_table ? c.page_table[(int64_t)b * c.max_pages + p] : b * c.max_pages + p;
   return ((uint32_t)pg < (uint32_t)c.num_pages) ? pg : -1;

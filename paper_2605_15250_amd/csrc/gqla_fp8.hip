@@ -10,18 +10,12 @@ namespace gqla {
 
 namespace {
 
-__device__ __forceinline__ uint32_t e4m3x4(float a, float b, float c, float d, float inv_scale) {
-  auto q = [&](float x) { return fminf(fmaxf(x * inv_scale, -448.f), 448.f); };
-  int w = __builtin_amdgcn_cvt_pk_fp8_f32(q(a), q(b), 0, false);
-  w = __builtin_amdgcn_cvt_pk_fp8_f32(q(c), q(d), w, true);
-  return (uint32_t)w;
-}
 // 8 bf16 (one 16-byte vector) -> 8 codes (two words)
 __device__ __forceinline__ u32x2 e4m3x8(u32x4 v, float inv_scale) {
   uint32_t lo, hi;
-  lo = e4m3x4(bf16_bits_to_float(v[0] & 0xffffu), bf16_bits_to_float(v[0] >> 16), bf16_bits_to_float(v[1] & 0xffffu),
+  lo = quantize_e4m3x4(bf16_bits_to_float(v[0] & 0xffffu), bf16_bits_to_float(v[0] >> 16), bf16_bits_to_float(v[1] & 0xffffu),
               bf16_bits_to_float(v[1] >> 16), inv_scale);
-  hi = e4m3x4(bf16_bits_to_float(v[2] & 0xffffu), bf16_bits_to_float(v[2] >> 16), bf16_bits_to_float(v[3] & 0xffffu),
+  hi = quantize_e4m3x4(bf16_bits_to_float(v[2] & 0xffffu), bf16_bits_to_float(v[2] >> 16), bf16_bits_to_float(v[3] & 0xffffu),
               bf16_bits_to_float(v[3] >> 16), inv_scale);
   return u32x2{lo, hi};
 }

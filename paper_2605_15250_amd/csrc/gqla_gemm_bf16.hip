@@ -279,7 +279,10 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 // Tokens of a tile belong to different sequences and pages, so results go out as 8-byte (K plane: 4 consecutive dims
 // of one token) and 2-byte (V plane: one token's element of an 8-token vector) stores; with a few hundred tokens per
 // step that is a few hundred KB.  The first stage's workgroups also copy the tokens' k_R.
-template <int DH, int RKV, int DR>
+// FP8 = true: `expanded` is an 8-bit cache (E4M3 code planes, see the header); every result is first rounded to bf16,
+// the value the 16-bit cache would hold, and then quantised, so that the codes equal those of expanding into a 16-bit
+// cache and converting it.
+template <int DH, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
@@ -315,8 +318,34 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
   for (int ks = 0; ks < KS; ++ks)
     acc = mfma32(*(const bf16x8*)(wf + (int64_t)ks * 1024), *(const bf16x8*)(row + ks * 16 + h * 8), acc);
   if (!ok) return;
-  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * DH + DR);
   const int d0 = 64 * mtp + 32 * e;  // register i holds dim d0 + 8*(i/4) + 4*h + i%4 of this lane's token
+  if constexpr (FP8) {
+    char* out8 = (char*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * DH + 2 * DR);
+    const float inv = kind == 0 ? a.k_inv_scale : a.v_inv_scale;
+    uint32_t code[4];  // code[q] = dims d0 + 8q + 4h + 0..3
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      code[q] = quantize_e4m3x4(round_to_bf16(acc[4 * q]), round_to_bf16(acc[4 * q + 1]), round_to_bf16(acc[4 * q + 2]),
+                                round_to_bf16(acc[4 * q + 3]), inv);
+    if (kind == 0) {  // dim 32 kp + 16 u + 8 h' + i: here kp = d0/32, u = q/2, h' = q%2, i = 4h + 0..3 -> four consecutive bytes
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *(uint32_t*)(out8 + ((int64_t)(jj * (DH / 16) + 2 * (d0 / 32) + (q & 1)) * P + slot) * 16 + 8 * (q >> 1) + 4 * h) = code[q];
+    } else {          // slot 32 T + 16 u + 8 h' + i: one byte per dim
+      char* vp = out8 + (int64_t)gc * P * DH + ((int64_t)(jj * (P / 32) + slot / 32) * DH * 2 + ((slot >> 3) & 1)) * 16 +
+                 8 * ((slot >> 4) & 1) + (slot & 7);
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        vp[(int64_t)(d0 + 8 * (i >> 2) + 4 * h + (i & 3)) * 32] = (char)((code[i >> 2] >> (8 * (i & 3))) & 0xffu);
+    }
+    if (stage == 0 && e == 0) {
+      char* rp = out8 + (int64_t)2 * gc * P * DH;
+#pragma unroll
+      for (int c = h; c < DR / 8; c += 2) *(u32x4*)(rp + ((int64_t)c * P + slot) * 16) = *(const u32x4*)(row + RKV + c * 8);
+    }
+    return;
+  }
+  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * DH + DR);
   if (kind == 0) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -349,7 +378,16 @@ hipError_t launch_expand_tail_bf16(const ExpandArgs& a, void* ws, hipStream_t s)
   pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  expand_tail_bf16_kernel<128, 512, 64><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
+  expand_tail_bf16_kernel<128, 512, 64, false><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_tail_fp8(const ExpandArgs& a, void* ws, hipStream_t s) {
+  const int tokens = a.B * a.tail;
+  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_tail_bf16_kernel<128, 512, 64, true><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }
 

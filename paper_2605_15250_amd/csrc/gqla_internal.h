@@ -57,6 +57,7 @@ struct ExpandArgs {
   const void* w_uv;
   int32_t B, g, d_h, r_kv, d_r, group_begin, group_count;
   int32_t tail;  // tail variants only: positions L_b - tail .. L_b - 1 of every sequence
+  float k_inv_scale, v_inv_scale;  // 8-bit tail variant only: 1 / scale of the two code planes
 };
 
 struct QuantizeArgs {
@@ -101,6 +102,7 @@ hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*group_count*r_kv*d_h bf16 */, hipStream_t);
 hipError_t launch_expand_tail_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_tail_bf16(const ExpandArgs&, void* ws /* as above */, hipStream_t);
+hipError_t launch_expand_tail_fp8(const ExpandArgs&, void* ws /* as above */, hipStream_t);  // `expanded` is an 8-bit cache
 hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);
 hipError_t launch_decode_gqa_fp8(const DecodeArgs&, float k_scale, float v_scale, hipStream_t);

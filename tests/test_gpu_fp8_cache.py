@@ -98,3 +98,44 @@ def test_fp8_chain_on_the_gpu():
         check("expand -> quantise -> decode_gqa_fp8", host(out), np.stack(ref), cfg.dtype)
     finally:
         case.close()
+
+
+def test_fp8_tail_expansion_equals_expand_then_quantise():
+    """The step's positions expanded straight into the 8-bit cache hold the codes of the two-step route (expand into a
+    16-bit cache, convert it), bit for bit, and nothing else is written."""
+    cfg = S.CONFIGS["C3"].with_(B=4, L=0, paged=True, seed=882)
+    case = Case(cfg, lens=[200, 2, 65, 1000])
+    dec = case.dec
+    ks, vs = 0.6, 1.7
+    try:
+        tail = cfg.s_q
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        dec.alloc_expanded_fp8(fill=0xAA)
+        dec.quantize_expanded(ks, vs)
+        torch.cuda.synchronize()
+        two_step = dec.expanded_fp8_pool.clone()
+        dec.alloc_expanded_fp8(fill=0xAA)
+        dec.expand_tail_fp8(case.d_w_uk, case.d_w_uv, tail, ks, vs)
+        torch.cuda.synchronize()
+        got = dec.expanded_fp8_pool.cpu().numpy()
+        ref = two_step.cpu().numpy()
+        per_tok = 2 * cfg.g * cfg.d_h + 2 * cfg.d_r
+        written = got != 0xAA
+        # codes equal to the fill pattern exist, so count with a margin: at most the tail's bytes were touched, most of them differ from the fill
+        assert int(written.sum()) <= cfg.B * tail * per_tok and int(written.sum()) >= 0.9 * cfg.B * tail * per_tok
+        assert np.array_equal(got[written], ref[written])
+        # every byte of every tail token (also those that happen to equal the fill) against the two-step route
+        for b in range(cfg.B):
+            for s in range(int(case.lens[b]) - tail, int(case.lens[b])):
+                page, slot = int(case.table[b][s // cfg.page_size]), s % cfg.page_size
+                for j in (0, cfg.g - 1):
+                    for d in range(cfg.d_h):
+                        ko = F8.k8_offset(page, j, slot, d, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r)
+                        vo = F8.v8_offset(page, j, slot, d, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r)
+                        assert got[ko] == ref[ko] and got[vo] == ref[vo]
+                for d in range(cfg.d_r):
+                    o = F8.kr16_offset(page, slot, d, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r)
+                    assert got[o] == ref[o] and got[o + 1] == ref[o + 1]
+    finally:
+        case.close()

@@ -152,6 +152,21 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_ALIGN, B.gqla_append_latent, ok, A + 4, lat, stream=0)
         _expect(B.GQLA_ERR_PAGE, B.gqla_append_latent, ok, A, B.make_cache(A, A, None, 48, 4, 8, 0), stream=0)
         _expect(B.GQLA_ERR_PAGE, B.gqla_append_latent, ok, A, B.make_cache(A, A, None, 64, 4, 7, 0), stream=0)
+        # the 8-bit expanded cache: bf16 shapes only, positive finite scales, matching geometry
+        f32 = B.make_shape(2, 8, 2, 16, 32, 8, 1, B.GQLA_F32)
+        full8 = B.make_cache(A, A, None, 64, 4, 8, 8)
+        _expect(B.GQLA_ERR_DTYPE, B.gqla_quantize_expanded, f32, B.make_cache(A, A, None, 8, 4, 8, 2), B.make_cache(A, A, None, 8, 4, 8, 2), 1.0, 1.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_expanded, ok, full, full8, 0.0, 1.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_expanded, ok, full, full8, 1.0, float("inf"), stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_expanded, ok, full, B.make_cache(A, A, None, 64, 4, 8, 4), 1.0, 1.0, stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_quantize_expanded, ok, full, B.make_cache(A, A, None, 64, 5, 8, 8), 1.0, 1.0, stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_quantize_expanded, ok, B.make_cache(A, None, None, 64, 4, 8, 8), full8, 1.0, 1.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_decode_gqa_fp8, ok, plan_g, A, A, full8, -1.0, 1.0, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_PLAN, B.gqla_decode_gqa_fp8, ok, plan_a, A, A, full8, 1.0, 1.0, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 0, 1.0, 1.0, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 2, 1.0, 0.0, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 2, 1.0, 1.0, None, 0, stream=0)
+        assert B.gqla_expanded_fp8_bytes_per_token(8, 128, 64) == 2176 and B.gqla_expanded_fp8_bytes_per_token(4, 128, 64) == 1152
     finally:
         B.gqla_plan_destroy(plan_a)
         B.gqla_plan_destroy(plan_g)
