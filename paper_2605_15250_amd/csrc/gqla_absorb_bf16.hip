@@ -587,13 +587,10 @@ template <int SPLIT>
 static hipError_t launch_decode_absorb_split(const DecodeArgs& a, hipStream_t s) {
   // tile ring, plus the team exchange (4 KB per wave) when waves share rows
   constexpr int kLds = kSlots * kTile * (512 + 64) * 2 + (SPLIT > 1 ? 4 * 4096 : 0);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)decode_absorb_bf16_kernel<512, 64, SPLIT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (function-local statics are initialised under a lock); an error is reported by every call
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)decode_absorb_bf16_kernel<512, 64, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
   const int row_blocks = (a.M + kRowsPerBlock / SPLIT - 1) / (kRowsPerBlock / SPLIT);
   const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
   decode_absorb_bf16_kernel<512, 64, SPLIT><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks);
@@ -612,13 +609,10 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
 
 hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {
   constexpr int kLds = 512 * 128 * 2;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)combine_project_bf16_kernel<512, 128>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (function-local statics are initialised under a lock); an error is reported by every call
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)combine_project_bf16_kernel<512, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
   const int rows_per_group = a.B * a.s_q * a.G;
   combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + 31) / 32, a.g), 256, kLds, s>>>(a, rows_per_group);
   return hipGetLastError();

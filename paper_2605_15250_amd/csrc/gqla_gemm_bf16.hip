@@ -393,13 +393,10 @@ hipError_t launch_expand_tail_fp8(const ExpandArgs& a, void* ws, hipStream_t s) 
 
 hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
   constexpr int kLds = 2 * (512 / 16) * 2 * 1024;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (function-local statics are initialised under a lock); an error is reported by every call
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
   const int64_t max_tokens = (int64_t)a.latent.max_pages * a.latent.page_size;
   dim3 grid((unsigned)((max_tokens + 255) / 256), a.B);
   pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
