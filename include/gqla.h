@@ -62,7 +62,7 @@ typedef enum {
   GQLA_OK = 0,
   GQLA_ERR_NULL = 1,       /* a required pointer is NULL                                  */
   GQLA_ERR_SHAPE = 2,      /* dimensions unsupported or inconsistent (g does not divide h_q, ...) */
-  GQLA_ERR_DTYPE = 3,      /* dtype not GQLA_F32 / GQLA_BF16                               */
+  GQLA_ERR_DTYPE = 3,      /* dtype not GQLA_F32 / GQLA_BF16, or not taken by this entry point */
   GQLA_ERR_ALIGN = 4,      /* a data pointer is not 16-byte aligned                         */
   GQLA_ERR_SEQLEN = 5,     /* some L_b < s_q, or L_b exceeds max_pages * page_size          */
   GQLA_ERR_PAGE = 6,       /* page_size / max_pages / num_pages inconsistent                */
