@@ -122,6 +122,54 @@ def test_c2_c3_canonical_both_paths_with_mtp():
         case.close()
 
 
+def test_c3_step_updates_and_fp8_cache_at_full_size():
+    """configs[3] at full size: the per-step cache updates (append + tail expansion on top of a one-shot expansion of
+    the prefix) must reproduce the one-shot expansion of everything bit for bit, and the decode over the 8-bit cache
+    (expand -> quantise on the GPU) is checked on sampled (sequence, group) slices against the oracle's chain."""
+    from oracle import fp8_cache as F8
+    cfg = S.CONFIGS["C3"]
+    case = FullCase(cfg)
+    dec = case.dec
+    try:
+        G = cfg.h_q // cfg.g
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        torch.cuda.synchronize()
+        one_shot = dec.expanded_pool.clone()
+        # the step's rows appended again (same values) and their positions expanded again into a zeroed copy of the tail
+        W = cfg.r_kv + cfg.d_r
+        flat = dec.latent_pool.view(-1, W)
+        idx = []
+        for b in range(cfg.B):
+            for t in range(int(case.lens[b]) - cfg.s_q, int(case.lens[b])):
+                idx.append(int(case.table[b][t // cfg.page_size]) * cfg.page_size + t % cfg.page_size)
+        idx_t = torch.tensor(idx, device="cuda")
+        rows = flat[idx_t].view(cfg.B, cfg.s_q, W).contiguous()
+        flat[idx_t] = 0
+        dec.append_latent(rows)
+        dec.expand_tail(case.d_w_uk, case.d_w_uv, cfg.s_q)
+        torch.cuda.synchronize()
+        assert torch.equal(dec.expanded_pool.view(torch.int16), one_shot.view(torch.int16)), "tail expansion vs one-shot expansion"
+        # 8-bit cache
+        dec.alloc_expanded_fp8(fill=0)
+        dec.quantize_expanded(1.0, 1.0)
+        out8, _ = dec.decode_gqa_fp8(case.d(case.q_c), case.d(case.q_r), 1.0, 1.0)
+        torch.cuda.synchronize()
+        o8 = out8.float().cpu().numpy()
+        assert np.isfinite(o8).all()
+        for b in (0, 63):
+            for j in (1, 6):
+                hs = slice(j * G, (j + 1) * G)
+                c, kR = case.rows(b)
+                KC, V = O.expand_latent(c, case.w_uk[j:j + 1], case.w_uv[j:j + 1])
+                kq = F8.dequantize_e4m3(F8.quantize_tensor(S.quantize(KC, cfg.dtype), 1.0))
+                vq = F8.dequantize_e4m3(F8.quantize_tensor(S.quantize(V, cfg.dtype), 1.0))
+                ref, _ = O.decode_gqa(case.q_c[b][:, hs], case.q_r[b][:, hs], kq, vq, kR)
+                check("gqa over the 8-bit cache  b=%d group %d" % (b, j), o8[b][:, hs], ref)
+    finally:
+        case.close()
+
+
 def test_c2_absorb_sq1():
     case = FullCase(S.CONFIGS["C2"])
     try:
