@@ -65,6 +65,25 @@ def expand_latent(c, W_UK, W_UV):
     return KC, V
 
 
+def left_inverse_uk(W_UK):
+    """The matrix that undoes the key half of the expansion (Sec. 3.1: the cache switch between the two paths is a
+    one-shot "compress/expand"; compression exists when the stacked key up-projection has full column rank, which
+    needs g d_h >= r_kv).  With A = [W_UK[0]^T; ...; W_UK[g-1]^T] in R^{g d_h x r_kv} (so that k^C = A c), the left
+    inverse is A^+ = (A^T A)^{-1} A^T in R^{r_kv x g d_h}; columns are ordered group-major, dim-minor like k^C."""
+    W_UK = np.asarray(W_UK, F64)
+    g, r_kv, d_h = W_UK.shape
+    A = np.concatenate([W_UK[j].T for j in range(g)], axis=0)       # [g d_h, r_kv]
+    return np.linalg.solve(A.T @ A, A.T)
+
+
+def compress_expanded(KC, W_UK):
+    """c_s = A^+ k^C_s for every cached token: KC [L, g, d_h] -> c [L, r_kv].  On exact expansions this returns the
+    latent exactly; on rounded ones it is the least-squares latent."""
+    KC = np.asarray(KC, F64)
+    L = KC.shape[0]
+    return KC.reshape(L, -1) @ left_inverse_uk(W_UK).T
+
+
 # ----------------------------------------------------------------------------------------
 # softmax over the visible rows, with its log-sum-exp
 # ----------------------------------------------------------------------------------------

@@ -372,3 +372,26 @@ def test_generators_are_reproducible_and_per_sequence():
     assert np.array_equal(a, b) and a.shape == (100, 576)
     w1, _ = S.weights(cfg)
     assert abs(float(w1.std()) - 512 ** -0.5) < 2e-3
+
+
+def test_compress_is_the_inverse_of_expand_and_the_least_squares_solution():
+    """Sec. 3.1, "one-shot cache compress/expand": compressing an exact expansion returns the latent (g d_h >= r_kv),
+    and on perturbed keys the result is numpy's least-squares solution of A c = k^C, token by token."""
+    rng = np.random.default_rng(5)
+    g, r_kv, d_h, L = 3, 10, 4, 7                     # g d_h = 12 >= r_kv = 10
+    W_UK = rng.normal(size=(g, r_kv, d_h))
+    W_UV = rng.normal(size=(g, r_kv, d_h))
+    c = rng.normal(size=(L, r_kv))
+    KC, _ = O.expand_latent(c, W_UK, W_UV)
+    assert np.max(np.abs(O.compress_expanded(KC, W_UK) - c)) < 1e-10
+    Linv = O.left_inverse_uk(W_UK)
+    A = np.concatenate([W_UK[j].T for j in range(g)], axis=0)
+    assert np.max(np.abs(Linv @ A - np.eye(r_kv))) < 1e-10           # a left inverse
+    assert np.max(np.abs(Linv - np.linalg.pinv(A))) < 1e-9            # the Moore-Penrose one
+    noisy = KC + 0.1 * rng.normal(size=KC.shape)
+    want = np.stack([np.linalg.lstsq(A, noisy[s].reshape(-1), rcond=None)[0] for s in range(L)])
+    assert np.max(np.abs(O.compress_expanded(noisy, W_UK) - want)) < 1e-9
+    # column order: group-major, dim-minor -- compressing keys that live in one group only uses that group's block
+    only1 = np.zeros_like(KC)
+    only1[:, 1, :] = KC[:, 1, :]
+    assert np.max(np.abs(O.compress_expanded(only1, W_UK) - KC[:, 1, :] @ Linv[:, d_h:2 * d_h].T)) < 1e-12
