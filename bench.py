@@ -158,6 +158,7 @@ def main():
     tp_slice = None
     step_updates = None
     fp8_kv = None
+    compress = None
     full_run = run_legs >= {"absorb", "gqa"} and "noexpand" not in run_legs
     if full_run and not args.no_extras:
         def timed(fn, reps):
@@ -228,6 +229,23 @@ def main():
                   "rel_l2_vs_16bit_cache": float(torch.linalg.norm(out8.float() - d16) / torch.linalg.norm(d16))}
         gd.expanded_fp8_pool = None
         del out8
+        # the reverse cache switch (expanded -> latent through the left inverse of the stacked key up-projection)
+        import time as _time
+        t0 = _time.perf_counter()
+        w_inv = B.gqla_left_inverse(gd.shape, Gq["w_uk"])
+        t_inv = _time.perf_counter() - t0
+        d_w_inv = to_device(S.quantize(w_inv, cg.dtype), cg.dtype)
+        truth = gd.latent_pool
+        gd.latent_pool = torch.zeros_like(truth)
+        t_cmp = timed(lambda: gd.compress(d_w_inv), 5)
+        rec = gd.latent_pool.view(-1, Wl)[pos.view(-1)][:, :cg.r_kv].float()
+        ref = truth.view(-1, Wl)[pos.view(-1)][:, :cg.r_kv].float()
+        cmp_flops = 2.0 * Lsum * cg.g * cg.d_h * cg.r_kv
+        compress = {"left_inverse_host_ms": t_inv * 1e3, "compress_cache_ms": t_cmp * 1e3, "TFLOP/s": cmp_flops / t_cmp / 1e12,
+                    "frac_mfma_peak": cmp_flops / t_cmp / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "rel_l2_recovered_latent": float(torch.linalg.norm(rec - ref) / torch.linalg.norm(ref))}
+        gd.latent_pool = truth
+        del rec, ref, d_w_inv
 
     other = None
     if args.all_configs:
@@ -417,6 +435,7 @@ def main():
         "tp_slice": tp_slice,
         "step_updates": step_updates,
         "fp8_kv": fp8_kv,
+        "compress": compress,
         "other_configs": other,
         "operating_points": points,
         "calls_ms": call_ms,

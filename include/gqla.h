@@ -188,6 +188,21 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
                             const gqla_cache* expanded, void* out, float* lse, void* ws, size_t ws_bytes,
                             void* stream);
 
+/* ---- cache compression: the reverse switch (Sec. 3.1: the cache is converted once, in either direction, at deployment) ----
+ * The expansion k^C = A c, A = [W_UK[0]^T; ...; W_UK[g-1]^T] in R^{g d_h x r_kv}, can be undone when A has full column
+ * rank (needs g d_h >= r_kv): c = A^+ k^C with the left inverse A^+ = (A^T A)^{-1} A^T in R^{r_kv x g d_h}.
+ * gqla_left_inverse computes A^+ on the HOST (both arguments host memory, fp32: w_uk_host [g][r_kv][d_h], w_inv_host
+ * [r_kv][g*d_h], columns ordered group-major, dim-minor like k^C), in double precision through the Cholesky factor of
+ * A^T A; GQLA_ERR_SHAPE when g d_h < r_kv or A^T A is not positive definite (a Cholesky pivot at or below 1e-12 of
+ * its diagonal entry).  gqla_compress_cache applies a left inverse
+ * (device memory, the cache's element type, same layout) to the K_C plane of every token t < L_b of `expanded` (all g
+ * groups; L_b read from expanded->seq_lens on the device) and writes c_kv | k_R into `latent`, which must use the same
+ * page_size, max_pages and page ids.  On a cache whose keys were rounded to 16 bits the result is the least-squares
+ * latent of the rounded keys. */
+gqla_status gqla_left_inverse(const gqla_shape* shape, const float* w_uk_host, float* w_inv_host);
+gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expanded, const void* w_inv,
+                                const gqla_cache* latent, void* stream);
+
 /* ---- 8-bit expanded cache for the GQA path --------------------------------------------------------------
  * The paper names quantised KV caches as complementary to the method and leaves them out of its model (Sec. 2
  * "Related work"; Sec. 5.1, item (i)); format and scales are this library's.  K_C and V are stored as E4M3 codes of

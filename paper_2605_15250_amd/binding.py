@@ -24,6 +24,7 @@ EXPORTS = [
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
     "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8",
+    "gqla_left_inverse", "gqla_compress_cache",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -101,6 +102,10 @@ def lib():
         L.gqla_decode_gqa_fp8.restype = i32
         L.gqla_expand_cache_tail_fp8.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, C.c_float, C.c_float, vp, C.c_size_t, vp]
         L.gqla_expand_cache_tail_fp8.restype = i32
+        L.gqla_left_inverse.argtypes = [sp, vp, vp]
+        L.gqla_left_inverse.restype = i32
+        L.gqla_compress_cache.argtypes = [sp, cp, vp, cp, vp]
+        L.gqla_compress_cache.restype = i32
         L.gqla_expanded_fp8_bytes_per_token.argtypes = [i32, i32, i32]
         L.gqla_expanded_fp8_bytes_per_token.restype = i64
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
@@ -291,6 +296,19 @@ def gqla_expand_cache_tail_fp8(shape, latent: gqla_cache, w_uk, w_uv, group_begi
     _check(lib().gqla_expand_cache_tail_fp8(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
                                             C.byref(expanded_fp8), tail_tokens, float(k_scale), float(v_scale), _ptr(ws), ws_bytes,
                                             _stream(stream)), "gqla_expand_cache_tail_fp8")
+
+
+def gqla_left_inverse(shape, w_uk_host: np.ndarray) -> np.ndarray:
+    """Host fp32 [g, r_kv, d_h] -> host fp32 [r_kv, g * d_h]."""
+    w = np.ascontiguousarray(w_uk_host, dtype=np.float32)
+    out = np.empty((shape.r_kv, shape.g * shape.d_h), dtype=np.float32)
+    _check(lib().gqla_left_inverse(C.byref(shape), w.ctypes.data, out.ctypes.data), "gqla_left_inverse")
+    return out
+
+
+def gqla_compress_cache(shape, expanded: gqla_cache, w_inv, latent: gqla_cache, stream=None):
+    _check(lib().gqla_compress_cache(C.byref(shape), C.byref(expanded), _ptr(w_inv), C.byref(latent), _stream(stream)),
+           "gqla_compress_cache")
 
 
 def gqla_expanded_fp8_bytes_per_token(groups, d_h, d_r) -> int:

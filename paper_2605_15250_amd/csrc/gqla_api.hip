@@ -424,6 +424,88 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
+gqla_status gqla_left_inverse(const gqla_shape* shape, const float* w_uk_host, float* w_inv_host) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!w_uk_host || !w_inv_host) return GQLA_ERR_NULL;
+  const int g = shape->g, r = shape->r_kv, d = shape->d_h;
+  const int K = g * d;
+  if (K < r) return GQLA_ERR_SHAPE;  // the stacked key up-projection cannot have full column rank
+  // Gram matrix G = A^T A = sum_j W_UK[j] W_UK[j]^T (r x r), in double
+  std::vector<double> G((size_t)r * r, 0.0);
+  for (int j = 0; j < g; ++j) {
+    const float* w = w_uk_host + (size_t)j * r * d;
+    for (int x = 0; x < r; ++x)
+      for (int y = 0; y <= x; ++y) {
+        double acc = 0.0;
+        for (int k = 0; k < d; ++k) acc += (double)w[(size_t)x * d + k] * (double)w[(size_t)y * d + k];
+        G[(size_t)x * r + y] += acc;
+      }
+  }
+  // Cholesky G = C C^T (lower triangle in place)
+  for (int x = 0; x < r; ++x) {
+    for (int y = 0; y <= x; ++y) {
+      const double diag = G[(size_t)x * r + y];
+      double acc = diag;
+      for (int k = 0; k < y; ++k) acc -= G[(size_t)x * r + k] * G[(size_t)y * r + k];
+      if (x == y) {
+        if (!(acc > 1e-12 * diag)) return GQLA_ERR_SHAPE;  // rank deficient up to the rounding of the Gram matrix
+        G[(size_t)x * r + x] = std::sqrt(acc);
+      } else {
+        G[(size_t)x * r + y] = acc / G[(size_t)y * r + y];
+      }
+    }
+  }
+  // columns of A^T are the rows of A: column (j, k) of A^T is W_UK[j][:, k]; solve G z = that column
+  std::vector<double> z(r);
+  for (int j = 0; j < g; ++j)
+    for (int k = 0; k < d; ++k) {
+      const float* w = w_uk_host + (size_t)j * r * d + k;
+      for (int x = 0; x < r; ++x) {  // forward: C u = a
+        double acc = (double)w[(size_t)x * d];
+        for (int y = 0; y < x; ++y) acc -= G[(size_t)x * r + y] * z[y];
+        z[x] = acc / G[(size_t)x * r + x];
+      }
+      for (int x = r - 1; x >= 0; --x) {  // backward: C^T z = u
+        double acc = z[x];
+        for (int y = x + 1; y < r; ++y) acc -= G[(size_t)y * r + x] * z[y];
+        z[x] = acc / G[(size_t)x * r + x];
+      }
+      for (int x = 0; x < r; ++x) w_inv_host[(size_t)x * K + (size_t)j * d + k] = (float)z[x];
+    }
+  return GQLA_OK;
+}
+
+gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expanded, const void* w_inv,
+                                const gqla_cache* latent, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!expanded || !latent || !w_inv || !expanded->pool || !latent->pool || !expanded->seq_lens) return GQLA_ERR_NULL;
+  if (!aligned16(w_inv) || !aligned16(expanded->pool) || !aligned16(latent->pool)) return GQLA_ERR_ALIGN;
+  if (expanded->groups != shape->g || shape->g * shape->d_h < shape->r_kv) return GQLA_ERR_SHAPE;
+  st = check_page_size(shape, expanded->page_size);
+  if (st != GQLA_OK) return st;
+  if (latent->page_size != expanded->page_size || latent->max_pages != expanded->max_pages || latent->max_pages <= 0 ||
+      latent->num_pages <= 0 || expanded->num_pages <= 0)
+    return GQLA_ERR_PAGE;
+  if (!latent->page_table && (int64_t)latent->num_pages < (int64_t)shape->batch * latent->max_pages) return GQLA_ERR_PAGE;
+  if (!expanded->page_table && (int64_t)expanded->num_pages < (int64_t)shape->batch * expanded->max_pages) return GQLA_ERR_PAGE;
+  if (shape->batch == 0) return GQLA_OK;
+  CompressArgs a;
+  a.expanded = view_of(expanded);
+  a.latent = view_of(latent);
+  a.seq_lens = expanded->seq_lens;
+  a.w_inv = w_inv;
+  a.B = shape->batch;
+  a.g = shape->g;
+  a.d_h = shape->d_h;
+  a.r_kv = shape->r_kv;
+  a.d_r = shape->d_r;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const hipError_t e = shape->dtype == GQLA_BF16 ? launch_compress_bf16(a, s) : launch_compress_f32(a, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
 gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* expanded, const gqla_cache* expanded_fp8,
                                    float k_scale, float v_scale, void* stream) {
   gqla_status st = check_shape(shape);

@@ -262,6 +262,37 @@ __global__ void expand_tail_f32_kernel(ExpandArgs a) {
   }
 }
 
+// Cache compression, fp32: one workgroup per (logical page, sequence); c = A^+ k^C per token, k_R copied.
+__global__ void compress_f32_kernel(CompressArgs a) {
+  const int p = blockIdx.x, b = blockIdx.y;
+  const int L = a.seq_lens[b];
+  const int P = a.expanded.page_size;
+  if ((int64_t)p * P >= L) return;
+  const int32_t pg_in = page_of(a.expanded, b, p), pg_out = page_of(a.latent, b, p);
+  if (pg_in < 0 || pg_out < 0) return;
+  const int valid = min(P, L - p * P);
+  const int g = a.g, W = a.r_kv + a.d_r, K = g * a.d_h;
+  const float* in = (const float*)a.expanded.pool + (int64_t)pg_in * P * (2 * g * a.d_h + a.d_r);
+  float* out = (float*)a.latent.pool + (int64_t)pg_out * P * W;
+  for (int idx = threadIdx.x; idx < valid * W; idx += blockDim.x) {
+    const int slot = idx / W, e = idx % W;
+    float v;
+    if (e < a.r_kv) {
+      const float* w = (const float*)a.w_inv + (int64_t)e * K;
+      float acc = 0.f;
+      for (int k = 0; k < K; ++k) {
+        const int j = k / a.d_h, d = k % a.d_h;
+        acc += w[k] * in[((int64_t)(j * (a.d_h / 8) + d / 8) * P + slot) * 8 + d % 8];
+      }
+      v = acc;
+    } else {
+      const int d = e - a.r_kv;
+      v = in[(int64_t)2 * g * P * a.d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8];
+    }
+    out[(int64_t)slot * W + e] = v;
+  }
+}
+
 // The step's latent rows into their cache slots (any element type: rows are copied as 16-byte vectors).
 // One workgroup per (step token, sequence).
 __global__ void append_latent_kernel(AppendArgs a) {
@@ -278,6 +309,10 @@ __global__ void append_latent_kernel(AppendArgs a) {
 
 }  // namespace
 
+hipError_t launch_compress_f32(const CompressArgs& a, hipStream_t s) {
+  compress_f32_kernel<<<dim3(a.expanded.max_pages, a.B), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
 hipError_t launch_expand_tail_f32(const ExpandArgs& a, hipStream_t s) {
   expand_tail_f32_kernel<<<dim3(a.tail, a.B), 256, 0, s>>>(a);
   return hipGetLastError();

@@ -364,7 +364,79 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
   }
 }
 
+// ---- cache compression: latent from the expanded keys (Sec. 3.1: the reverse cache switch) ----------------
+// c_s = A^+ k^C_s with the caller's left inverse A^+ ([r_kv][g*d_h], k^C ordered group-major, dim-minor); k_R copied.
+// One workgroup of 4 waves per (64 tokens of a page, sequence); wave w owns latent dims [128w, 128w + 128) for both
+// 32-token tiles:
+//   C^T[r][tok] = A^+[r][k] * K^T[k][tok]     A = rows of the left inverse straight from global memory (L2-resident),
+//                                             B = K_C plane vectors (lane = token, 8 consecutive dims)
+// A one-shot deployment step like the expansion; not tuned beyond that.
+template <int DH, int RKV, int DR>
+__global__ void __launch_bounds__(256) compress_bf16_kernel(CompressArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int b = blockIdx.y;
+  const int L = a.seq_lens[b];
+  const int tok0 = blockIdx.x * 64;
+  if (tok0 >= L) return;
+  const int P = a.expanded.page_size;
+  const int g = a.g;
+  const int32_t pg_in = page_of(a.expanded, b, tok0 / P), pg_out = page_of(a.latent, b, tok0 / P);
+  if (pg_in < 0 || pg_out < 0) return;
+  const int slot0 = tok0 % P;
+  const __bf16* in_page = (const __bf16*)a.expanded.pool + (int64_t)pg_in * P * (2 * g * DH + DR);
+  __bf16* out_page = (__bf16*)a.latent.pool + (int64_t)pg_out * P * (RKV + DR);
+  const int K = g * DH;
+  const __bf16* wrow = (const __bf16*)a.w_inv + (int64_t)(128 * wave + n) * K + h * 8;  // row r = 128*wave + 32*rt + n
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[tt][rt][i] = 0.f;
+  for (int j = 0; j < g; ++j) {
+#pragma unroll 2
+    for (int ksl = 0; ksl < DH / 16; ++ksl) {
+      bf16x8 kf[2], wf[4];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+        kf[tt] = *(const bf16x8*)(in_page + ((int64_t)(j * (DH / 8) + 2 * ksl + h) * P + slot0 + 32 * tt + n) * 8);
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt) wf[rt] = *(const bf16x8*)(wrow + (int64_t)rt * 32 * K + j * DH + ksl * 16);
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) acc[tt][rt] = mfma32(wf[rt], kf[tt], acc[tt][rt]);
+    }
+  }
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int slot = slot0 + 32 * tt + n;
+    if (tok0 + 32 * tt + n >= L) continue;
+    __bf16* row = out_page + (int64_t)slot * (RKV + DR);
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const u32x2 v = {pack_bf16(acc[tt][rt][4 * q], acc[tt][rt][4 * q + 1]), pack_bf16(acc[tt][rt][4 * q + 2], acc[tt][rt][4 * q + 3])};
+        *(u32x2*)(row + 128 * wave + 32 * rt + 8 * q + 4 * h) = v;
+      }
+    if (wave == 0) {  // k_R: dims 8c .. 8c + 7 for c = h, h + 2, ...
+      const __bf16* rp = in_page + (int64_t)2 * g * P * DH;
+#pragma unroll
+      for (int c = h; c < DR / 8; c += 2) *(u32x4*)(row + RKV + c * 8) = *(const u32x4*)(rp + ((int64_t)c * P + slot) * 8);
+    }
+  }
+}
+
 }  // namespace
+
+hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
+  const int64_t max_tokens = (int64_t)a.expanded.max_pages * a.expanded.page_size;
+  compress_bf16_kernel<128, 512, 64><<<dim3((unsigned)((max_tokens + 63) / 64), a.B), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
 
 hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   const int rows_per_group = a.rows * a.G;

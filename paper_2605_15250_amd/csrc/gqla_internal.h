@@ -60,6 +60,14 @@ struct ExpandArgs {
   float k_inv_scale, v_inv_scale;  // 8-bit tail variant only: 1 / scale of the two code planes
 };
 
+struct CompressArgs {
+  CacheView expanded;  // all g groups
+  CacheView latent;
+  const int32_t* seq_lens;
+  const void* w_inv;   // [r_kv][g*d_h], the cache's element type
+  int32_t B, g, d_h, r_kv, d_r;
+};
+
 struct QuantizeArgs {
   CacheView src;  // 16-bit expanded cache
   CacheView dst;  // 8-bit expanded cache, same geometry and page ids
@@ -105,6 +113,8 @@ hipError_t launch_expand_tail_bf16(const ExpandArgs&, void* ws /* as above */, h
 hipError_t launch_expand_tail_fp8(const ExpandArgs&, void* ws /* as above */, hipStream_t);  // `expanded` is an 8-bit cache
 hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);
+hipError_t launch_compress_f32(const CompressArgs&, hipStream_t);
+hipError_t launch_compress_bf16(const CompressArgs&, hipStream_t);
 hipError_t launch_decode_gqa_fp8(const DecodeArgs&, float k_scale, float v_scale, hipStream_t);
 
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t);

@@ -131,6 +131,11 @@ class Decoder:
         """rows: [B, s_q, r_kv + d_r] contiguous, the cache's element type."""
         B.gqla_append_latent(self.shape, rows, self.latent_cache())
 
+    def compress(self, w_inv):
+        """Expanded cache -> latent cache (all g groups must be held)."""
+        B.gqla_compress_cache(self.shape, self.expanded_cache(), w_inv, self.latent_cache())
+        return self.latent_pool
+
     # -- 8-bit expanded cache ------------------------------------------------------------------------------
     def fp8_page_bytes(self):
         c = self.cfg

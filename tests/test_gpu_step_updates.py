@@ -107,3 +107,59 @@ def test_tail_expand_of_a_group_slice():
             assert np.array_equal(r2[lo:], case.kR(b)[lo:])
     finally:
         case.close()
+
+
+@pytest.mark.parametrize("key,lens,page_size", [
+    ("C3", [300, 2, 129, 1000], 64),
+    ("C0", [40, 7, 17], 8),
+])
+def test_compress_is_the_reverse_cache_switch(key, lens, page_size):
+    """Sec. 3.1 (the cache is converted once, in either direction): expanded cache -> latent cache through the left inverse of the stacked
+    key up-projection.  Isolated: GPU and oracle both consume the oracle's expansion rounded to the storage type and
+    the same (rounded) left inverse.  Round trip on the GPU: expand, compress, decode on the recovered latent."""
+    from paper_2605_15250_amd import binding as B
+    if key == "C0":
+        cfg = S.CONFIGS[key].with_(B=len(lens), L=0, paged=True, page_size=page_size, seed=3141, g=4, h_q=8)   # g d_h = 64 >= r_kv = 32
+    else:
+        cfg = S.CONFIGS[key].with_(B=len(lens), L=0, paged=True, page_size=page_size, seed=3141)
+    case = Case(cfg, lens=lens)
+    dec = case.dec
+    try:
+        W = cfg.r_kv + cfg.d_r
+        w_inv = B.gqla_left_inverse(dec.shape, case.w_uk)                 # host, fp32
+        w_inv_q = S.quantize(w_inv, cfg.dtype)
+        d_w_inv = case.to_device(w_inv_q, cfg.dtype)
+        KCq, Vq, kR = [], [], []
+        for b in range(cfg.B):
+            KC, V = O.expand_latent(case.c(b), case.w_uk, case.w_uv)
+            KCq.append(S.quantize(KC, cfg.dtype)); Vq.append(S.quantize(V, cfg.dtype)); kR.append(case.kR(b))
+        dec.expanded_pool = case.to_device(Lay.pack_expanded_pool(KCq, Vq, kR, case.table, case.num_pages, cfg.page_size, fill=0.0), cfg.dtype)
+        truth = dec.latent_pool
+        dec.latent_pool = torch.full_like(truth, float("nan"))
+        dec.compress(d_w_inv)
+        torch.cuda.synchronize()
+        got = host(dec.latent_pool).reshape(case.num_pages, cfg.page_size, W)
+        assert int(np.isnan(got).sum()) == got.size - int(case.lens.sum()) * W      # nothing beyond the tokens is written
+        for b in range(cfg.B):
+            L = int(case.lens[b])
+            t = np.arange(L)
+            rows = got[case.table[b][t // cfg.page_size], t % cfg.page_size]
+            ref = KCq[b].reshape(L, -1).astype(np.float64) @ w_inv_q.astype(np.float64).T
+            check("compress c_kv seq %d" % b, rows[:, :cfg.r_kv], ref, cfg.dtype, scale_abs=4.0)
+            assert np.array_equal(rows[:, cfg.r_kv:], case.kR(b)), "k_R must be copied bit for bit"
+            # and it is the latent again, up to what the 16-bit roundings of the keys and of the left inverse cost
+            err = np.linalg.norm(rows[:, :cfg.r_kv] - case.c(b)) / np.linalg.norm(case.c(b))
+            print("recovered latent vs the original, seq %d: rel_l2 %.3e" % (b, err), flush=True)
+            assert err < (2e-2 if cfg.dtype == "bf16" else 1e-4)
+        # round trip on the GPU: the decode on the recovered latent cache
+        q_hat = dec.absorb_query(case.d_q_c, case.d_w_uk)
+        out, _ = dec.decode_absorb(q_hat, case.d_q_r, case.d_w_uv)
+        torch.cuda.synchronize()
+        ref_o = np.stack([O.decode_gqa(case.q_c[b], case.q_r[b], *O.expand_latent(case.c(b), case.w_uk, case.w_uv), case.kR(b))[0]
+                          for b in range(cfg.B)])
+        o = host(out)
+        rl = float(np.linalg.norm(o - ref_o) / np.linalg.norm(ref_o))
+        print("decode on the recovered latent vs the exact decode: rel_l2 %.3e" % rl, flush=True)
+        assert np.isfinite(o).all() and rl < (3e-2 if cfg.dtype == "bf16" else 1e-4)
+    finally:
+        case.close()

@@ -240,3 +240,23 @@ def test_calibrated_path_choice_matches_the_measured_operating_points():
             assert ch["faster_path"] == (B.GQLA_PATH_GQA if t_g < t_a else B.GQLA_PATH_ABSORB), (Bn, g, s_q)
     with pytest.raises(B.GqlaError):
         B.gqla_select_path(B.make_shape(1, 8, 2, 16, 32, 8, 1, B.GQLA_F32), 64)
+
+
+def test_left_inverse_on_the_host_matches_the_oracle():
+    """gqla_left_inverse (Cholesky of A^T A in double, host only) against the oracle's left inverse, on the tiny config
+    and on a canonical-size group count; error codes for a rank that cannot be inverted."""
+    from oracle import gqla_oracle as O
+    rng = np.random.default_rng(12)
+    for g, r_kv, d_h in ((2, 32, 16), (4, 64, 32)):
+        w = rng.normal(size=(g, r_kv, d_h)).astype(np.float32) / np.sqrt(r_kv)
+        sh = B.make_shape(1, g * 4, g, d_h, r_kv, 8, 1, B.GQLA_F32)
+        got = B.gqla_left_inverse(sh, w)
+        want = O.left_inverse_uk(w)
+        assert got.shape == want.shape == (r_kv, g * d_h)
+        assert np.max(np.abs(got - want)) <= 1e-5 * np.max(np.abs(want))
+    # g d_h < r_kv: no left inverse
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_left_inverse, B.make_shape(1, 8, 1, 16, 32, 8, 1, B.GQLA_F32), np.zeros((1, 32, 16), np.float32))
+    # rank-deficient keys (two identical rows of every W_UK[j])
+    w = rng.normal(size=(2, 32, 16)).astype(np.float32)
+    w[:, 1, :] = w[:, 0, :]
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_left_inverse, B.make_shape(1, 8, 2, 16, 32, 8, 1, B.GQLA_F32), w)

@@ -375,7 +375,7 @@ def test_generators_are_reproducible_and_per_sequence():
 
 
 def test_compress_is_the_inverse_of_expand_and_the_least_squares_solution():
-    """Sec. 3.1, "one-shot cache compress/expand": compressing an exact expansion returns the latent (g d_h >= r_kv),
+    """Sec. 3.1 (the cache is converted once, in either direction): compressing an exact expansion returns the latent (g d_h >= r_kv),
     and on perturbed keys the result is numpy's least-squares solution of A c = k^C, token by token."""
     rng = np.random.default_rng(5)
     g, r_kv, d_h, L = 3, 10, 4, 7                     # g d_h = 12 >= r_kv = 10
