@@ -237,7 +237,7 @@ def main():
         d_w_inv = to_device(S.quantize(w_inv, cg.dtype), cg.dtype)
         truth = gd.latent_pool
         gd.latent_pool = torch.zeros_like(truth)
-        t_cmp = timed(lambda: gd.compress(d_w_inv), 5)
+        t_cmp = timed_steady(lambda: gd.compress(d_w_inv), 10)
         rec = gd.latent_pool.view(-1, Wl)[pos.view(-1)][:, :cg.r_kv].float()
         ref = truth.view(-1, Wl)[pos.view(-1)][:, :cg.r_kv].float()
         cmp_flops = 2.0 * Lsum * cg.g * cg.d_h * cg.r_kv

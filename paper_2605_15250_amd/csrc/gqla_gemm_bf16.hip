@@ -364,30 +364,79 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
   }
 }
 
-// ---- cache compression: latent from the expanded keys (Sec. 3.1: the reverse cache switch) ----------------
+// ---- cache compression: latent from the expanded keys (Sec. 3.1: the reverse cache switch) --------------------------
 // c_s = A^+ k^C_s with the caller's left inverse A^+ ([r_kv][g*d_h], k^C ordered group-major, dim-minor); k_R copied.
-// One workgroup of 4 waves per (64 tokens of a page, sequence); wave w owns latent dims [128w, 128w + 128) for both
-// 32-token tiles:
-//   C^T[r][tok] = A^+[r][k] * K^T[k][tok]     A = rows of the left inverse straight from global memory (L2-resident),
-//                                             B = K_C plane vectors (lane = token, 8 consecutive dims)
-// A one-shot deployment step like the expansion; not tuned beyond that.
+// One workgroup of 8 waves per (128 tokens, sequence) computes all r_kv latent dims of its tokens; wave (tw, rw)
+// owns tokens [64 tw, 64 tw + 64) x latent dims [128 rw, 128 rw + 128):
+//   C^T[r][tok] = A^+[r][k] * K^T[k][tok]
+// The contraction runs in stages of 32 k.  Per stage the workgroup stages the [512 x 32] slice of A^+ and the
+// [128 tokens x 32] slice of the K_C plane through LDS (registers -> LDS, three buffers, one barrier per stage), as
+// planes of 8-element vectors, so that each MFMA operand is one conflict-free 16-byte LDS read; every element of A^+
+// is fetched once per 128 tokens instead of once per wave.
+constexpr int kCompressKS = 32;                       // contraction elements per stage
+constexpr int kCompressTok = 128;                     // tokens per workgroup
+template <int RKV>
+constexpr int compress_lds_bytes() {
+  return 3 * (kCompressKS / 8) * ((RKV + 4) + kCompressTok) * 16;
+}
+
 template <int DH, int RKV, int DR>
-__global__ void __launch_bounds__(256) compress_bf16_kernel(CompressArgs a) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__global__ void __launch_bounds__(512) compress_bf16_kernel(CompressArgs a) {
+  static_assert(RKV == 512 && DH % kCompressKS == 0, "wave tiling below assumes 4 blocks of 128 latent dims");
+  constexpr int NC = kCompressKS / 8;                 // vector planes per stage
+  constexpr int WPL = RKV + 4;                        // plane stride of the A^+ tile, in vectors (padding spreads the writes)
+  constexpr int BUF = NC * (WPL + kCompressTok);      // vectors per buffer
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  u32x4* smem = (u32x4*)smem_raw;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
+  const int tw = wave & 1, rw = wave >> 1;
   const int b = blockIdx.y;
   const int L = a.seq_lens[b];
-  const int tok0 = blockIdx.x * 64;
+  const int tok0 = blockIdx.x * kCompressTok;
   if (tok0 >= L) return;
   const int P = a.expanded.page_size;
   const int g = a.g;
-  const int32_t pg_in = page_of(a.expanded, b, tok0 / P), pg_out = page_of(a.latent, b, tok0 / P);
-  if (pg_in < 0 || pg_out < 0) return;
-  const int slot0 = tok0 % P;
-  const __bf16* in_page = (const __bf16*)a.expanded.pool + (int64_t)pg_in * P * (2 * g * DH + DR);
-  __bf16* out_page = (__bf16*)a.latent.pool + (int64_t)pg_out * P * (RKV + DR);
   const int K = g * DH;
-  const __bf16* wrow = (const __bf16*)a.w_inv + (int64_t)(128 * wave + n) * K + h * 8;  // row r = 128*wave + 32*rt + n
+  const int64_t in_page_elems = (int64_t)P * (2 * g * DH + DR);
+
+  // staging role of this thread: one K vector per stage (token kt of the tile, plane kc) and four A^+ vectors
+  const int kt = tid & (kCompressTok - 1), kc = tid >> 7;
+  const __bf16* ksrc = nullptr;
+  {
+    const int tk = tok0 + (kt & 64);
+    if (tk < L) {
+      const int32_t pg = page_of(a.expanded, b, tk / P);
+      if (pg >= 0) ksrc = (const __bf16*)a.expanded.pool + pg * in_page_elems + ((int64_t)kc * P + tk % P + (kt & 63)) * 8;
+    }
+  }
+  const __bf16* wsrc = (const __bf16*)a.w_inv + (int64_t)(tid >> 2) * K + (tid & 3) * 8;   // + i * 128 rows, + stage * 32
+  const int wdst = (tid & 3) * WPL + (tid >> 2);                                            // + i * 128
+  const int kdst = NC * WPL + kc * kCompressTok + kt;
+
+  // Global memory is read in pairs of stages (64 contraction elements: whole 128-byte lines of A^+, the two halves
+  // requested back to back) into two register sets.  Rows of A^+ are 2 g d_h bytes apart, a power of two; as a
+  // precaution against all workgroups of an L2 asking for the same address bits at once, every eighth workgroup starts
+  // the contraction at a different stage pair and walks it cyclically (measured: neutral on this chip).
+  u32x4 wreg[2][4], kreg[2];
+  const int stages = K / kCompressKS, pairs = stages / 2;
+  const int rot = (int)((blockIdx.x + gridDim.x * blockIdx.y) >> 3) % pairs;
+  auto fetch = [&](int e, int step) {                 // half e of the step-th stage pair of this workgroup's walk
+    const int pr = step + rot < pairs ? step + rot : step + rot - pairs;
+    const int st = 2 * pr + e;
+    const int j = st / (DH / kCompressKS), v0 = j * (DH / 8) + (st % (DH / kCompressKS)) * NC;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wreg[e][i] = *(const u32x4*)(wsrc + (int64_t)i * 128 * K + st * kCompressKS);
+    kreg[e] = ksrc ? *(const u32x4*)(ksrc + (int64_t)v0 * P * 8) : u32x4{0u, 0u, 0u, 0u};
+  };
+  auto stash = [&](int e, int buf) {
+    u32x4* dst = smem + buf * BUF;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[wdst + i * 128] = wreg[e][i];
+    dst[kdst] = kreg[e];
+  };
+
   f32x16 acc[2][4];
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt)
@@ -395,34 +444,67 @@ __global__ void __launch_bounds__(256) compress_bf16_kernel(CompressArgs a) {
     for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[tt][rt][i] = 0.f;
-  for (int j = 0; j < g; ++j) {
-#pragma unroll 2
-    for (int ksl = 0; ksl < DH / 16; ++ksl) {
-      bf16x8 kf[2], wf[4];
+
+  auto compute = [&](int buf) {
+    const u32x4* wt = smem + buf * BUF;
+    const u32x4* ktile = wt + NC * WPL;
+#pragma unroll
+    for (int ks = 0; ks < kCompressKS / 16; ++ks) {
+      u32x4 kf[2], wf[4];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) kf[tt] = ktile[(2 * ks + h) * kCompressTok + 64 * tw + 32 * tt + n];
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt) wf[rt] = wt[(2 * ks + h) * WPL + 128 * rw + 32 * rt + n];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
-        kf[tt] = *(const bf16x8*)(in_page + ((int64_t)(j * (DH / 8) + 2 * ksl + h) * P + slot0 + 32 * tt + n) * 8);
 #pragma unroll
-      for (int rt = 0; rt < 4; ++rt) wf[rt] = *(const bf16x8*)(wrow + (int64_t)rt * 32 * K + j * DH + ksl * 16);
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int rt = 0; rt < 4; ++rt) acc[tt][rt] = mfma32(wf[rt], kf[tt], acc[tt][rt]);
+        for (int rt = 0; rt < 4; ++rt)
+          acc[tt][rt] = mfma32(__builtin_bit_cast(bf16x8, wf[rt]), __builtin_bit_cast(bf16x8, kf[tt]), acc[tt][rt]);
     }
+  };
+
+  // Step s (in the rotated order) is computed from buffer s % 3 while step s + 1 goes from registers into buffer
+  // (s + 1) % 3 -- last read in iteration s - 2, which every wave has left through the barrier of iteration s - 1.
+  // Each register set is refilled from global memory right after it has been written to LDS, two steps before it is
+  // needed again.
+  fetch(0, 0);
+  fetch(1, 0);
+  stash(0, 0);
+  if (pairs > 1) fetch(0, 1);
+  __syncthreads();
+  int buf = 0;                                        // buffer of the even step of the pair
+  for (int pr = 0; pr < pairs; ++pr) {
+    const int b1 = buf == 2 ? 0 : buf + 1, b2 = b1 == 2 ? 0 : b1 + 1;
+    stash(1, b1);                                     // odd step of this pair
+    if (pr + 1 < pairs) fetch(1, pr + 1);
+    compute(buf);
+    __syncthreads();
+    if (pr + 1 < pairs) stash(0, b2);                 // even step of the next pair
+    if (pr + 2 < pairs) fetch(0, pr + 2);
+    compute(b1);
+    __syncthreads();
+    buf = b2;
   }
+
+  const int tokh = tok0 + 64 * tw;                    // this wave's 64 tokens lie in one page
+  if (tokh >= L) return;
+  const int32_t pg_in = page_of(a.expanded, b, tokh / P), pg_out = page_of(a.latent, b, tokh / P);
+  if (pg_in < 0 || pg_out < 0) return;
+  const __bf16* in_page = (const __bf16*)a.expanded.pool + pg_in * in_page_elems;
+  __bf16* out_page = (__bf16*)a.latent.pool + (int64_t)pg_out * P * (RKV + DR);
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt) {
-    const int slot = slot0 + 32 * tt + n;
-    if (tok0 + 32 * tt + n >= L) continue;
+    const int slot = tokh % P + 32 * tt + n;
+    if (tokh + 32 * tt + n >= L) continue;
     __bf16* row = out_page + (int64_t)slot * (RKV + DR);
 #pragma unroll
     for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const u32x2 v = {pack_bf16(acc[tt][rt][4 * q], acc[tt][rt][4 * q + 1]), pack_bf16(acc[tt][rt][4 * q + 2], acc[tt][rt][4 * q + 3])};
-        *(u32x2*)(row + 128 * wave + 32 * rt + 8 * q + 4 * h) = v;
+        *(u32x2*)(row + 128 * rw + 32 * rt + 8 * q + 4 * h) = v;
       }
-    if (wave == 0) {  // k_R: dims 8c .. 8c + 7 for c = h, h + 2, ...
+    if (rw == 0) {  // k_R: dims 8c .. 8c + 7 for c = h, h + 2, ...
       const __bf16* rp = in_page + (int64_t)2 * g * P * DH;
 #pragma unroll
       for (int c = h; c < DR / 8; c += 2) *(u32x4*)(row + RKV + c * 8) = *(const u32x4*)(rp + ((int64_t)c * P + slot) * 8);
@@ -433,8 +515,12 @@ __global__ void __launch_bounds__(256) compress_bf16_kernel(CompressArgs a) {
 }  // namespace
 
 hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
+  constexpr int lds = compress_lds_bytes<512>();
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)compress_bf16_kernel<128, 512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr != hipSuccess) return attr;
   const int64_t max_tokens = (int64_t)a.expanded.max_pages * a.expanded.page_size;
-  compress_bf16_kernel<128, 512, 64><<<dim3((unsigned)((max_tokens + 63) / 64), a.B), 256, 0, s>>>(a);
+  compress_bf16_kernel<128, 512, 64><<<dim3((unsigned)((max_tokens + kCompressTok - 1) / kCompressTok), a.B), 512, lds, s>>>(a);
   return hipGetLastError();
 }
 
