@@ -276,3 +276,46 @@ def gather_rows(pool_rows, page_row, L_b, page_size):
     row t lives in page page_row[t // page_size] at slot t % page_size."""
     t = np.arange(int(L_b))
     return pool_rows[np.asarray(page_row)[t // page_size], t % page_size]
+
+
+# ----------------------------------------------------------------------------------------
+# the steps either side of the path: decoupled RoPE (Sec. 3.1, "Architecture") and W^O (last
+# line of both path equations)
+# ----------------------------------------------------------------------------------------
+def rope(x, t, base=10000.0):
+    """rope_t(x) of Sec. 3.1 ("Architecture": q^R and k^R carry the position).  The paper takes the rotary
+    embedding over from MLA without restating it; the reading here is the rotary embedding as published:
+    the vector is d/2 adjacent pairs (x[2p], x[2p+1]) and pair p turns by the angle t * base^(-2p/d).
+    x [..., d] (d even), t an integer position (scalar or broadcastable to x[..., 0])."""
+    x = np.asarray(x, F64)
+    d = x.shape[-1]
+    if d % 2:
+        raise ValueError("rope needs an even dimension")
+    p = np.arange(d // 2, dtype=F64)
+    theta = float(base) ** (-2.0 * p / d)                    # one frequency per pair
+    ang = np.asarray(t, F64)[..., None] * theta              # [..., d/2]
+    cos, sin = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    out[..., 0::2] = x[..., 0::2] * cos - x[..., 1::2] * sin
+    out[..., 1::2] = x[..., 0::2] * sin + x[..., 1::2] * cos
+    return out
+
+
+def rope_step(qR_raw, kR_raw, L, base=10000.0):
+    """The step's rotated inputs: q^R_{t,i} = rope_t(.) for every head and k^R_t = rope_t(.) of the new tokens
+    (Sec. 3.1, "Architecture"), with step token t at position L - s_q + t (L counts the step's own tokens, as in
+    n_visible).  qR_raw [s_q, h_q, d_R], kR_raw [s_q, d_R]."""
+    qR_raw = np.asarray(qR_raw, F64)
+    kR_raw = np.asarray(kR_raw, F64)
+    s_q = qR_raw.shape[0]
+    pos = L - s_q + np.arange(s_q)
+    return rope(qR_raw, pos[:, None], base), rope(kR_raw, pos, base)
+
+
+def output_projection(o, W_O):
+    """y_t = W^O [o_{t,1}; ...; o_{t,h_q}] (last line of the GQA-path and of the MQA-absorb equation).
+    o [s_q, h_q, d_h]; W_O [D, h_q * d_h] -> y [s_q, D]."""
+    o = np.asarray(o, F64)
+    W_O = np.asarray(W_O, F64)
+    s_q = o.shape[0]
+    return o.reshape(s_q, -1) @ W_O.T

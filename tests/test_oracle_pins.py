@@ -395,3 +395,85 @@ def test_compress_is_the_inverse_of_expand_and_the_least_squares_solution():
     only1 = np.zeros_like(KC)
     only1[:, 1, :] = KC[:, 1, :]
     assert np.max(np.abs(O.compress_expanded(only1, W_UK) - KC[:, 1, :] @ Linv[:, d_h:2 * d_h].T)) < 1e-12
+
+
+def test_rope_closed_forms_and_relative_position_property():
+    """Sec. 3.1 ("Architecture"): rope_t.  Pins: identity at t = 0; a unit vector in pair 0 turns by exactly t
+    radians, counter-clockwise; pair p turns base^(-2p/d) times as fast; the complex-number form of the same
+    rotation; norm preservation; and what the method relies on: <rope_t q, rope_s k> depends on t - s only."""
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(3, 8))
+    assert np.array_equal(O.rope(x, 0), x)
+    # d = 2: the plane rotation by t radians, whatever the base
+    for base in (10000.0, 7.0):
+        got = O.rope(np.array([1.0, 0.0]), 1, base)
+        assert np.allclose(got, [np.cos(1.0), np.sin(1.0)], atol=1e-15)
+        got = O.rope(np.array([0.0, 1.0]), 2, base)
+        assert np.allclose(got, [-np.sin(2.0), np.cos(2.0)], atol=1e-15)
+    # d = 4, base 10000: pair 1 has frequency 10000^(-2/4) = 0.01, and it is the pair of elements 2 and 3
+    got = O.rope(np.array([0.0, 0.0, 1.0, 0.0]), 50, 10000.0)
+    assert np.allclose(got, [0.0, 0.0, np.cos(0.5), np.sin(0.5)], atol=1e-15)
+    got = O.rope(np.array([1.0, 0.0, 0.0, 0.0]), 50, 10000.0)
+    assert np.allclose(got, [np.cos(50.0), np.sin(50.0), 0.0, 0.0], atol=1e-13)
+    # complex form: (x[2p] + i x[2p+1]) * exp(i t theta_p)
+    d, t, base = 8, 37, 10000.0
+    z = (x[:, 0::2] + 1j * x[:, 1::2]) * np.exp(1j * t * base ** (-np.arange(d // 2) * 2.0 / d))
+    got = O.rope(x, t, base)
+    assert np.allclose(got[:, 0::2], z.real, atol=1e-13) and np.allclose(got[:, 1::2], z.imag, atol=1e-13)
+    # per-row positions broadcast
+    pos = np.array([3, 11, 29])
+    got = O.rope(x, pos)
+    for r in range(3):
+        assert np.allclose(got[r], O.rope(x[r], int(pos[r])), atol=1e-15)
+    assert np.allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(x, axis=-1), atol=1e-13)
+    # relative positions
+    q, k = rng.normal(size=64), rng.normal(size=64)
+    for t, s in ((100, 90), (5000, 4990), (17, 7)):
+        assert abs(O.rope(q, t) @ O.rope(k, s) - O.rope(q, t - s) @ k) < 1e-10
+    assert abs(O.rope(q, 100) @ O.rope(k, 90) - O.rope(q, 100) @ O.rope(k, 91)) > 1e-3      # and on nothing less
+
+
+def test_rope_step_positions_follow_the_in_step_mask():
+    """Step token t sits at position L - s_q + t, the position n_visible uses; decoding with rotated inputs is
+    invariant under shifting every position by the same amount (the logits see position differences only)."""
+    rng = np.random.default_rng(6)
+    s_q, h_q, g, d_h, d_r, r_kv, L = 2, 4, 2, 8, 4, 16, 9
+    qR_raw, kR_raw_all = rng.normal(size=(s_q, h_q, d_r)), rng.normal(size=(L, d_r))
+    qR, kR_new = O.rope_step(qR_raw, kR_raw_all[L - s_q:], L)
+    assert np.allclose(qR[0], O.rope(qR_raw[0], L - 2)) and np.allclose(qR[1], O.rope(qR_raw[1], L - 1))
+    assert np.allclose(kR_new[0], O.rope(kR_raw_all[L - 2], L - 2)) and np.allclose(kR_new[1], O.rope(kR_raw_all[L - 1], L - 1))
+    qC = rng.normal(size=(s_q, h_q, d_h))
+    c = rng.normal(size=(L, r_kv))
+    W_UK, W_UV = rng.normal(size=(g, r_kv, d_h)), rng.normal(size=(g, r_kv, d_h))
+    KC, V = O.expand_latent(c, W_UK, W_UV)
+    outs = []
+    for shift in (0, 1000):
+        kR = O.rope(kR_raw_all, np.arange(L) + shift)
+        qRs = O.rope(qR_raw, (L - s_q + np.arange(s_q) + shift)[:, None])
+        outs.append(O.decode_gqa(qC, qRs, KC, V, kR)[0])
+    assert np.max(np.abs(outs[0] - outs[1])) < 1e-10
+    # the cache of shift 0 is what rope_step produces token by token
+    kR0 = O.rope(kR_raw_all, np.arange(L))
+    assert np.allclose(kR0[L - s_q:], kR_new, atol=1e-15)
+
+
+def test_output_projection_is_the_sum_of_per_head_blocks():
+    """Last line of both path equations: y = W^O [o_1; ...; o_hq] = sum_i W^O[:, i d_h:(i+1) d_h] o_i; the identity
+    returns the concatenation; and the whole layer agrees between the two paths."""
+    rng = np.random.default_rng(7)
+    s_q, h_q, g, d_h, d_r, r_kv, L, D = 2, 4, 2, 8, 4, 16, 11, 12
+    o = rng.normal(size=(s_q, h_q, d_h))
+    W_O = rng.normal(size=(D, h_q * d_h))
+    want = np.zeros((s_q, D))
+    for t in range(s_q):
+        for i in range(h_q):
+            want[t] += W_O[:, i * d_h:(i + 1) * d_h] @ o[t, i]
+    assert np.max(np.abs(O.output_projection(o, W_O) - want)) < 1e-12
+    assert np.array_equal(O.output_projection(o, np.eye(h_q * d_h)), o.reshape(s_q, -1))
+    qC, qR = rng.normal(size=(s_q, h_q, d_h)), rng.normal(size=(s_q, h_q, d_r))
+    c, kR = rng.normal(size=(L, r_kv)), rng.normal(size=(L, d_r))
+    W_UK, W_UV = rng.normal(size=(g, r_kv, d_h)), rng.normal(size=(g, r_kv, d_h))
+    KC, V = O.expand_latent(c, W_UK, W_UV)
+    y_g = O.output_projection(O.decode_gqa(qC, qR, KC, V, kR)[0], W_O)
+    y_a = O.output_projection(O.decode_absorb(O.absorb_query(qC, W_UK), qR, c, kR, W_UV)[0], W_O)
+    assert np.max(np.abs(y_g - y_a)) < 1e-10
