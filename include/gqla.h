@@ -188,6 +188,29 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
                             const gqla_cache* expanded, void* out, float* lse, void* ws, size_t ws_bytes,
                             void* stream);
 
+/* ---- the steps either side of the path: rotary embedding of the step's inputs, output projection ------------------
+ * gqla_rope_step applies rope_t (Sec. 3.1, "Architecture": q^R_{t,i} = rope_t(.), k^R_t = rope_t(.)) IN PLACE to the
+ * step's un-rotated vectors: q_r [B][s_q][h_q][d_r] (every head) and the k_R part (columns r_kv .. r_kv + d_r - 1) of
+ * rows [B][s_q][r_kv + d_r], the rows gqla_append_latent takes; either pointer may be NULL (not both).  Step token i of
+ * sequence b has position t = L_b - s_q + i, L_b read from seq_lens (device memory, int32[B], the lengths that already
+ * count the step's tokens); tokens with t < 0 are left alone.  The paper takes the rotary embedding over from MLA
+ * without restating it; this library uses the published form: d_r/2 adjacent pairs (x[2p], x[2p+1]), pair p turned by
+ * the angle t * rope_base^(-2p/d_r) (angle, sine and cosine in double precision, the rotation in fp32, the result
+ * rounded to the element type).  Errors: GQLA_ERR_SHAPE unless rope_base is finite and > 1 and d_r, r_kv are even.
+ *
+ * gqla_output_projection computes y_t = W^O [o_{t,1}; ...; o_{t,h_q}] (last line of the GQA-path and of the MQA-absorb
+ * equation): o is a decode call's output [B][s_q][h_q][d_h], w_o is [d_model][h_q * d_h] row-major (the paper's
+ * W^O in R^{D x h_q d_h}), y is [B][s_q][d_model]; all device memory of the shape's element type, fp32 accumulation.
+ * With GQLA_BF16, d_model must be a multiple of 128 and h_q * d_h of 256 (GQLA_ERR_SHAPE otherwise), and the call may
+ * need device scratch: ws of at least gqla_output_projection_workspace_bytes(shape, d_model) bytes, 16-byte aligned
+ * (fp32 partial sums over ranges of the contraction, added in a fixed order; GQLA_ERR_NULL / GQLA_ERR_WORKSPACE when
+ * it is needed and missing or too small).  GQLA_F32 needs none.  Both calls only enqueue work on `stream`. */
+gqla_status gqla_rope_step(const gqla_shape* shape, const int32_t* seq_lens, float rope_base, void* q_r, void* rows,
+                           void* stream);
+gqla_status gqla_output_projection(const gqla_shape* shape, int32_t d_model, const void* o, const void* w_o, void* y,
+                                   void* ws, size_t ws_bytes, void* stream);
+size_t gqla_output_projection_workspace_bytes(const gqla_shape* shape, int32_t d_model);
+
 /* ---- cache compression: the reverse switch (Sec. 3.1: the cache is converted once, in either direction, at deployment) ----
  * The expansion k^C = A c, A = [W_UK[0]^T; ...; W_UK[g-1]^T] in R^{g d_h x r_kv}, can be undone when A has full column
  * rank (needs g d_h >= r_kv): c = A^+ k^C with the left inverse A^+ = (A^T A)^{-1} A^T in R^{r_kv x g d_h}.

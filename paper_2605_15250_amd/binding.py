@@ -24,7 +24,8 @@ EXPORTS = [
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
     "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8",
-    "gqla_left_inverse", "gqla_compress_cache",
+    "gqla_left_inverse", "gqla_compress_cache", "gqla_rope_step", "gqla_output_projection",
+    "gqla_output_projection_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
 ]
@@ -106,6 +107,12 @@ def lib():
         L.gqla_left_inverse.restype = i32
         L.gqla_compress_cache.argtypes = [sp, cp, vp, cp, vp]
         L.gqla_compress_cache.restype = i32
+        L.gqla_rope_step.argtypes = [sp, vp, C.c_float, vp, vp, vp]
+        L.gqla_rope_step.restype = i32
+        L.gqla_output_projection.argtypes = [sp, i32, vp, vp, vp, vp, C.c_size_t, vp]
+        L.gqla_output_projection.restype = i32
+        L.gqla_output_projection_workspace_bytes.argtypes = [sp, i32]
+        L.gqla_output_projection_workspace_bytes.restype = C.c_size_t
         L.gqla_expanded_fp8_bytes_per_token.argtypes = [i32, i32, i32]
         L.gqla_expanded_fp8_bytes_per_token.restype = i64
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
@@ -309,6 +316,22 @@ def gqla_left_inverse(shape, w_uk_host: np.ndarray) -> np.ndarray:
 def gqla_compress_cache(shape, expanded: gqla_cache, w_inv, latent: gqla_cache, stream=None):
     _check(lib().gqla_compress_cache(C.byref(shape), C.byref(expanded), _ptr(w_inv), C.byref(latent), _stream(stream)),
            "gqla_compress_cache")
+
+
+def gqla_rope_step(shape, seq_lens, rope_base, q_r, rows, stream=None):
+    _check(lib().gqla_rope_step(C.byref(shape), _ptr(seq_lens), float(rope_base), _ptr(q_r), _ptr(rows), _stream(stream)),
+           "gqla_rope_step")
+
+
+def gqla_output_projection(shape, d_model, o, w_o, y, ws=None, ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().gqla_output_projection(C.byref(shape), int(d_model), _ptr(o), _ptr(w_o), _ptr(y), _ptr(ws), ws_bytes,
+                                        _stream(stream)), "gqla_output_projection")
+
+
+def gqla_output_projection_workspace_bytes(shape, d_model) -> int:
+    return lib().gqla_output_projection_workspace_bytes(C.byref(shape), int(d_model))
 
 
 def gqla_expanded_fp8_bytes_per_token(groups, d_h, d_r) -> int:

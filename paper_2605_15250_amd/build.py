@@ -13,7 +13,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgqla.so")
 
 SOURCES = ["gqla_api.hip", "gqla_f32.hip", "gqla_gqa_bf16.hip", "gqla_absorb_bf16.hip", "gqla_gemm_bf16.hip",
-           "gqla_probe.hip", "gqla_fp8.hip"]
+           "gqla_probe.hip", "gqla_fp8.hip", "gqla_step_ops.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fno-gpu-rdc",

@@ -424,6 +424,70 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
+gqla_status gqla_rope_step(const gqla_shape* shape, const int32_t* seq_lens, float rope_base, void* q_r, void* rows,
+                           void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!seq_lens || (!q_r && !rows)) return GQLA_ERR_NULL;
+  if ((q_r && !aligned16(q_r)) || (rows && !aligned16(rows))) return GQLA_ERR_ALIGN;
+  if (!(rope_base > 1.0f) || !std::isfinite(rope_base) || shape->d_r % 2 || shape->r_kv % 2) return GQLA_ERR_SHAPE;
+  if (shape->batch == 0) return GQLA_OK;
+  RopeArgs a;
+  a.q_r = q_r;
+  a.rows = rows;
+  a.seq_lens = seq_lens;
+  a.log2_base = std::log2((double)rope_base);
+  a.B = shape->batch;
+  a.s_q = shape->s_q;
+  a.h_q = shape->h_q;
+  a.d_r = shape->d_r;
+  a.r_kv = shape->r_kv;
+  a.row_elems = shape->r_kv + shape->d_r;
+  const hipError_t e = launch_rope_step(a, shape->dtype == GQLA_BF16, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+size_t gqla_output_projection_workspace_bytes(const gqla_shape* shape, int32_t d_model) {
+  if (check_shape(shape) != GQLA_OK || d_model <= 0 || shape->dtype != GQLA_BF16) return 0;
+  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * shape->d_h;
+  if (M == 0 || d_model % 128 || K % 256) return 0;
+  int krange = 0;
+  const int ksplit = out_proj_split((int)M, (int)K, d_model, &krange);
+  return ksplit > 1 ? (size_t)ksplit * M * d_model * sizeof(float) : 0;
+}
+
+gqla_status gqla_output_projection(const gqla_shape* shape, int32_t d_model, const void* o, const void* w_o, void* y,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (!o || !w_o || !y) return GQLA_ERR_NULL;
+  if (!aligned16(o) || !aligned16(w_o) || !aligned16(y) || (ws && !aligned16(ws))) return GQLA_ERR_ALIGN;
+  if (d_model <= 0) return GQLA_ERR_SHAPE;
+  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * shape->d_h;
+  if (M > INT32_MAX || K > INT32_MAX) return GQLA_ERR_SHAPE;
+  if (M == 0) return GQLA_OK;
+  OutProjArgs a;
+  a.o = o;
+  a.w_o = w_o;
+  a.y = y;
+  a.partial = nullptr;
+  a.M = (int32_t)M;
+  a.K = (int32_t)K;
+  a.D = d_model;
+  a.ksplit = 1;
+  a.krange = (int32_t)K;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (shape->dtype != GQLA_BF16) return launch_out_proj_f32(a, s) == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+  if (d_model % 128 || K % 256) return GQLA_ERR_SHAPE;
+  a.ksplit = out_proj_split(a.M, a.K, a.D, &a.krange);
+  if (a.ksplit > 1) {
+    if (!ws) return GQLA_ERR_NULL;
+    if (ws_bytes < (size_t)a.ksplit * M * d_model * sizeof(float)) return GQLA_ERR_WORKSPACE;
+    a.partial = static_cast<float*>(ws);
+  }
+  return launch_out_proj_bf16(a, s) == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
 gqla_status gqla_left_inverse(const gqla_shape* shape, const float* w_uk_host, float* w_inv_host) {
   gqla_status st = check_shape(shape);
   if (st != GQLA_OK) return st;

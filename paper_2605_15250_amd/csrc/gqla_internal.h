@@ -83,6 +83,22 @@ struct AppendArgs {
   int32_t B, s_q, row_bytes;
 };
 
+struct RopeArgs {
+  void* q_r;   // [B][s_q][h_q][d_r] or null
+  void* rows;  // [B][s_q][row_elems], k_R at column r_kv; or null
+  const int32_t* seq_lens;
+  double log2_base;
+  int32_t B, s_q, h_q, d_r, r_kv, row_elems;
+};
+
+struct OutProjArgs {
+  const void* o;    // [M][K]
+  const void* w_o;  // [D][K]
+  void* y;          // [M][D]
+  float* partial;   // [ksplit][M][D] when ksplit > 1
+  int32_t M, K, D, ksplit, krange;
+};
+
 struct AbsorbQueryArgs {
   const void* q_c;
   const void* w_uk;
@@ -115,6 +131,10 @@ hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);
 hipError_t launch_compress_f32(const CompressArgs&, hipStream_t);
 hipError_t launch_compress_bf16(const CompressArgs&, hipStream_t);
+hipError_t launch_rope_step(const RopeArgs&, bool bf16, hipStream_t);
+hipError_t launch_out_proj_f32(const OutProjArgs&, hipStream_t);
+hipError_t launch_out_proj_bf16(const OutProjArgs&, hipStream_t);
+int out_proj_split(int M, int K, int D, int* krange);  // k-ranges of the bf16 kernel (needs D % 128 == 0, K % 256 == 0)
 hipError_t launch_decode_gqa_fp8(const DecodeArgs&, float k_scale, float v_scale, hipStream_t);
 
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int blocks, hipStream_t);

@@ -68,6 +68,7 @@ class Decoder:
         self.expanded_pool = None
         self.expanded_fp8_pool = None
         self.ws_e = None                                        # scratch of the expand call
+        self.ws_o = None                                        # scratch of the output projection
 
     def close(self):
         for p in (self.plan_a, self.plan_g):
@@ -130,6 +131,22 @@ class Decoder:
     def append_latent(self, rows):
         """rows: [B, s_q, r_kv + d_r] contiguous, the cache's element type."""
         B.gqla_append_latent(self.shape, rows, self.latent_cache())
+
+    def rope_step(self, rope_base, q_r=None, rows=None):
+        """In place: q_r [B, s_q, h_q, d_r] and the k_R part of rows [B, s_q, r_kv + d_r]."""
+        B.gqla_rope_step(self.shape, self.d_lens, rope_base, q_r, rows)
+
+    def output_projection(self, o, w_o, y=None):
+        """o [B, s_q, h_q, d_h], w_o [d_model, h_q * d_h] -> y [B, s_q, d_model]."""
+        c = self.cfg
+        d_model = w_o.shape[0]
+        if y is None:
+            y = torch.empty((c.B, c.s_q, d_model), dtype=torch_dtype(c.dtype), device="cuda")
+        nbytes = B.gqla_output_projection_workspace_bytes(self.shape, d_model)
+        if nbytes and (self.ws_o is None or self.ws_o.numel() < nbytes):
+            self.ws_o = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+        B.gqla_output_projection(self.shape, d_model, o, w_o, y, self.ws_o if nbytes else None)
+        return y
 
     def compress(self, w_inv):
         """Expanded cache -> latent cache (all g groups must be held)."""

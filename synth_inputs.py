@@ -91,6 +91,13 @@ def weights(cfg: GqlaConfig):
     return quantize(w_uk, cfg.dtype), quantize(w_uv, cfg.dtype)
 
 
+def output_weights(cfg: GqlaConfig, d_model: int) -> np.ndarray:
+    """W^O [d_model, h_q * d_h], storage-rounded."""
+    r = rng(cfg.seed, 3)
+    K = cfg.h_q * cfg.d_h
+    return quantize(r.standard_normal((int(d_model), K), dtype=np.float32) * np.float32(K ** -0.5), cfg.dtype)
+
+
 def queries(cfg: GqlaConfig):
     r = rng(cfg.seed, 1)
     q_c = r.standard_normal((cfg.B, cfg.s_q, cfg.h_q, cfg.d_h), dtype=np.float32)

@@ -260,3 +260,42 @@ def test_left_inverse_on_the_host_matches_the_oracle():
     w = rng.normal(size=(2, 32, 16)).astype(np.float32)
     w[:, 1, :] = w[:, 0, :]
     _expect(B.GQLA_ERR_SHAPE, B.gqla_left_inverse, B.make_shape(1, 8, 2, 16, 32, 8, 1, B.GQLA_F32), w)
+
+
+def test_step_ops_validate_on_the_host():
+    """gqla_rope_step, gqla_compress_cache and gqla_output_projection reject bad arguments before any launch; the
+    scratch size of the output projection follows the documented k-range rule."""
+    A = 0x10000
+    ok = B.make_shape(2, 32, 8, 128, 512, 64, 2, B.GQLA_BF16)
+    _expect(B.GQLA_ERR_NULL, B.gqla_rope_step, ok, None, 10000.0, A, A, stream=0)
+    _expect(B.GQLA_ERR_NULL, B.gqla_rope_step, ok, A, 10000.0, None, None, stream=0)
+    _expect(B.GQLA_ERR_ALIGN, B.gqla_rope_step, ok, A, 10000.0, A + 8, A, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_rope_step, ok, A, 1.0, A, A, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_rope_step, ok, A, float("inf"), A, A, stream=0)
+    # output projection: M = 4 rows, K = 4096
+    _expect(B.GQLA_ERR_NULL, B.gqla_output_projection, ok, 4096, A, None, A, A, 1 << 30, stream=0)
+    _expect(B.GQLA_ERR_ALIGN, B.gqla_output_projection, ok, 4096, A, A, A + 2, A, 1 << 30, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_output_projection, ok, 0, A, A, A, A, 1 << 30, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_output_projection, ok, 4000, A, A, A, A, 1 << 30, stream=0)          # not a multiple of 128
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_output_projection, B.make_shape(2, 1, 1, 128, 512, 64, 2, B.GQLA_BF16), 4096, A, A, A, A, 1 << 30, stream=0)  # K = 128
+    need = B.gqla_output_projection_workspace_bytes(ok, 4096)
+    # 32 column tiles x 1 row block -> 16 k-ranges of one 256-element phase each
+    assert need == 16 * 4 * 4096 * 4
+    _expect(B.GQLA_ERR_NULL, B.gqla_output_projection, ok, 4096, A, A, A, None, 0, stream=0)
+    _expect(B.GQLA_ERR_WORKSPACE, B.gqla_output_projection, ok, 4096, A, A, A, A, need - 1, stream=0)
+    assert B.gqla_output_projection_workspace_bytes(ok, 4000) == 0
+    assert B.gqla_output_projection_workspace_bytes(B.make_shape(2, 8, 2, 16, 32, 8, 1, B.GQLA_F32), 24) == 0
+    # 7168 columns (56 tiles), K = 16384 (64 phases): ceil(512 / 56) = 10 ranges wanted -> 7 phases each -> 10 ranges
+    big = B.make_shape(64, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
+    assert B.gqla_output_projection_workspace_bytes(big, 7168) == 10 * 64 * 7168 * 4
+    # compress: needs all groups, matching geometry, g d_h >= r_kv
+    full = B.make_cache(A, A, None, 64, 4, 8, 8)
+    lat = B.make_cache(A, A, None, 64, 4, 8, 0)
+    ok8 = B.make_shape(2, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
+    _expect(B.GQLA_ERR_NULL, B.gqla_compress_cache, ok8, full, None, lat, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_compress_cache, ok8, B.make_cache(A, A, None, 64, 4, 8, 4), A, lat, stream=0)
+    _expect(B.GQLA_ERR_PAGE, B.gqla_compress_cache, ok8, full, A, B.make_cache(A, A, None, 64, 5, 8, 0), stream=0)
+    _expect(B.GQLA_ERR_ALIGN, B.gqla_compress_cache, ok8, full, A + 4, lat, stream=0)
+    # empty batch: nothing to do
+    B.gqla_rope_step(B.make_shape(0, 32, 8, 128, 512, 64, 2, B.GQLA_BF16), A, 10000.0, A, A, stream=0)
+    B.gqla_output_projection(B.make_shape(0, 32, 8, 128, 512, 64, 2, B.GQLA_BF16), 4096, A, A, A, None, 0, stream=0)
