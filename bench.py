@@ -159,6 +159,7 @@ def main():
     step_updates = None
     fp8_kv = None
     compress = None
+    step_ops = None
     full_run = run_legs >= {"absorb", "gqa"} and "noexpand" not in run_legs
     if full_run and not args.no_extras:
         def timed(fn, reps):
@@ -246,6 +247,24 @@ def main():
                     "rel_l2_recovered_latent": float(torch.linalg.norm(rec - ref) / torch.linalg.norm(ref))}
         gd.latent_pool = truth
         del rec, ref, d_w_inv
+        # the steps either side of the path: rotary embedding of the step's q_R / k_R and the output projection W^O
+        # (d_model 4096 with 32 heads, 7168 with 128: the model widths the two head counts come from)
+        step_ops = {}
+        for nm, leg in (("absorb", A), ("gqa", Gq)):
+            c_, d_ = leg["cfg"], leg["dec"]
+            d_model = 4096 if c_.h_q * c_.d_h <= 4096 else 7168
+            w_o = to_device(S.output_weights(c_, d_model), c_.dtype)
+            y = torch.empty((c_.B, c_.s_q, d_model), dtype=torch.bfloat16, device="cuda")
+            o_in = leg["out"]
+            t_o = timed_steady(lambda: d_.output_projection(o_in, w_o, y), 20)
+            q_tmp = leg["d_q_r"].clone()
+            rows_tmp = torch.zeros((c_.B, c_.s_q, c_.r_kv + c_.d_r), dtype=torch.bfloat16, device="cuda")
+            t_r = timed_steady(lambda: d_.rope_step(10000.0, q_tmp, rows_tmp), 20)
+            wbytes = 2.0 * d_model * c_.h_q * c_.d_h
+            step_ops[nm] = {"d_model": d_model, "rows": c_.B * c_.s_q, "output_projection_ms": t_o * 1e3,
+                            "output_projection_GB/s": wbytes / t_o / 1e9, "frac_hbm_peak": wbytes / t_o / 1e9 / HBM_PEAK_GBS,
+                            "rope_step_ms": t_r * 1e3}
+            del w_o, y, q_tmp, rows_tmp
 
     other = None
     if args.all_configs:
@@ -436,6 +455,7 @@ def main():
         "step_updates": step_updates,
         "fp8_kv": fp8_kv,
         "compress": compress,
+        "step_ops": step_ops,
         "other_configs": other,
         "operating_points": points,
         "calls_ms": call_ms,

@@ -150,11 +150,11 @@ hipError_t launch_out_proj_f32(const OutProjArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-// k-ranges of the bf16 kernel: as many as bring the launch to about two workgroups per compute unit of a 256-unit chip,
-// whole 256-element phases each.  Returns ksplit, sets *krange.
+// k-ranges of the bf16 kernel: as many as keep the launch within two workgroups per compute unit of a 256-unit chip (one
+// round of resident workgroups), whole 256-element phases each.  Returns ksplit, sets *krange.
 int out_proj_split(int M, int K, int D, int* krange) {
   const int tiles = (D / kOpN) * ((M + kOpM - 1) / kOpM), phases = K / kOpK;
-  int want = (512 + tiles - 1) / tiles;
+  int want = 512 / tiles;
   if (want > phases) want = phases;
   if (want < 1) want = 1;
   const int per = (phases + want - 1) / want;

@@ -285,9 +285,9 @@ def test_step_ops_validate_on_the_host():
     _expect(B.GQLA_ERR_WORKSPACE, B.gqla_output_projection, ok, 4096, A, A, A, A, need - 1, stream=0)
     assert B.gqla_output_projection_workspace_bytes(ok, 4000) == 0
     assert B.gqla_output_projection_workspace_bytes(B.make_shape(2, 8, 2, 16, 32, 8, 1, B.GQLA_F32), 24) == 0
-    # 7168 columns (56 tiles), K = 16384 (64 phases): ceil(512 / 56) = 10 ranges wanted -> 7 phases each -> 10 ranges
+    # 7168 columns (56 tiles), K = 16384 (64 phases): 512 // 56 = 9 ranges wanted -> 8 phases each -> 8 ranges
     big = B.make_shape(64, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
-    assert B.gqla_output_projection_workspace_bytes(big, 7168) == 10 * 64 * 7168 * 4
+    assert B.gqla_output_projection_workspace_bytes(big, 7168) == 8 * 64 * 7168 * 4
     # compress: needs all groups, matching geometry, g d_h >= r_kv
     full = B.make_cache(A, A, None, 64, 4, 8, 8)
     lat = B.make_cache(A, A, None, 64, 4, 8, 0)
