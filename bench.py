@@ -264,7 +264,41 @@ def main():
             step_ops[nm] = {"d_model": d_model, "rows": c_.B * c_.s_q, "output_projection_ms": t_o * 1e3,
                             "output_projection_GB/s": wbytes / t_o / 1e9, "frac_hbm_peak": wbytes / t_o / 1e9 / HBM_PEAK_GBS,
                             "rope_step_ms": t_r * 1e3}
-            del w_o, y, q_tmp, rows_tmp
+            # the whole decode step of this path as one HIP graph: rope -> append -> (absorb: query absorption + latent
+            # decode | GQA: tail expansion + grouped decode) -> W^O.  The step's rows are the ones the cache already
+            # holds at those positions (their k_R gets rotated by the replays; restored below).
+            Wl_ = c_.r_kv + c_.d_r
+            lens_ = leg["lens"]
+            pos_ = torch.stack([torch.from_numpy(leg["table"][b][np.arange(int(lens_[b]) - c_.s_q, int(lens_[b])) // c_.page_size].astype(np.int64)
+                                                 * c_.page_size + np.arange(int(lens_[b]) - c_.s_q, int(lens_[b])) % c_.page_size)
+                                for b in range(c_.B)]).cuda()
+            rows0 = d_.latent_pool.view(-1, Wl_)[pos_.view(-1)].view(c_.B, c_.s_q, Wl_).contiguous()
+            rows_t, q_r_t = rows0.clone(), leg["d_q_r"].clone()
+            out_t, lse_t = torch.empty_like(leg["out"]), torch.empty_like(leg["lse"])
+
+            def whole_step():
+                d_.rope_step(10000.0, q_r_t, rows_t)
+                d_.append_latent(rows_t)
+                if nm == "absorb":
+                    d_.absorb_query(leg["d_q_c"], leg["d_w_uk"], leg["q_hat"])
+                    d_.decode_absorb(leg["q_hat"], q_r_t, leg["d_w_uv"], out_t, lse_t)
+                else:
+                    d_.expand_tail(leg["d_w_uk"], leg["d_w_uv"], c_.s_q)
+                    d_.decode_gqa(leg["d_q_c"], q_r_t, out_t, lse_t)
+                d_.output_projection(out_t, w_o, y)
+
+            whole_step()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                whole_step()
+            t_s = timed_steady(graph.replay, 20)
+            step_ops[nm].update({"whole_step_graph_ms": t_s * 1e3, "whole_step_tokens_per_s": c_.B * c_.s_q / t_s})
+            d_.append_latent(rows0)                              # put the cache back as it was
+            if nm == "gqa":
+                d_.expand_tail(leg["d_w_uk"], leg["d_w_uv"], c_.s_q)
+            torch.cuda.synchronize()
+            del graph, w_o, y, q_tmp, rows_tmp, rows_t, q_r_t, out_t, lse_t
 
     other = None
     if args.all_configs:
