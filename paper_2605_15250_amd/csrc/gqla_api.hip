@@ -430,7 +430,7 @@ gqla_status gqla_rope_step(const gqla_shape* shape, const int32_t* seq_lens, flo
   if (st != GQLA_OK) return st;
   if (!seq_lens || (!q_r && !rows)) return GQLA_ERR_NULL;
   if ((q_r && !aligned16(q_r)) || (rows && !aligned16(rows))) return GQLA_ERR_ALIGN;
-  if (!(rope_base > 1.0f) || !std::isfinite(rope_base) || shape->d_r % 2 || shape->r_kv % 2) return GQLA_ERR_SHAPE;
+  if (!(rope_base > 1.0f) || !std::isfinite(rope_base) || shape->d_r % 2 || shape->d_r > 512 || shape->r_kv % 2) return GQLA_ERR_SHAPE;
   if (shape->batch == 0) return GQLA_OK;
   RopeArgs a;
   a.q_r = q_r;

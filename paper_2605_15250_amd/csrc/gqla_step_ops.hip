@@ -10,22 +10,29 @@ namespace {
 // One workgroup per (step token, sequence): position t = L_b - s_q + i; vectors 0 .. h_q-1 are the heads of q^R, vector
 // h_q is the k^R part of the token's latent row.  Pair p of a vector turns by t * base^(-2p/d_R); angle, sine and
 // cosine in double (t reaches 10^5 and the fastest pair turns a radian per position), the rotation itself in fp32.
+constexpr int kRopeMaxPairs = 256;   // d_R <= 512
 template <typename T>
 __global__ void __launch_bounds__(256) rope_step_kernel(RopeArgs a) {
+  __shared__ float cs_tab[2 * kRopeMaxPairs];
   const int i = blockIdx.x, b = blockIdx.y;
   const int t = a.seq_lens[b] - a.s_q + i;
   if (t < 0) return;
   const int half = a.d_r / 2;
+  for (int p = threadIdx.x; p < half; p += blockDim.x) {   // one sine / cosine per pair, shared by all vectors of the token
+    const double theta = exp2(-2.0 * (double)p / (double)a.d_r * a.log2_base);
+    double sn, cs;
+    sincos((double)t * theta, &sn, &cs);
+    cs_tab[2 * p] = (float)cs;
+    cs_tab[2 * p + 1] = (float)sn;
+  }
+  __syncthreads();
   const int vecs = (a.q_r ? a.h_q : 0) + (a.rows ? 1 : 0);
   T* q = a.q_r ? (T*)a.q_r + ((int64_t)b * a.s_q + i) * a.h_q * a.d_r : nullptr;
   T* k = a.rows ? (T*)a.rows + ((int64_t)b * a.s_q + i) * a.row_elems + a.r_kv : nullptr;
   for (int idx = threadIdx.x; idx < vecs * half; idx += blockDim.x) {
     const int v = idx / half, p = idx % half;
     T* x = (q && v < a.h_q) ? q + (int64_t)v * a.d_r : k;
-    const double theta = exp2(-2.0 * (double)p / (double)a.d_r * a.log2_base);
-    double sn, cs;
-    sincos((double)t * theta, &sn, &cs);
-    const float c = (float)cs, s = (float)sn;
+    const float c = cs_tab[2 * p], s = cs_tab[2 * p + 1];
     if constexpr (sizeof(T) == 2) {
       uint32_t* w = (uint32_t*)x + p;
       const uint32_t bits = *w;
@@ -62,14 +69,18 @@ constexpr int kOpN = 128, kOpM = 128, kOpK = 256;
 constexpr int kOpPlane = kOpM + 1;                   // plane stride in 16-byte vectors (odd: writes of a row spread over banks)
 constexpr int kOpLds = (kOpK / 8) * kOpPlane * 16;
 
+// MT: 32-row tiles per row block (2 when the call has at most 64 rows, else 4).  PIPE: the loads of the next phase are
+// issued before the MFMAs of the current one (two register sets for W^O; affordable with MT = 2).
+template <int MT, bool PIPE>
 __global__ void __launch_bounds__(256, 2) out_proj_bf16_kernel(OutProjArgs a) {
+  constexpr int AI = 4 * MT;                           // staging loads per thread: rows arow + 8 i < 32 MT
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   u32x4* lds = (u32x4*)smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
   const int split = blockIdx.y;
   const int m0 = blockIdx.z * kOpM;
-  const int rows = min(kOpM, a.M - m0);
+  const int rows = min(32 * MT, a.M - m0);
   const int mts = (rows + 31) / 32;
   const int kbeg = split * a.krange, kend = min(a.K, kbeg + a.krange);
   const int ncol0 = blockIdx.x * kOpN + wave * 32;
@@ -77,40 +88,75 @@ __global__ void __launch_bounds__(256, 2) out_proj_bf16_kernel(OutProjArgs a) {
   const int arow = tid >> 5, ac = tid & 31;            // staging role: rows arow + 8 i, vector ac of the phase
   const __bf16* osrc = (const __bf16*)a.o + (int64_t)(m0 + arow) * a.K + ac * 8;
 
-  f32x16 acc[4];
+  f32x16 acc[MT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
 
-  for (int k0 = kbeg; k0 < kend; k0 += kOpK) {
-    u32x4 wv[16], av[16];
+  auto load_w = [&](u32x4(&wv)[16], int k0) {
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
       for (int v = 0; v < 4; ++v) wv[blk * 4 + v] = *(const u32x4*)(wrow + k0 + 64 * blk + 8 * v);
+  };
+  auto load_a = [&](u32x4(&av)[AI], int k0) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < AI; ++i)
       av[i] = (arow + 8 * i < rows) ? *(const u32x4*)(osrc + (int64_t)8 * i * a.K + k0) : u32x4{0u, 0u, 0u, 0u};
+  };
+  auto stash = [&](const u32x4(&av)[AI]) {
     __syncthreads();                                   // the previous phase's LDS reads are done
 #pragma unroll
-    for (int i = 0; i < 16; ++i) lds[ac * kOpPlane + arow + 8 * i] = av[i];
+    for (int i = 0; i < AI; ++i) lds[ac * kOpPlane + arow + 8 * i] = av[i];
     __syncthreads();
+  };
+  auto compute = [&](const u32x4(&wv)[16]) {
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const u32x4* plane = lds + (blk * 8 + 4 * h + v) * kOpPlane + n;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
           if (mt < mts)
             acc[mt] = mfma32(__builtin_bit_cast(bf16x8, wv[blk * 4 + v]), __builtin_bit_cast(bf16x8, plane[32 * mt]), acc[mt]);
       }
+  };
+
+  if constexpr (!PIPE) {
+    for (int k0 = kbeg; k0 < kend; k0 += kOpK) {
+      u32x4 wv[16], av[AI];
+      load_w(wv, k0);
+      load_a(av, k0);
+      stash(av);
+      compute(wv);
+    }
+  } else {
+    u32x4 w0[16], w1[16], av[AI];
+    load_w(w0, kbeg);
+    load_a(av, kbeg);
+    for (int k0 = kbeg; k0 < kend; k0 += 2 * kOpK) {
+      stash(av);
+      const bool odd = k0 + kOpK < kend;
+      if (odd) {
+        load_w(w1, k0 + kOpK);
+        load_a(av, k0 + kOpK);
+      }
+      compute(w0);
+      if (!odd) break;
+      stash(av);
+      if (k0 + 2 * kOpK < kend) {
+        load_w(w0, k0 + 2 * kOpK);
+        load_a(av, k0 + 2 * kOpK);
+      }
+      compute(w1);
+    }
   }
 
   // C fragment: register 4 q + i holds column ncol0 + 8 q + 4 h + i of row 32 mt + n
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
+  for (int mt = 0; mt < MT; ++mt) {
     const int m = 32 * mt + n;
     if (m >= rows) continue;
     if (a.ksplit == 1) {
@@ -163,10 +209,15 @@ int out_proj_split(int M, int K, int D, int* krange) {
 }
 
 hipError_t launch_out_proj_bf16(const OutProjArgs& a, hipStream_t s) {
-  static const hipError_t attr =
-      hipFuncSetAttribute((const void*)out_proj_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kOpLds);
-  if (attr != hipSuccess) return attr;
-  out_proj_bf16_kernel<<<dim3(a.D / kOpN, a.ksplit, (a.M + kOpM - 1) / kOpM), 256, kOpLds, s>>>(a);
+  static const hipError_t attr2 =
+      hipFuncSetAttribute((const void*)out_proj_bf16_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kOpLds);
+  static const hipError_t attr4 =
+      hipFuncSetAttribute((const void*)out_proj_bf16_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, kOpLds);
+  if (attr2 != hipSuccess) return attr2;
+  if (attr4 != hipSuccess) return attr4;
+  const dim3 grid(a.D / kOpN, a.ksplit, (a.M + kOpM - 1) / kOpM);
+  if (a.M <= 64) out_proj_bf16_kernel<2, true><<<grid, 256, kOpLds, s>>>(a);
+  else out_proj_bf16_kernel<4, false><<<grid, 256, kOpLds, s>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.ksplit == 1) return e;
   const int64_t total = (int64_t)a.M * a.D / 4;
