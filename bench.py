@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-extras", action="store_true", help="skip the ceiling probes and the single-group slice timing")
     ap.add_argument("--operating-points", action="store_true",
                     help="also time both decode paths at the operating points of the paper's Sec. 4.2.3 table (g, s_q) for B = 1 and 64")
+    ap.add_argument("--crossover", action="store_true",
+                    help="also time both decode paths over B = 1 .. 128 (canonical shape, L = 8192, s_q = 1 and 2): where the faster path changes")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time both decode paths and the expansion on the other bf16 workload shapes (C1, C3, C4); "
                          "adds about a minute; their parity is covered by tests/, here they are timed on device-generated N(0,1) latents")
@@ -336,12 +338,19 @@ def main():
     # Calls are timed with events (absorb: query absorption + decode; GQA: decode only, the expansion is one-shot at
     # deployment), the model columns are the paper's max(F/peak, B/BW) with this run's measured ceilings.
     points = None
-    if args.operating_points:
+    crossover = None
+    if args.operating_points or args.crossover:
         timed3 = timed_steady
         rates = (measured["hbm_stream_read_GBs"] * 1e9, measured["mfma_bf16_TFLOPs"] * 1e12) if measured else (HBM_PEAK_GBS * 1e9, MFMA_BF16_PEAK_TFLOPS * 1e12)
-        points = []
-        for Bn in (1, 64):
-            for g_k, sq_k in ((8, 1), (8, 2), (4, 1), (4, 2)):
+        points = [] if args.operating_points else None
+        crossover = [] if args.crossover else None
+        todo = []
+        if args.operating_points:       # the paper's table (Sec. 4.2.3), at B = 1 and 64
+            todo += [(points, Bn, g_k, sq_k) for Bn in (1, 64) for g_k, sq_k in ((8, 1), (8, 2), (4, 1), (4, 2))]
+        if args.crossover:              # where the faster path changes with the batch, canonical shape
+            todo += [(crossover, Bn, 8, sq_k) for sq_k in (1, 2) for Bn in (1, 2, 4, 8, 16, 32, 64, 128)]
+        for sink_list, Bn, g_k, sq_k in todo:
+            if True:
                 c = S.CONFIGS["C2"].with_(B=Bn, g=g_k, s_q=sq_k)
                 lens_k = S.seq_lens(c)
                 table_k, np_k = S.page_table(c, lens_k)
@@ -363,7 +372,7 @@ def main():
                 t_g = timed3(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 20)
                 Ls = int(lens_k.sum())
                 est = B.gqla_estimate_paths(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls, rates[0], rates[1])
-                points.append({"batch": Bn, "context": c.L, "g": g_k, "s_q": sq_k,
+                sink_list.append({"batch": Bn, "context": c.L, "g": g_k, "s_q": sq_k,
                                "absorb_bytes_per_token": 2 * (c.r_kv + c.d_r), "gqa_bytes_per_token": 2 * (2 * c.g * c.d_h + c.d_r),
                                "absorb_intensity": est["absorb_intensity"], "gqa_intensity": est["gqa_intensity"],
                                "absorb_us": t_a * 1e6, "gqa_us": t_g * 1e6,
@@ -492,6 +501,7 @@ def main():
         "step_ops": step_ops,
         "other_configs": other,
         "operating_points": points,
+        "crossover": crossover,
         "calls_ms": call_ms,
         "paths": {"absorb_tokens_per_s": ca.B * ca.s_q / (max(call_ms["absorb_query"] + call_ms["decode_absorb"], 1e-6) * 1e-3),
                   "gqa_decode_tokens_per_s": cg.B * cg.s_q / (max(call_ms["decode_gqa"], 1e-6) * 1e-3),

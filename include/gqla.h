@@ -285,11 +285,15 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
                                 double mfma_flops_per_s, gqla_path_estimate* out);
 
 /* The same choice for THIS library's kernels on the MI355X (GQLA_BF16 only; GQLA_ERR_DTYPE otherwise): the paper's
- * two-roof form with the rates the kernels sustain instead of the chip's peaks, a fixed cost per call, and a floor
- * that a call's chain of dependent kernels never gets under.  All constants are measurements of this build (the
- * operating-point and all-config tables under profiles/):
- *   absorb (query absorption + decode):  max(50 us, 28 us + max(bytes / 5.5 TB/s, flops / 0.95 PFLOP/s))
- *   gqa    (decode on the expanded cache): max(28 us, 10 us + f * bytes / 6.6 TB/s),
+ * two-roof form with the rates the kernels sustain instead of the chip's peaks and a fixed cost per call, and, for
+ * the absorb path, the critical path of one workgroup when the batch is too small to fill the chip.  All constants are
+ * measurements of this build (the operating-point, batch-sweep and all-config tables under profiles/):
+ *   absorb (query absorption + decode):  28 us + max(bytes / 5.5 TB/s, flops / 0.95 PFLOP/s, rounds * (per + 4) * page)
+ *          where the split-plan rule of gqla_plan_create, applied to `batch` sequences of cached_tokens / batch tokens
+ *          on 64-token pages and 256 compute units, gives every workgroup `rounds` chunks of `per` pages, and a page
+ *          costs a workgroup 4.4 us (1.6 us when h_q s_q <= 32; 2.6 us when chunks * ceil(h_q s_q / 32) <= 256, where
+ *          the launch gives every 32 rows their own workgroup)
+ *   gqa    (decode on the expanded cache): 24 us + f * bytes / 7.0 TB/s,
  *          f = 1 + 0.45 * (ceil(G s_q / 32) - 1): a group's rows beyond 32 stream the cache again, mostly from the caches
  * with bytes and flops as in gqla_estimate_paths.  faster_path is the path with the smaller time (absorb on a tie). */
 typedef struct {

@@ -667,10 +667,30 @@ gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gql
   st = gqla_estimate_paths(shape, cached_tokens, 1.0, 1.0, &e);  // only its byte and FLOP counts are used
   if (st != GQLA_OK) return st;
   const double row_blocks = (double)(((shape->h_q / shape->g) * shape->s_q + 31) / 32);
-  const double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 0.95e15);
-  const double tg = 10e-6 + (1.0 + 0.45 * (row_blocks - 1.0)) * e.gqa_bytes / 6.6e12;
-  out->absorb_seconds = std::max(50e-6, ta);
-  out->gqa_seconds = std::max(28e-6, tg);
+  // absorb, throughput form: the rates the kernel sustains when every compute unit has a long chunk
+  double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 0.95e15);
+  // absorb, critical path of one workgroup: the split plan of `batch` equal sequences on 64-token pages and 256 compute
+  // units gives every workgroup `rounds` chunks of `per` pages; a page costs a workgroup 4.4 us (128 rows, one wave
+  // per 32 rows), 2.6 us when the chunks are so few that the launch gives every 32 rows a workgroup of their own, and
+  // 1.6 us when a sequence has at most 32 rows; a chunk's fixed cost is that of 4 pages.
+  if (shape->batch > 0 && cached_tokens > 0) {
+    const int64_t np = ceil_div(ceil_div(cached_tokens, shape->batch), 64);
+    const int64_t slots = plan_slots(*shape, 256, GQLA_PATH_ABSORB);
+    int64_t best = -1, cp = 1;
+    for (int64_t c = 1; c <= np; ++c) {
+      const int64_t cost = 16 * ceil_div(shape->batch * ceil_div(np, c), slots) * (c + 4) + 4 * ceil_div(np, c);
+      if (best < 0 || cost <= best) {
+        best = cost;
+        cp = c;
+      }
+    }
+    const int64_t per_seq = ceil_div(np, cp), per = ceil_div(np, per_seq), chunks = shape->batch * per_seq;
+    const int64_t M = (int64_t)shape->h_q * shape->s_q;
+    const double page_s = M <= 32 ? 1.6e-6 : (chunks * ceil_div(M, 32) <= 256 ? 2.6e-6 : 4.4e-6);
+    ta = std::max(ta, 28e-6 + (double)(ceil_div(chunks, slots) * (per + 4)) * page_s);
+  }
+  out->absorb_seconds = ta;
+  out->gqa_seconds = 24e-6 + (1.0 + 0.45 * (row_blocks - 1.0)) * e.gqa_bytes / 7.0e12;
   out->faster_path = out->gqa_seconds < out->absorb_seconds ? GQLA_PATH_GQA : GQLA_PATH_ABSORB;
   return GQLA_OK;
 }
