@@ -195,8 +195,8 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
  * sequence b has position t = L_b - s_q + i, L_b read from seq_lens (device memory, int32[B], the lengths that already
  * count the step's tokens); tokens with t < 0 are left alone.  The paper takes the rotary embedding over from MLA
  * without restating it; this library uses the published form: d_r/2 adjacent pairs (x[2p], x[2p+1]), pair p turned by
- * the angle t * rope_base^(-2p/d_r) (angle, sine and cosine in double precision, the rotation in fp32, the result
- * rounded to the element type).  Errors: GQLA_ERR_SHAPE unless rope_base is finite and > 1, d_r and r_kv are even and d_r <= 512.
+ * the angle t * rope_base^(-2p/d_r) (the angle is formed and reduced modulo a full turn in double precision; sine,
+ * cosine and the rotation are fp32, the result rounded to the element type).  Errors: GQLA_ERR_SHAPE unless rope_base is finite and > 1, d_r and r_kv are even and d_r <= 512.
  *
  * gqla_output_projection computes y_t = W^O [o_{t,1}; ...; o_{t,h_q}] (last line of the GQA-path and of the MQA-absorb
  * equation): o is a decode call's output [B][s_q][h_q][d_h], w_o is [d_model][h_q * d_h] row-major (the paper's

@@ -1,5 +1,7 @@
 // The steps either side of the decode path: the decoupled rotary embedding of the step's q^R and k^R (Sec. 3.1,
 // "Architecture") and the output projection y = W^O [o_1; ...; o_hq] (last line of both path equations).
+#include <type_traits>
+
 #include "gqla_device.h"
 
 namespace gqla {
@@ -8,11 +10,12 @@ namespace {
 
 // ---- rope_t on the step's rows ------------------------------------------------------------------------------------
 // One workgroup per (step token, sequence): position t = L_b - s_q + i; vectors 0 .. h_q-1 are the heads of q^R, vector
-// h_q is the k^R part of the token's latent row.  Pair p of a vector turns by t * base^(-2p/d_R); angle, sine and
-// cosine in double (t reaches 10^5 and the fastest pair turns a radian per position), the rotation itself in fp32.
+// h_q is the k^R part of the token's latent row.  Pair p of a vector turns by t * base^(-2p/d_R); the angle is
+// formed and reduced to a fraction of a turn in double (t reaches 10^5 and the fastest pair turns a radian per position);
+// sine, cosine and the rotation itself are fp32.
 constexpr int kRopeMaxPairs = 256;   // d_R <= 512
 template <typename T>
-__global__ void __launch_bounds__(256) rope_step_kernel(RopeArgs a) {
+__global__ void __launch_bounds__(512) rope_step_kernel(RopeArgs a) {
   __shared__ float cs_tab[2 * kRopeMaxPairs];
   const int i = blockIdx.x, b = blockIdx.y;
   const int t = a.seq_lens[b] - a.s_q + i;
@@ -20,28 +23,46 @@ __global__ void __launch_bounds__(256) rope_step_kernel(RopeArgs a) {
   const int half = a.d_r / 2;
   for (int p = threadIdx.x; p < half; p += blockDim.x) {   // one sine / cosine per pair, shared by all vectors of the token
     const double theta = exp2(-2.0 * (double)p / (double)a.d_r * a.log2_base);
-    double sn, cs;
-    sincos((double)t * theta, &sn, &cs);
-    cs_tab[2 * p] = (float)cs;
-    cs_tab[2 * p + 1] = (float)sn;
+    double turns = (double)t * theta * 0.15915494309189535;   // angle / 2 pi; its fraction keeps 1e-11 at t = 10^5
+    turns -= floor(turns);
+    float sn, cs;
+    sincospif(2.0f * (float)turns, &sn, &cs);                  // sin and cos of pi * x: the argument is already reduced
+    cs_tab[2 * p] = cs;
+    cs_tab[2 * p + 1] = sn;
   }
   __syncthreads();
   const int vecs = (a.q_r ? a.h_q : 0) + (a.rows ? 1 : 0);
   T* q = a.q_r ? (T*)a.q_r + ((int64_t)b * a.s_q + i) * a.h_q * a.d_r : nullptr;
   T* k = a.rows ? (T*)a.rows + ((int64_t)b * a.s_q + i) * a.row_elems + a.r_kv : nullptr;
-  for (int idx = threadIdx.x; idx < vecs * half; idx += blockDim.x) {
-    const int v = idx / half, p = idx % half;
-    T* x = (q && v < a.h_q) ? q + (int64_t)v * a.d_r : k;
-    const float c = cs_tab[2 * p], s = cs_tab[2 * p + 1];
-    if constexpr (sizeof(T) == 2) {
-      uint32_t* w = (uint32_t*)x + p;
-      const uint32_t bits = *w;
-      const float x0 = bf16_bits_to_float(bits & 0xffffu), x1 = bf16_bits_to_float(bits >> 16);
-      *w = pack_bf16(x0 * c - x1 * s, x0 * s + x1 * c);
-    } else {
-      const float x0 = x[2 * p], x1 = x[2 * p + 1];
-      x[2 * p] = x0 * c - x1 * s;
-      x[2 * p + 1] = x0 * s + x1 * c;
+  // One pair (two adjacent elements: 4 or 8 bytes) per thread and pass; four passes are loaded before any is stored, so
+  // that a thread pays the memory latency once per four pairs (the in-place stores would otherwise order the loads).
+  typedef typename std::conditional<sizeof(T) == 2, uint32_t, f32x2>::type Pair;
+  const int total = vecs * half;
+  for (int base = threadIdx.x; base < total; base += 4 * blockDim.x) {
+    Pair* at[4];
+    Pair v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int idx = base + j * blockDim.x;
+      at[j] = nullptr;
+      if (idx < total) {
+        const int vec = idx / half;
+        T* x = (q && vec < a.h_q) ? q + (int64_t)vec * a.d_r : k;
+        at[j] = (Pair*)x + idx % half;
+        v[j] = *at[j];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (!at[j]) continue;
+      const int p = (base + j * blockDim.x) % half;
+      const float c = cs_tab[2 * p], s = cs_tab[2 * p + 1];
+      if constexpr (sizeof(T) == 2) {
+        const float x0 = bf16_bits_to_float(v[j] & 0xffffu), x1 = bf16_bits_to_float(v[j] >> 16);
+        *at[j] = pack_bf16(x0 * c - x1 * s, x0 * s + x1 * c);
+      } else {
+        *at[j] = f32x2{v[j][0] * c - v[j][1] * s, v[j][0] * s + v[j][1] * c};
+      }
     }
   }
 }
@@ -186,8 +207,8 @@ __global__ void __launch_bounds__(256) out_proj_reduce_kernel(OutProjArgs a) {
 }  // namespace
 
 hipError_t launch_rope_step(const RopeArgs& a, bool bf16, hipStream_t s) {
-  if (bf16) rope_step_kernel<__bf16><<<dim3(a.s_q, a.B), 256, 0, s>>>(a);
-  else rope_step_kernel<float><<<dim3(a.s_q, a.B), 256, 0, s>>>(a);
+  if (bf16) rope_step_kernel<__bf16><<<dim3(a.s_q, a.B), 512, 0, s>>>(a);
+  else rope_step_kernel<float><<<dim3(a.s_q, a.B), 512, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@ ROPE_BASE = 10000.0
     ("C3", [300, 2, 64, 129, 70000], 2, 10000.0),     # a position beyond 2^16: the angle needs more than fp32
     ("C1", [65, 64, 1], 1, 500000.0),
     ("C0", [40, 7, 2, 17, 1], 2, 10000.0),            # fp32; the last sequence has L < s_q: its first row has no position
+    ("C0", [100000, 65537, 3], 2, 10000.0),           # fp32 at large positions: the fp32 bar needs the angle reduced in double
 ])
 def test_rope_step_matches_the_oracle(key, lens, s_q, base):
     from paper_2605_15250_amd import binding as B
