@@ -350,42 +350,41 @@ def main():
         if args.crossover:              # where the faster path changes with the batch, canonical shape
             todo += [(crossover, Bn, 8, sq_k) for sq_k in (1, 2) for Bn in (1, 2, 4, 8, 16, 32, 64, 128)]
         for sink_list, Bn, g_k, sq_k in todo:
-            if True:
-                c = S.CONFIGS["C2"].with_(B=Bn, g=g_k, s_q=sq_k)
-                lens_k = S.seq_lens(c)
-                table_k, np_k = S.page_table(c, lens_k)
-                dk = Decoder(c, lens_k, table_k, np_k, use_page_table=False)
-                dk.latent_pool = torch.empty(np_k * c.page_size * (c.r_kv + c.d_r), dtype=torch.bfloat16, device="cuda").normal_()
-                wk, wv = S.weights(c)
-                qc_k, qr_k = S.queries(c)
-                d_wk, d_wv, d_qc, d_qr = (to_device(x, c.dtype) for x in (wk, wv, qc_k, qr_k))
-                o_k = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch.bfloat16, device="cuda")
-                l_k = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
-                qh_k = torch.empty((c.B, c.s_q, c.h_q, c.r_kv), dtype=torch.bfloat16, device="cuda")
+            c = S.CONFIGS["C2"].with_(B=Bn, g=g_k, s_q=sq_k)
+            lens_k = S.seq_lens(c)
+            table_k, np_k = S.page_table(c, lens_k)
+            dk = Decoder(c, lens_k, table_k, np_k, use_page_table=False)
+            dk.latent_pool = torch.empty(np_k * c.page_size * (c.r_kv + c.d_r), dtype=torch.bfloat16, device="cuda").normal_()
+            wk, wv = S.weights(c)
+            qc_k, qr_k = S.queries(c)
+            d_wk, d_wv, d_qc, d_qr = (to_device(x, c.dtype) for x in (wk, wv, qc_k, qr_k))
+            o_k = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch.bfloat16, device="cuda")
+            l_k = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
+            qh_k = torch.empty((c.B, c.s_q, c.h_q, c.r_kv), dtype=torch.bfloat16, device="cuda")
 
-                def absorb_step():
-                    dk.absorb_query(d_qc, d_wk, qh_k)
-                    dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k)
-                t_a = timed3(absorb_step, 20)
-                dk.alloc_expanded(fill=0.0)
-                dk.expanded_pool.normal_()
-                t_g = timed3(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 20)
-                Ls = int(lens_k.sum())
-                est = B.gqla_estimate_paths(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls, rates[0], rates[1])
-                sink_list.append({"batch": Bn, "context": c.L, "g": g_k, "s_q": sq_k,
-                               "absorb_bytes_per_token": 2 * (c.r_kv + c.d_r), "gqa_bytes_per_token": 2 * (2 * c.g * c.d_h + c.d_r),
-                               "absorb_intensity": est["absorb_intensity"], "gqa_intensity": est["gqa_intensity"],
-                               "absorb_us": t_a * 1e6, "gqa_us": t_g * 1e6,
-                               "absorb_tokens_per_s": Bn * sq_k / t_a, "gqa_tokens_per_s": Bn * sq_k / t_g,
-                               "faster_path": "gqa" if t_g < t_a else "absorb",
-                               "model_absorb_us": est["absorb_seconds"] * 1e6, "model_gqa_us": est["gqa_seconds"] * 1e6,
-                               "model_faster_path": "gqa" if est["faster_path"] == B.GQLA_PATH_GQA else "absorb",
-                               "calibrated": (lambda ch: {"absorb_us": ch["absorb_seconds"] * 1e6, "gqa_us": ch["gqa_seconds"] * 1e6,
-                                                          "path": "gqa" if ch["faster_path"] == B.GQLA_PATH_GQA else "absorb"})(
-                                   B.gqla_select_path(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls))})
-                dk.close()
-                del dk, o_k, l_k, qh_k
-                torch.cuda.empty_cache()
+            def absorb_step():
+                dk.absorb_query(d_qc, d_wk, qh_k)
+                dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k)
+            t_a = timed3(absorb_step, 20)
+            dk.alloc_expanded(fill=0.0)
+            dk.expanded_pool.normal_()
+            t_g = timed3(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 20)
+            Ls = int(lens_k.sum())
+            est = B.gqla_estimate_paths(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls, rates[0], rates[1])
+            sink_list.append({"batch": Bn, "context": c.L, "g": g_k, "s_q": sq_k,
+                           "absorb_bytes_per_token": 2 * (c.r_kv + c.d_r), "gqa_bytes_per_token": 2 * (2 * c.g * c.d_h + c.d_r),
+                           "absorb_intensity": est["absorb_intensity"], "gqa_intensity": est["gqa_intensity"],
+                           "absorb_us": t_a * 1e6, "gqa_us": t_g * 1e6,
+                           "absorb_tokens_per_s": Bn * sq_k / t_a, "gqa_tokens_per_s": Bn * sq_k / t_g,
+                           "faster_path": "gqa" if t_g < t_a else "absorb",
+                           "model_absorb_us": est["absorb_seconds"] * 1e6, "model_gqa_us": est["gqa_seconds"] * 1e6,
+                           "model_faster_path": "gqa" if est["faster_path"] == B.GQLA_PATH_GQA else "absorb",
+                           "calibrated": (lambda ch: {"absorb_us": ch["absorb_seconds"] * 1e6, "gqa_us": ch["gqa_seconds"] * 1e6,
+                                                      "path": "gqa" if ch["faster_path"] == B.GQLA_PATH_GQA else "absorb"})(
+                               B.gqla_select_path(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls))})
+            dk.close()
+            del dk, o_k, l_k, qh_k
+            torch.cuda.empty_cache()
 
     # ---- accounting: the paper's closed forms (Sec. 4.2.1 / 4.2.2) ----------------------------------------------
     La, Lg = int(A["lens"].sum()), int(Gq["lens"].sum())
