@@ -111,6 +111,7 @@ def test_tail_expand_of_a_group_slice():
 
 @pytest.mark.parametrize("key,lens,page_size", [
     ("C3", [300, 2, 129, 1000], 64),
+    ("C3", [257, 128, 70], 128),             # 128-token pages: a workgroup's two 64-token halves share a page
     ("C0", [40, 7, 17], 8),
 ])
 def test_compress_is_the_reverse_cache_switch(key, lens, page_size):
