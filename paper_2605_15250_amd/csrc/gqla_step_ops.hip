@@ -17,30 +17,19 @@ constexpr int kRopeMaxPairs = 256;   // d_R <= 512
 template <typename T>
 __global__ void __launch_bounds__(512) rope_step_kernel(RopeArgs a) {
   __shared__ float cs_tab[2 * kRopeMaxPairs];
+  typedef typename std::conditional<sizeof(T) == 2, uint32_t, f32x2>::type Pair;  // two adjacent elements
   const int i = blockIdx.x, b = blockIdx.y;
-  const int t = a.seq_lens[b] - a.s_q + i;
-  if (t < 0) return;
   const int half = a.d_r / 2;
-  for (int p = threadIdx.x; p < half; p += blockDim.x) {   // one sine / cosine per pair, shared by all vectors of the token
-    const double theta = exp2(-2.0 * (double)p / (double)a.d_r * a.log2_base);
-    double turns = (double)t * theta * 0.15915494309189535;   // angle / 2 pi; its fraction keeps 1e-11 at t = 10^5
-    turns -= floor(turns);
-    float sn, cs;
-    sincospif(2.0f * (float)turns, &sn, &cs);                  // sin and cos of pi * x: the argument is already reduced
-    cs_tab[2 * p] = cs;
-    cs_tab[2 * p + 1] = sn;
-  }
-  __syncthreads();
   const int vecs = (a.q_r ? a.h_q : 0) + (a.rows ? 1 : 0);
+  const int total = vecs * half;
   T* q = a.q_r ? (T*)a.q_r + ((int64_t)b * a.s_q + i) * a.h_q * a.d_r : nullptr;
   T* k = a.rows ? (T*)a.rows + ((int64_t)b * a.s_q + i) * a.row_elems + a.r_kv : nullptr;
-  // One pair (two adjacent elements: 4 or 8 bytes) per thread and pass; four passes are loaded before any is stored, so
-  // that a thread pays the memory latency once per four pairs (the in-place stores would otherwise order the loads).
-  typedef typename std::conditional<sizeof(T) == 2, uint32_t, f32x2>::type Pair;
-  const int total = vecs * half;
-  for (int base = threadIdx.x; base < total; base += 4 * blockDim.x) {
-    Pair* at[4];
-    Pair v[4];
+  // One pair per thread and pass; four passes are loaded before any is stored, so that a thread pays the memory latency
+  // once per four pairs (in place, the stores would otherwise order the loads).  The addresses do not depend on the
+  // position: the first four passes are requested before the sequence length is looked at.
+  Pair* at[4];
+  Pair v[4];
+  auto fetch = [&](int base) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int idx = base + j * blockDim.x;
@@ -52,6 +41,22 @@ __global__ void __launch_bounds__(512) rope_step_kernel(RopeArgs a) {
         v[j] = *at[j];
       }
     }
+  };
+  fetch(threadIdx.x);
+  const int t = a.seq_lens[b] - a.s_q + i;
+  if (t < 0) return;
+  for (int p = threadIdx.x; p < half; p += blockDim.x) {   // one sine / cosine per pair, shared by all vectors of the token
+    const double theta = exp2(-2.0 * (double)p / (double)a.d_r * a.log2_base);
+    double turns = (double)t * theta * 0.15915494309189535;   // angle / 2 pi; its fraction keeps 1e-11 at t = 10^5
+    turns -= floor(turns);
+    float sn, cs;
+    sincospif(2.0f * (float)turns, &sn, &cs);                  // sin and cos of pi * x: the argument is already reduced
+    cs_tab[2 * p] = cs;
+    cs_tab[2 * p + 1] = sn;
+  }
+  __syncthreads();
+  for (int base = threadIdx.x; base < total; base += 4 * blockDim.x) {
+    if (base != (int)threadIdx.x) fetch(base);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (!at[j]) continue;
