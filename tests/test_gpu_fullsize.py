@@ -216,3 +216,72 @@ def test_c4_ragged_paged_both_paths():
         run_both_paths(case, groups_to_check=[6])
     finally:
         case.close()
+
+
+def test_c3_compress_rope_and_output_projection_at_full_size():
+    """configs[3] at full size, the shapes bench.py times: the reverse cache switch over all 524288 tokens (sampled
+    sequences against the oracle's compression of the oracle's expansion; every recovered latent finite and close to
+    the original), the rotary step on all 64 x 2 x 129 vectors (sampled tokens), and W^O with d_model = 7168 on the
+    128 rows (four whole rows and 2000 sampled elements against the oracle)."""
+    from paper_2605_15250_amd import binding as B
+    cfg = S.CONFIGS["C3"]
+    case = FullCase(cfg)
+    dec = case.dec
+    try:
+        W = cfg.r_kv + cfg.d_r
+        # ---- compress(expand(latent)) ----
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        w_inv = S.quantize(B.gqla_left_inverse(dec.shape, case.w_uk), cfg.dtype)
+        truth = dec.latent_pool
+        dec.latent_pool = torch.full_like(truth, float("nan"))
+        dec.compress(case.d(w_inv))
+        torch.cuda.synchronize()
+        rec = dec.latent_pool.view(-1, W)
+        ref_all = truth.view(-1, W)
+        valid = ~torch.isnan(ref_all[:, 0])
+        assert bool(torch.isfinite(rec[valid].float()).all())
+        assert torch.equal(rec[valid][:, cfg.r_kv:].view(torch.int16), ref_all[valid][:, cfg.r_kv:].view(torch.int16)), "k_R copied bit for bit"
+        err = float(torch.linalg.norm(rec[valid][:, :cfg.r_kv].float() - ref_all[valid][:, :cfg.r_kv].float()) /
+                    torch.linalg.norm(ref_all[valid][:, :cfg.r_kv].float()))
+        print("recovered latent vs the original, all tokens: rel_l2 %.3e" % err, flush=True)
+        assert err < 1e-2
+        for b in (0, 37):
+            c, _ = case.rows(b)
+            KC, _ = O.expand_latent(c, case.w_uk, case.w_uv)
+            ref = S.quantize(KC, cfg.dtype).reshape(len(c), -1).astype(np.float64) @ w_inv.astype(np.float64).T   # the rounded left inverse the GPU uses
+            t = np.arange(int(case.lens[b]))
+            slots = torch.from_numpy(case.table[b][t // cfg.page_size].astype(np.int64) * cfg.page_size + t % cfg.page_size).cuda()
+            check("compress c_kv  b=%d" % b, rec[slots][:, :cfg.r_kv].float().cpu().numpy(), ref)
+        dec.latent_pool = truth
+        # ---- rotary step ----
+        r = S.rng(cfg.seed, 7)
+        rows_raw = S.quantize(r.standard_normal((cfg.B, cfg.s_q, W), dtype=np.float32), cfg.dtype)
+        d_q, d_rows = case.d(case.q_r), case.d(rows_raw)
+        dec.rope_step(10000.0, d_q, d_rows)
+        torch.cuda.synchronize()
+        got_q, got_rows = d_q.float().cpu().numpy(), d_rows.float().cpu().numpy()
+        assert np.array_equal(got_rows[..., :cfg.r_kv], rows_raw[..., :cfg.r_kv])
+        for b in (0, 31, 63):
+            for i in range(cfg.s_q):
+                t = int(case.lens[b]) - cfg.s_q + i
+                check("rope q_R  b=%d tok %d" % (b, i), got_q[b, i], O.rope(case.q_r[b, i], t))
+                check("rope k_R  b=%d tok %d" % (b, i), got_rows[b, i, cfg.r_kv:], O.rope(rows_raw[b, i, cfg.r_kv:], t))
+        # ---- output projection ----
+        d_model = 7168
+        w_o = S.output_weights(cfg, d_model)
+        o = S.quantize(S.rng(cfg.seed, 8).standard_normal((cfg.B, cfg.s_q, cfg.h_q, cfg.d_h), dtype=np.float32), cfg.dtype)
+        y = dec.output_projection(case.d(o), case.d(w_o))
+        torch.cuda.synchronize()
+        yh = y.float().cpu().numpy().reshape(cfg.B * cfg.s_q, d_model)
+        of = o.reshape(cfg.B * cfg.s_q, -1).astype(np.float64)
+        assert np.isfinite(yh).all()
+        rows4 = [0, 1, 64, 127]
+        ref4 = (w_o.astype(np.float64) @ of[rows4].T).T
+        for k, m in enumerate(rows4):
+            check("W^O row %d" % m, yh[m], ref4[k])
+        pick = np.random.default_rng(3).integers(0, [cfg.B * cfg.s_q, d_model], size=(2000, 2))
+        ref = np.einsum("ik,ik->i", of[pick[:, 0]], w_o[pick[:, 1]].astype(np.float64))
+        check("W^O 2000 sampled elements", yh[pick[:, 0], pick[:, 1]], ref)
+    finally:
+        case.close()
