@@ -145,13 +145,24 @@ def plan_overhead_pages(path):
 
 
 def plan_merge_cost(path):
-    """Sixteenths of a page time that each chunk partial of the longest sequence adds to the combine."""
-    return 4 if path == PATH_ABSORB else 1
+    """Eightieths of a page time that each chunk partial of the longest sequence adds to the combine."""
+    return 16 if path == PATH_ABSORB else 5
+
+
+def plan_page_weight(path, n_chunks, num_cus, h_q, s_q):
+    """Eightieths of the reference page time that one page costs a workgroup: 80, or 53 on the absorb path when the
+    launch gives every 32 query rows a workgroup of their own -- at most 32 rows per sequence, or so few chunks
+    (counted in eights) that one workgroup per chunk and 32 rows still fits the device in one round."""
+    if path != PATH_ABSORB:
+        return 80
+    M = h_q * s_q
+    padded = -(-n_chunks // 8) * 8
+    return 53 if (M <= 32 or padded * (-(-M // 32)) <= num_cus) else 80
 
 
 def plan_chunk_pages(lens, P, num_cus, path, h_q, g, s_q):
     """Chunk size (in pages): the cp in 1..max_b npages_b minimising
-    16 * ceil(n_chunks(cp) / slots) * (cp + overhead) + merge * ceil(max_b npages_b / cp),
+    weight(cp) * ceil(n_chunks(cp) / slots) * (cp + overhead) + merge * ceil(max_b npages_b / cp),
     n_chunks(cp) = sum_b ceil(npages_b / cp); ties go to the larger cp."""
     npages = [pages_needed(L, P) for L in lens]
     slots = plan_slots(num_cus, path, h_q, g, s_q)
@@ -161,7 +172,8 @@ def plan_chunk_pages(lens, P, num_cus, path, h_q, g, s_q):
     for cp in range(1, longest + 1):
         n_chunks = sum(-(-n // cp) for n in npages)
         rounds = -(-n_chunks // slots)
-        cost = 16 * rounds * (cp + ovh) + plan_merge_cost(path) * (-(-longest // cp))
+        cost = (plan_page_weight(path, n_chunks, num_cus, h_q, s_q) * rounds * (cp + ovh)
+                + plan_merge_cost(path) * (-(-longest // cp)))
         if best_cost is None or cost <= best_cost:
             best_cp, best_cost = cp, cost
     return best_cp

@@ -458,12 +458,12 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 }
 
 // ---- combine + latent-output projection: out = W_UV[j]^T (sum_k w_k o_hat_k)   (MQA-absorb equation, line 6) ----
-// One workgroup of 4 waves per (group j, 32 query rows of that group).  W_UV[j] ([r_kv][d_h], 128 KB) is staged in LDS
+// One workgroup of 4 waves per (group j, 32 query rows of that group; 8 rows when the batch is small).  W_UV[j] ([r_kv][d_h], 128 KB) is staged in LDS
 // and read transposed; wave w contracts over latent dims [w*RKV/4, (w+1)*RKV/4):
 //   O^T[d][row] += W^T[d][r] * Ohat^T[r][row]     A = transposed LDS fragments, B = the combined chunk partials
 // and the four partial O^T are summed through LDS.
 template <int RKV, int DH>
-__global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a, int rows_per_group) {
+__global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a, int rows_per_group, int rows_per_wg) {
   constexpr int KSW = RKV / 16 / 4;  // k-steps per wave
   constexpr int MT = DH / 32;
   static_assert(MT == 4, "one output tile per wave in the final reduction");
@@ -475,8 +475,10 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
   stage_panels_full<RKV, DH / 64, 4, DH * 2>(smem, (const char*)a.w_uv + (int64_t)j * RKV * DH * 2, wave, lane);
 
   // row of this lane among the rows of group j: x = (b * s_q + t) * G + head-in-group
-  const int x = blockIdx.x * 32 + n;
-  const bool row_ok = x < rows_per_group;
+  // rows_per_wg < 32 (small batches): more workgroups, each with only its first lanes holding a row, so that the merge of
+  // many chunk partials is spread over the chip; lanes without a row compute on row 0 and store nothing.
+  const int x = blockIdx.x * rows_per_wg + n;
+  const bool row_ok = n < rows_per_wg && x < rows_per_group;
   const int xc = row_ok ? x : 0;
   const int b = xc / (a.s_q * a.G);
   const int t = (xc / a.G) % a.s_q;
@@ -614,7 +616,9 @@ hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {
       hipFuncSetAttribute((const void*)combine_project_bf16_kernel<512, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
   if (attr != hipSuccess) return attr;
   const int rows_per_group = a.B * a.s_q * a.G;
-  combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + 31) / 32, a.g), 256, kLds, s>>>(a, rows_per_group);
+  // 32 rows per workgroup fill the MFMA tile; with fewer than half a chip's worth of such workgroups, 8 rows each
+  const int rows_per_wg = ((rows_per_group + 31) / 32) * a.g >= 128 ? 32 : (((rows_per_group + 7) / 8) * a.g >= 128 ? 8 : 4);
+  combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + rows_per_wg - 1) / rows_per_wg, a.g), 256, kLds, s>>>(a, rows_per_group, rows_per_wg);
   return hipGetLastError();
 }
 

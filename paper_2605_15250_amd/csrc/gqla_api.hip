@@ -66,6 +66,33 @@ int32_t plan_slots(const gqla_shape& s, int32_t num_cus, int32_t path) {
   return std::max<int64_t>(1, (int64_t)num_cus * 8 / ((int64_t)s.g * rb));
 }
 
+// Chunk size of the split plan (the rule documented in gqla.h).  Cost of a candidate cp, in eightieths of the time a
+// 128-row absorb workgroup (or a GQA wave) spends on one page: rounds of chunks on the device, each a chunk plus its
+// fixed cost, then the combine, whose time is set by the longest chain of chunk partials it merges for one sequence.
+// On the absorb path a page costs 53 instead of 80 when the launch gives every 32 query rows a workgroup of their own
+// (at most 32 rows per sequence, or so few chunks that all those workgroups run at once).
+int32_t choose_chunk_pages(const std::vector<int32_t>& npages, const gqla_shape& s, int32_t num_cus, int32_t path) {
+  int32_t max_np = 1;
+  for (int32_t v : npages) max_np = std::max(max_np, v);
+  const int64_t slots = plan_slots(s, num_cus, path);
+  const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : 2;
+  const int64_t merge = path == GQLA_PATH_ABSORB ? 16 : 5;
+  const int64_t M = (int64_t)s.h_q * s.s_q;
+  int64_t best = -1;
+  int32_t cp = 1;
+  for (int32_t c = 1; c <= max_np; ++c) {
+    int64_t n = 0;
+    for (int32_t v : npages) n += ceil_div(v, c);
+    const bool shared_rows = path == GQLA_PATH_ABSORB && (M <= 32 || ceil_div(n, 8) * 8 * ceil_div(M, 32) <= num_cus);
+    const int64_t cost = (shared_rows ? 53 : 80) * ceil_div(n, slots) * (c + ovh) + merge * ceil_div(max_np, c);
+    if (best < 0 || cost <= best) {
+      best = cost;
+      cp = c;
+    }
+  }
+  return cp;
+}
+
 WsLayout make_layout(const gqla_plan& p) {
   WsLayout w;
   const size_t n = p.chunks.size();
@@ -188,24 +215,7 @@ gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_ho
     max_np = std::max(max_np, npages[b]);
   }
   int32_t cp = chunk_pages_override;
-  if (cp == 0) {
-    const int64_t slots = plan_slots(*shape, num_cus, path);
-    // Cost in sixteenths of the time one page takes: rounds of chunks on the device, each a chunk plus its fixed cost,
-    // then the combine, whose time is set by the longest chain of chunk partials it merges for one sequence.
-    const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : 2;
-    const int64_t merge = path == GQLA_PATH_ABSORB ? 4 : 1;
-    int64_t best = -1;
-    cp = 1;
-    for (int32_t c = 1; c <= max_np; ++c) {
-      int64_t n = 0;
-      for (int32_t b = 0; b < shape->batch; ++b) n += ceil_div(npages[b], c);
-      const int64_t cost = 16 * ceil_div(n, slots) * (c + ovh) + merge * ceil_div(max_np, c);
-      if (best < 0 || cost <= best) {
-        best = cost;
-        cp = c;
-      }
-    }
-  }
+  if (cp == 0) cp = choose_chunk_pages(npages, *shape, num_cus, path);
   p->chunk_pages = cp;
   p->first_slot.resize(shape->batch + 1);
   for (int32_t b = 0; b < shape->batch; ++b) {
@@ -676,17 +686,10 @@ gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gql
   if (shape->batch > 0 && cached_tokens > 0) {
     const int64_t np = ceil_div(ceil_div(cached_tokens, shape->batch), 64);
     const int64_t slots = plan_slots(*shape, 256, GQLA_PATH_ABSORB);
-    int64_t best = -1, cp = 1;
-    for (int64_t c = 1; c <= np; ++c) {
-      const int64_t cost = 16 * ceil_div(shape->batch * ceil_div(np, c), slots) * (c + 4) + 4 * ceil_div(np, c);
-      if (best < 0 || cost <= best) {
-        best = cost;
-        cp = c;
-      }
-    }
+    const int64_t cp = choose_chunk_pages(std::vector<int32_t>((size_t)shape->batch, (int32_t)np), *shape, 256, GQLA_PATH_ABSORB);
     const int64_t per_seq = ceil_div(np, cp), per = ceil_div(np, per_seq), chunks = shape->batch * per_seq;
     const int64_t M = (int64_t)shape->h_q * shape->s_q;
-    const double page_s = M <= 32 ? 1.6e-6 : (chunks * ceil_div(M, 32) <= 256 ? 2.6e-6 : 4.4e-6);
+    const double page_s = M <= 32 ? 1.6e-6 : (ceil_div(chunks, 8) * 8 * ceil_div(M, 32) <= 256 ? 2.6e-6 : 4.4e-6);
     ta = std::max(ta, 28e-6 + (double)(ceil_div(chunks, slots) * (per + 4)) * page_s);
   }
   out->absorb_seconds = ta;

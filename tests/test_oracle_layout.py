@@ -98,15 +98,27 @@ def test_plan_known_cases():
     # canonical uniform cases: one chunk per compute unit
     assert Lay.plan_chunk_pages([8192] * 64, 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 32
     assert Lay.plan_chunk_pages([4096] * 32, 64, 256, Lay.PATH_GQA, 32, 8, 1) == 8
-    # one 8192-token sequence (128 pages) on 256 compute units, costs by hand in sixteenths of a page time
-    # (16 * rounds * (cp + overhead) + merge * chunks of the sequence):
-    #   absorb (overhead 4, merge 4): cp 5 -> 16*9 + 4*26 = 248, cp 6 -> 16*10 + 4*22 = 248, cp 7 -> 16*11 + 4*19 = 252,
-    #   cp 4 -> 16*8 + 4*32 = 256; the tie goes to the larger chunk
+    # one 8192-token sequence (128 pages) on 256 compute units, costs by hand in eightieths of a page time
+    # (weight * rounds * (cp + overhead) + merge * chunks of the sequence):
+    #   absorb (overhead 4, merge 16; every cp >= 2 gives at most 64 chunks, i.e. 64 * 4 row blocks <= 256 workgroups, so
+    #   the shared-row launch applies and a page weighs 53): cp 5 -> 53*9 + 16*26 = 893, cp 6 -> 53*10 + 16*22 = 882,
+    #   cp 7 -> 53*11 + 16*19 = 887, cp 8 -> 53*12 + 16*16 = 892
     assert Lay.plan_chunk_pages([8192], 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 6
-    #   gqa (overhead 2, merge 1): cp 2 -> 64 + 64 = 128, cp 3 -> 80 + 43 = 123, cp 4 -> 96 + 32 = 128
+    #   gqa (overhead 2, merge 5, weight 80): cp 2 -> 320 + 320 = 640, cp 3 -> 400 + 215 = 615, cp 4 -> 480 + 160 = 640
     assert Lay.plan_chunk_pages([8192], 64, 256, Lay.PATH_GQA, 128, 8, 1) == 3
     # without the merge term both would be cut into one-page chunks: a longer chain of partials costs more than it saves
-    assert Lay.plan_chunk_pages([65536], 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 16   # 16*20 + 4*64 = 576 < cp 8: 16*12 + 4*128 = 704
+    #   1024 pages: cp 18 -> 57 chunks: 53*22 + 16*57 = 2078; cp 19 -> 54: 53*23 + 16*54 = 2083; cp 17 -> 61: 53*21 + 16*61 = 2089
+    assert Lay.plan_chunk_pages([65536], 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 18
+    # four such sequences: with cp 8 there are 64 chunks, the last count at which every 32 rows get a workgroup of their
+    # own (64 * 4 = 256): 53*12 + 16*16 = 892; cp 6 (88 chunks, ordinary launch) would cost 80*10 + 16*22 = 1152
+    assert Lay.plan_chunk_pages([8192] * 4, 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 8
+    # and four sequences of 32768 tokens: the shared-row launch needs cp >= 32 (53*36 + 16*16 = 2164), the ordinary one
+    # gets by with cp 11 or 12 (80*15 + 16*47 = 1952, 80*16 + 16*43 = 1968)
+    assert Lay.plan_chunk_pages([32768] * 4, 64, 256, Lay.PATH_ABSORB, 128, 8, 1) == 11
+    assert Lay.plan_page_weight(Lay.PATH_ABSORB, 64, 256, 128, 1) == 53 and Lay.plan_page_weight(Lay.PATH_ABSORB, 65, 256, 128, 1) == 80
+    assert Lay.plan_page_weight(Lay.PATH_ABSORB, 10**6, 256, 32, 1) == 53 and Lay.plan_page_weight(Lay.PATH_GQA, 1, 256, 128, 1) == 80
+    #   s_q = 2 halves the chunk count at which that launch applies (256 rows = 8 row blocks)
+    assert Lay.plan_page_weight(Lay.PATH_ABSORB, 32, 256, 128, 2) == 53 and Lay.plan_page_weight(Lay.PATH_ABSORB, 33, 256, 128, 2) == 80
     chunks, first = Lay.plan_chunks([130, 64], 64, 2)
     assert chunks == [(0, 0, 128), (0, 128, 130), (1, 0, 64)] and first == [0, 2]
     chunks, _ = Lay.plan_chunks([64 * 5], 64, 2)              # 5 pages, cp 2 -> 3 chunks of 2,2,1
