@@ -294,8 +294,8 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
  *   absorb (query absorption + decode):  28 us + max(bytes / 5.5 TB/s, flops / 0.95 PFLOP/s, rounds * (per + 4) * page)
  *          where the split-plan rule of gqla_plan_create, applied to `batch` sequences of cached_tokens / batch tokens
  *          on 64-token pages and 256 compute units, gives every workgroup `rounds` chunks of `per` pages, and a page
- *          costs a workgroup 4.4 us (1.6 us when h_q s_q <= 32; 2.6 us when chunks * ceil(h_q s_q / 32) <= 256, where
- *          the launch gives every 32 rows their own workgroup)
+ *          costs a workgroup 4.4 us (1.6 us when h_q s_q <= 32; 2.6 us when 8 * ceil(chunks / 8) * ceil(h_q s_q / 32) <= 256,
+ *          where the launch gives every 32 rows their own workgroup)
  *   gqa    (decode on the expanded cache): 24 us + f * bytes / 7.0 TB/s,
  *          f = 1 + 0.45 * (ceil(G s_q / 32) - 1): a group's rows beyond 32 stream the cache again, mostly from the caches
  * with bytes and flops as in gqla_estimate_paths.  faster_path is the path with the smaller time (absorb on a tie). */
