@@ -221,13 +221,18 @@ def main():
         # per token; the quantising cache switch is one-shot, like the expansion
         gd.alloc_expanded_fp8(fill=0)
         t_q = timed(lambda: gd.quantize_expanded(1.0, 1.0), 5)
+        two_step = gd.expanded_fp8_pool.clone()
+        t_e8 = timed_steady(lambda: gd.expand_fp8(Gq["d_w_uk"], Gq["d_w_uv"], 1.0, 1.0), 5)   # latent -> 8-bit cache in one pass
+        same8 = bool(torch.equal(two_step, gd.expanded_fp8_pool))
+        del two_step
         out8 = torch.empty_like(Gq["out"])
         t_d8 = timed_steady(lambda: gd.decode_gqa_fp8(Gq["d_q_c"], Gq["d_q_r"], 1.0, 1.0, out8, Gq["lse"]), 20)
         gd.decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
         torch.cuda.synchronize()
         b8 = int(Gq["lens"].sum()) * B.gqla_expanded_fp8_bytes_per_token(cg.g, cg.d_h, cg.d_r)
         d16 = Gq["out"].float()
-        fp8_kv = {"quantize_expanded_ms": t_q * 1e3, "decode_gqa_fp8_ms": t_d8 * 1e3, "bytes_per_token": b8 // int(Gq["lens"].sum()),
+        fp8_kv = {"quantize_expanded_ms": t_q * 1e3, "expand_cache_fp8_ms": t_e8 * 1e3, "expand_cache_fp8_equals_expand_then_quantize": same8,
+                  "decode_gqa_fp8_ms": t_d8 * 1e3, "bytes_per_token": b8 // int(Gq["lens"].sum()),
                   "GB/s": b8 / t_d8 / 1e9, "frac_hbm_peak": b8 / t_d8 / 1e9 / HBM_PEAK_GBS, "tokens_per_s": cg.B * cg.s_q / t_d8,
                   "rel_l2_vs_16bit_cache": float(torch.linalg.norm(out8.float() - d16) / torch.linalg.norm(d16))}
         gd.expanded_fp8_pool = None

@@ -259,6 +259,12 @@ gqla_status gqla_expand_cache_tail_fp8(const gqla_shape* shape, const gqla_cache
                                        const void* w_uv, int32_t group_begin, int32_t group_count,
                                        const gqla_cache* expanded_fp8, int32_t tail_tokens, float k_scale, float v_scale,
                                        void* ws, size_t ws_bytes, void* stream);
+/* gqla_expand_cache whose destination is an 8-bit cache (every token t < L_b): the cache switch latent -> 8-bit expanded
+ * in one pass, with the codes that gqla_expand_cache followed by gqla_quantize_expanded would give, at half the bytes
+ * written and without the 16-bit intermediate.  Arguments and errors as for gqla_expand_cache, plus the two scales. */
+gqla_status gqla_expand_cache_fp8(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                                  int32_t group_begin, int32_t group_count, const gqla_cache* expanded_fp8, float k_scale,
+                                  float v_scale, void* ws, size_t ws_bytes, void* stream);
 int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r);
 
 /* ---- sizes and diagnostics ------------------------------------------------------------------------------ */

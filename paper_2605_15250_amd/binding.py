@@ -23,7 +23,7 @@ EXPORTS = [
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
-    "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8",
+    "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8", "gqla_expand_cache_fp8",
     "gqla_left_inverse", "gqla_compress_cache", "gqla_rope_step", "gqla_output_projection",
     "gqla_output_projection_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
@@ -103,6 +103,8 @@ def lib():
         L.gqla_decode_gqa_fp8.restype = i32
         L.gqla_expand_cache_tail_fp8.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, C.c_float, C.c_float, vp, C.c_size_t, vp]
         L.gqla_expand_cache_tail_fp8.restype = i32
+        L.gqla_expand_cache_fp8.argtypes = [sp, cp, vp, vp, i32, i32, cp, C.c_float, C.c_float, vp, C.c_size_t, vp]
+        L.gqla_expand_cache_fp8.restype = i32
         L.gqla_left_inverse.argtypes = [sp, vp, vp]
         L.gqla_left_inverse.restype = i32
         L.gqla_compress_cache.argtypes = [sp, cp, vp, cp, vp]
@@ -316,6 +318,15 @@ def gqla_left_inverse(shape, w_uk_host: np.ndarray) -> np.ndarray:
 def gqla_compress_cache(shape, expanded: gqla_cache, w_inv, latent: gqla_cache, stream=None):
     _check(lib().gqla_compress_cache(C.byref(shape), C.byref(expanded), _ptr(w_inv), C.byref(latent), _stream(stream)),
            "gqla_compress_cache")
+
+
+def gqla_expand_cache_fp8(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded_fp8: gqla_cache, k_scale,
+                          v_scale, ws=None, ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().gqla_expand_cache_fp8(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
+                                       C.byref(expanded_fp8), float(k_scale), float(v_scale), _ptr(ws), ws_bytes,
+                                       _stream(stream)), "gqla_expand_cache_fp8")
 
 
 def gqla_rope_step(shape, seq_lens, rope_base, q_r, rows, stream=None):

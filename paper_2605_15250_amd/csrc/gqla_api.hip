@@ -368,7 +368,7 @@ gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const
   a.v_inv_scale = 1.0f / v_scale;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (fp8) e = launch_expand_tail_fp8(a, ws, s);
+  if (fp8) e = tail > 0 ? launch_expand_tail_fp8(a, ws, s) : launch_expand_fp8(a, ws, s);
   else if (tail > 0) e = shape->dtype == GQLA_BF16 ? launch_expand_tail_bf16(a, ws, s) : launch_expand_tail_f32(a, s);
   else e = shape->dtype == GQLA_BF16 ? launch_expand_bf16(a, ws, s) : launch_expand_f32(a, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
@@ -397,6 +397,15 @@ gqla_status gqla_expand_cache_tail_fp8(const gqla_shape* shape, const gqla_cache
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
   return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded_fp8, tail_tokens, ws, ws_bytes, stream, true,
                      k_scale, v_scale);
+}
+
+gqla_status gqla_expand_cache_fp8(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
+                                  int32_t group_begin, int32_t group_count, const gqla_cache* expanded_fp8, float k_scale,
+                                  float v_scale, void* ws, size_t ws_bytes, void* stream) {
+  if (shape && shape->dtype != GQLA_BF16) return check_shape(shape) == GQLA_OK ? GQLA_ERR_DTYPE : check_shape(shape);
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
+  return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded_fp8, 0, ws, ws_bytes, stream, true, k_scale,
+                     v_scale);
 }
 
 gqla_status gqla_append_latent(const gqla_shape* shape, const void* rows, const gqla_cache* latent, void* stream) {

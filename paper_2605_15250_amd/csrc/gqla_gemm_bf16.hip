@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __
 // The two output orientations put 4 consecutive dims (K plane) or 4 consecutive tokens (V plane) of the expanded
 // page's 8-element vectors in one lane.  A stage's results are stored while the next stage is being multiplied, so
 // that the end-of-stage wait (which also covers stores on this hardware) finds them long gone.
-template <int DH, int RKV, int DR>
+template <int DH, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
@@ -143,7 +143,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   // stays in that token's outputs, and those are never stored.
   bf16x8 xf[2][KS];
   const __bf16* in_page = (const __bf16*)a.latent.pool + (int64_t)(wave_ok ? pg_in : 0) * P * W;
-  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (2 * gc * DH + DR);
+  // FP8: `expanded` is an 8-bit cache (E4M3 code planes and a 16-bit k_R plane, see the header): 2 gc DH + 2 DR bytes per token
+  constexpr int EB = FP8 ? 1 : 2;  // bytes per K_C / V element
+  char* const page_bytes = (char*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (2 * gc * DH * EB + 2 * DR);
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const bool tok_ok = wave_ok && (tokw + 32 * nt + n < L);
@@ -156,7 +158,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 #pragma unroll
       for (int cb = h; cb < DR / 8; cb += 2) {
         const u32x4 v = *(const u32x4*)(in_row + RKV + cb * 8);
-        __builtin_nontemporal_store(v, (u32x4*)(out_page + (int64_t)2 * gc * DH * P + ((int64_t)cb * P + slot0 + 32 * nt + n) * 8));
+        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (int64_t)2 * gc * DH * P * EB + ((int64_t)cb * P + slot0 + 32 * nt + n) * 16));
       }
     }
   }
@@ -175,7 +177,6 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   // results of the previous stage ([token tile][32-column half]), kept until the next stage's arithmetic is under way
   f32x16 accs[2][2][2];  // [stage parity][token tile][32-column half]: one set accumulates while the other is stored
   // stores address the page through one uniform base and 32-bit offsets (a page is at most a few MB)
-  char* const page_bytes = (char*)out_page;
   const uint32_t plane = (uint32_t)DH * P;                            // elements of one group's K (or V) plane
   const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + (uint32_t)h * P * 8;        // K plane: token slot0 + n, 8-dim block + h
   const uint32_t v_lane = (uint32_t)((slot0 >> 3) + h) * DH * 8 + n * 8;          // V plane: dim n, 8-token block slot0/8 + h
@@ -183,6 +184,43 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   // One 16-byte store per lane: piece (nt, e, qp) of the previous stage's results; kind, mtp and the piece are compile-time.
   // A lane holds rows 4h..4h+3 of each 8-row block of its column; the two half-waves trade so that lane (n, h) ends up
   // with all 8 rows of block 2*qp + h, i.e. one complete vector of the page layout.
+  // 8-bit destination: one 16-byte store per lane and (nt, e): the 32 results of the lane's column as the two code
+  // vectors of the page layout (a vector holds 8-row blocks h' and 2 + h' of the 32 rows, each block 4 rows from either
+  // half-wave); every result is rounded to bf16 first, so that the codes are those of expanding and then converting.
+  auto store_prev8 = [&](int kind, int mtp, int jj, int nt, int e) {
+    if (jj < 0 || !wave_ok) return;
+    const f32x16& acc = accs[(kind * 2 + mtp) & 1][nt][e];
+    const float inv = kind == 0 ? a.k_inv_scale : a.v_inv_scale;
+    uint32_t code[4];  // code[q] = rows 8q + 4h + 0..3
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      code[q] = quantize_e4m3x4(round_to_bf16(acc[4 * q]), round_to_bf16(acc[4 * q + 1]), round_to_bf16(acc[4 * q + 2]),
+                                round_to_bf16(acc[4 * q + 3]), inv);
+    uint32_t r0, r1, r2, r3;
+    half_swap(code[0], code[1], r0, r1);  // lower half: block 0 own, block 0 of the upper half; upper: block 1 of the lower half, block 1 own
+    half_swap(code[2], code[3], r2, r3);
+    const u32x4 v = {r0, r1, r2, r3};
+    if (kind == 0) {
+      // lane = token; vector h of pair kp = 2 mtp + e of the K8 plane
+      if (wave_full || tokw + 32 * nt + n < L) {
+        const uint32_t off = ((uint32_t)(jj * (DH / 16) + 2 * (2 * mtp + e) + h) * P + slot0 + 32 * nt + n) * 16;
+        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + off));
+      }
+    } else {
+      // lane = dim 64 mtp + 32 e + n; vector h of 32-token tile (slot0 + 32 nt) / 32 of the V8 plane: tokens 8h + 0..7, 16 + 8h + 0..7
+      const uint32_t off = (uint32_t)gc * P * DH +
+                           (((uint32_t)(jj * (P / 32) + (slot0 >> 5) + nt) * DH + 64 * mtp + 32 * e + n) * 2 + h) * 16;
+      char* dst = page_bytes + off;
+      const int tk = tokw + 32 * nt + 8 * h;  // first token of the vector's first half; the second half starts 16 later
+      if (wave_full || tk + 23 < L) {
+        __builtin_nontemporal_store(v, (u32x4*)dst);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (tk + 16 * (i >> 3) + (i & 7) < L) dst[i] = (char)((v[i >> 2] >> (8 * (i & 3))) & 0xffu);
+      }
+    }
+  };
   auto store_prev = [&](int kind, int mtp, int jj, int nt, int e, int qp) {
     if (jj < 0 || !wave_ok) return;
     const f32x16& acc = accs[(kind * 2 + mtp) & 1][nt][e];
@@ -254,8 +292,12 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
             }
           __builtin_amdgcn_sched_barrier(0);
           // the previous stage's results leave one store at a time, in the shadow of this stage's MFMAs
-          if (ks >= 1 && ks <= 15 && (ks & 1))
+          if constexpr (FP8) {
+            if ((ks & 3) == 3 && ks <= 15)  // four pieces (nt, e)
+              store_prev8(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj, (ks >> 2) >> 1, (ks >> 2) & 1);
+          } else if (ks >= 1 && ks <= 15 && (ks & 1)) {
             store_prev(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj, (ks >> 1) >> 2, ((ks >> 1) >> 1) & 1, (ks >> 1) & 1);
+          }
         }
         mfma_results_ready(acc[0][0], acc[0][1], acc[1][0], acc[1][1]);
       } else if (stage + 1 < n_stages) {
@@ -265,8 +307,13 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       __syncthreads();  // next stage has landed; everyone is done with this stage's buffer
     }
   }
+  if constexpr (FP8) {
 #pragma unroll
-  for (int piece = 0; piece < 8; ++piece) store_prev(1, 1, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
+    for (int piece = 0; piece < 4; ++piece) store_prev8(1, 1, gc - 1, piece >> 1, piece & 1);
+  } else {
+#pragma unroll
+    for (int piece = 0; piece < 8; ++piece) store_prev(1, 1, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
+  }
 }
 
 // ---- cache expansion of the last a.tail positions of every sequence (the step's new tokens) ------------------------
@@ -549,19 +596,22 @@ hipError_t launch_expand_tail_fp8(const ExpandArgs& a, void* ws, hipStream_t s) 
   return hipGetLastError();
 }
 
-hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
+template <bool FP8>
+static hipError_t launch_expand_one_shot(const ExpandArgs& a, void* ws, hipStream_t s) {
   constexpr int kLds = 2 * (512 / 16) * 2 * 1024;
   // once per process (function-local statics are initialised under a lock); an error is reported by every call
   static const hipError_t attr =
-      hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+      hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
   if (attr != hipSuccess) return attr;
   const int64_t max_tokens = (int64_t)a.latent.max_pages * a.latent.page_size;
   dim3 grid((unsigned)((max_tokens + 255) / 256), a.B);
   pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  expand_bf16_kernel<128, 512, 64><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);
+  expand_bf16_kernel<128, 512, 64, FP8><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }
+hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_one_shot<false>(a, ws, s); }
+hipError_t launch_expand_fp8(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_one_shot<true>(a, ws, s); }
 
 }  // namespace gqla

@@ -126,6 +126,7 @@ hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_bf16(const ExpandArgs&, void* ws /* packed weights, 2*group_count*r_kv*d_h bf16 */, hipStream_t);
 hipError_t launch_expand_tail_f32(const ExpandArgs&, hipStream_t);
 hipError_t launch_expand_tail_bf16(const ExpandArgs&, void* ws /* as above */, hipStream_t);
+hipError_t launch_expand_fp8(const ExpandArgs&, void* ws /* as above */, hipStream_t);       // one-shot, `expanded` is an 8-bit cache
 hipError_t launch_expand_tail_fp8(const ExpandArgs&, void* ws /* as above */, hipStream_t);  // `expanded` is an 8-bit cache
 hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);

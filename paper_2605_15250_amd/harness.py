@@ -170,6 +170,16 @@ class Decoder:
         B.gqla_quantize_expanded(self.shape, self.expanded_cache(), self.expanded_fp8_cache(), k_scale, v_scale)
         return self.expanded_fp8_pool
 
+    def expand_fp8(self, w_uk, w_uv, k_scale, v_scale):
+        if self.expanded_fp8_pool is None:
+            self.alloc_expanded_fp8()
+        if self.ws_e is None:
+            nbytes = B.gqla_expand_workspace_bytes(self.shape, self.groups)
+            self.ws_e = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+        B.gqla_expand_cache_fp8(self.shape, self.latent_cache(), w_uk, w_uv, self.group_begin, self.groups,
+                                self.expanded_fp8_cache(), k_scale, v_scale, self.ws_e)
+        return self.expanded_fp8_pool
+
     def expand_tail_fp8(self, w_uk, w_uv, tail_tokens, k_scale, v_scale):
         if self.ws_e is None:
             nbytes = B.gqla_expand_workspace_bytes(self.shape, self.groups)

@@ -139,3 +139,32 @@ def test_fp8_tail_expansion_equals_expand_then_quantise():
                     assert got[o] == ref[o] and got[o + 1] == ref[o + 1]
     finally:
         case.close()
+
+
+@pytest.mark.parametrize("lens,page_size,groups,group_begin", [
+    ([200, 2, 65, 1000, 256, 31], 64, None, 0),     # ragged tails inside a 32-token tile, a full page, a tiny sequence
+    ([300, 129], 128, None, 0),                     # 128-token pages
+    ([257, 64], 64, 2, 5),                          # a two-group slice
+])
+def test_fp8_one_shot_expansion_equals_expand_then_quantise(lens, page_size, groups, group_begin):
+    """The whole cache switch latent -> 8-bit expanded in one pass holds the bytes of the two-step route (expand into a
+    16-bit cache, convert it) -- the two-step route itself is checked against the oracle above -- and leaves every byte
+    no token owns as it was."""
+    cfg = S.CONFIGS["C3"].with_(B=len(lens), L=0, paged=True, page_size=page_size, seed=883)
+    case = Case(cfg, lens=lens, groups=groups, group_begin=group_begin)
+    dec = case.dec
+    ks, vs = 0.6, 1.7
+    try:
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        dec.alloc_expanded_fp8(fill=0xAA)
+        dec.quantize_expanded(ks, vs)
+        torch.cuda.synchronize()
+        ref = dec.expanded_fp8_pool.clone()
+        dec.alloc_expanded_fp8(fill=0xAA)
+        dec.expand_fp8(case.d_w_uk, case.d_w_uv, ks, vs)
+        torch.cuda.synchronize()
+        assert torch.equal(dec.expanded_fp8_pool, ref), "one-shot 8-bit expansion differs from expand + quantise in %d bytes" % int(
+            (dec.expanded_fp8_pool != ref).sum().item())
+    finally:
+        case.close()

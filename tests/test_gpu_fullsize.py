@@ -153,6 +153,12 @@ def test_c3_step_updates_and_fp8_cache_at_full_size():
         # 8-bit cache
         dec.alloc_expanded_fp8(fill=0)
         dec.quantize_expanded(1.0, 1.0)
+        two_step = dec.expanded_fp8_pool.clone()
+        dec.alloc_expanded_fp8(fill=0)
+        dec.expand_fp8(case.d_w_uk, case.d_w_uv, 1.0, 1.0)
+        torch.cuda.synchronize()
+        assert torch.equal(dec.expanded_fp8_pool, two_step), "one-shot 8-bit expansion vs expand + quantise"
+        del two_step
         out8, _ = dec.decode_gqa_fp8(case.d(case.q_c), case.d(case.q_r), 1.0, 1.0)
         torch.cuda.synchronize()
         o8 = out8.float().cpu().numpy()

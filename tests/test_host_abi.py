@@ -166,6 +166,11 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 0, 1.0, 1.0, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 2, 1.0, 0.0, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_fp8, ok, lat, A, A, 0, 8, full8, 2, 1.0, 1.0, None, 0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_fp8, ok, lat, A, A, 0, 8, full8, 1.0, -2.0, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_fp8, ok, lat, A, A, 4, 8, full8, 1.0, 1.0, A, 1 << 24, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_fp8, ok, lat, A, A, 0, 8, full8, 1.0, 1.0, None, 0, stream=0)
+        _expect(B.GQLA_ERR_DTYPE, B.gqla_expand_cache_fp8, f32, B.make_cache(A, A, None, 8, 4, 8, 0), A, A, 0, 2,
+                B.make_cache(A, A, None, 8, 4, 8, 2), 1.0, 1.0, A, 1 << 24, stream=0)
         assert B.gqla_expanded_fp8_bytes_per_token(8, 128, 64) == 2176 and B.gqla_expanded_fp8_bytes_per_token(4, 128, 64) == 1152
     finally:
         B.gqla_plan_destroy(plan_a)
