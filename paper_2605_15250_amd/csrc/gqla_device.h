@@ -79,13 +79,19 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 // Four fp32 values -> four E4M3 codes of x * inv_scale (OCP 8-bit float, "FN" variant), round to nearest even; magnitudes
 // above 448 saturate (the conversion instruction alone would turn them into NaN).  Byte k of the result is value k.
 __device__ __forceinline__ uint32_t quantize_e4m3x4(float a, float b, float c, float d, float inv_scale) {
-  auto q = [&](float x) { return fminf(fmaxf(x * inv_scale, -448.f), 448.f); };
+  auto q = [&](float x) { return __builtin_amdgcn_fmed3f(x * inv_scale, -448.f, 448.f); };  // clamp in one instruction
   int w = __builtin_amdgcn_cvt_pk_fp8_f32(q(a), q(b), 0, false);
   w = __builtin_amdgcn_cvt_pk_fp8_f32(q(c), q(d), w, true);
   return (uint32_t)w;
 }
 // the value a float has after one rounding to bf16 (what a 16-bit cache would hold)
 __device__ __forceinline__ float round_to_bf16(float x) { return bf16_bits_to_float(pack_bf16(x, 0.f) & 0xffffu); }
+// the same for two values with one conversion instruction
+__device__ __forceinline__ void round_to_bf16x2(float& x, float& y) {
+  const uint32_t w = pack_bf16(x, y);
+  x = __builtin_bit_cast(float, w << 16);
+  y = __builtin_bit_cast(float, w & 0xffff0000u);
+}
 
 __device__ __forceinline__ int32_t page_of(const CacheView& c, int32_t b, int32_t p) {
   int32_t pg = c.page_table ? c.page_table[(int64_t)b * c.max_pages + p] : b * c.max_pages + p;

@@ -193,9 +193,12 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
     const float inv = kind == 0 ? a.k_inv_scale : a.v_inv_scale;
     uint32_t code[4];  // code[q] = rows 8q + 4h + 0..3
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      code[q] = quantize_e4m3x4(round_to_bf16(acc[4 * q]), round_to_bf16(acc[4 * q + 1]), round_to_bf16(acc[4 * q + 2]),
-                                round_to_bf16(acc[4 * q + 3]), inv);
+    for (int q = 0; q < 4; ++q) {
+      float x0 = acc[4 * q], x1 = acc[4 * q + 1], x2 = acc[4 * q + 2], x3 = acc[4 * q + 3];
+      round_to_bf16x2(x0, x1);
+      round_to_bf16x2(x2, x3);
+      code[q] = quantize_e4m3x4(x0, x1, x2, x3, inv);
+    }
     uint32_t r0, r1, r2, r3;
     half_swap(code[0], code[1], r0, r1);  // lower half: block 0 own, block 0 of the upper half; upper: block 1 of the lower half, block 1 own
     half_swap(code[2], code[3], r2, r3);
