@@ -307,6 +307,34 @@ def main():
             torch.cuda.synchronize()
             del graph, w_o, y, q_tmp, rows_tmp, rows_t, q_r_t, out_t, lse_t
 
+    # the absorb path with a value dim of its own (Sec. 3.2.2: the MLA checkpoint shape h_q = 20, d_h = 192, d_h^V = 256,
+    # r_kv = 512, here with g = 4): B = 64 sequences of 8192 tokens, device-generated latents (timing only; parity of
+    # the shape is in the tests)
+    mla_shape = None
+    if full_run and not args.no_extras:
+        c = S.CONFIGS["C2"].with_(h_q=20, g=4, d_h=192, d_v=256, B=64, L=8192, s_q=1)
+        lens_k = S.seq_lens(c)
+        table_k, np_k = S.page_table(c, lens_k)
+        dk = Decoder(c, lens_k, table_k, np_k, use_page_table=False)
+        dk.latent_pool = torch.empty(np_k * c.page_size * (c.r_kv + c.d_r), dtype=torch.bfloat16, device="cuda").normal_()
+        wk, wv = S.weights(c)
+        qc_k, qr_k = S.queries(c)
+        d_wk, d_wv, d_qc, d_qr = (to_device(x, c.dtype) for x in (wk, wv, qc_k, qr_k))
+        o_k = torch.empty((c.B, c.s_q, c.h_q, c.dv), dtype=torch.bfloat16, device="cuda")
+        l_k = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
+        qh_k = torch.empty((c.B, c.s_q, c.h_q, c.r_kv), dtype=torch.bfloat16, device="cuda")
+
+        def mla_step():
+            dk.absorb_query(d_qc, d_wk, qh_k)
+            dk.decode_absorb(qh_k, d_qr, d_wv, o_k, l_k)
+        t_m = timed_steady(mla_step, 20)
+        b_m = 2 * int(lens_k.sum()) * (c.r_kv + c.d_r)
+        mla_shape = {"h_q": c.h_q, "g": c.g, "d_h": c.d_h, "d_v": c.dv, "batch": c.B, "context": c.L, "absorb_step_ms": t_m * 1e3,
+                     "GB/s": b_m / t_m / 1e9, "frac_hbm_peak": b_m / t_m / 1e9 / HBM_PEAK_GBS, "tokens_per_s": c.B * c.s_q / t_m,
+                     "finite": bool(torch.isfinite(o_k.float()).all())}
+        dk.close()
+        del dk, o_k, l_k, qh_k
+
     other = None
     if args.all_configs:
         timed2 = timed_steady
@@ -503,6 +531,7 @@ def main():
         "fp8_kv": fp8_kv,
         "compress": compress,
         "step_ops": step_ops,
+        "mla_shape": mla_shape,
         "other_configs": other,
         "operating_points": points,
         "crossover": crossover,

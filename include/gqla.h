@@ -78,12 +78,19 @@ typedef struct {
   int32_t batch;   /* B   sequences in the step                              */
   int32_t h_q;     /*     query heads                                        */
   int32_t g;       /*     KV groups (divides h_q)                            */
-  int32_t d_h;     /*     per-head content dim (value dim equals it)         */
+  int32_t d_h;     /*     per-head content (key) dim                         */
   int32_t r_kv;    /*     latent rank                                        */
   int32_t d_r;     /*     decoupled-RoPE dim                                 */
   int32_t s_q;     /*     step tokens per sequence, 1 or 2                   */
   int32_t dtype;   /*     gqla_dtype                                         */
   float scale;     /*     softmax scale; 0 selects 1/sqrt(d_h + d_r) (Sec. 3.1) */
+  int32_t d_v;     /*     per-head value dim d_h^V; 0 selects d_h.  A value dim of its own (the MLA checkpoints of
+                          Sec. 3.2.2: d_h = 192, d_h^V = 256) exists on the absorb path only: gqla_plan_create
+                          (GQLA_PATH_ABSORB), gqla_absorb_query, gqla_decode_absorb (w_uv [g][r_kv][d_v], out
+                          [B][s_q][h_q][d_v]), gqla_rope_step, gqla_append_latent, gqla_output_projection (w_o
+                          [d_model][h_q * d_v]) and gqla_estimate_paths accept it; every call that touches an expanded
+                          cache returns GQLA_ERR_SHAPE.  GQLA_BF16 supports d_h in {128, 192}, d_v in {128, 256},
+                          r_kv = 512, d_r = 64 (expanded cache: d_h = d_v = 128). */
 } gqla_shape;
 
 typedef struct {

@@ -51,14 +51,16 @@ def n_visible(L: int, s_q: int, t: int) -> int:
 # ----------------------------------------------------------------------------------------
 def expand_latent(c, W_UK, W_UV):
     """k^C_s = W^UK c_s and v^C_s = W^UV c_s for every cached token (Sec. 3.1, Eq. (1) and
-    first line of the GQA-path equation).  c [L, r_kv]; W [g, r_kv, d_h] -> KC, V [L, g, d_h]."""
+    first line of the GQA-path equation).  c [L, r_kv]; W_UK [g, r_kv, d_h], W_UV [g, r_kv, d_v] -> KC [L, g, d_h],
+    V [L, g, d_v] (the value dim may differ from the key dim: d_h^V of Sec. 3.2.2)."""
     c = np.asarray(c, F64)
     W_UK = np.asarray(W_UK, F64)
     W_UV = np.asarray(W_UV, F64)
     L = c.shape[0]
     g, r_kv, d_h = W_UK.shape
+    d_v = W_UV.shape[2]
     KC = np.empty((L, g, d_h), F64)
-    V = np.empty((L, g, d_h), F64)
+    V = np.empty((L, g, d_v), F64)
     for j in range(g):
         KC[:, j, :] = c @ W_UK[j]          # (W_UK[j]^T c_s) for all s
         V[:, j, :] = c @ W_UV[j]
@@ -100,13 +102,13 @@ def _softmax_lse(z):
 def decode_gqa(qC, qR, KC, V, kR, scale=None):
     """o[t,i] = sum_s softmax_s( (qC[t,i].KC[s,j(i)] + qR[t,i].kR[s]) * sigma ) V[s,j(i)].
 
-    qC [s_q,h_q,d_h], qR [s_q,h_q,d_R], KC/V [L,g,d_h], kR [L,d_R] -> o [s_q,h_q,d_h], lse [s_q,h_q]."""
+    qC [s_q,h_q,d_h], qR [s_q,h_q,d_R], KC [L,g,d_h], V [L,g,d_v], kR [L,d_R] -> o [s_q,h_q,d_v], lse [s_q,h_q]."""
     qC, qR, KC, V, kR = (np.asarray(a, F64) for a in (qC, qR, KC, V, kR))
     s_q, h_q, d_h = qC.shape
     L, g, _ = KC.shape
     d_r = qR.shape[2]
     sigma = softmax_scale(d_h, d_r) if scale is None else float(scale)
-    o = np.empty((s_q, h_q, d_h), F64)
+    o = np.empty((s_q, h_q, V.shape[2]), F64)
     lse = np.empty((s_q, h_q), F64)
     for t in range(s_q):
         nv = n_visible(L, s_q, t)
@@ -169,9 +171,11 @@ def project_latent_output(o_hat, W_UV):
     return o
 
 
-def decode_absorb(q_hat, qR, c, kR, W_UV, scale=None):
-    """The whole MQA-absorb decode after query absorption: latent attention, then W^UV."""
-    d_h = np.asarray(W_UV).shape[2]
+def decode_absorb(q_hat, qR, c, kR, W_UV, scale=None, d_h=None):
+    """The whole MQA-absorb decode after query absorption: latent attention, then W^UV.  d_h is the key dim that
+    enters the softmax scale; it defaults to W^UV's column count, i.e. to equal key and value dims."""
+    if d_h is None:
+        d_h = np.asarray(W_UV).shape[2]
     o_hat, lse = decode_absorb_latent(q_hat, qR, c, kR, d_h, scale)
     return project_latent_output(o_hat, W_UV), lse
 
@@ -187,21 +191,24 @@ def decode_mha_bruteforce(qC, qR, c, kR, W_UK, W_UV, scale=None):
     d_r = np.shape(qR)[2]
     L, r_kv = np.shape(c)
     g = np.shape(W_UK)[0]
+    d_v = np.shape(W_UV)[2]
     G = h_q // g
     sigma = 1.0 / math.sqrt(d_h + d_r) if scale is None else float(scale)
-    o = np.zeros((s_q, h_q, d_h), F64)
+    o = np.zeros((s_q, h_q, d_v), F64)
     for i in range(h_q):
         j = i // G
         K_i = [[0.0] * (d_h + d_r) for _ in range(L)]
-        V_i = [[0.0] * d_h for _ in range(L)]
+        V_i = [[0.0] * d_v for _ in range(L)]
         for s in range(L):
             for d in range(d_h):
                 ak = 0.0
-                av = 0.0
                 for r in range(r_kv):
                     ak += float(W_UK[j][r][d]) * float(c[s][r])
-                    av += float(W_UV[j][r][d]) * float(c[s][r])
                 K_i[s][d] = ak
+            for d in range(d_v):
+                av = 0.0
+                for r in range(r_kv):
+                    av += float(W_UV[j][r][d]) * float(c[s][r])
                 V_i[s][d] = av
             for d in range(d_r):
                 K_i[s][d_h + d] = float(kR[s][d])
@@ -217,7 +224,7 @@ def decode_mha_bruteforce(qC, qR, c, kR, W_UK, W_UV, scale=None):
             mx = max(logits)
             w = [math.exp(x - mx) for x in logits]
             den = sum(w)
-            for d in range(d_h):
+            for d in range(d_v):
                 acc = 0.0
                 for s in range(last + 1):
                     acc += w[s] * V_i[s][d]

@@ -39,7 +39,7 @@ class GqlaError(RuntimeError):
 
 class gqla_shape(C.Structure):
     _fields_ = [("batch", C.c_int32), ("h_q", C.c_int32), ("g", C.c_int32), ("d_h", C.c_int32), ("r_kv", C.c_int32),
-                ("d_r", C.c_int32), ("s_q", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float)]
+                ("d_r", C.c_int32), ("s_q", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float), ("d_v", C.c_int32)]
 
 
 class gqla_cache(C.Structure):
@@ -173,8 +173,8 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def make_shape(batch, h_q, g, d_h, r_kv, d_r, s_q, dtype, scale=0.0) -> gqla_shape:
-    return gqla_shape(batch, h_q, g, d_h, r_kv, d_r, s_q, dtype, scale)
+def make_shape(batch, h_q, g, d_h, r_kv, d_r, s_q, dtype, scale=0.0, d_v=0) -> gqla_shape:
+    return gqla_shape(batch, h_q, g, d_h, r_kv, d_r, s_q, dtype, scale, d_v)
 
 
 def make_cache(pool, seq_lens, page_table, page_size, max_pages, num_pages, groups=0) -> gqla_cache:

@@ -462,7 +462,9 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 // and read transposed; wave w contracts over latent dims [w*RKV/4, (w+1)*RKV/4):
 //   O^T[d][row] += W^T[d][r] * Ohat^T[r][row]     A = transposed LDS fragments, B = the combined chunk partials
 // and the four partial O^T are summed through LDS.
-template <int RKV, int DH>
+// DV: value dims per head (columns of W_UV[j], elements of an output row); a workgroup projects onto DH = 128 of them,
+// blockIdx.z selects which (the staged slice of W_UV is then 128 KB whatever DV is; the merge is repeated per slice).
+template <int RKV, int DH, int DV>
 __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a, int rows_per_group, int rows_per_wg) {
   constexpr int KSW = RKV / 16 / 4;  // k-steps per wave
   constexpr int MT = DH / 32;
@@ -472,7 +474,8 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 31, h = lane >> 5;
   const int j = blockIdx.y;
-  stage_panels_full<RKV, DH / 64, 4, DH * 2>(smem, (const char*)a.w_uv + (int64_t)j * RKV * DH * 2, wave, lane);
+  const int col0 = blockIdx.z * DH;  // first value dim of this workgroup
+  stage_panels_full<RKV, DH / 64, 4, DV * 2>(smem, (const char*)a.w_uv + ((int64_t)j * RKV * DV + col0) * 2, wave, lane);
 
   // row of this lane among the rows of group j: x = (b * s_q + t) * G + head-in-group
   // rows_per_wg < 32 (small batches): more workgroups, each with only its first lanes holding a row, so that the merge of
@@ -574,13 +577,13 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
     for (int w = 0; w < 4; ++w) r[i] += red[((w * MT + wave) * 16 + i) * 64 + lane];
   }
   if (!row_ok) return;
-  __bf16* out = (__bf16*)a.out + ((int64_t)b * a.M + rho) * DH + wave * 32;  // this wave writes dims 32*wave .. +31
+  __bf16* out = (__bf16*)a.out + ((int64_t)b * a.M + rho) * DV + col0 + wave * 32;  // this wave writes dims col0 + 32*wave .. +31
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     u32x2 v = {pack_bf16(r[4 * q], r[4 * q + 1]), pack_bf16(r[4 * q + 2], r[4 * q + 3])};
     *(u32x2*)(out + 8 * q + 4 * h) = v;
   }
-  if (a.lse && h == 0 && wave == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
+  if (a.lse && h == 0 && wave == 0 && col0 == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
 }
 
 }  // namespace
@@ -609,17 +612,23 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   return launch_decode_absorb_split<1>(a, s);
 }
 
-hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {
+template <int DV>
+static hipError_t launch_combine_project_dv(const CombineArgs& a, hipStream_t s) {
   constexpr int kLds = 512 * 128 * 2;
   // once per process (function-local statics are initialised under a lock); an error is reported by every call
   static const hipError_t attr =
-      hipFuncSetAttribute((const void*)combine_project_bf16_kernel<512, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+      hipFuncSetAttribute((const void*)combine_project_bf16_kernel<512, 128, DV>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
   if (attr != hipSuccess) return attr;
   const int rows_per_group = a.B * a.s_q * a.G;
-  // 32 rows per workgroup fill the MFMA tile; with fewer than half a chip's worth of such workgroups, 8 rows each
+  // 32 rows per workgroup fill the MFMA tile; with fewer than half a chip's worth of such workgroups, 8 or 4 rows each
   const int rows_per_wg = ((rows_per_group + 31) / 32) * a.g >= 128 ? 32 : (((rows_per_group + 7) / 8) * a.g >= 128 ? 8 : 4);
-  combine_project_bf16_kernel<512, 128><<<dim3((rows_per_group + rows_per_wg - 1) / rows_per_wg, a.g), 256, kLds, s>>>(a, rows_per_group, rows_per_wg);
+  combine_project_bf16_kernel<512, 128, DV><<<dim3((rows_per_group + rows_per_wg - 1) / rows_per_wg, a.g, DV / 128), 256, kLds, s>>>(
+      a, rows_per_group, rows_per_wg);
   return hipGetLastError();
+}
+
+hipError_t launch_combine_project_bf16(const CombineArgs& a, hipStream_t s) {
+  return a.d_h == 256 ? launch_combine_project_dv<256>(a, s) : launch_combine_project_dv<128>(a, s);  // a.d_h: value dims here
 }
 
 }  // namespace gqla

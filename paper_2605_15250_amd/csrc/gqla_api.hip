@@ -14,18 +14,31 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// per-head value dim (0 in the struct selects d_h)
+int32_t value_dim(const gqla_shape* s) { return s->d_v > 0 ? s->d_v : s->d_h; }
+
 gqla_status check_shape(const gqla_shape* s) {
   if (!s) return GQLA_ERR_NULL;
   if (s->dtype != GQLA_F32 && s->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
   if (s->batch < 0 || s->h_q <= 0 || s->g <= 0 || s->h_q % s->g != 0) return GQLA_ERR_SHAPE;
   if (s->s_q != 1 && s->s_q != 2) return GQLA_ERR_SHAPE;
-  if (s->d_h <= 0 || s->r_kv <= 0 || s->d_r <= 0) return GQLA_ERR_SHAPE;
+  if (s->d_h <= 0 || s->r_kv <= 0 || s->d_r <= 0 || s->d_v < 0) return GQLA_ERR_SHAPE;
+  const int32_t d_v = value_dim(s);
   if (!(s->scale >= 0.f) || std::isinf(s->scale)) return GQLA_ERR_SHAPE;
   if (s->dtype == GQLA_BF16) {
-    if (s->d_h != 128 || s->d_r != 64 || s->r_kv != 512) return GQLA_ERR_SHAPE;
+    if ((s->d_h != 128 && s->d_h != 192) || (d_v != 128 && d_v != 256) || s->d_r != 64 || s->r_kv != 512) return GQLA_ERR_SHAPE;
   } else {
-    if (s->d_h % 8 || s->d_r % 8 || s->r_kv % 8 || s->d_h > 512 || s->r_kv > 512) return GQLA_ERR_SHAPE;
+    if (s->d_h % 8 || d_v % 8 || s->d_r % 8 || s->r_kv % 8 || s->d_h > 512 || d_v > 512 || s->r_kv > 512) return GQLA_ERR_SHAPE;
   }
+  return GQLA_OK;
+}
+
+// The expanded cache and everything that reads or writes it (GQA path, cache switches, 8-bit cache) is built for equal
+// key and value dims (and, in bf16, for d_h = 128); a value dim of its own exists on the absorb path only.
+gqla_status check_shape_equal_dims(const gqla_shape* s) {
+  const gqla_status st = check_shape(s);
+  if (st != GQLA_OK) return st;
+  if (value_dim(s) != s->d_h || (s->dtype == GQLA_BF16 && s->d_h != 128)) return GQLA_ERR_SHAPE;
   return GQLA_OK;
 }
 
@@ -45,7 +58,7 @@ float resolved_scale(const gqla_shape* s) {
 
 bool same_shape(const gqla_shape& a, const gqla_shape& b) {
   return a.batch == b.batch && a.h_q == b.h_q && a.g == b.g && a.d_h == b.d_h && a.r_kv == b.r_kv &&
-         a.d_r == b.d_r && a.s_q == b.s_q && a.dtype == b.dtype;
+         a.d_r == b.d_r && a.s_q == b.s_q && a.dtype == b.dtype && value_dim(&a) == value_dim(&b);
 }
 
 gqla_status check_cache(const gqla_shape* s, const gqla_cache* c, int32_t page_size, int32_t max_len) {
@@ -111,7 +124,7 @@ WsLayout make_layout(const gqla_plan& p) {
 gqla_status check_decode_common(const gqla_shape* shape, const gqla_plan* plan, int32_t path, const gqla_cache* cache,
                                 const void* qa, const void* qr, const void* out, const float* lse, const void* ws,
                                 size_t ws_bytes) {
-  gqla_status st = check_shape(shape);
+  gqla_status st = path == GQLA_PATH_GQA ? check_shape_equal_dims(shape) : check_shape(shape);
   if (st != GQLA_OK) return st;
   if (!plan || !qa || !qr || !out || !ws) return GQLA_ERR_NULL;
   if (!same_shape(plan->shape, *shape) || plan->path != path) return GQLA_ERR_PLAN;
@@ -191,6 +204,7 @@ gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_ho
   if (st != GQLA_OK) return st;
   if (!seq_lens_host && shape->batch > 0) return GQLA_ERR_NULL;
   if (path != GQLA_PATH_ABSORB && path != GQLA_PATH_GQA) return GQLA_ERR_PLAN;
+  if (path == GQLA_PATH_GQA && check_shape_equal_dims(shape) != GQLA_OK) return GQLA_ERR_SHAPE;
   if (num_cus <= 0 || chunk_pages_override < 0) return GQLA_ERR_SHAPE;
   st = check_page_size(shape, page_size);
   if (st != GQLA_OK) return st;
@@ -310,7 +324,8 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
   if (shape->batch == 0) return GQLA_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const DecodeArgs a = decode_args(shape, plan, q_hat, q_r, latent, ws);
-  const CombineArgs c = combine_args(shape, plan, ws, w_uv, out, lse);
+  CombineArgs c = combine_args(shape, plan, ws, w_uv, out, lse);
+  c.d_h = value_dim(shape);  // the projection's output (and W_UV's columns) are value dims
   hipError_t e;
   if (shape->dtype == GQLA_BF16) {
     e = launch_decode_absorb_bf16(a, s);
@@ -323,7 +338,7 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
 }
 
 size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count) {
-  if (!shape || check_shape(shape) != GQLA_OK || shape->dtype != GQLA_BF16 || group_count <= 0) return 0;
+  if (!shape || check_shape_equal_dims(shape) != GQLA_OK || shape->dtype != GQLA_BF16 || group_count <= 0) return 0;
   return (size_t)2 * group_count * shape->r_kv * shape->d_h * 2;  // both weight slices in fragment order, bf16
 }
 
@@ -332,7 +347,7 @@ namespace {
 gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
                         int32_t group_begin, int32_t group_count, const gqla_cache* expanded, int32_t tail, void* ws,
                         size_t ws_bytes, void* stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f) {
-  gqla_status st = check_shape(shape);
+  gqla_status st = check_shape_equal_dims(shape);
   if (st != GQLA_OK) return st;
   if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
   if (!aligned16(w_uk) || !aligned16(w_uv) || !aligned16(latent->pool) || !aligned16(expanded->pool)) return GQLA_ERR_ALIGN;
@@ -468,7 +483,7 @@ gqla_status gqla_rope_step(const gqla_shape* shape, const int32_t* seq_lens, flo
 
 size_t gqla_output_projection_workspace_bytes(const gqla_shape* shape, int32_t d_model) {
   if (check_shape(shape) != GQLA_OK || d_model <= 0 || shape->dtype != GQLA_BF16) return 0;
-  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * shape->d_h;
+  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * value_dim(shape);
   if (M == 0 || d_model % 128 || K % 256) return 0;
   int krange = 0;
   const int ksplit = out_proj_split((int)M, (int)K, d_model, &krange);
@@ -482,7 +497,7 @@ gqla_status gqla_output_projection(const gqla_shape* shape, int32_t d_model, con
   if (!o || !w_o || !y) return GQLA_ERR_NULL;
   if (!aligned16(o) || !aligned16(w_o) || !aligned16(y) || (ws && !aligned16(ws))) return GQLA_ERR_ALIGN;
   if (d_model <= 0) return GQLA_ERR_SHAPE;
-  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * shape->d_h;
+  const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * value_dim(shape);
   if (M > INT32_MAX || K > INT32_MAX) return GQLA_ERR_SHAPE;
   if (M == 0) return GQLA_OK;
   OutProjArgs a;
@@ -561,7 +576,7 @@ gqla_status gqla_left_inverse(const gqla_shape* shape, const float* w_uk_host, f
 
 gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expanded, const void* w_inv,
                                 const gqla_cache* latent, void* stream) {
-  gqla_status st = check_shape(shape);
+  gqla_status st = check_shape_equal_dims(shape);
   if (st != GQLA_OK) return st;
   if (!expanded || !latent || !w_inv || !expanded->pool || !latent->pool || !expanded->seq_lens) return GQLA_ERR_NULL;
   if (!aligned16(w_inv) || !aligned16(expanded->pool) || !aligned16(latent->pool)) return GQLA_ERR_ALIGN;
@@ -591,7 +606,7 @@ gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expan
 
 gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* expanded, const gqla_cache* expanded_fp8,
                                    float k_scale, float v_scale, void* stream) {
-  gqla_status st = check_shape(shape);
+  gqla_status st = check_shape_equal_dims(shape);
   if (st != GQLA_OK) return st;
   if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
   if (!expanded || !expanded_fp8 || !expanded->pool || !expanded_fp8->pool || !expanded->seq_lens) return GQLA_ERR_NULL;
@@ -621,7 +636,7 @@ gqla_status gqla_quantize_expanded(const gqla_shape* shape, const gqla_cache* ex
 gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_c, const void* q_r,
                                 const gqla_cache* expanded_fp8, float k_scale, float v_scale, void* out, float* lse,
                                 void* ws, size_t ws_bytes, void* stream) {
-  gqla_status st = check_shape(shape);
+  gqla_status st = check_shape_equal_dims(shape);
   if (st != GQLA_OK) return st;
   if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) return GQLA_ERR_SHAPE;
@@ -664,9 +679,10 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
   out->absorb_bytes = L * elem * (shape->r_kv + shape->d_r);
   out->absorb_flops = 2.0 * L * rows * (2.0 * shape->r_kv + shape->d_r);
   out->absorb_intensity = rows * (2.0 * shape->r_kv + shape->d_r) / (elem / 2.0 * (shape->r_kv + shape->d_r));
-  out->gqa_bytes = L * elem * (2.0 * shape->g * shape->d_h + shape->d_r);
-  out->gqa_flops = 2.0 * L * rows * (2.0 * shape->d_h + shape->d_r);
-  out->gqa_intensity = rows * (2.0 * shape->d_h + shape->d_r) / (elem / 2.0 * (2.0 * shape->g * shape->d_h + shape->d_r));
+  const double d_v = value_dim(shape);
+  out->gqa_bytes = L * elem * (shape->g * (shape->d_h + d_v) + shape->d_r);
+  out->gqa_flops = 2.0 * L * rows * (shape->d_h + d_v + shape->d_r);
+  out->gqa_intensity = rows * (shape->d_h + d_v + shape->d_r) / (elem / 2.0 * (shape->g * (shape->d_h + d_v) + shape->d_r));
   const double ta_m = out->absorb_bytes / hbm_bytes_per_s, ta_c = out->absorb_flops / mfma_flops_per_s;
   const double tg_m = out->gqa_bytes / hbm_bytes_per_s, tg_c = out->gqa_flops / mfma_flops_per_s;
   out->absorb_seconds = ta_m > ta_c ? ta_m : ta_c;
@@ -678,7 +694,7 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
 
 gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gqla_path_choice* out) {
   if (!out) return GQLA_ERR_NULL;
-  gqla_status st = check_shape(shape);
+  gqla_status st = check_shape_equal_dims(shape);
   if (st != GQLA_OK) return st;
   if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
   if (cached_tokens < 0) return GQLA_ERR_SHAPE;

@@ -577,7 +577,8 @@ hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
 hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   const int rows_per_group = a.rows * a.G;
   dim3 grid((rows_per_group + 31) / 32, (512 / 128 + 3) / 4, a.g);
-  absorb_query_bf16_kernel<128, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
+  if (a.d_h == 192) absorb_query_bf16_kernel<192, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
+  else absorb_query_bf16_kernel<128, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
   return hipGetLastError();
 }
 

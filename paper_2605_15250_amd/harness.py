@@ -51,7 +51,8 @@ class Decoder:
         self.max_pages = self.table.shape[1]
         self.groups = cfg.g if groups is None else groups       # groups held by the expanded cache (TP slice if < g)
         self.group_begin = group_begin
-        self.shape = B.make_shape(cfg.B, cfg.h_q, cfg.g, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q, lib_dtype(cfg.dtype))
+        self.shape = B.make_shape(cfg.B, cfg.h_q, cfg.g, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q, lib_dtype(cfg.dtype), 0.0, cfg.d_v)
+        self.absorb_only = cfg.dv != cfg.d_h                    # a value dim of its own exists on the absorb path only
         G = cfg.h_q // cfg.g
         # shape seen by the GQA decode: for a slice, only the heads and groups of the slice
         self.shape_gqa = B.make_shape(cfg.B, G * self.groups, self.groups, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q,
@@ -59,11 +60,13 @@ class Decoder:
         self.d_lens = torch.from_numpy(self.lens).cuda()
         self.d_table = torch.from_numpy(self.table).cuda() if use_page_table else None
         self.plan_a = B.gqla_plan_create(self.shape, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_ABSORB, chunk_pages_absorb)
-        self.plan_g = B.gqla_plan_create(self.shape_gqa, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_GQA, chunk_pages_gqa)
         self.ws_a = torch.empty(B.gqla_plan_workspace_bytes(self.plan_a), dtype=torch.uint8, device="cuda")
-        self.ws_g = torch.empty(B.gqla_plan_workspace_bytes(self.plan_g), dtype=torch.uint8, device="cuda")
         B.gqla_plan_upload(self.plan_a, self.ws_a)
-        B.gqla_plan_upload(self.plan_g, self.ws_g)
+        self.plan_g = self.ws_g = None
+        if not self.absorb_only:
+            self.plan_g = B.gqla_plan_create(self.shape_gqa, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_GQA, chunk_pages_gqa)
+            self.ws_g = torch.empty(B.gqla_plan_workspace_bytes(self.plan_g), dtype=torch.uint8, device="cuda")
+            B.gqla_plan_upload(self.plan_g, self.ws_g)
         self.latent_pool = None
         self.expanded_pool = None
         self.expanded_fp8_pool = None
@@ -104,7 +107,7 @@ class Decoder:
     def decode_absorb(self, q_hat, q_r, w_uv, out=None, lse=None):
         c = self.cfg
         if out is None:
-            out = torch.empty((c.B, c.s_q, c.h_q, c.d_h), dtype=torch_dtype(c.dtype), device="cuda")
+            out = torch.empty((c.B, c.s_q, c.h_q, c.dv), dtype=torch_dtype(c.dtype), device="cuda")
         if lse is None:
             lse = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
         B.gqla_decode_absorb(self.shape, self.plan_a, q_hat, q_r, self.latent_cache(), w_uv, out, lse, self.ws_a)

@@ -35,6 +35,11 @@ class GqlaConfig:
     L_max: int = 0
     page_size: int = 64
     paged: bool = False   # True => randomly permuted page table
+    d_v: int = 0          # per-head value dim; 0 => d_h
+
+    @property
+    def dv(self) -> int:
+        return self.d_v if self.d_v > 0 else self.d_h
 
     @property
     def G(self) -> int:
@@ -87,14 +92,14 @@ def weights(cfg: GqlaConfig):
     r = rng(cfg.seed, 0)
     std = np.float32(cfg.r_kv ** -0.5)
     w_uk = r.standard_normal((cfg.g, cfg.r_kv, cfg.d_h), dtype=np.float32) * std
-    w_uv = r.standard_normal((cfg.g, cfg.r_kv, cfg.d_h), dtype=np.float32) * std
+    w_uv = r.standard_normal((cfg.g, cfg.r_kv, cfg.dv), dtype=np.float32) * std
     return quantize(w_uk, cfg.dtype), quantize(w_uv, cfg.dtype)
 
 
 def output_weights(cfg: GqlaConfig, d_model: int) -> np.ndarray:
     """W^O [d_model, h_q * d_h], storage-rounded."""
     r = rng(cfg.seed, 3)
-    K = cfg.h_q * cfg.d_h
+    K = cfg.h_q * cfg.dv
     return quantize(r.standard_normal((int(d_model), K), dtype=np.float32) * np.float32(K ** -0.5), cfg.dtype)
 
 

@@ -291,3 +291,24 @@ def test_c3_compress_rope_and_output_projection_at_full_size():
         check("W^O 2000 sampled elements", yh[pick[:, 0], pick[:, 1]], ref)
     finally:
         case.close()
+
+
+def test_mla_checkpoint_shape_absorb_path_at_full_size():
+    """The absorb path with a value dim of its own at the size bench.py times it (Sec. 3.2.2 shape: h_q = 20, g = 4,
+    d_h = 192, d_h^V = 256; B = 64, L = 8192): every output finite, three sequences element by element against the
+    oracle (all 20 heads)."""
+    cfg = S.CONFIGS["C2"].with_(h_q=20, g=4, d_h=192, d_v=256, B=64, L=8192, s_q=1, seed=15259)
+    case = FullCase(cfg)
+    try:
+        q_hat = case.dec.absorb_query(case.d(case.q_c), case.d_w_uk)
+        out, lse = case.dec.decode_absorb(q_hat, case.d(case.q_r), case.d_w_uv)
+        torch.cuda.synchronize()
+        o, l = out.float().cpu().numpy(), lse.cpu().numpy()
+        assert o.shape == (cfg.B, 1, 20, 256) and np.isfinite(o).all() and np.isfinite(l).all()
+        for b in (0, 29, 63):
+            c, kR = case.rows(b)
+            ref_o, ref_l = O.decode_absorb(O.absorb_query(case.q_c[b], case.w_uk), case.q_r[b], c, kR, case.w_uv, d_h=cfg.d_h)
+            check("absorb, d_h 192 / d_v 256  b=%d" % b, o[b], ref_o)
+            assert float(np.max(np.abs(l[b] - ref_l))) <= 2e-2
+    finally:
+        case.close()

@@ -84,12 +84,12 @@ def run_absorb_path(case, seqs=None):
     ref_o = np.zeros_like(out_h, dtype=np.float64)
     ref_l = np.zeros_like(lse_h, dtype=np.float64)
     for b in seqs:
-        ref_o[b], ref_l[b] = O.decode_absorb(q_hat_h[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv)
+        ref_o[b], ref_l[b] = O.decode_absorb(q_hat_h[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv, d_h=cfg.d_h)
     sel = list(seqs)
     check("decode_absorb (isolated)", out_h[sel], ref_o[sel], cfg.dtype)
     check("decode_absorb lse", lse_h[sel], ref_l[sel], cfg.dtype)
     # chained against the unrounded oracle
-    ref_c = np.stack([O.decode_absorb(ref_qh[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv)[0] for b in seqs])
+    ref_c = np.stack([O.decode_absorb(ref_qh[b], case.q_r[b], case.c(b), case.kR(b), case.w_uv, d_h=cfg.d_h)[0] for b in seqs])
     check("absorb path (chained)", out_h[sel], ref_c, cfg.dtype)
     return out_h
 
@@ -328,3 +328,33 @@ def test_page_permutation_is_bit_identical():
             case.close()
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("key,h_q,g,d_h,d_v,s_q,lens", [
+    ("C2", 20, 4, 192, 256, 1, [300, 4000, 64]),     # the MLA checkpoint shape of Sec. 3.2.2 (h_q = 20, d_h = 192, d_h^V = 256), g = 4
+    ("C2", 20, 5, 192, 256, 2, [129, 1000]),         # the same with g = 5 and two step tokens
+    ("C2", 128, 8, 128, 256, 2, [700, 65]),          # only the value dim differs; 256 query rows
+    ("C2", 32, 8, 192, 128, 1, [513]),               # only the key dim differs
+    ("C0", 8, 2, 16, 24, 2, [40, 7, 2]),             # fp32 kernels
+])
+def test_absorb_path_with_a_value_dim_of_its_own(key, h_q, g, d_h, d_v, s_q, lens):
+    """d_h^V != d_h (Sec. 3.2.2) on the absorb path: query absorption over d_h key dims, the latent decode with the scale
+    1/sqrt(d_h + d_R), W_UV with d_v columns, and W^O over h_q d_v columns, against the oracle."""
+    cfg = S.CONFIGS[key].with_(B=len(lens), h_q=h_q, g=g, d_h=d_h, d_v=d_v, s_q=s_q, L=0, paged=True,
+                               page_size=64 if key != "C0" else 8, seed=6006 + d_h + d_v)
+    case = Case(cfg, lens=lens)
+    try:
+        out = run_absorb_path(case)
+        assert out.shape == (cfg.B, s_q, h_q, d_v)
+        d_model = 256 if cfg.dtype == "bf16" else 24
+        w_o = S.output_weights(cfg, d_model)
+        assert w_o.shape == (d_model, h_q * d_v)
+        if cfg.dtype == "bf16" and (h_q * d_v) % 256:
+            return
+        o_dev = case.to_device(out, cfg.dtype)                       # the GPU's own (storage-rounded) outputs
+        y = case.dec.output_projection(o_dev, case.to_device(w_o, cfg.dtype))
+        torch.cuda.synchronize()
+        ref = np.stack([O.output_projection(S.quantize(out[b], cfg.dtype), w_o) for b in range(cfg.B)])
+        check("W^O over h_q * d_v columns", host(y), ref, cfg.dtype, scale_abs=2.0)
+    finally:
+        case.close()

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(B.gqla_shape) == 36
+    assert C.sizeof(B.gqla_shape) == 40      # nine 4-byte fields and d_v
     assert C.sizeof(B.gqla_cache) == 40
 
 
@@ -309,3 +309,34 @@ def test_step_ops_validate_on_the_host():
     # empty batch: nothing to do
     B.gqla_rope_step(B.make_shape(0, 32, 8, 128, 512, 64, 2, B.GQLA_BF16), A, 10000.0, A, A, stream=0)
     B.gqla_output_projection(B.make_shape(0, 32, 8, 128, 512, 64, 2, B.GQLA_BF16), 4096, A, A, A, None, 0, stream=0)
+
+
+def test_value_dim_is_accepted_on_the_absorb_path_only():
+    """gqla_shape.d_v: 0 means d_h; bf16 takes d_h in {128, 192} and d_v in {128, 256}; every entry point that touches
+    an expanded cache refuses a value dim that differs from the key dim (and bf16 key dims other than 128)."""
+    A = 0x10000
+    glm = B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 256)
+    lens = [300, 4000]
+    p = B.gqla_plan_create(glm, lens, 64, 256, B.GQLA_PATH_ABSORB)
+    try:
+        assert B.gqla_plan_num_chunks(p) > 0
+        # a plan made for another value dim does not fit
+        other = B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 128)
+        lat = B.make_cache(A, A, None, 64, 63, 126, 0)
+        _expect(B.GQLA_ERR_PLAN, B.gqla_decode_absorb, other, p, A, A, lat, A, A, None, A, 1 << 30, stream=0)
+    finally:
+        B.gqla_plan_destroy(p)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, glm, lens, 64, 256, B.GQLA_PATH_GQA)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 160, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, B.GQLA_PATH_ABSORB)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 128, 512, 64, 1, B.GQLA_BF16, 0.0, 192), lens, 64, 256, B.GQLA_PATH_ABSORB)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, B.GQLA_PATH_ABSORB)  # d_v = d_h = 192
+    lat = B.make_cache(A, A, None, 64, 4, 8, 0)
+    full = B.make_cache(A, A, None, 64, 4, 8, 4)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache, glm, lat, A, A, 0, 4, full, A, 1 << 24, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_fp8, glm, lat, A, A, 0, 4, full, 1.0, 1.0, A, 1 << 24, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_compress_cache, glm, full, A, lat, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_expanded, glm, full, full, 1.0, 1.0, stream=0)
+    assert B.gqla_expand_workspace_bytes(glm, 4) == 0
+    # W^O takes h_q * d_v columns: 20 * 256 = 5120 = 20 phases of 256
+    # 32 column tiles -> 16 ranges wanted -> 2 phases each -> 10 ranges
+    assert B.gqla_output_projection_workspace_bytes(glm, 4096) == 10 * 2 * 4096 * 4

@@ -477,3 +477,26 @@ def test_output_projection_is_the_sum_of_per_head_blocks():
     y_g = O.output_projection(O.decode_gqa(qC, qR, KC, V, kR)[0], W_O)
     y_a = O.output_projection(O.decode_absorb(O.absorb_query(qC, W_UK), qR, c, kR, W_UV)[0], W_O)
     assert np.max(np.abs(y_g - y_a)) < 1e-10
+
+
+def test_value_dim_may_differ_from_the_key_dim():
+    """Sec. 3.2.2 (MLA checkpoints with d_h^V != d_h, e.g. 192 / 256): both paths against the scalar-loop brute force
+    with d_v != d_h; the softmax scale keeps the key dim; the extra value dims are plain extra columns of W^UV."""
+    rng = np.random.default_rng(11)
+    s_q, h_q, g, d_h, d_v, d_r, r_kv, L = 2, 6, 3, 4, 6, 2, 5, 7
+    qC, qR = rng.normal(size=(s_q, h_q, d_h)), rng.normal(size=(s_q, h_q, d_r))
+    c, kR = rng.normal(size=(L, r_kv)), rng.normal(size=(L, d_r))
+    W_UK, W_UV = rng.normal(size=(g, r_kv, d_h)), rng.normal(size=(g, r_kv, d_v))
+    ref = O.decode_mha_bruteforce(qC, qR, c, kR, W_UK, W_UV)
+    assert ref.shape == (s_q, h_q, d_v)
+    KC, V = O.expand_latent(c, W_UK, W_UV)
+    assert KC.shape == (L, g, d_h) and V.shape == (L, g, d_v)
+    o_g, lse_g = O.decode_gqa(qC, qR, KC, V, kR)
+    o_a, lse_a = O.decode_absorb(O.absorb_query(qC, W_UK), qR, c, kR, W_UV, d_h=d_h)
+    assert np.max(np.abs(o_g - ref)) < 1e-10 and np.max(np.abs(o_a - ref)) < 1e-10 and np.max(np.abs(lse_g - lse_a)) < 1e-10
+    # the scale is 1/sqrt(d_h + d_R) with the KEY dim: taking the value dim instead changes the result
+    o_wrong, _ = O.decode_absorb(O.absorb_query(qC, W_UK), qR, c, kR, W_UV)         # default: W^UV's columns
+    assert np.max(np.abs(o_wrong - ref)) > 1e-4
+    # the first d_h value columns do not care about the others
+    o_cut, _ = O.decode_gqa(qC, qR, KC, V[:, :, :d_h], kR)
+    assert np.max(np.abs(o_cut - ref[:, :, :d_h])) < 1e-12
