@@ -6,7 +6,10 @@ B=64 sequences of L=8192 cached tokens, on seeded synthetic data already residen
     absorb leg (s_q=1):  gqla_absorb_query -> gqla_decode_absorb   (split-L flash-decode over the latent cache, combine, W_UV)
     GQA leg   (s_q=2):   gqla_expand_cache -> gqla_decode_gqa      (latent -> per-group cache, grouped decode, combine)
 Prints ONE JSON line.  `value` = decoded step tokens per second of the whole step (B*1 + B*2 tokens per step);
-the per-call figures, their roofline fractions and the oracle's CPU rate on a bounded sample ride along."""
+the per-call figures, their roofline fractions and the oracle's CPU rate on a bounded sample ride along, and so do
+timings of the calls around the path (outside the timed step): measured ceilings of the chip, the single-group slice,
+the per-step cache updates, the 8-bit expanded cache, the reverse cache switch, the rotary step and W^O, each path's
+whole decode step as one HIP graph, and the absorb step with a value dim of its own."""
 from __future__ import annotations
 
 import argparse
