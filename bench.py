@@ -39,7 +39,7 @@ def parse_args():
     ap.add_argument("--ctx", type=int, default=0, help="override L (debugging only)")
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
     ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences per leg in the oracle's bounded sample (0 = skip)")
-    ap.add_argument("--no-extras", action="store_true", help="skip the ceiling probes and the single-group slice timing")
+    ap.add_argument("--no-extras", action="store_true", help="skip everything outside the timed step (ceiling probes, slice, cache updates, 8-bit cache, compression, step ops)")
     ap.add_argument("--operating-points", action="store_true",
                     help="also time both decode paths at the operating points of the paper's Sec. 4.2.3 table (g, s_q) for B = 1 and 64")
     ap.add_argument("--crossover", action="store_true",
