@@ -30,7 +30,8 @@
  *     and the log-sum-exps are fp32 (split partials: fp32 on the GQA path, bf16 in latent space on the absorb
  *     path); QK^T and PV run on bf16 MFMA.  Shape limits of the MFMA
  *     kernels: d_h = 128, d_r = 64, r_kv = 512, page_size a multiple of 64 (<= 1024).
- *     dtype GQLA_F32: everything fp32 on the vector ALU; d_h, d_r, r_kv, page_size multiples of 8.
+ *     dtype GQLA_F32: everything fp32 on the vector ALU; d_h, d_v, d_r, r_kv, page_size multiples of 8, and
+ *     d_h, d_v, r_kv at most 512 (GQLA_ERR_SHAPE beyond).
  *
  * Tensor layouts (row-major, last index fastest)
  *   q_c   [B][s_q][h_q][d_h]      q_r  [B][s_q][h_q][d_r]     q_hat [B][s_q][h_q][r_kv]
@@ -284,7 +285,8 @@ int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d,
 int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 
-/* Path selection (Sec. 4: "the runtime selects the path that matches the target hardware").  The paper's Roofline
+/* Path selection: one set of weights serves both paths and the serving runtime picks, per device, the one its
+ * hardware runs faster (Abstract); the two-roof time model that decides it is Sec. 4.2.3.  The paper's Roofline
  * model of one decode step over `cached_tokens` tokens (summed over the batch): the absorb path moves
  * 2(r_kv + d_r) bytes and performs 2 h_q s_q (2 r_kv + d_r) FLOPs per cached token (Sec. 4.2.1), the GQA path
  * 2(2 g d_h + d_r) bytes and 2 h_q s_q (2 d_h + d_r) FLOPs (Sec. 4.2.2); the predicted time of a path is

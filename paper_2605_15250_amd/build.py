@@ -52,12 +52,25 @@ def _compile(src: str, extra) -> str:
 NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"], "gqla_gemm_bf16.hip": ["expand_bf16_kernel"]}
 
 
-def _check_named_agprs(src: str, kernels, extra) -> None:
+# Kernels whose loops wait on hand-counted numbers of outstanding vector-memory instructions (s_waitcnt vmcnt(N) written
+# for the loads the source issues): a register spill would add scratch loads and stores of the compiler's own to that
+# count and silently break the waits.  The build reads the compiler's resource report and refuses any vector-register
+# spill or scratch use in them.
+COUNTED_WAIT_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"],
+                        "gqla_gemm_bf16.hip": ["expand_bf16_kernel"],
+                        "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"]}
+
+
+def _check_device_code(src: str, extra) -> None:
+    """One device-only compile to assembly with the resource report: no compiler-made accumulation-register traffic in
+    the kernels of NAMED_AGPR_SOURCES, no spills and no scratch in those of COUNTED_WAIT_KERNELS."""
     asm_path = os.path.join(BUILD, os.path.splitext(src)[0] + ".s")
-    cmd = [_hipcc(), *FLAGS, *extra, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm_path]
+    cmd = [_hipcc(), *FLAGS, *extra, "--cuda-device-only", "-S", "-Rpass-analysis=kernel-resource-usage",
+           os.path.join(CSRC, src), "-o", asm_path]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stderr))
+    kernels = NAMED_AGPR_SOURCES.get(src, [])
     current, in_asm = None, False
     with open(asm_path) as fh:
         for line in fh:
@@ -71,12 +84,37 @@ def _check_named_agprs(src: str, kernels, extra) -> None:
             elif current and not in_asm and t.startswith("v_accvgpr_"):
                 raise RuntimeError("%s: the compiler uses accumulation registers of its own in %s (%s); "
                                    "lower the kernel's VGPR pressure" % (src, current, t))
+    # resource report: "remark: Function Name: <mangled>" followed by one remark per figure
+    watched = COUNTED_WAIT_KERNELS.get(src, [])
+    current, seen = None, set()
+    for line in r.stderr.splitlines():
+        if "remark:" not in line:
+            continue
+        body = line.split("remark:", 1)[1].strip()
+        if body.startswith("Function Name:"):
+            current = next((k for k in watched if k in body), None)
+            if current:
+                seen.add(current)
+            continue
+        if not current:
+            continue
+        # (scalar registers spilled into lanes of a vector register cost no memory instruction and are allowed)
+        for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):
+            if body.startswith(key):
+                val = body[len(key):].split("[")[0].strip()
+                if val != "0":
+                    raise RuntimeError("%s: %s has %s %s; its hand-counted memory waits need a spill-free kernel"
+                                       % (src, current, key, val))
+    missing = [k for k in watched if k not in seen]
+    if missing:
+        raise RuntimeError("%s: no resource report for %s (kernel renamed?)" % (src, ", ".join(missing)))
 
 
 def build(extra_flags=(), jobs: int = 5) -> str:
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        checks = [ex.submit(_check_named_agprs, src, ks, list(extra_flags)) for src, ks in NAMED_AGPR_SOURCES.items()]
+        checks = [ex.submit(_check_device_code, src, list(extra_flags))
+                  for src in sorted(set(NAMED_AGPR_SOURCES) | set(COUNTED_WAIT_KERNELS))]
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
         for c in checks:
             c.result()

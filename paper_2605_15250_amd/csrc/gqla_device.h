@@ -75,7 +75,6 @@ __device__ __forceinline__ float pair_sum(float v) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-// Page id of logical page p of sequence b, or -1 when the table entry is outside the pool.
 // Four fp32 values -> four E4M3 codes of x * inv_scale (OCP 8-bit float, "FN" variant), round to nearest even; magnitudes
 // above 448 saturate (the conversion instruction alone would turn them into NaN).  Byte k of the result is value k.
 __device__ __forceinline__ uint32_t quantize_e4m3x4(float a, float b, float c, float d, float inv_scale) {
@@ -93,7 +92,11 @@ __device__ __forceinline__ void round_to_bf16x2(float& x, float& y) {
   y = __builtin_bit_cast(float, w & 0xffff0000u);
 }
 
+// Page id of logical page p of sequence b, or -1 when the table entry is outside the pool.
+// A logical page outside the sequence's table row (a device-side length beyond max_pages * page_size) is -1 as well:
+// the row of the table is never read past its end, and without a table no page of the next sequence is formed.
 __device__ __forceinline__ int32_t page_of(const CacheView& c, int32_t b, int32_t p) {
+  if ((uint32_t)p >= (uint32_t)c.max_pages) return -1;
   int32_t pg = c.page_table ? c.page_table[(int64_t)b * c.max_pages + p] : b * c.max_pages + p;
   return ((uint32_t)pg < (uint32_t)c.num_pages) ? pg : -1;
 }

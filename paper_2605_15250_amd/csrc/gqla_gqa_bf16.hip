@@ -181,8 +181,12 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       for (int i = 0; i < 16; ++i) s[i] *= k_scale;
     }
     if (share_kr) {
-      // this tile's k_R was requested before the 16 cache loads that followed it (loads complete in issue order)
-      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      // this tile's k_R was requested before the cache loads that followed it (loads complete in issue order): the
+      // tile's key and value vectors, 16-byte loads each -- KS_C + 2*MT of them in 16 bits, half as many as codes
+      constexpr int kLoadsBehindKr = FP8 ? KS_C / 2 + MT : KS_C + 2 * MT;
+      static_assert(kLoadsBehindKr == (FP8 ? 8 : 16), "the wait below is written for these counts");
+      if constexpr (FP8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       __syncthreads();
       const char* kr = kr_lds[((tok - ce.tok_begin) >> 5) & 1] + lane * 16;
 #pragma unroll

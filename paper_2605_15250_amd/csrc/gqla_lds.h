@@ -22,32 +22,8 @@ typedef __attribute__((ext_vector_type(8))) short i16x8;
 
 __device__ __forceinline__ int lds_swz(int row) { return (row >> 1) & 7; }
 
-// Asynchronously stage rows [0, rows_valid) of a row-major global matrix with ROWS rows of NP*128 bytes (row stride
-// GSTRIDE bytes) and zero rows [rows_valid, ROWS).  Every wave of the workgroup (NWAVES of them, NWAVES even and
-// dividing ROWS/8) must call it.  Completion: s_waitcnt vmcnt(0) lgkmcnt(0) by each wave, then a workgroup barrier.
-template <int ROWS, int NP, int NWAVES, int GSTRIDE>
-__device__ __forceinline__ void stage_panels(char* lds, const char* g, int rows_valid, int wave, int lane) {
-  static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
-  constexpr int K = ROWS / 8 / NWAVES;  // instructions per wave and panel
-  const int row0 = 8 * wave + (lane >> 3);
-  const int c = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);  // chunk whose swizzled position is lane & 7
-  const uint32_t lane_off = row0 * GSTRIDE + c * 16;
-#pragma unroll
-  for (int a = 0; a < NP; ++a) {
-#pragma unroll
-    for (int v = 0; v < K; ++v) {
-      const int row = row0 + 8 * NWAVES * v;
-      char* dst = lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024;
-      if (row < rows_valid) {
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(g + (lane_off + (uint32_t)(8 * NWAVES * v * GSTRIDE + a * 128))),
-                                         (lds_ptr_t)dst, 16, 0, 0);
-      } else {
-        *(u32x4*)(dst + lane * 16) = u32x4{0u, 0u, 0u, 0u};
-      }
-    }
-  }
-}
-
+// Staging of a whole matrix with ROWS rows of NP*128 bytes (row stride GSTRIDE bytes) by the NWAVES waves of a
+// workgroup (NWAVES even and dividing ROWS/8).  Completion: s_waitcnt vmcnt(..) by each wave, then a workgroup barrier.
 template <int ROWS, int NP, int NWAVES, int GSTRIDE>
 __device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane) {
   const int row0 = 8 * wave + (lane >> 3);
@@ -69,7 +45,10 @@ __device__ __forceinline__ void stage_panels_step(char* lds, const char* g, int 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(dst), "v"(lane_off), "s"(base)
-               : "memory");  // M0 is written here; nothing else in these kernels uses it
+               : "memory");  // M0 is written here.  It cannot be named as a clobber (the compiler treats it as reserved and
+                             // warns that such a clobber is not honoured); the kernels that use these blocks contain
+                             // nothing for which the compiler itself needs M0 (no LDS-DMA builtin, no indirect register
+                             // indexing, no messages), and every block sets M0 before it uses it.
 }
 
 // Whole matrix (all ROWS rows present), this wave's share in one burst of asm steps.

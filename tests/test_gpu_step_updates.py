@@ -164,3 +164,46 @@ def test_compress_is_the_reverse_cache_switch(key, lens, page_size):
         assert np.isfinite(o).all() and rl < (3e-2 if cfg.dtype == "bf16" else 1e-4)
     finally:
         case.close()
+
+
+@pytest.mark.parametrize("key,use_table", [("C3", True), ("C3", False), ("C0", True)])
+def test_device_length_beyond_the_table_row_writes_nothing(key, use_table):
+    """The cache-update calls read L_b on the device, where the host cannot check it.  A length whose step positions
+    fall beyond max_pages * page_size must write nothing: not through the entries that follow the sequence's table row
+    (the next sequence's row, or whatever lies behind the last one), and, without a table, not into the next
+    sequence's pages."""
+    from paper_2605_15250_amd.harness import Decoder
+    page_size = 64 if key == "C3" else 8
+    cfg = S.CONFIGS[key].with_(B=3, s_q=2, L=0, paged=True, page_size=page_size, seed=5150)
+    lens = np.array([3 * page_size, 2 * page_size, 3 * page_size], dtype=np.int32)
+    table, num_pages = S.page_table(cfg, lens)
+    dec = Decoder(cfg, lens, table, num_pages, use_page_table=use_table)
+    if not use_table:
+        dec.num_pages = cfg.B * dec.max_pages
+    try:
+        W = cfg.r_kv + cfg.d_r
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        dec.latent_pool = torch.full((dec.num_pages, cfg.page_size, W), float("nan"), dtype=tdt, device="cuda")
+        dec.alloc_expanded()
+        # sequence 0 claims a length one page beyond its table row, the last sequence one far beyond the whole table
+        bad = lens.copy()
+        bad[0] = dec.max_pages * page_size + 2
+        bad[2] = (dec.max_pages + 40) * page_size + 1
+        dec.d_lens = torch.from_numpy(bad).cuda()
+        rows = torch.ones((cfg.B, cfg.s_q, W), dtype=tdt, device="cuda")
+        w_uk, w_uv = S.weights(cfg)
+        from paper_2605_15250_amd.harness import to_device
+        dec.append_latent(rows)
+        dec.expand_tail(to_device(w_uk, cfg.dtype), to_device(w_uv, cfg.dtype), cfg.s_q)
+        torch.cuda.synchronize()
+        lat = dec.latent_pool.float().cpu().numpy()
+        # only sequence 1 (the honest one) received its two rows
+        written = np.argwhere(~np.isnan(lat).all(axis=2))
+        pg1 = int(table[1][(lens[1] - 1) // page_size]) if use_table else 1 * dec.max_pages + (int(lens[1]) - 1) // page_size
+        expect = {(pg1, (int(lens[1]) - 2) % page_size), (pg1, (int(lens[1]) - 1) % page_size)}
+        assert {tuple(int(v) for v in x) for x in written} == expect, written
+        per_tok = 2 * cfg.g * cfg.d_h + cfg.d_r
+        exp = dec.expanded_pool.float().cpu().numpy()
+        assert int((~np.isnan(exp)).sum()) == 2 * per_tok
+    finally:
+        dec.close()
