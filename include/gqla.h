@@ -331,6 +331,15 @@ gqla_status gqla_probe_stream_read(const void* src, size_t bytes, void* sink, in
 gqla_status gqla_probe_mfma_bf16(void* sink, int32_t iters, int32_t num_cus, void* stream);
 double gqla_probe_mfma_flops(int32_t iters, int32_t num_cus);
 
+/* Kernel timing (measurement only).  A decode call launches two kernels, the split-L decode kernel and the small
+ * combine; events placed around the call time both.  After gqla_time_next_decode_kernel(event_begin, event_end) -- two
+ * hipEvent_t created by the caller with timing enabled, passed as void* -- the NEXT gqla_decode_absorb, gqla_decode_gqa
+ * or gqla_decode_gqa_fp8 call made by the same host thread records event_begin immediately before and event_end
+ * immediately after its split-L decode kernel, on the call's stream; the pair is then forgotten (one call only; a call
+ * that fails its argument checks still consumes it once it got past them).  Two NULLs forget a pending pair;
+ * one NULL is GQLA_ERR_NULL.  The library keeps no reference to the events after that decode call returns. */
+gqla_status gqla_time_next_decode_kernel(void* event_begin, void* event_end);
+
 const char* gqla_status_string(int32_t status);
 
 #ifdef __cplusplus

@@ -28,6 +28,7 @@ EXPORTS = [
     "gqla_output_projection_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
+    "gqla_time_next_decode_kernel",
 ]
 
 
@@ -138,6 +139,8 @@ def lib():
             getattr(L, name).restype = i64
         L.gqla_expanded_kr_offset.argtypes = [i64, i32, i32, i32, i32, i32, i32]
         L.gqla_expanded_kr_offset.restype = i64
+        L.gqla_time_next_decode_kernel.argtypes = [vp, vp]
+        L.gqla_time_next_decode_kernel.restype = i32
         L.gqla_status_string.argtypes = [i32]
         L.gqla_status_string.restype = C.c_char_p
         _lib = L
@@ -250,6 +253,14 @@ def gqla_probe_stream_read(src, nbytes, sink, num_cus, stream=None):
 
 def gqla_probe_mfma_bf16(sink, iters, num_cus, stream=None):
     _check(lib().gqla_probe_mfma_bf16(_ptr(sink), iters, num_cus, _stream(stream)), "gqla_probe_mfma_bf16")
+
+
+def gqla_time_next_decode_kernel(event_begin, event_end):
+    """event_begin / event_end: raw hipEvent_t handles (ints), torch.cuda.Event objects that have been recorded at
+    least once (torch creates the underlying event on first use), or None for both."""
+    def raw(e):
+        return e if e is None or isinstance(e, int) else e.cuda_event
+    _check(lib().gqla_time_next_decode_kernel(raw(event_begin), raw(event_end)), "gqla_time_next_decode_kernel")
 
 
 def gqla_probe_mfma_flops(iters, num_cus) -> float:

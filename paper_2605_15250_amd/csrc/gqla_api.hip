@@ -138,6 +138,18 @@ gqla_status check_decode_common(const gqla_shape* shape, const gqla_plan* plan, 
   return GQLA_OK;
 }
 
+// Measurement aid (gqla_time_next_decode_kernel): events that the next decode call of this thread records around its
+// split-L decode kernel.
+thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
+
+struct KernelTimer {  // takes the pending pair; record_begin / record_end are no-ops without one
+  hipEvent_t e0, e1;
+  hipStream_t s;
+  explicit KernelTimer(hipStream_t stream) : e0(t_ev_begin), e1(t_ev_end), s(stream) { t_ev_begin = t_ev_end = nullptr; }
+  hipError_t begin() const { return e0 ? hipEventRecord(e0, s) : hipSuccess; }
+  hipError_t end() const { return e1 ? hipEventRecord(e1, s) : hipSuccess; }
+};
+
 CacheView view_of(const gqla_cache* c) {
   CacheView v;
   v.pool = c->pool;
@@ -326,12 +338,16 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
   const DecodeArgs a = decode_args(shape, plan, q_hat, q_r, latent, ws);
   CombineArgs c = combine_args(shape, plan, ws, w_uv, out, lse);
   c.d_h = value_dim(shape);  // the projection's output (and W_UV's columns) are value dims
-  hipError_t e;
+  const KernelTimer timer(s);
+  hipError_t e = timer.begin();
+  if (e != hipSuccess) return GQLA_ERR_DEVICE;
   if (shape->dtype == GQLA_BF16) {
     e = launch_decode_absorb_bf16(a, s);
+    if (e == hipSuccess) e = timer.end();
     if (e == hipSuccess) e = launch_combine_project_bf16(c, s);
   } else {
     e = launch_decode_absorb_f32(a, s);
+    if (e == hipSuccess) e = timer.end();
     if (e == hipSuccess) e = launch_combine_project_f32(c, s);
   }
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
@@ -453,7 +469,10 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded, ws);
   const CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
-  hipError_t e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
+  const KernelTimer timer(s);
+  hipError_t e = timer.begin();
+  if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
+  if (e == hipSuccess) e = timer.end();
   if (e == hipSuccess) e = launch_combine_f32(c, shape->dtype == GQLA_BF16, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
@@ -647,7 +666,10 @@ gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded_fp8, ws);
   const CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
-  hipError_t e = launch_decode_gqa_fp8(a, k_scale, v_scale, s);
+  const KernelTimer timer(s);
+  hipError_t e = timer.begin();
+  if (e == hipSuccess) e = launch_decode_gqa_fp8(a, k_scale, v_scale, s);
+  if (e == hipSuccess) e = timer.end();
   if (e == hipSuccess) e = launch_combine_f32(c, true, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
@@ -736,6 +758,13 @@ gqla_status gqla_probe_mfma_bf16(void* sink, int32_t iters, int32_t num_cus, voi
   if (num_cus <= 0 || iters <= 0) return GQLA_ERR_SHAPE;
   const hipError_t e = launch_probe_mfma(static_cast<uint32_t*>(sink), iters, num_cus, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_time_next_decode_kernel(void* event_begin, void* event_end) {
+  if (!event_begin != !event_end) return GQLA_ERR_NULL;  // both or neither (neither: forget a pending pair)
+  t_ev_begin = static_cast<hipEvent_t>(event_begin);
+  t_ev_end = static_cast<hipEvent_t>(event_end);
+  return GQLA_OK;
 }
 
 double gqla_probe_mfma_flops(int32_t iters, int32_t num_cus) {

@@ -53,15 +53,30 @@ class FullCase:
         r = S.sequence_rows(self.cfg, b, self.lens[b])
         return r[:, :self.cfg.r_kv], r[:, self.cfg.r_kv:]
 
-    def sample_sequences(self):
+    def named_sequences(self):
+        """the shortest, the longest, and one whose length is not a multiple of the page size"""
         picks = {int(np.argmin(self.lens)), int(np.argmax(self.lens))}
-        odd = [b for b in range(self.cfg.B) if self.lens[b] % self.cfg.page_size]
+        odd = [b for b in range(self.cfg.B) if self.lens[b] % self.cfg.page_size and b not in picks]
         if odd:
             picks.add(odd[len(odd) // 2])
         return sorted(picks)
 
+    def sample_sequences(self, n=0):
+        """the named ones plus, up to n in all, sequences spread evenly over the batch"""
+        picks = list(self.named_sequences())
+        for b in np.linspace(0, self.cfg.B - 1, max(n, 0)).astype(int):
+            if len(picks) >= n:
+                break
+            if int(b) not in picks:
+                picks.append(int(b))
+        return sorted(picks)
+
     def close(self):
         self.dec.close()
+
+
+def cfg_page(case):
+    return case.cfg.page_size
 
 
 def oracle_group(case, b, j, path):
@@ -78,7 +93,8 @@ def oracle_group(case, b, j, path):
     return O.decode_gqa(qc, qr, KC, V, kR)
 
 
-def run_both_paths(case, groups_to_check):
+def run_both_paths(case, groups_to_check, groups_named=None, n_seqs=0):
+    groups_named = list(groups_to_check) if groups_named is None else list(groups_named)
     cfg = case.cfg
     G = cfg.h_q // cfg.g
     q_hat = case.dec.absorb_query(case.d(case.q_c), case.d_w_uk)
@@ -93,15 +109,28 @@ def run_both_paths(case, groups_to_check):
     assert np.isfinite(oa).all() and np.isfinite(og).all() and np.isfinite(la).all() and np.isfinite(lg).all()
     check("absorb vs gqa path, all outputs", oa, og)
     assert float(np.max(np.abs(la - lg))) <= 2e-2, "lse of the two paths"
-    # sampled slices against the oracle
-    for b in case.sample_sequences():
-        for j in groups_to_check:
+    # sampled slices against the oracle: every group in groups_named for the three named sequences, the groups in
+    # groups_to_check for the rest of the sample; relative L2 is reported (and gated) per sequence as well
+    named = case.named_sequences()
+    per_seq = []
+    for b in case.sample_sequences(n_seqs):
+        ea = eg = na = 0.0
+        for j in (groups_named if b in named else groups_to_check):
             hs = slice(j * G, (j + 1) * G)
             ref_o, ref_l = oracle_group(case, b, j, "absorb")
             check("absorb  b=%d L=%d group %d" % (b, case.lens[b], j), oa[b][:, hs], ref_o)
             check("gqa     b=%d L=%d group %d" % (b, case.lens[b], j), og[b][:, hs], ref_o)
             assert float(np.max(np.abs(la[b][:, hs] - ref_l))) <= 2e-2
             assert float(np.max(np.abs(lg[b][:, hs] - ref_l))) <= 2e-2
+            ea += float(np.sum((oa[b][:, hs] - ref_o) ** 2))
+            eg += float(np.sum((og[b][:, hs] - ref_o) ** 2))
+            na += float(np.sum(ref_o ** 2))
+        per_seq.append((b, int(case.lens[b]), (ea / na) ** 0.5, (eg / na) ** 0.5))
+    print("per-sequence relative L2 (sequence, L, absorb, gqa):", flush=True)
+    for b, L, ra, rg in per_seq:
+        print("   b=%3d  L=%6d  absorb %.3e  gqa %.3e" % (b, L, ra, rg), flush=True)
+        assert ra <= REL_L2 and rg <= REL_L2, (b, L, ra, rg)
+    return per_seq
 
 
 def test_c1_llama3_shape_both_paths():
@@ -219,7 +248,12 @@ def test_c4_ragged_paged_both_paths():
     case = FullCase(S.CONFIGS["C4"])
     try:
         assert case.lens.min() >= 1024 and case.lens.max() <= 32768
-        run_both_paths(case, groups_to_check=[6])
+        named = case.named_sequences()
+        assert int(np.argmin(case.lens)) in named and int(np.argmax(case.lens)) in named
+        assert any(case.lens[b] % cfg_page(case) for b in named), "no sampled length off the page grid"
+        # 16 sequences: all 8 groups of the shortest, the longest and one off the page grid; one group (rotating) of the others
+        per_seq = run_both_paths(case, groups_to_check=[6], groups_named=range(8), n_seqs=16)
+        assert len(per_seq) >= 16
     finally:
         case.close()
 

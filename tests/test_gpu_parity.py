@@ -20,7 +20,7 @@ def rel_l2(a, ref):
     return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-def check(name, got, ref, dtype, scale_abs=1.0):
+def check(name, got, ref, dtype):
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert np.isfinite(got).all(), name + ": non-finite output"
@@ -28,7 +28,7 @@ def check(name, got, ref, dtype, scale_abs=1.0):
     err = float(np.max(np.abs(got - ref)))
     r = rel_l2(got, ref)
     print("%-34s max_abs %.3e  rel_l2 %.3e" % (name, err, r), flush=True)
-    assert err <= ma * scale_abs, "%s: max abs %.3e" % (name, err)
+    assert err <= ma, "%s: max abs %.3e" % (name, err)
     assert r <= rl, "%s: rel l2 %.3e" % (name, r)
 
 
@@ -76,7 +76,7 @@ def run_absorb_path(case, seqs=None):
     torch.cuda.synchronize()
     q_hat_h = host(q_hat)
     ref_qh = np.stack([O.absorb_query(case.q_c[b], case.w_uk) for b in range(cfg.B)])
-    check("absorb_query", q_hat_h, ref_qh, cfg.dtype, scale_abs=4.0)   # |q_hat| ~ sqrt(d_h) * N(0, 1/r_kv) * ... O(1); bf16 ulp at 4
+    check("absorb_query", q_hat_h, ref_qh, cfg.dtype)
     # a2-a4 in isolation: the oracle consumes exactly the q_hat bits the GPU consumes
     out, lse = case.dec.decode_absorb(q_hat, case.d_q_r, case.d_w_uv)
     torch.cuda.synchronize()
@@ -112,8 +112,8 @@ def run_gqa_path(case, seqs=None):
         KC, V = O.expand_latent(case.c(b), case.w_uk[j0:j0 + gc], case.w_uv[j0:j0 + gc])
         exp_ref[b] = (KC, V)
         k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], case.lens[b], cfg.page_size, gc, cfg.d_h, cfg.d_r)
-        check("expand K_C seq %d" % b, k2, KC, cfg.dtype, scale_abs=2.0)
-        check("expand V seq %d" % b, v2, V, cfg.dtype, scale_abs=2.0)
+        check("expand K_C seq %d" % b, k2, KC, cfg.dtype)
+        check("expand V seq %d" % b, v2, V, cfg.dtype)
         assert np.array_equal(r2, case.kR(b)), "k_R must be copied bit for bit"
     # slots no token owns were never written: still NaN, and their count is exact
     per_tok = 2 * gc * cfg.d_h + cfg.d_r
@@ -355,6 +355,6 @@ def test_absorb_path_with_a_value_dim_of_its_own(key, h_q, g, d_h, d_v, s_q, len
         y = case.dec.output_projection(o_dev, case.to_device(w_o, cfg.dtype))
         torch.cuda.synchronize()
         ref = np.stack([O.output_projection(S.quantize(out[b], cfg.dtype), w_o) for b in range(cfg.B)])
-        check("W^O over h_q * d_v columns", host(y), ref, cfg.dtype, scale_abs=2.0)
+        check("W^O over h_q * d_v columns", host(y), ref, cfg.dtype)
     finally:
         case.close()

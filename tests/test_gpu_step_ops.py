@@ -43,8 +43,8 @@ def test_rope_step_matches_the_oracle(key, lens, s_q, base):
             if t < 0:
                 assert np.array_equal(got_q[b, i], q_raw[b, i]) and np.array_equal(got_rows[b, i], rows_raw[b, i])
                 continue
-            check("rope q_R seq %d tok %d (t=%d)" % (b, i, t), got_q[b, i], O.rope(q_raw[b, i], t, base), cfg.dtype, scale_abs=2.0)
-            check("rope k_R seq %d tok %d" % (b, i), got_rows[b, i, cfg.r_kv:], O.rope(rows_raw[b, i, cfg.r_kv:], t, base), cfg.dtype, scale_abs=2.0)
+            check("rope q_R seq %d tok %d (t=%d)" % (b, i, t), got_q[b, i], O.rope(q_raw[b, i], t, base), cfg.dtype)
+            check("rope k_R seq %d tok %d" % (b, i), got_rows[b, i, cfg.r_kv:], O.rope(rows_raw[b, i, cfg.r_kv:], t, base), cfg.dtype)
     # either pointer alone
     d_q2, d_rows2 = to_device(q_raw, cfg.dtype), to_device(rows_raw, cfg.dtype)
     B.gqla_rope_step(shape, d_lens, base, d_q2, None)
@@ -74,7 +74,7 @@ def test_output_projection_matches_the_oracle(key, Bsz, s_q, d_model):
         dec.output_projection(to_device(o, cfg.dtype), to_device(w_o, cfg.dtype), y)
         torch.cuda.synchronize()
         ref = np.stack([O.output_projection(o[b], w_o) for b in range(cfg.B)])
-        check("output projection", host(y), ref, cfg.dtype, scale_abs=4.0)
+        check("output projection", host(y), ref, cfg.dtype)
         if cfg.dtype == "bf16":
             assert B.gqla_output_projection_workspace_bytes(dec.shape, d_model) > 0
             y2 = torch.empty_like(y)
@@ -131,7 +131,7 @@ def test_whole_decode_step_from_raw_inputs(key, lens, page_size, s_q, d_model):
             KC, V = O.expand_latent(case.c(b), case.w_uk, case.w_uv)
             ref.append(O.output_projection(O.decode_gqa(case.q_c[b], qR, KC, V, kR)[0], w_o))
         ref = np.stack(ref)
-        check("step y, GQA path", host(y_g), ref, cfg.dtype, scale_abs=2.0)
-        check("step y, absorb path", host(y_a), ref, cfg.dtype, scale_abs=2.0)
+        check("step y, GQA path", host(y_g), ref, cfg.dtype)
+        check("step y, absorb path", host(y_a), ref, cfg.dtype)
     finally:
         case.close()
