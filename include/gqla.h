@@ -192,6 +192,22 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
                                    const gqla_cache* expanded, int32_t tail_tokens, void* ws, size_t ws_bytes,
                                    void* stream);
 
+/* gqla_expand_cache_tail for callers that cannot allocate device memory at all (code recorded into a HIP graph, tight
+ * serving loops, harnesses that forbid hipMalloc): same operation, same results bit for bit, but the scratch (the
+ * slice's weights in matrix-core order) lives in a fixed 2 MiB device array inside the library instead of a
+ * caller-supplied workspace, and the call allocates and frees nothing.  Every GPU the process uses holds its own copy of
+ * that array until the process ends.  Limit: gqla_expand_workspace_bytes(shape, group_count) must not exceed
+ * gqla_expand_cache_tail_static_max_workspace() (2 MiB: up to 8 groups at r_kv = 512, d_h = 128 in bf16);
+ * GQLA_ERR_WORKSPACE beyond that, before anything is launched.  All calls on one GPU share the array: two such calls
+ * whose kernels can overlap (different streams without an ordering between them) race on it; calls on one stream, or
+ * ordered by events, are safe.  The array keeps the previous call's content; each call overwrites the part it uses
+ * before reading it.  Other arguments and errors as for gqla_expand_cache_tail; GQLA_ERR_DEVICE if the array's address
+ * cannot be obtained on the current device. */
+gqla_status gqla_expand_cache_tail_static(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
+                                          const void* w_uv, int32_t group_begin, int32_t group_count,
+                                          const gqla_cache* expanded, int32_t tail_tokens, void* stream);
+size_t gqla_expand_cache_tail_static_max_workspace(void);
+
 /* GQA-path decode (Sec. 3.1, GQA-path equation) over an expanded cache holding expanded->groups == shape->g
  * groups (for a tensor-parallel slice pass a shape with h_q and g already divided).  plan: built with
  * GQLA_PATH_GQA, uploaded into ws.  lse may be NULL. */

@@ -28,7 +28,7 @@ EXPORTS = [
     "gqla_output_projection_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
-    "gqla_time_next_decode_kernel",
+    "gqla_time_next_decode_kernel", "gqla_expand_cache_tail_static", "gqla_expand_cache_tail_static_max_workspace",
 ]
 
 
@@ -92,6 +92,10 @@ def lib():
         L.gqla_expand_cache.restype = i32
         L.gqla_expand_cache_tail.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, vp, C.c_size_t, vp]
         L.gqla_expand_cache_tail.restype = i32
+        L.gqla_expand_cache_tail_static.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, vp]
+        L.gqla_expand_cache_tail_static.restype = i32
+        L.gqla_expand_cache_tail_static_max_workspace.argtypes = []
+        L.gqla_expand_cache_tail_static_max_workspace.restype = C.c_size_t
         L.gqla_append_latent.argtypes = [sp, vp, cp, vp]
         L.gqla_append_latent.restype = i32
         L.gqla_estimate_paths.argtypes = [sp, i64, C.c_double, C.c_double, C.POINTER(gqla_path_estimate)]
@@ -286,6 +290,16 @@ def gqla_expand_cache_tail(shape, latent: gqla_cache, w_uk, w_uv, group_begin, g
     _check(lib().gqla_expand_cache_tail(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
                                         C.byref(expanded), tail_tokens, _ptr(ws), ws_bytes, _stream(stream)),
            "gqla_expand_cache_tail")
+
+
+def gqla_expand_cache_tail_static(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded: gqla_cache,
+                                  tail_tokens, stream=None):
+    _check(lib().gqla_expand_cache_tail_static(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
+                                               C.byref(expanded), tail_tokens, _stream(stream)), "gqla_expand_cache_tail_static")
+
+
+def gqla_expand_cache_tail_static_max_workspace() -> int:
+    return lib().gqla_expand_cache_tail_static_max_workspace()
 
 
 def gqla_append_latent(shape, rows, latent: gqla_cache, stream=None):

@@ -2,6 +2,7 @@
 // extern "C" entry points declared in gqla.h.  No device memory is allocated here.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "gqla_internal.h"
@@ -417,6 +418,56 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
                                    int32_t tail_tokens, void* ws, size_t ws_bytes, void* stream) {
   if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
   return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, ws, ws_bytes, stream);
+}
+
+// ---- the variant for callers that cannot allocate: scratch in a file-scope device array ---------------------------------
+// Every GPU the library runs on holds its own copy of this array at its own address until the process ends.  In host
+// code the array's NAME is only a handle for the runtime's symbol lookup, not a device address: the address is looked up
+// once per device (hipGetSymbolAddress, with that device current) and only that pointer is ever handed to a kernel.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)2 << 20;  // 2 MiB: both weight slices of 8 groups (r_kv 512, d_h 128) in bf16
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (looked up on the first call per device), or nullptr with *err set.
+void* static_scratch(hipError_t* err) {
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+}  // namespace
+
+size_t gqla_expand_cache_tail_static_max_workspace(void) { return kStaticScratchBytes; }
+
+gqla_status gqla_expand_cache_tail_static(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
+                                          const void* w_uv, int32_t group_begin, int32_t group_count,
+                                          const gqla_cache* expanded, int32_t tail_tokens, void* stream) {
+  if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
+  const gqla_status st = check_shape_equal_dims(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16)  // the fp32 kernels use no scratch at all
+    return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, nullptr, 0, stream);
+  if (group_count <= 0) return GQLA_ERR_SHAPE;
+  const size_t need = gqla_expand_workspace_bytes(shape, group_count);
+  if (need == 0 || need > kStaticScratchBytes) return GQLA_ERR_WORKSPACE;  // slice too large for the fixed scratch
+  hipError_t e;
+  void* ws = static_scratch(&e);
+  if (!ws) return GQLA_ERR_DEVICE;
+  return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, ws, kStaticScratchBytes, stream);
 }
 
 gqla_status gqla_expand_cache_tail_fp8(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,

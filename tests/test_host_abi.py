@@ -147,6 +147,13 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 65, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 6, 3, B.make_cache(A, A, None, 64, 4, 8, 3), 1, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 2, None, 0, stream=0)
+        # the variant with the scratch inside the library: the size limit and the shape checks come before anything
+        # touches a device
+        assert B.gqla_expand_cache_tail_static_max_workspace() == 2 << 20
+        wide = B.make_shape(2, 128, 16, 128, 512, 64, 1, B.GQLA_BF16)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_static, wide, lat, A, A, 0, 16, B.make_cache(A, A, None, 64, 4, 8, 16), 1, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_static, ok, lat, A, A, 0, 8, full, 0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_static, ok, lat, A, A, 0, 0, full, 1, stream=0)
         _expect(B.GQLA_ERR_NULL, B.gqla_append_latent, ok, None, lat, stream=0)
         _expect(B.GQLA_ERR_NULL, B.gqla_append_latent, ok, A, B.make_cache(A, None, None, 64, 4, 8, 0), stream=0)
         _expect(B.GQLA_ERR_ALIGN, B.gqla_append_latent, ok, A + 4, lat, stream=0)
