@@ -10,7 +10,9 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgqla.so")
+# GQLA_LIB_PATH: another build of the same library (the CPU tests point it at the build whose host code is
+# instrumented by the sanitizers); there is still no fallback if the file is missing.
+LIB_PATH = os.environ.get("GQLA_LIB_PATH") or os.path.join(_HERE, "libgqla.so")
 
 GQLA_OK = 0
 GQLA_ERR_NULL, GQLA_ERR_SHAPE, GQLA_ERR_DTYPE, GQLA_ERR_ALIGN, GQLA_ERR_SEQLEN = 1, 2, 3, 4, 5

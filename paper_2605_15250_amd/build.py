@@ -125,5 +125,36 @@ def build(extra_flags=(), jobs: int = 5) -> str:
     return LIB
 
 
+HOSTCHECK_LIB = os.path.join(BUILD, "hostcheck", "libgqla_hostcheck.so")
+HOST_SANITIZERS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                   "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-g", "-Xarch_host", "-O1"]
+
+
+def build_hostcheck(jobs: int = 8):
+    """The same library with its HOST code instrumented by the address and undefined-behaviour sanitizers (the GPU code
+    objects are built as usual and are not instrumented): what the CPU tests load to run the planner, the argument
+    validation and the left-inverse solve under the sanitizers.  Returns (library, sanitizer runtime to preload into an
+    uninstrumented interpreter)."""
+    out = os.path.join(BUILD, "hostcheck")
+    os.makedirs(out, exist_ok=True)
+
+    def one(src):
+        obj = os.path.join(out, os.path.splitext(src)[0] + ".o")
+        r = subprocess.run([_hipcc(), *FLAGS, *HOST_SANITIZERS, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc (host sanitizers) failed for %s:\n%s" % (src, r.stderr))
+        return obj
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(one, SOURCES))
+    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                        "-shared-libsan", "-Wno-option-ignored", "-o", HOSTCHECK_LIB, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link (host sanitizers) failed:\n" + r.stderr)
+    rt = subprocess.run([_hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True).stdout.strip()
+    if not os.path.isabs(rt) or not os.path.exists(rt):
+        raise RuntimeError("address-sanitizer runtime not found next to the compiler: %r" % rt)
+    return HOSTCHECK_LIB, rt
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:]))
