@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 CALIB_COPY_BYTES = 1 << 30
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_canonical_bench.txt")   # measured with rocprofv3 --pmc
-TRAFFIC_ROWS = {"decode_gqa_bf16_kernel": "decode_gqa", "decode_absorb_bf16_kernel": "decode_absorb", "expand_bf16_kernel": "expand_cache"}
+TRAFFIC_ROWS = {"decode_gqa_bf16_kernel": "decode_gqa", "decode_absorb_shared_bf16_kernel": "decode_absorb", "expand_bf16_kernel": "expand_cache"}
 
 
 def parse_args():
@@ -98,7 +98,7 @@ def main():
     Gq["dec"].alloc_expanded(fill=0.0)
 
     names = ["absorb_query", "decode_absorb", "append_latent", "expand_cache_tail", "decode_gqa"]
-    kernel_of = {"decode_absorb": "decode_absorb_bf16_kernel", "decode_gqa": "decode_gqa_bf16_kernel"}
+    kernel_of = {"decode_absorb": "decode_absorb_shared_bf16_kernel", "decode_gqa": "decode_gqa_bf16_kernel"}
 
     run_legs = set(args.legs.split(","))
 

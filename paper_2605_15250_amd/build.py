@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -49,14 +50,15 @@ def _compile(src: str, extra) -> str:
 # stale data).  The compiler touches accumulation registers itself (v_accvgpr_write / _read / _mov outside the assembly
 # blocks) only when it runs out of ordinary registers: the build checks the generated assembly and refuses such a
 # kernel instead of shipping silent corruption.
-NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"], "gqla_gemm_bf16.hip": ["expand_bf16_kernel"]}
+NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "decode_absorb_shared_bf16_kernel"],
+                      "gqla_gemm_bf16.hip": ["expand_bf16_kernel"]}
 
 
 # Kernels whose loops wait on hand-counted numbers of outstanding vector-memory instructions (s_waitcnt vmcnt(N) written
 # for the loads the source issues): a register spill would add scratch loads and stores of the compiler's own to that
 # count and silently break the waits.  The build reads the compiler's resource report and refuses any vector-register
 # spill or scratch use in them.
-COUNTED_WAIT_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"],
+COUNTED_WAIT_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "decode_absorb_shared_bf16_kernel"],
                         "gqla_gemm_bf16.hip": ["expand_bf16_kernel"],
                         "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"]}
 
@@ -71,12 +73,16 @@ def _check_device_code(src: str, extra) -> None:
     if r.returncode != 0:
         raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stderr))
     kernels = NAMED_AGPR_SOURCES.get(src, [])
-    current, in_asm = None, False
+    current, in_asm, seen_labels = None, False, set()
     with open(asm_path) as fh:
         for line in fh:
             t = line.strip()
-            if t.endswith(":") and not t.startswith(".") and not t.startswith(";"):
-                current = next((k for k in kernels if k in t), None)
+            m = re.match(r"^([A-Za-z_$][\w$.]*):", line)      # a function label ("name:" at the start of the line, maybe a comment behind)
+            if m:
+                current = next((k for k in kernels if k in m.group(1)), None)
+                seen_labels.add(current)
+            elif t.startswith(".Lfunc_end"):
+                current = None
             elif ";;#ASMSTART" in t:
                 in_asm = True
             elif ";;#ASMEND" in t:
@@ -84,6 +90,9 @@ def _check_device_code(src: str, extra) -> None:
             elif current and not in_asm and t.startswith("v_accvgpr_"):
                 raise RuntimeError("%s: the compiler uses accumulation registers of its own in %s (%s); "
                                    "lower the kernel's VGPR pressure" % (src, current, t))
+    missing = [k for k in kernels if k not in seen_labels]
+    if missing:
+        raise RuntimeError("%s: no function label found for %s (kernel renamed?)" % (src, ", ".join(missing)))
     # resource report: "remark: Function Name: <mangled>" followed by one remark per figure
     watched = COUNTED_WAIT_KERNELS.get(src, [])
     current, seen = None, set()

@@ -12,12 +12,52 @@
 // Each chunk's normalised latent-space output is written as bf16 with its log-sum-exp; the combine kernel merges
 // chunks and applies W_UV.  Intensity h_q s_q (2 r_kv + d_r) / (r_kv + d_r) (Sec. 4.2.1): 242 FLOP/byte for 128 rows,
 // 484 for 256 (s_q = 2), against a ridge of about 310 on this chip.
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
+
 #include "gqla_device.h"
 #include "gqla_lds.h"
+
+#ifdef GQLA_PHASE_TIMING
+__device__ unsigned long long gqla_phase_cycles[16];
+extern "C" int gqla_debug_read_phases(unsigned long long* host16, int reset) {
+  if (hipMemcpyFromSymbol(host16, HIP_SYMBOL(gqla_phase_cycles), 16 * 8) != hipSuccess) return 1;
+  if (reset) {
+    unsigned long long z[16] = {};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(gqla_phase_cycles), z, 16 * 8) != hipSuccess) return 1;
+  }
+  return 0;
+}
+#if GQLA_PHASE_TIMING >= 2
+#define GQLA_STAMP(k) do { const long long now_ = __builtin_readcyclecounter(); ph_[k] += now_ - last_; last_ = now_; } while (0)
+#else
+#define GQLA_STAMP(k) do { (void)ph_; (void)last_; } while (0)   // level 1: kernel entry and exit only
+#endif
+#else
+#define GQLA_STAMP(k) do { } while (0)
+#endif
 
 namespace gqla {
 
 namespace {
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), straight-line code from the start
+// (register arrays indexed by the counter are then promoted to registers even when the body is large)
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 
 constexpr int kTile = 32;                 // tokens per LDS tile
 constexpr int kSlots = 4;                 // tile buffers in the LDS ring
@@ -31,6 +71,23 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 // below is `asm volatile`, so they keep their program order; the callers keep the hardware's timing rules
 // (results of an MFMA are read by non-MFMA instructions only after its last pass has long retired).
 #define GQLA_ACC(D) "a[" #D "*16:" #D "*16+15]"
+#define GQLA_ACC_CLOBBER(D) GQLA_ACC_CLOBBER_##D
+#define GQLA_ACC_CLOBBER_0 "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15"
+#define GQLA_ACC_CLOBBER_1 "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31"
+#define GQLA_ACC_CLOBBER_2 "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47"
+#define GQLA_ACC_CLOBBER_3 "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63"
+#define GQLA_ACC_CLOBBER_4 "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79"
+#define GQLA_ACC_CLOBBER_5 "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95"
+#define GQLA_ACC_CLOBBER_6 "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111"
+#define GQLA_ACC_CLOBBER_7 "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127"
+#define GQLA_ACC_CLOBBER_8 "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143"
+#define GQLA_ACC_CLOBBER_9 "a144", "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159"
+#define GQLA_ACC_CLOBBER_10 "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", "a173", "a174", "a175"
+#define GQLA_ACC_CLOBBER_11 "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191"
+#define GQLA_ACC_CLOBBER_12 "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207"
+#define GQLA_ACC_CLOBBER_13 "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", "a221", "a222", "a223"
+#define GQLA_ACC_CLOBBER_14 "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239"
+#define GQLA_ACC_CLOBBER_15 "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
 #define GQLA_FOR_DT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
 
 __device__ __forceinline__ void acc_zero() {
@@ -39,7 +96,9 @@ __device__ __forceinline__ void acc_zero() {
 // O^T tile dt += A * B (dt is a compile-time value at every call site: the switch folds away)
 __device__ __forceinline__ void acc_mfma(int dt, bf16x8 a, bf16x8 b) {
   switch (dt) {
-#define X(D) case D: asm volatile("v_mfma_f32_32x32x16_bf16 " GQLA_ACC(D) ", %0, %1, " GQLA_ACC(D) : : "v"(a), "v"(b)); break;
+    // (the tile's registers are named as clobbered: the compiler must not keep values of its own in them across this
+    // statement -- it would otherwise use "free" accumulation registers as parking space when ordinary ones run short)
+#define X(D) case D: asm volatile("v_mfma_f32_32x32x16_bf16 " GQLA_ACC(D) ", %0, %1, " GQLA_ACC(D) : : "v"(a), "v"(b) : GQLA_ACC_CLOBBER(D)); break;
     GQLA_FOR_DT(X)
 #undef X
   }
@@ -189,9 +248,9 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   int st_slot = (kAhead * kTile) % P;                                       // slot of tile it + 3 in its page
   int lk_slot = ((kAhead + 1) * kTile) % P, lk_p = p_first + ((kAhead + 1) * kTile) / P;  // tile it + 4
   static_assert(kAhead == 3, "the page-id shift register holds four tiles");
-  stage_panels_full<kTile, NP, 4, ROWB>(smem, tile_src(pg0, 0), wave, lane);
-  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB>(smem + TILE_BYTES, tile_src(pg1, kTile % P), wave, lane);
-  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB>(smem + 2 * TILE_BYTES, tile_src(pg2, (2 * kTile) % P), wave, lane);
+  stage_panels_full<kTile, NP, 4, ROWB, true>(smem, tile_src(pg0, 0), wave, lane);
+  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB, true>(smem + TILE_BYTES, tile_src(pg1, kTile % P), wave, lane);
+  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB, true>(smem + 2 * TILE_BYTES, tile_src(pg2, (2 * kTile) % P), wave, lane);
 
   // queries of this lane's row, as B fragments: [q_hat (RKV) | q_R (DR)], 8 consecutive dims per k-step; this wave's
   // k-steps are 4*a4 + part*KB + b
@@ -264,7 +323,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       }
     };
     if (!wave_active) {  // waves without query rows only help staging (uniform per wave): their share, in one burst
-      if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+      if (stage_next) stage_panels_full<kTile, NP, 4, ROWB, true>(next_buf, next_g, wave, lane);
       shift_pages();
       continue;
     }
@@ -279,7 +338,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // With few query rows the kernel is bound by how many bytes it keeps in flight, not by its MFMAs: the request
       // for tile it + kAhead goes out first (no LDS read is outstanding here either).
       if constexpr (SPLIT > 1) {
-        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB, true>(next_buf, next_g, wave, lane);
       }
       if constexpr (SPLIT == 1) {
         bf16x8 f[3][4];  // ring of fragment batches: loads run two batches (8 MFMAs) ahead of their use
@@ -321,7 +380,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
       // (An LDS-DMA instruction issued while reads are in flight holds the wave, and with it the MFMA stream, until
       // they have returned.)
       if constexpr (SPLIT == 1) {
-        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB>(next_buf, next_g, wave, lane);
+        if (stage_next) stage_panels_full<kTile, NP, 4, ROWB, true>(next_buf, next_g, wave, lane);
       }
       // first batches of value fragments: issued now, consumed after the softmax
       i16x4 r[3][4][2];
@@ -455,6 +514,444 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
     }
   }
   if (h == 0 && part == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+}
+
+// every accumulator of row block rb (tiles 4*dtl + rb, dtl = 0..3) of this lane times alpha
+__device__ __forceinline__ void acc_scale_rb(int rb, float alpha) {
+  float t0, t1;
+  switch (rb) {
+#define X(R)                                                                                                             \
+  case R:                                                                                                                \
+    asm volatile(".irp gqla_t, " #R ", 4+" #R ", 8+" #R ", 12+" #R "\n.set gqla_i, 0\n.rept 8\n"                          \
+                 "\tv_accvgpr_read_b32 %0, a[(\\gqla_t)*16+gqla_i]\n\tv_accvgpr_read_b32 %1, a[(\\gqla_t)*16+gqla_i+1]\n"  \
+                 "\tv_mul_f32 %0, %0, %2\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n"                                              \
+                 "\tv_accvgpr_write_b32 a[(\\gqla_t)*16+gqla_i], %0\n\tv_accvgpr_write_b32 a[(\\gqla_t)*16+gqla_i+1], %1\n" \
+                 ".set gqla_i, gqla_i+2\n.endr\n.endr"                                                                     \
+                 : "=&v"(t0), "=&v"(t1)                                                                                    \
+                 : "v"(alpha));                                                                                            \
+    break;
+    X(0) X(1) X(2) X(3)
+#undef X
+  }
+}
+
+// More than 32 query rows per sequence and enough chunks to fill the chip: one workgroup of 4 waves per (chunk, block of
+// 128 rows), and the two contractions are dealt over the waves in two different ways.
+//   S^T: wave w owns row block w (rows 32w..32w+31) against the whole tile, queries in registers.
+//   O^T: wave w owns latent dims 128w..128w+127 of ALL four row blocks: accumulator tile 4*d + rb holds dims
+//        128w + 32d.. of row block rb.  Each transposed value fragment read from LDS then feeds four MFMAs (one per row
+//        block) instead of one, which cuts the transposed reads per tile by four; the price is that the waves trade
+//        their probabilities: wave rb writes its two P^T operand fragments (1 KB each, already in B-operand order) into a
+//        double-buffered 8 KB exchange behind the tile ring, and every wave reads all eight.
+// The loop is software-pipelined so that nothing but MFMAs (and what fits in their shadows) is on a wave's critical path
+// (measured on this chip: behind each 32-cycle MFMA a wave issues four simple vector-ALU instructions or two
+// exponentials for free, an LDS read costs about 5 cycles, an LDS-DMA instruction 10-20):
+//   iteration i:   S^T(i)          36 MFMAs; in their gaps: the key-fragment reads (a ring of 8 fragments, 8 MFMAs ahead),
+//                                  the 9 LDS-DMA instructions that stage tile i+2, and the first operands of the next phase
+//                  O^T += (i-1)    32 MFMAs; in their gaps: the softmax of tile i (maximum, exponentials, packing) and the
+//                                  write of its probabilities
+//                  one workgroup barrier, then the first key fragments of tile i+1 are requested
+// The barrier is the only one of the tile: each wave waits for its share of tile i+1's staging before it arrives, so
+// passing it means "tile i+1 has landed for everyone", "the probabilities of tile i are visible" and "everyone is done
+// with tile i-1", whose buffer the staging of tile i+3 (issued in the next iteration's gaps) overwrites.
+// The softmax state (reference maximum, denominator) of a row lives in the wave that owns its row block.  A move of the
+// reference maximum of rows that already have output (rare: the maximum must grow by more than 2^8) has to rescale
+// accumulators in all four waves: the owning wave announces it in the sign bit of its first probability (probabilities
+// are never negative), all waves see the same bits, and together they take a slow path that passes the factors through
+// the idle half of the exchange.
+// Requires whole blocks of 128 rows (h_q s_q a multiple of 128; the launcher sends other row counts to the kernel above):
+// there is no branch per row block, and the register budget is exact -- the compiler must never run out of ordinary
+// registers here, or it would park values in accumulation registers, which hold O^T behind its back (the MFMA
+// statements name their accumulators as clobbered, and the build checks the generated code for both).
+template <int RKV, int DR>
+__global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeArgs a, int row_blocks) {
+  constexpr int W = RKV + DR;
+  constexpr int ROWB = W * 2;
+  constexpr int NP = W / 64;
+  constexpr int PANEL = kTile * 128;
+  constexpr int KS = W / 16;
+  constexpr int DT = RKV / 32;
+  constexpr int TILE_BYTES = kTile * ROWB;
+  constexpr int EX = kSlots * TILE_BYTES;  // exchange: [2 buffers][4 row blocks][2 k-steps][64 lanes][16 bytes]
+  constexpr int KR = 4;                    // key fragments in flight (more do not fit the 256 ordinary registers)
+  static_assert(DT == 16, "O^T fills the 256 accumulation registers exactly: 4 dim tiles x 4 row blocks per wave");
+  static_assert(W % 64 == 0 && RKV % 128 == 0, "latent row must be a whole number of 128-byte panels, two per wave");
+  static_assert(KS == 36 && NP == 9, "the gap schedule below is written for 36 key k-steps and 9 staging instructions");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  int chunk, rbk;
+  {
+    const int id = blockIdx.x;
+    const int grp = id / (8 * row_blocks), rem = id % (8 * row_blocks);
+    rbk = rem / 8;
+    chunk = grp * 8 + rem % 8;
+  }
+  if (chunk >= a.n_chunks) return;  // whole workgroup leaves together
+#ifdef GQLA_PHASE_TIMING
+  const long long t_entry_ = __builtin_readcyclecounter();
+  long long ph_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long last_ = t_entry_;
+#endif
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const ChunkEntry ce = a.chunks[chunk];
+
+  const int row0 = rbk * kRowsPerBlock;
+  const int rho = row0 + wave * 32 + n;  // row = t * h_q + i (always a real row here)
+  const int t = rho / a.h_q;
+  const int vis_end = min(ce.tok_end, ce.L - a.s_q + t + 1);
+  const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);
+
+  const int P = a.cache.page_size;
+  const char* pool = (const char*)a.cache.pool;
+  const int32_t* table_row = a.cache.page_table ? a.cache.page_table + (int64_t)ce.b * a.cache.max_pages : nullptr;
+  auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
+  auto tile_src = [&](int32_t pg, int slot) -> const char* { return pool + ((int64_t)(pg >= 0 ? pg : 0) * P + slot) * ROWB; };
+
+  // per-lane LDS offsets inside a tile (panel layout of gqla_lds.h): key fragment of k-step ks = 4*a4 + b at
+  // kbase[b] + a4*PANEL; transposed value reads at vbase + compile-time offsets (this wave's dims: panels 2w, 2w+1)
+  uint32_t kbase[4], vbase;
+  {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) kbase[b] = n * 128 + (((2 * b + h) ^ lds_swz(n)) << 4);
+    const int i16 = lane & 15, e = i16 >> 2, q = i16 & 3, g1 = (lane >> 4) & 1;
+    vbase = (4 * h + e) * 128 + (((2 * g1 + (q >> 1)) ^ (2 * h + (e >> 1))) << 4) + (q & 1) * 8;
+    vbase += wave * 2 * PANEL;
+  }
+  const uint32_t stage_off = stage_lane_offset<kTile, NP, 4, ROWB>(wave, lane);
+
+  GQLA_STAMP(4);
+  acc_zero();
+  float m_ref = GQLA_NEG_INF, l_run = 0.f;
+
+  const int n_tiles = (ce.tok_end - ce.tok_begin + kTile - 1) / kTile;
+  // page ids of tiles it .. it+3; iteration `it` stages tile it+2 (the first three are staged up front), the table entry
+  // of tile it+4 travels through the scalar cache meanwhile
+  int32_t pg0, pg1, pg2, pg3;
+  {
+    const int p_last = (ce.tok_end - 1) / P;
+    int32_t raw[4];
+    if (table_row) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int p = __builtin_amdgcn_readfirstlane(min(ce.tok_begin / P + (k * kTile) / P, p_last));
+        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(raw[k]) : "s"(table_row + p) : "memory");
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(raw[0]), "+s"(raw[1]), "+s"(raw[2]), "+s"(raw[3]) : : "memory");
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) raw[k] = ce.b * a.cache.max_pages + min(ce.tok_begin / P + (k * kTile) / P, p_last);
+    }
+    pg0 = checked(raw[0]);
+    pg1 = n_tiles > 1 ? checked(raw[1]) : -1;
+    pg2 = n_tiles > 2 ? checked(raw[2]) : -1;
+    pg3 = n_tiles > 3 ? checked(raw[3]) : -1;
+  }
+  GQLA_STAMP(5);
+  int32_t pg_raw = 0;
+  const char* next_g = pool;  // first row of the tile the next iteration stages (set when the window moves)
+  const int p_first = ce.tok_begin / P;
+  int st_slot = (3 * kTile) % P;                                     // slot of tile it+3 in its page
+  int lk_slot = (4 * kTile) % P, lk_p = p_first + (4 * kTile) / P;   // tile it+4
+
+  // Start-up: all workgroups begin at once, so the first requests of the whole chip queue at the memory system (the
+  // queries alone are 147 KB per workgroup, 38 MB over the chip: about 12 k cycles before the first MFMA, and the same
+  // when they are staged through LDS in whole lines -- it is their volume, not the shape of the loads).  The queries
+  // go first, then tile 0; tiles 1 and 2 are requested once those have landed, while tile 0 is being multiplied.
+  bf16x8 qf[KS];
+  {
+    const int64_t qrow = (int64_t)ce.b * a.M + rho;
+    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(ks < RKV / 16 ? ph + ks * 16 : pr + (ks - RKV / 16) * 16);
+  }
+  stage_panels_full<kTile, NP, 4, ROWB, true>(smem, tile_src(pg0, 0), wave, lane);
+  // The query loads complete here, before the loop (the compiler's wait for them also covers the request for tile 0
+  // above); inside the loop only hand-counted waits remain.
+#pragma unroll
+  for (int k = 0; k < KS; k += 9)
+    asm volatile("" : "+v"(qf[k]), "+v"(qf[k + 1]), "+v"(qf[k + 2]), "+v"(qf[k + 3]), "+v"(qf[k + 4]), "+v"(qf[k + 5]),
+                      "+v"(qf[k + 6]), "+v"(qf[k + 7]), "+v"(qf[k + 8]));
+
+  // rows of a tile past the chunk end (or a whole tile behind an out-of-pool page id) hold whatever the page holds:
+  // zeroed in LDS by the whole workgroup before anyone reads them, so that 0 * v stays 0
+  auto zero_rows = [&](int slot, int valid) {
+    for (int idx = threadIdx.x; idx < (kTile - valid) * (W / 8); idx += 256) {
+      const int r = valid + idx / (W / 8), c = idx % (W / 8);
+      *(u32x4*)(smem + slot * TILE_BYTES + (c >> 3) * PANEL + r * 128 + (c & 7) * 16) = u32x4{0u, 0u, 0u, 0u};
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __syncthreads();
+  };
+  GQLA_STAMP(6);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // the first tiles have landed for every wave
+  GQLA_STAMP(7);
+  if (n_tiles > 1) stage_panels_full<kTile, NP, 4, ROWB, true>(smem + TILE_BYTES, tile_src(pg1, kTile % P), wave, lane);
+  if (n_tiles > 2) stage_panels_full<kTile, NP, 4, ROWB, true>(smem + 2 * TILE_BYTES, tile_src(pg2, (2 * kTile) % P), wave, lane);
+  {
+    const int valid0 = pg0 >= 0 ? min(kTile, ce.tok_end - ce.tok_begin) : 0;
+    if (valid0 < kTile) zero_rows(0, valid0);
+  }
+
+  // operands that live across the phases of the pipeline
+  bf16x8 kf[KR];        // key fragments, requested KR MFMAs ahead of their use
+  bf16x8 pfr[4][2];     // probabilities of the tile whose O^T update is running: [row block][k-step]
+  i16x4 vr[2][4][2];    // its value fragments [k-step][dim tile][read]
+  f32x16 s;             // raw logits of the tile whose softmax is running
+  float alpha_prev = 1.f;   // factor of this wave's rows announced with the probabilities of the previous tile
+  bool announce_prev = false;
+
+  auto load_k = [&](const char* tb, int ks) __attribute__((always_inline)) {  // key fragment of k-step ks of the tile at tb
+    kf[ks % KR] = *(const bf16x8*)(tb + kbase[ks & 3] + (ks >> 2) * PANEL);
+  };
+  auto load_v = [&](const char* tb, int u, int d) __attribute__((always_inline)) {
+    const int off = (d >> 1) * PANEL + (16 * u) * 128;
+    vr[u][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(tb + vbase + (off + 64 * (d & 1))));
+    vr[u][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(tb + vbase + (off + 8 * 128 + 64 * (1 - (d & 1)))));
+  };
+  auto load_p = [&](const char* exr, int rb, int u) __attribute__((always_inline)) { pfr[rb][u] = *(const bf16x8*)(exr + (rb * 2 + u) * 1024); };
+
+#pragma unroll
+  for (int ks = 0; ks < KR; ++ks) load_k(smem, ks);
+
+  // Iterations 0 .. n_tiles: iteration it computes S^T of tile it (HAS_S: it < n_tiles) and updates O^T with tile it-1
+  // (HAS_PV: it > 0); STAGE: tile it+2 exists and is staged in this iteration (tiles 0..2 were staged up front).  The
+  // three flags are compile-time so that the steady-state body has no branch per gap.
+  auto iteration = [&](int it, auto HAS_S_T, auto HAS_PV_T, auto STAGE_T) __attribute__((always_inline)) {
+    constexpr bool HAS_S = decltype(HAS_S_T)::value, HAS_PV = decltype(HAS_PV_T)::value, STAGE = decltype(STAGE_T)::value;
+    const int tok = ce.tok_begin + it * kTile;
+    const char* buf = smem + (it & (kSlots - 1)) * TILE_BYTES;                 // tile it
+    const char* pbuf = smem + ((it + kSlots - 1) & (kSlots - 1)) * TILE_BYTES;  // tile it-1
+    const char* exr = smem + EX + ((it + 1) & 1) * 8192 + lane * 16;           // probabilities of tile it-1
+    char* exw = smem + EX + (it & 1) * 8192;                                   // probabilities of tile it
+    char* next_buf = smem + ((it + 2) & (kSlots - 1)) * TILE_BYTES;
+    const bool lookup = it + 4 < n_tiles;
+    const bool new_page = lookup && lk_slot == 0;
+    if (new_page && table_row)  // scalar load, consumed at the end of the iteration (its wait is written out there)
+      asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pg_raw) : "s"(table_row + lk_p) : "memory");
+    const bool tile_ok = pg0 >= 0;
+    const int lk_p_prev = lk_p;
+    // Tile it+1 becomes current: the window of page ids moves, and the source of the tile that the next iteration
+    // stages (tile it+3) is formed.  Scalar work; it runs in the shadow of the first MFMA of phase 2.
+    auto move_window = [&]() __attribute__((always_inline)) {
+      pg0 = pg1;
+      pg1 = pg2;
+      pg2 = pg3;  // pg3 (tile it+4) is the same page unless a new one was looked up; set behind the barrier
+      next_g = tile_src(pg2, st_slot);
+      st_slot = lk_slot;
+      lk_slot += kTile;
+      if (lk_slot == P) {
+        lk_slot = 0;
+        ++lk_p;
+      }
+    };
+
+    // ---------------- phase 1: S^T(it), staging of tile it+2, first operands of phase 2 ----------------
+    if constexpr (HAS_S) {
+      static_for<KS>([&](auto KSI) __attribute__((always_inline)) {
+        constexpr int ks = decltype(KSI)::value;
+        if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kf[0]), "v"(qf[0]));
+        else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf[ks % KR]), "v"(qf[ks]));
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + KR < KS) load_k(buf, ks + KR);
+        if (STAGE && ks % 3 == 1 && ks / 3 < 9) stage_panels_step<kTile, NP, 4, ROWB, true>(next_buf, next_g, wave, stage_off, ks / 3);
+        if (HAS_PV) {  // operands of the first k-step of the O^T update, in the last gaps
+          if (ks >= 28 && ks < 32) load_p(exr, ks - 28, 0);
+          if (ks >= 32) load_v(pbuf, 0, ks - 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    } else {  // the last iteration: only the O^T update of the last tile is left
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) load_p(exr, rb, 0);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) load_v(pbuf, 0, d);
+    }
+    GQLA_STAMP(0);
+
+    // ---------------- phase 2: O^T += tile it-1, softmax of tile it in the gaps ----------------
+    if (HAS_PV) {
+      // announced moves of the reference maximum (uniform over the workgroup: every wave sees the same bits)
+      uint32_t flags = 0;
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+        flags |= __builtin_bit_cast(u32x4, pfr[rb][0])[0];
+      if (__builtin_amdgcn_readfirstlane(flags & 0x8000u) != 0) {
+        // the factors travel through the idle half of the exchange (no probabilities of tile it are written before the
+        // second barrier below)
+        float* al = (float*)exw;
+        if (announce_prev) al[wave * 32 + n] = alpha_prev;  // both half-waves hold the row's factor and write the same value
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __syncthreads();
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          u32x4 w = __builtin_bit_cast(u32x4, pfr[rb][0]);
+          if (__builtin_amdgcn_readfirstlane(w[0] & 0x8000u) != 0) {
+            acc_scale_rb(rb, al[rb * 32 + n]);
+            w[0] &= ~0x8000u;
+            pfr[rb][0] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __syncthreads();
+      }
+    }
+    // softmax state of this iteration (pieces run in the gaps below)
+    constexpr bool sm = HAS_S;
+    const bool need_mask = (tok + kTile > unmasked_end) || !tile_ok;
+    const int lim = tile_ok ? vis_end : 0;
+    float tmax = 0.f, m_use = 0.f, psum = 0.f, alpha = 1.f;
+    bool announce = false;
+    u32x4 w0 = {0u, 0u, 0u, 0u}, w1 = {0u, 0u, 0u, 0u};
+    auto softmax_piece = [&](auto GI) __attribute__((always_inline)) {  // g = 0..31: position in the phase
+      constexpr int g = decltype(GI)::value;
+      if (g == 2) {
+        // S^T is read here for the first time: three MFMAs of the O^T update have been issued since its last MFMA, which
+        // has therefore retired (the matrix pipeline's result is not interlocked against vector-ALU reads)
+        if (__builtin_amdgcn_ballot_w64(need_mask) != 0) {  // wave-uniform: only tiles at the chunk end, or padding rows
+          // register i is token tok + 4h + 8*(i/4) + i%4: compared as a constant against one per-lane distance (formed
+          // here, so that no per-register offsets are kept alive across the loop)
+          int dist = lim - tok - 4 * h;
+          asm volatile("" : "+v"(dist));
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (need_mask && 8 * (i >> 2) + (i & 3) >= dist) s[i] = GQLA_NEG_INF;
+        }
+        // the row maximum of the tile: eight three-way maxima (written as instructions: the logits come out of inline
+        // assembly, and the compiler would first canonicalise every one of them)
+        tmax = max3(s[0], s[1], s[2]);
+        tmax = max3(tmax, s[3], s[4]);
+      } else if (g == 3) {
+        tmax = max3(tmax, s[5], s[6]);
+        tmax = max3(tmax, s[7], s[8]);
+      } else if (g == 4) {
+        tmax = max3(tmax, s[9], s[10]);
+        tmax = max3(tmax, s[11], s[12]);
+      } else if (g == 5) {
+        tmax = max3(tmax, s[13], s[14]);
+        tmax = max3(tmax, s[15], s[15]);
+      } else if (g == 6) {
+        tmax = pair_max(tmax) * a.scale_log2e;
+        if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRescaleThreshold) != 0) {
+          const float m_new = fmaxf(m_ref, tmax);
+          alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
+          // a row whose maximum was -inf has seen no token yet: its accumulators are zero and need no factor
+          announce = __builtin_amdgcn_ballot_w64(m_new != m_ref && m_ref != GQLA_NEG_INF) != 0;
+          m_ref = m_new;
+          l_run *= alpha;
+        }
+        m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
+      } else if (g >= 7 && g < 23) {
+        constexpr int e = g >= 7 && g < 23 ? g - 7 : 0;
+        s[e] = fast_exp2(__builtin_fmaf(s[e], a.scale_log2e, -m_use));  // the probability replaces the logit
+        psum += s[e];
+      } else if (g >= 23 && g < 27) {
+        constexpr int q = g >= 23 && g < 27 ? g - 23 : 0;
+        w0[q] = pack_bf16(s[2 * q], s[2 * q + 1]);
+        w1[q] = pack_bf16(s[8 + 2 * q], s[8 + 2 * q + 1]);
+      } else if (g == 27) {
+        l_run += psum;
+        if (announce) w0[0] |= 0x8000u;  // sign bit of the first probability
+        *(u32x4*)(exw + (wave * 2 + 0) * 1024 + lane * 16) = w0;
+      } else if (g == 28) {
+        *(u32x4*)(exw + (wave * 2 + 1) * 1024 + lane * 16) = w1;
+      }
+    };
+    if (HAS_PV) {
+      static_for<32>([&](auto GI) __attribute__((always_inline)) {
+        constexpr int g = decltype(GI)::value;
+        constexpr int u = g >> 4, d = (g >> 2) & 3, rb = g & 3;
+        {
+          const i16x4 lo = vr[u][d][0], hi = vr[u][d][1];
+          const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          acc_mfma(4 * d + rb, __builtin_bit_cast(bf16x8, fr), pfr[rb][u]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (g == 0 && HAS_S) move_window();
+        if (g >= 8 && g < 12) load_p(exr, g - 8, 1);  // second k-step's operands, as the first k-step's registers free up
+        if (g >= 12 && g < 16) load_v(pbuf, 1, g - 12);
+        if (sm) softmax_piece(GI);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    } else {  // the first iteration: there is no O^T update yet to hide the softmax behind
+      move_window();
+      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));  // the matrix pipeline's result is not interlocked against vector-ALU reads
+      static_for<32>([&](auto GI) __attribute__((always_inline)) { softmax_piece(GI); });
+    }
+    alpha_prev = alpha;
+    announce_prev = announce;
+    GQLA_STAMP(1);
+
+    // ---------------- the tile's barrier ----------------
+    if (HAS_S) {
+      if (it + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");  // this wave's share of tile it+1 has landed
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the probabilities are written
+      __syncthreads();
+      GQLA_STAMP(2);
+      if (it + 1 < n_tiles) {
+        const int valid1 = pg0 >= 0 ? min(kTile, ce.tok_end - (tok + kTile)) : 0;  // (the window has moved: pg0 is tile it+1)
+        if (valid1 < kTile) zero_rows((it + 1) & (kSlots - 1), valid1);  // only the chunk's last tile can have invalid rows
+        const char* nbuf = smem + ((it + 1) & (kSlots - 1)) * TILE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KR; ++ks) load_k(nbuf, ks);
+      }
+      // the page of tile it+4 joins the window (the scalar load was requested at the top of the iteration; no LDS
+      // operation is outstanding here, so its wait costs nothing extra)
+      if (new_page && table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pg_raw) : : "memory");
+      if (new_page) pg3 = checked(table_row ? pg_raw : ce.b * a.cache.max_pages + lk_p_prev);
+      if (!lookup) pg3 = -1;
+    }
+    GQLA_STAMP(3);
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  iteration(0, T_{}, F_{}, F_{});
+  {
+    int it = 1;
+#pragma unroll 1
+    for (; it + 2 < n_tiles; ++it) iteration(it, T_{}, T_{}, T_{});
+#pragma unroll 1
+    for (; it < n_tiles; ++it) iteration(it, T_{}, T_{}, F_{});
+  }
+  iteration(n_tiles, F_{}, T_{}, F_{});
+
+#ifdef GQLA_PHASE_TIMING
+  if (threadIdx.x == 0) {
+    for (int k = 0; k < 8; ++k) atomicAdd(&gqla_phase_cycles[k], (unsigned long long)ph_[k]);
+    atomicAdd(&gqla_phase_cycles[15], (unsigned long long)n_tiles);
+    atomicAdd(&gqla_phase_cycles[14], (unsigned long long)(__builtin_readcyclecounter() - t_entry_));
+    atomicAdd(&gqla_phase_cycles[13], 1ull);
+  }
+#endif
+  // ---- chunk partial: O^T / l as bf16 in latent space, log-sum-exp per row ----
+  const float l_tot = pair_sum(l_run);
+  __syncthreads();  // every wave is done with the exchange
+  float* inv_l = (float*)(smem + EX);
+  if (h == 0) inv_l[wave * 32 + n] = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __syncthreads();
+  if (h == 0)
+    a.part_lse[(int64_t)chunk * a.M + rho] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+#pragma unroll
+  for (int rb = 0; rb < 4; ++rb) {
+    const int row = row0 + rb * 32 + n;
+    const float inv = inv_l[rb * 32 + n];
+    __bf16* po = (__bf16*)a.part_o + ((int64_t)chunk * a.M + row) * RKV + wave * 128;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      float x[16];
+      acc_read(4 * d + rb, rb == 0 && d == 0, x);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
+        *(u32x2*)(po + d * 32 + 8 * q + 4 * h) = v;
+      }
+    }
+  }
 }
 
 // ---- combine + latent-output projection: out = W_UV[j]^T (sum_k w_k o_hat_k)   (MQA-absorb equation, line 6) ----
@@ -602,6 +1099,17 @@ static hipError_t launch_decode_absorb_split(const DecodeArgs& a, hipStream_t s)
   return hipGetLastError();
 }
 
+static hipError_t launch_decode_absorb_shared(const DecodeArgs& a, hipStream_t s) {
+  constexpr int kLds = kSlots * kTile * (512 + 64) * 2 + 2 * 8192;  // tile ring + the double-buffered exchange: all 160 KB
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)decode_absorb_shared_bf16_kernel<512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
+  const int row_blocks = a.M / kRowsPerBlock;
+  const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
+  decode_absorb_shared_bf16_kernel<512, 64><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks);
+  return hipGetLastError();
+}
+
 hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   // At most 32 query rows: the four waves share them, so that none is left without work.  More rows but few chunks
   // (small batches): one workgroup per (chunk, 32 rows) with the four waves sharing its rows, as long as all of them
@@ -609,7 +1117,11 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   // with so few chunks the chip is nowhere near its memory rate).
   const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
   if (a.M <= 32 || chunks_padded * ((a.M + 31) / 32) <= a.num_cus) return launch_decode_absorb_split<4>(a, s);
-  return launch_decode_absorb_split<1>(a, s);
+  static const bool old_kernel = getenv("GQLA_ABSORB_OLD") != nullptr;  // TEMPORARY: A/B switch while the new kernel is measured
+  if (old_kernel) return launch_decode_absorb_split<1>(a, s);
+  // whole blocks of 128 rows (h_q s_q a multiple of 128): the pipelined kernel with shared probabilities; other row
+  // counts above 32: one wave per 32 rows, each with its own probabilities
+  return a.M % kRowsPerBlock == 0 ? launch_decode_absorb_shared(a, s) : launch_decode_absorb_split<1>(a, s);
 }
 
 template <int DV>

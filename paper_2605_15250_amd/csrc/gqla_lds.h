@@ -35,14 +35,20 @@ __device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane) {
 // behind its back, and does not put a "wait for every outstanding load" in front of the next LDS read (it cannot see
 // that the reads go to another buffer).  The caller orders things itself: s_waitcnt vmcnt(0) and a workgroup barrier
 // before the staged tile is read.
-template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+// STREAM: the source is read once (a cache tile): the request carries the non-temporal hint, which on this chip
+// raises the rate at which LDS-DMA streams from HBM from 6.0 to 6.8 TB/s (own probe: 256 workgroups of 4 waves, ring
+// of four 36 KB buffers; the number of tiles in flight made no difference).
+template <int ROWS, int NP, int NWAVES, int GSTRIDE, bool STREAM = false>
 __device__ __forceinline__ void stage_panels_step(char* lds, const char* g, int wave, uint32_t lane_off, int u) {
   static_assert(NWAVES % 2 == 0 && (ROWS / 8) % NWAVES == 0, "wave count must be even and divide ROWS/8");
   constexpr int K = ROWS / 8 / NWAVES;
   const int a = u / K, v = u % K;
   const char* base = g + (8 * NWAVES * v * GSTRIDE + a * 128);
   const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + a * (ROWS * 128) + (wave + NWAVES * v) * 1024);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" : : "s"(dst), "v"(lane_off), "s"(base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(dst), "v"(lane_off), "s"(base)
                : "memory");  // M0 is written here.  It cannot be named as a clobber (the compiler treats it as reserved and
@@ -52,11 +58,11 @@ __device__ __forceinline__ void stage_panels_step(char* lds, const char* g, int 
 }
 
 // Whole matrix (all ROWS rows present), this wave's share in one burst of asm steps.
-template <int ROWS, int NP, int NWAVES, int GSTRIDE>
+template <int ROWS, int NP, int NWAVES, int GSTRIDE, bool STREAM = false>
 __device__ __forceinline__ void stage_panels_full(char* lds, const char* g, int wave, int lane) {
   const uint32_t lane_off = stage_lane_offset<ROWS, NP, NWAVES, GSTRIDE>(wave, lane);
 #pragma unroll
-  for (int u = 0; u < NP * (ROWS / 8 / NWAVES); ++u) stage_panels_step<ROWS, NP, NWAVES, GSTRIDE>(lds, g, wave, lane_off, u);
+  for (int u = 0; u < NP * (ROWS / 8 / NWAVES); ++u) stage_panels_step<ROWS, NP, NWAVES, GSTRIDE, STREAM>(lds, g, wave, lane_off, u);
 }
 
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
