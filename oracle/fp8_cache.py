@@ -118,3 +118,43 @@ def pack_fp8_pool(KC_codes, V_codes, kR_bits, table, num_pages, P, fill=0xAA):
         pool[ro] = (bits & 0xFF).astype(np.uint8)
         pool[ro + 1] = (bits >> 8).astype(np.uint8)
     return pool
+
+
+# ---- 8-bit LATENT cache for the MQA-absorb path -----------------------------------------------------------------------
+# Same idea, other cache (the paper's Sec. 4.2.1 cache: r_kv latent elements plus the shared RoPE key per token): c_kv as
+# E4M3 codes with one positive scale for the whole cache, k_R left in the 16-bit type.  A token then takes r_kv + 2 d_R
+# bytes (640 at the canonical shape, against the 1152 of Sec. 4.2.1).  The decode is the MQA-absorb equation (Sec. 3.1) on
+# the dequantised latent c' = value(code) * scale: keys [c'; k_R], values c'.
+# Page format (P tokens; byte offsets inside a page of P * (r_kv + 2 d_R) bytes), this build's own reading:
+#     codes : [P][r_kv]        one byte per latent element, token rows back to back
+#     k_R   : [P][d_R] 16-bit  behind the codes
+
+
+def latent_fp8_page_bytes(P, r_kv, d_r):
+    return P * (r_kv + 2 * d_r)
+
+
+def latent_code_offset(page, slot, d, P, r_kv, d_r):
+    return page * latent_fp8_page_bytes(P, r_kv, d_r) + slot * r_kv + d
+
+
+def latent_kr16_offset(page, slot, d, P, r_kv, d_r):
+    """Byte offset of the 16-bit element d of the token's shared RoPE key."""
+    return page * latent_fp8_page_bytes(P, r_kv, d_r) + P * r_kv + (slot * d_r + d) * 2
+
+
+def pack_latent_fp8_pool(c_codes, kR_bits, table, num_pages, P, fill=0xAA):
+    """c_codes[b] = uint8 [L_b, r_kv]; kR_bits[b] = uint16 [L_b, d_r].  Returns the pool as uint8; bytes no token owns = fill."""
+    r_kv, d_r = c_codes[0].shape[1], kR_bits[0].shape[1]
+    pb = latent_fp8_page_bytes(P, r_kv, d_r)
+    pool = np.full((num_pages * pb,), fill, dtype=np.uint8)
+    for b in range(len(c_codes)):
+        for t in range(c_codes[b].shape[0]):
+            page, slot = int(np.asarray(table[b])[t // P]), t % P
+            o = page * pb + slot * r_kv
+            pool[o: o + r_kv] = c_codes[b][t]
+            o = page * pb + P * r_kv + slot * d_r * 2
+            bits = np.asarray(kR_bits[b][t], dtype=np.uint16)
+            pool[o: o + 2 * d_r: 2] = (bits & 0xFF).astype(np.uint8)
+            pool[o + 1: o + 2 * d_r: 2] = (bits >> 8).astype(np.uint8)
+    return pool

@@ -105,3 +105,64 @@ def test_page_format_is_a_bijection_and_matches_the_written_rule():
         for d in (0, 15):
             o = F8.kr16_offset(page, slot, d, P, g, d_h, d_r)
             assert int(pool[o]) | (int(pool[o + 1]) << 8) == int(kr[s, d])
+
+
+def test_latent_page_format_is_a_bijection_and_matches_the_written_rule():
+    """8-bit latent cache (absorb path): codes [P][r_kv] then k_R [P][d_R] in 16 bits; r_kv + 2 d_R bytes per token."""
+    P, r_kv, d_r = 64, 32, 16
+    pb = F8.latent_fp8_page_bytes(P, r_kv, d_r)
+    assert pb == P * (r_kv + 2 * d_r)
+    # the canonical shape: 512 code bytes + 128 bytes of 16-bit RoPE key against 2 (r_kv + d_R) = 1152 (Sec. 4.2.1)
+    assert F8.latent_fp8_page_bytes(1, 512, 64) == 640 and 2 * (512 + 64) == 1152
+    seen = np.zeros(2 * pb, dtype=np.int32)
+    for page in (0, 1):
+        for s in range(P):
+            for d in range(r_kv):
+                seen[F8.latent_code_offset(page, s, d, P, r_kv, d_r)] += 1
+            for d in range(d_r):
+                o = F8.latent_kr16_offset(page, s, d, P, r_kv, d_r)
+                seen[o] += 1
+                seen[o + 1] += 1
+    assert (seen == 1).all()
+    assert F8.latent_code_offset(0, 0, 0, P, r_kv, d_r) == 0
+    assert F8.latent_code_offset(0, 3, 5, P, r_kv, d_r) == 3 * r_kv + 5           # token rows back to back
+    assert F8.latent_code_offset(1, 0, 0, P, r_kv, d_r) == pb
+    assert F8.latent_kr16_offset(0, 0, 0, P, r_kv, d_r) == P * r_kv                # the key plane starts behind all codes
+    assert F8.latent_kr16_offset(0, 2, 1, P, r_kv, d_r) == P * r_kv + (2 * d_r + 1) * 2
+    rng = np.random.default_rng(2)
+    L = 70
+    cc = rng.integers(0, 255, size=(L, r_kv), dtype=np.uint8)
+    kr = rng.integers(0, 65535, size=(L, d_r), dtype=np.uint16)
+    table = [np.array([1, 0])]
+    pool = F8.pack_latent_fp8_pool([cc], [kr], table, 2, P, fill=0x55)
+    for s in (0, 7, 63, 64, 69):
+        page, slot = table[0][s // P], s % P
+        for d in (0, 9, 31):
+            assert pool[F8.latent_code_offset(page, slot, d, P, r_kv, d_r)] == cc[s, d]
+        for d in (0, 15):
+            o = F8.latent_kr16_offset(page, slot, d, P, r_kv, d_r)
+            assert int(pool[o]) | (int(pool[o + 1]) << 8) == int(kr[s, d])
+    # bytes of slots no token owns keep the fill pattern: 2 * 64 - 70 = 58 empty slots
+    assert int((pool == 0x55).sum()) >= 58 * (r_kv + 2 * d_r) - 58 * 4   # (a few data bytes may equal the pattern)
+
+
+def test_absorb_decode_on_a_dequantised_latent_is_the_plain_decode_on_those_values():
+    """The 8-bit latent decode is defined as the MQA-absorb equation on c' = value(code) * scale.  Two consequences that
+    do not depend on the decode routine's inner workings: the scale can be pulled out of both uses of c' (logits
+    linear in c', output linear in c'), and with codes that represent the latent exactly the result is the 16-bit one."""
+    from oracle import gqla_oracle as O
+    rng = np.random.default_rng(11)
+    h_q, g, d_h, r_kv, d_r, L = 4, 2, 8, 16, 8, 40
+    w_uk = rng.normal(size=(g, r_kv, d_h)); w_uv = rng.normal(size=(g, r_kv, d_h))
+    q_c = rng.normal(size=(1, h_q, d_h)); q_r = rng.normal(size=(1, h_q, d_r))
+    kR = rng.normal(size=(L, d_r))
+    # latents that E4M3 holds exactly at scale 0.25: multiples of 0.25 * 2^-3 in [-1, 1] ... take code values directly
+    codes = rng.integers(0x20, 0x48, size=(L, r_kv)).astype(np.uint8) | (rng.integers(0, 2, size=(L, r_kv)).astype(np.uint8) << 7)
+    scale = 0.25
+    c = F8.dequantize_e4m3(codes) * scale
+    assert np.array_equal(F8.quantize_tensor(c.astype(np.float32), scale), codes)          # exact round trip
+    q_hat = O.absorb_query(q_c, w_uk)
+    o1, l1 = O.decode_absorb(q_hat, q_r, c, kR, w_uv)
+    # scale pulled out by hand: logits with (scale * q_hat) on unscaled values, output scaled afterwards
+    o2, l2 = O.decode_absorb(q_hat * scale, q_r, F8.dequantize_e4m3(codes), kR, w_uv)
+    assert np.allclose(o1, o2 * scale, rtol=1e-12, atol=1e-12) and np.allclose(l1, l2, rtol=1e-12, atol=1e-12)
