@@ -291,6 +291,27 @@ gqla_status gqla_expand_cache_fp8(const gqla_shape* shape, const gqla_cache* lat
                                   float v_scale, void* ws, size_t ws_bytes, void* stream);
 int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r);
 
+/* ---- 8-bit latent cache for the MQA-absorb path ----------------------------------------------------------
+ * The same reading (Sec. 2; Sec. 5.1, item (i): quantised caches are complementary, no format given) applied to the
+ * cache of Sec. 4.2.1: c_kv as E4M3 codes with ONE positive scale for the whole cache (conversion rule as above),
+ * k_R kept in 16 bits.  A token takes r_kv + 2 d_r bytes (640 at r_kv 512, d_r 64, against 1152).  A page of P tokens
+ * (byte offsets inside the page of P * (r_kv + 2 d_r) bytes):
+ *     codes : [P][r_kv]          s * r_kv + d
+ *     k_R   : [P][d_r] 16-bit    P * r_kv + (s * d_r + d) * 2
+ * gqla_quantize_latent converts a 16-bit latent cache (every token t < L_b, L_b read from latent->seq_lens on the
+ * device) into an 8-bit one with the same page geometry and page ids (each cache may have its own page table); bytes
+ * of slots no token owns are left as they are.  gqla_decode_absorb_fp8 is gqla_decode_absorb over such a cache (same
+ * plan, workspace and outputs): the MQA-absorb equation (Sec. 3.1) with keys [c'; k_R] and values c', c' = value(code)
+ * * c_scale; the codes are widened to bf16 (exactly) on their way into LDS, the scale is applied to the content part
+ * of the logits and to the output.  GQLA_BF16 shapes only (GQLA_ERR_DTYPE otherwise); a scale that is not positive and
+ * finite: GQLA_ERR_SHAPE; other errors as for gqla_decode_absorb. */
+gqla_status gqla_quantize_latent(const gqla_shape* shape, const gqla_cache* latent, const gqla_cache* latent_fp8,
+                                 float c_scale, void* stream);
+gqla_status gqla_decode_absorb_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_hat, const void* q_r,
+                                   const gqla_cache* latent_fp8, float c_scale, const void* w_uv, void* out, float* lse,
+                                   void* ws, size_t ws_bytes, void* stream);
+int64_t gqla_latent_fp8_bytes_per_token(int32_t r_kv, int32_t d_r);
+
 /* ---- sizes and diagnostics ------------------------------------------------------------------------------ */
 /* Elements per token of the two caches (Sec. 4.2.1: r_kv + d_r;  Sec. 4.2.2: 2 g d_h + d_r). */
 int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r);

@@ -25,6 +25,7 @@ EXPORTS = [
     "gqla_plan_workspace_bytes", "gqla_plan_upload", "gqla_absorb_query", "gqla_decode_absorb", "gqla_expand_cache",
     "gqla_expand_workspace_bytes", "gqla_expand_cache_tail", "gqla_append_latent", "gqla_probe_stream_read",
     "gqla_probe_mfma_bf16", "gqla_probe_mfma_flops", "gqla_estimate_paths", "gqla_select_path",
+    "gqla_quantize_latent", "gqla_decode_absorb_fp8", "gqla_latent_fp8_bytes_per_token",
     "gqla_quantize_expanded", "gqla_decode_gqa_fp8", "gqla_expanded_fp8_bytes_per_token", "gqla_expand_cache_tail_fp8", "gqla_expand_cache_fp8",
     "gqla_left_inverse", "gqla_compress_cache", "gqla_rope_step", "gqla_output_projection",
     "gqla_output_projection_workspace_bytes",
@@ -122,6 +123,12 @@ def lib():
         L.gqla_output_projection.restype = i32
         L.gqla_output_projection_workspace_bytes.argtypes = [sp, i32]
         L.gqla_output_projection_workspace_bytes.restype = C.c_size_t
+        L.gqla_quantize_latent.argtypes = [sp, cp, cp, C.c_float, vp]
+        L.gqla_quantize_latent.restype = i32
+        L.gqla_decode_absorb_fp8.argtypes = [sp, vp, vp, vp, cp, C.c_float, vp, vp, vp, vp, sz, vp]
+        L.gqla_decode_absorb_fp8.restype = i32
+        L.gqla_latent_fp8_bytes_per_token.argtypes = [i32, i32]
+        L.gqla_latent_fp8_bytes_per_token.restype = i64
         L.gqla_expanded_fp8_bytes_per_token.argtypes = [i32, i32, i32]
         L.gqla_expanded_fp8_bytes_per_token.restype = i64
         L.gqla_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
@@ -312,6 +319,21 @@ def gqla_decode_gqa(shape, plan, q_c, q_r, expanded: gqla_cache, out, lse, ws, w
     nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
     _check(lib().gqla_decode_gqa(C.byref(shape), plan, _ptr(q_c), _ptr(q_r), C.byref(expanded), _ptr(out), _ptr(lse),
                                  _ptr(ws), nbytes, _stream(stream)), "gqla_decode_gqa")
+
+
+def gqla_quantize_latent(shape, latent: gqla_cache, latent_fp8: gqla_cache, c_scale, stream=None):
+    _check(lib().gqla_quantize_latent(C.byref(shape), C.byref(latent), C.byref(latent_fp8), float(c_scale), _stream(stream)),
+           "gqla_quantize_latent")
+
+
+def gqla_decode_absorb_fp8(shape, plan, q_hat, q_r, latent_fp8: gqla_cache, c_scale, w_uv, out, lse, ws, ws_bytes=None, stream=None):
+    nbytes = ws_bytes if ws_bytes is not None else ws.numel() * ws.element_size()
+    _check(lib().gqla_decode_absorb_fp8(C.byref(shape), plan, _ptr(q_hat), _ptr(q_r), C.byref(latent_fp8), float(c_scale),
+                                        _ptr(w_uv), _ptr(out), _ptr(lse), _ptr(ws), nbytes, _stream(stream)), "gqla_decode_absorb_fp8")
+
+
+def gqla_latent_fp8_bytes_per_token(r_kv, d_r) -> int:
+    return lib().gqla_latent_fp8_bytes_per_token(r_kv, d_r)
 
 
 def gqla_quantize_expanded(shape, expanded: gqla_cache, expanded_fp8: gqla_cache, k_scale, v_scale, stream=None):

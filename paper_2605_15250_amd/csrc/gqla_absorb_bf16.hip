@@ -954,6 +954,331 @@ __global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeAr
   }
 }
 
+// ---- MQA-absorb decode over an 8-bit latent cache (c_kv as E4M3 codes with one scale, k_R in 16 bits) ----
+// The paper names quantised caches as complementary and fixes no format (Sec. 2; Sec. 5.1, item (i)); the page format is
+// this library's (gqla.h): code rows [P][r_kv] back to back, then k_R [P][d_r] in 16 bits -- r_kv + 2 d_r bytes per token.
+// The decode is the MQA-absorb equation on c' = value(code) * scale.  Same mapping of rows to waves as
+// decode_absorb_bf16_kernel above (one wave per 32 rows, or four waves sharing 32 rows), same MFMAs: the codes are
+// widened to bf16 ONCE per tile on their way into LDS, by the wave that fetched them, so that every row block reads
+// ready-made bf16 fragments:
+//   tile it+2:  four 16-byte loads of codes per lane (whole 128-byte lines: 8 rows x 128 code bytes per wave
+//               instruction) and one of k_R, in flight in 20 registers for one whole iteration
+//   tile it+1:  its codes (requested one iteration ago) are widened (v_cvt_scalef32_pk_bf16_fp8, exact) and written to
+//               the idle one of two LDS tile buffers in the panel layout of gqla_lds.h -- the lanes of a 16-lane group
+//               cover 4 rows x 4 chunk pairs, which the layout's XOR spreads over all 64 banks; its k_R rows (already
+//               16-bit) are written as they came
+// Everything in flight is an ordinary load into registers: the compiler places every wait itself, and no wait of this
+// kernel is counted by hand.
+// The scale enters twice, both times outside the MFMAs: on the content part of the logits (between the latent k-steps
+// and the RoPE k-steps of S^T) and on the normalised output.
+__device__ __forceinline__ bf16x8 widen_e4m3x8(uint32_t w0, uint32_t w1) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2v;
+  const bf16x2v p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false), p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
+  const bf16x2v p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false), p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
+  const u32x4 r = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1), __builtin_bit_cast(uint32_t, p2), __builtin_bit_cast(uint32_t, p3)};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int RKV, int DR, int SPLIT>
+__global__ void __launch_bounds__(256) decode_absorb_fp8_kernel(DecodeArgs a, int row_blocks, float c_scale) {
+  constexpr int W = RKV + DR;        // elements per latent row (in LDS: all bf16)
+  constexpr int NP = W / 64;         // 128-byte panels per latent row in LDS
+  constexpr int PANEL = kTile * 128; // bytes per panel
+  constexpr int KS = W / 16;         // k-steps of the key contraction
+  constexpr int KS_C = RKV / 16;     // ... of which over the latent (the rest over the RoPE key)
+  constexpr int DT = RKV / 32;       // 32-wide tiles of the latent output
+  constexpr int TILE_BYTES = kTile * W * 2;
+  constexpr int RPB = kRowsPerBlock / SPLIT;
+  constexpr int KB = 4 / SPLIT;
+  constexpr int DTW = DT / SPLIT;
+  static_assert(SPLIT == 1 || SPLIT == 4, "one wave or the whole workgroup per 32 rows");
+  static_assert(RKV == 512 && DR == 64, "the staging below is written for 8 code panels of 64 bytes per row and one k_R panel");
+  static_assert(DT == 16, "O^T fills the 256 accumulation registers exactly");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  int chunk, rbk;
+  {
+    const int id = blockIdx.x;
+    const int grp = id / (8 * row_blocks), rem = id % (8 * row_blocks);
+    rbk = rem / 8;
+    chunk = grp * 8 + rem % 8;
+  }
+  if (chunk >= a.n_chunks) return;  // whole workgroup leaves together
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const ChunkEntry ce = a.chunks[chunk];
+
+  const int part = wave & (SPLIT - 1), team = wave / SPLIT;
+  const int rho = rbk * RPB + team * 32 + n;  // row = t * h_q + i
+  const bool row_ok = rho < a.M;
+  const int t = row_ok ? rho / a.h_q : 0;
+  const int vis_end = row_ok ? min(ce.tok_end, ce.L - a.s_q + t + 1) : 0;
+  const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);
+  const bool wave_active = SPLIT > 1 || rbk * RPB + team * 32 < a.M;
+
+  const int P = a.cache.page_size;
+  const char* pool = (const char*)a.cache.pool;
+  const int64_t page_bytes = (int64_t)P * (RKV + 2 * DR);
+  const int32_t* table_row = a.cache.page_table ? a.cache.page_table + (int64_t)ce.b * a.cache.max_pages : nullptr;
+  auto checked = [&](int32_t pg) -> int32_t { return ((uint32_t)pg < (uint32_t)a.cache.num_pages) ? pg : -1; };
+  // first code row / first k_R row of a tile: page pg (page 0 for an id outside the pool; such a tile is zeroed), slot `slot`
+  auto code_src = [&](int32_t pg, int slot) -> const char* { return pool + (int64_t)(pg >= 0 ? pg : 0) * page_bytes + (int64_t)slot * RKV; };
+  auto kr_src = [&](int32_t pg, int slot) -> const char* {
+    return pool + (int64_t)(pg >= 0 ? pg : 0) * page_bytes + (int64_t)P * RKV + (int64_t)slot * (DR * 2);
+  };
+
+  uint32_t kbase[KB], vbase;
+  {
+#pragma unroll
+    for (int b = 0; b < KB; ++b) kbase[b] = n * 128 + (((2 * (part * KB + b) + h) ^ lds_swz(n)) << 4);
+    const int i16 = lane & 15, e = i16 >> 2, q = i16 & 3, g1 = (lane >> 4) & 1;
+    vbase = (4 * h + e) * 128 + (((2 * g1 + (q >> 1)) ^ (2 * h + (e >> 1))) << 4) + (q & 1) * 8;
+    vbase += part * (DTW / 2) * PANEL;
+  }
+  // staging: load i (0..3) of this lane fetches the 16 codes of row R, dims 16*k .. 16*k+15, k = 4*(2i + hp) + kq, and
+  // writes them as chunks 2k, 2k+1 of row R: panel 2i + hp, in-panel slots (2kq) ^ swz, (2kq+1) ^ swz
+  const int st_R = 8 * wave + 4 * ((lane >> 4) & 1) + ((lane >> 2) & 3), st_kq = lane & 3, st_hp = lane >> 5;
+  const uint32_t st_goff = st_R * RKV + (4 * st_hp + st_kq) * 16;
+  const uint32_t st_w0 = st_R * 128 + (((2 * st_kq) ^ lds_swz(st_R)) << 4) + st_hp * PANEL;
+  const uint32_t st_w1 = st_R * 128 + (((2 * st_kq + 1) ^ lds_swz(st_R)) << 4) + st_hp * PANEL;
+  // ... and one 16-byte piece of k_R: row kr_R, chunk lane % 8 (eight lanes per 128-byte row)
+  const int kr_R = 8 * wave + (lane >> 3);
+  const uint32_t kr_goff = kr_R * (DR * 2) + (lane & 7) * 16;
+  const uint32_t kr_w = (RKV / 64) * PANEL + kr_R * 128 + (((lane & 7) ^ lds_swz(kr_R)) << 4);
+
+  acc_zero();
+  float m_ref = GQLA_NEG_INF, l_run = 0.f;
+  const int n_tiles = (ce.tok_end - ce.tok_begin + kTile - 1) / kTile;
+
+  u32x4 codes[4], kr16;  // in flight: 4 x 16 codes and 8 elements of k_R per lane
+  auto load_tile = [&](int32_t pg, int slot) __attribute__((always_inline)) {
+    const char* src = code_src(pg, slot);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) codes[i] = __builtin_nontemporal_load((const u32x4*)(src + st_goff + i * 128));
+    kr16 = __builtin_nontemporal_load((const u32x4*)(kr_src(pg, slot) + kr_goff));
+  };
+  // widen the codes in flight and write them as rows of the bf16 tile at `slot`; rows >= valid are written as zeros
+  // (slots past the chunk end hold whatever the page holds, and 0 * v must stay 0)
+  auto write_tile = [&](char* slot, int valid) __attribute__((always_inline)) {
+    const bool keep = st_R < valid;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      u32x4 lo = __builtin_bit_cast(u32x4, widen_e4m3x8(codes[i][0], codes[i][1]));
+      u32x4 hi = __builtin_bit_cast(u32x4, widen_e4m3x8(codes[i][2], codes[i][3]));
+      if (!keep) lo = hi = u32x4{0u, 0u, 0u, 0u};
+      *(u32x4*)(slot + st_w0 + i * 2 * PANEL) = lo;
+      *(u32x4*)(slot + st_w1 + i * 2 * PANEL) = hi;
+    }
+    *(u32x4*)(slot + kr_w) = kr_R < valid ? kr16 : u32x4{0u, 0u, 0u, 0u};
+  };
+  auto page_now = [&](int tile) -> int32_t {  // synchronous lookup (start-up only)
+    const int p = (ce.tok_begin + tile * kTile) / P;
+    return checked(table_row ? table_row[p] : ce.b * a.cache.max_pages + p);
+  };
+
+  // queries of this lane's row, as B fragments (requested first: their latency overlaps the first tile's)
+  bf16x8 qf[KS / SPLIT];
+  {
+    const int64_t qrow = (int64_t)ce.b * a.M + min(rho, a.M - 1);
+    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8 + part * KB * 16;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8 + part * KB * 16;
+#pragma unroll
+    for (int a4 = 0; a4 < KS / 4; ++a4)
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+        qf[a4 * KB + b] = *(const bf16x8*)((a4 < RKV / 64 ? ph + a4 * 64 : pr + (a4 - RKV / 64) * 64) + b * 16);
+  }
+  // start-up: tile 0 into buffer 0, codes of tile 1 in flight
+  int32_t pg_cur = page_now(0);
+  int32_t pg_n1 = n_tiles > 1 ? page_now(1) : -1;  // page of tile it+1
+  load_tile(pg_cur, 0);
+  // the query loads complete here
+#pragma unroll
+  for (int k = 0; k < KS / SPLIT; k += 9)
+    asm volatile("" : "+v"(qf[k]), "+v"(qf[k + 1]), "+v"(qf[k + 2]), "+v"(qf[k + 3]), "+v"(qf[k + 4]), "+v"(qf[k + 5]),
+                      "+v"(qf[k + 6]), "+v"(qf[k + 7]), "+v"(qf[k + 8]));
+  static_assert((KS / SPLIT) % 9 == 0, "query fragments are touched nine at a time");
+  write_tile(smem, pg_cur >= 0 ? min(kTile, ce.tok_end - ce.tok_begin) : 0);
+  if (n_tiles > 1) load_tile(pg_n1, kTile % P);
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile is written
+  __syncthreads();
+  int32_t pg_lane = 0;
+  int lane_zero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+
+#pragma unroll 1
+  for (int it = 0; it < n_tiles; ++it) {
+    const int tok = ce.tok_begin + it * kTile;
+    const char* buf = smem + (it & 1) * TILE_BYTES;
+    char* nbuf = smem + ((it + 1) & 1) * TILE_BYTES;
+    // page of tile it+2: looked up when that tile starts a page, consumed behind the S phase.  An ordinary load into a
+    // vector register (every lane reads the same entry; the lane-dependent zero keeps the compiler from turning it into
+    // a load-and-wait on the spot), so that the compiler itself waits for it where the value is first read.  (A scalar
+    // load issued and awaited by hand is not safe here: this loop's control flow makes the compiler copy the value
+    // between registers, and a copy ahead of the hand-placed wait reads the register while the load is pending.)
+    const int tok2 = tok + 2 * kTile;
+    const bool has2 = it + 2 < n_tiles;
+    const bool new_page = has2 && (tok2 % P) == 0;
+    if (new_page && table_row) pg_lane = table_row[tok2 / P + lane_zero];
+    const bool tile_ok = pg_cur >= 0;
+
+    // tile it+1 into the idle buffer (every wave passed the last barrier: nobody reads tile it-1 any more), the codes of
+    // tile it+2 into flight.  No LDS read of this wave is outstanding where this is called.
+    auto stage_step = [&]() __attribute__((always_inline)) {
+      const int32_t pg_n2 = !has2 ? -1 : (new_page ? checked(table_row ? __builtin_amdgcn_readfirstlane(pg_lane)
+                                                                           : ce.b * a.cache.max_pages + tok2 / P) : pg_n1);
+      if (it + 1 < n_tiles) {
+        write_tile(nbuf, pg_n1 >= 0 ? min(kTile, ce.tok_end - (tok + kTile)) : 0);
+      }
+      if (has2) load_tile(pg_n2, tok2 % P);
+      pg_cur = pg_n1;  // (used again only in the next iteration)
+      pg_n1 = pg_n2;
+    };
+    auto end_of_tile = [&]() __attribute__((always_inline)) {
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's rows of tile it+1 are written
+      __syncthreads();
+    };
+    const bool need_mask = (tok + kTile > unmasked_end) || !row_ok || !tile_ok;
+    const int lim = tile_ok ? vis_end : 0;
+
+    // ---- S^T[token][row] = Kt * Qhat^T: latent k-steps, the scale, RoPE k-steps ----
+    // (waves without query rows only stage: ONE call site of stage_step for both kinds, so that the codes in flight
+    // live in the same registers on every path and nothing has to wait for them before the staging itself)
+    f32x16 s;
+    if (wave_active) {
+      bf16x8 f[2][KB];  // fragment batches: loads run one batch (one panel) ahead of their use
+#pragma unroll
+      for (int b = 0; b < KB; ++b) f[0][b] = *(const bf16x8*)(buf + kbase[b]);
+#pragma unroll
+      for (int a4 = 0; a4 < KS / 4; ++a4) {
+        if (a4 + 1 < KS / 4) {
+#pragma unroll
+          for (int b = 0; b < KB; ++b) f[(a4 + 1) & 1][b] = *(const bf16x8*)(buf + kbase[b] + ((a4 + 1) * PANEL));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (a4 == KS_C / 4) {  // the latent part is complete: the cache's scale, before the RoPE part is added
+          asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[i] *= c_scale;
+          asm volatile("s_nop 1" : "+v"(s));
+        }
+#pragma unroll
+        for (int b = 0; b < KB; ++b) {
+          if (a4 == 0 && b == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(f[0][0]), "v"(qf[0]));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(f[a4 & 1][b]), "v"(qf[a4 * KB + b]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    stage_step();
+    if (wave_active) {
+    // first batch of value fragments: issued now, consumed after the softmax
+    i16x4 r[2][4][2];
+    auto load_v = [&](int slot, int u, int p4) __attribute__((always_inline)) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int dt = 4 * p4 + d;
+        const int off = (dt >> 1) * PANEL + (16 * u) * 128;
+        r[slot][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 64 * (dt & 1))));
+        r[slot][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(buf + vbase + (off + 8 * 128 + 64 * (1 - (dt & 1)))));
+      }
+    };
+    constexpr int NBT = 2 * (DTW / 4);
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s));  // the matrix pipeline's result is not interlocked against vector-ALU reads
+    if constexpr (SPLIT > 1) {
+      // team sum of the partial S^T: [wave][quarter][lane] 16-byte slots behind the two tile buffers.  (The scale was
+      // applied to every wave's latent part; the RoPE part is spread over the waves like the latent part.)
+      char* ex = smem + 2 * TILE_BYTES;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *(f32x4*)(ex + wave * 4096 + q * 1024 + lane * 16) = f32x4{s[4 * q], s[4 * q + 1], s[4 * q + 2], s[4 * q + 3]};
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __syncthreads();  // the next write to these slots comes after the end-of-tile barrier, which follows these reads
+#pragma unroll
+      for (int w = 0; w < SPLIT; ++w)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 x = *(const f32x4*)(ex + (team * SPLIT + w) * 4096 + q * 1024 + lane * 16);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[4 * q + e] = (w == 0) ? x[e] : s[4 * q + e] + x[e];
+        }
+    }
+    load_v(0, 0, 0);
+
+    // ---- online softmax (base 2); register i is token tok + 8*(i/4) + 4*h + i%4 ----
+    if (__builtin_amdgcn_ballot_w64(need_mask) != 0) {
+      int dist = lim - tok - 4 * h;
+      asm volatile("" : "+v"(dist));
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (need_mask && 8 * (i >> 2) + (i & 3) >= dist) s[i] = GQLA_NEG_INF;
+    }
+    float tmax = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
+    tmax = pair_max(tmax) * a.scale_log2e;
+    if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRescaleThreshold) != 0) {
+      const float m_new = fmaxf(m_ref, tmax);
+      const float alpha = fast_exp2(m_ref - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
+      m_ref = m_new;
+      l_run *= alpha;
+      if (it > 0) acc_scale(alpha);
+    }
+    const float m_use = (m_ref == GQLA_NEG_INF) ? 0.f : m_ref;
+    bf16x8 pf[2];
+    {
+      float p[16], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        p[e] = fast_exp2(__builtin_fmaf(s[e], a.scale_log2e, -m_use));
+        psum += p[e];
+      }
+      l_run += psum;
+      const u32x4 w0 = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+      const u32x4 w1 = {pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]), pack_bf16(p[14], p[15])};
+      pf[0] = __builtin_bit_cast(bf16x8, w0);
+      pf[1] = __builtin_bit_cast(bf16x8, w1);
+    }
+    asm volatile("s_nop 1" : "+v"(pf[0]), "+v"(pf[1]));  // two wait states between a vector-ALU write and an MFMA that reads it
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- O^T[r][row] += C^T * P^T, value fragments one batch of four tiles ahead ----
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt) {
+      const int u = bt / (DTW / 4), p4 = bt % (DTW / 4);
+      if (bt + 1 < NBT) load_v((bt + 1) & 1, (bt + 1) / (DTW / 4), (bt + 1) % (DTW / 4));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const i16x4 lo = r[bt & 1][d][0], hi = r[bt & 1][d][1];
+        const i16x8 fr = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        acc_mfma(4 * p4 + d, __builtin_bit_cast(bf16x8, fr), pf[u]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    }
+    end_of_tile();
+  }
+
+  const float l_tot = pair_sum(l_run);
+  if (!row_ok) return;
+  const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * c_scale;  // o_hat = scale * sum_s p_s value(code_s)
+  const int64_t prow = (int64_t)chunk * a.M + rho;
+  __bf16* po = (__bf16*)a.part_o + prow * RKV;
+#pragma unroll
+  for (int dt = 0; dt < DTW; ++dt) {
+    float x[16];
+    acc_read(dt, dt == 0, x);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
+      *(u32x2*)(po + (part * DTW + dt) * 32 + 8 * q + 4 * h) = v;
+    }
+  }
+  if (h == 0 && part == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+}
+
 // ---- combine + latent-output projection: out = W_UV[j]^T (sum_k w_k o_hat_k)   (MQA-absorb equation, line 6) ----
 // One workgroup of 4 waves per (group j, 32 query rows of that group; 8 rows when the batch is small).  W_UV[j] ([r_kv][d_h], 128 KB) is staged in LDS
 // and read transposed; wave w contracts over latent dims [w*RKV/4, (w+1)*RKV/4):
@@ -1122,6 +1447,25 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   // whole blocks of 128 rows (h_q s_q a multiple of 128): the pipelined kernel with shared probabilities; other row
   // counts above 32: one wave per 32 rows, each with its own probabilities
   return a.M % kRowsPerBlock == 0 ? launch_decode_absorb_shared(a, s) : launch_decode_absorb_split<1>(a, s);
+}
+
+template <int SPLIT>
+static hipError_t launch_decode_absorb_fp8_split(const DecodeArgs& a, float c_scale, hipStream_t s) {
+  constexpr int kLds = 2 * kTile * (512 + 64) * 2 + (SPLIT > 1 ? 4 * 4096 : 0);  // two bf16 tile buffers (+ the team exchange)
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)decode_absorb_fp8_kernel<512, 64, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
+  const int row_blocks = (a.M + kRowsPerBlock / SPLIT - 1) / (kRowsPerBlock / SPLIT);
+  const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
+  decode_absorb_fp8_kernel<512, 64, SPLIT><<<chunks_padded * row_blocks, 256, kLds, s>>>(a, row_blocks, c_scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_absorb_fp8(const DecodeArgs& a, float c_scale, hipStream_t s) {
+  // the same choice of row mapping as for the 16-bit cache
+  const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
+  if (a.M <= 32 || chunks_padded * ((a.M + 31) / 32) <= a.num_cus) return launch_decode_absorb_fp8_split<4>(a, c_scale, s);
+  return launch_decode_absorb_fp8_split<1>(a, c_scale, s);
 }
 
 template <int DV>

@@ -725,6 +725,59 @@ gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, 
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
+gqla_status gqla_quantize_latent(const gqla_shape* shape, const gqla_cache* latent, const gqla_cache* latent_fp8,
+                                 float c_scale, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (!latent || !latent_fp8 || !latent->pool || !latent_fp8->pool || !latent->seq_lens) return GQLA_ERR_NULL;
+  if (!aligned16(latent->pool) || !aligned16(latent_fp8->pool)) return GQLA_ERR_ALIGN;
+  if (!(c_scale > 0.f) || !std::isfinite(c_scale)) return GQLA_ERR_SHAPE;
+  st = check_page_size(shape, latent->page_size);
+  if (st != GQLA_OK) return st;
+  if (latent->page_size != latent_fp8->page_size || latent->max_pages != latent_fp8->max_pages || latent->max_pages <= 0 ||
+      latent->num_pages <= 0 || latent_fp8->num_pages <= 0)
+    return GQLA_ERR_PAGE;
+  if (!latent->page_table && (int64_t)latent->num_pages < (int64_t)shape->batch * latent->max_pages) return GQLA_ERR_PAGE;
+  if (!latent_fp8->page_table && (int64_t)latent_fp8->num_pages < (int64_t)shape->batch * latent_fp8->max_pages)
+    return GQLA_ERR_PAGE;
+  if (shape->batch == 0) return GQLA_OK;
+  QuantizeArgs a;
+  a.src = view_of(latent);
+  a.dst = view_of(latent_fp8);
+  a.seq_lens = latent->seq_lens;
+  a.B = shape->batch;
+  a.k_inv_scale = 1.0f / c_scale;
+  a.v_inv_scale = a.k_inv_scale;
+  const hipError_t e = launch_quantize_latent(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_decode_absorb_fp8(const gqla_shape* shape, const gqla_plan* plan, const void* q_hat, const void* q_r,
+                                   const gqla_cache* latent_fp8, float c_scale, const void* w_uv, void* out, float* lse,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  gqla_status st = check_shape(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;
+  if (!(c_scale > 0.f) || !std::isfinite(c_scale)) return GQLA_ERR_SHAPE;
+  st = check_decode_common(shape, plan, GQLA_PATH_ABSORB, latent_fp8, q_hat, q_r, out, lse, ws, ws_bytes);
+  if (st != GQLA_OK) return st;
+  if (!w_uv) return GQLA_ERR_NULL;
+  if (!aligned16(w_uv)) return GQLA_ERR_ALIGN;
+  if (shape->batch == 0) return GQLA_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const DecodeArgs a = decode_args(shape, plan, q_hat, q_r, latent_fp8, ws);
+  CombineArgs c = combine_args(shape, plan, ws, w_uv, out, lse);
+  c.d_h = value_dim(shape);
+  const KernelTimer timer(s);
+  hipError_t e = timer.begin();
+  if (e == hipSuccess) e = launch_decode_absorb_fp8(a, c_scale, s);
+  if (e == hipSuccess) e = timer.end();
+  if (e == hipSuccess) e = launch_combine_project_bf16(c, s);
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+int64_t gqla_latent_fp8_bytes_per_token(int32_t r_kv, int32_t d_r) { return (int64_t)r_kv + 2ll * d_r; }
 int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + 2ll * d_r; }
 int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r) { return (int64_t)r_kv + d_r; }
 int64_t gqla_expanded_elems_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + d_r; }

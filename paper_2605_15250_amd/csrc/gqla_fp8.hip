@@ -82,7 +82,39 @@ __global__ void __launch_bounds__(256) quantize_expanded_kernel(QuantizeArgs a) 
     if (idx % P < valid) *(u32x4*)(rout + (int64_t)idx * 16) = *(const u32x4*)(rin + (int64_t)idx * 16);
 }
 
+// Cache switch 16-bit latent cache -> 8-bit latent cache of the absorb path (gqla.h: code rows [P][r_kv], then k_R
+// [P][d_r] in 16 bits).  One workgroup per (logical page, sequence); a lane converts 8 latent elements at a time, so a
+// wave reads and writes whole rows; only tokens t < L_b are touched.
+template <int RKV, int DR>
+__global__ void __launch_bounds__(256) quantize_latent_kernel(QuantizeArgs a) {
+  const int p = blockIdx.x, b = blockIdx.y;
+  const int L = a.seq_lens[b];
+  const int P = a.src.page_size;
+  if ((int64_t)p * P >= L) return;
+  const int32_t pg_in = page_of(a.src, b, p), pg_out = page_of(a.dst, b, p);
+  if (pg_in < 0 || pg_out < 0) return;
+  const int valid = min(P, L - p * P);
+  const char* in = (const char*)a.src.pool + (int64_t)pg_in * P * (RKV + DR) * 2;
+  char* out = (char*)a.dst.pool + (int64_t)pg_out * P * (RKV + 2 * DR);
+  constexpr int VC = RKV / 8, VR = DR / 8;  // 16-byte input vectors per row: latent, RoPE key
+  for (int idx = threadIdx.x; idx < valid * VC; idx += 256) {
+    const int slot = idx / VC, v = idx % VC;
+    const u32x2 c = e4m3x8(*(const u32x4*)(in + ((int64_t)slot * (RKV + DR) + v * 8) * 2), a.k_inv_scale);
+    *(u32x2*)(out + (int64_t)slot * RKV + v * 8) = c;
+  }
+  for (int idx = threadIdx.x; idx < valid * VR; idx += 256) {
+    const int slot = idx / VR, v = idx % VR;
+    *(u32x4*)(out + (int64_t)P * RKV + ((int64_t)slot * DR + v * 8) * 2) =
+        *(const u32x4*)(in + ((int64_t)slot * (RKV + DR) + RKV + v * 8) * 2);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_quantize_latent(const QuantizeArgs& a, hipStream_t s) {
+  quantize_latent_kernel<512, 64><<<dim3(a.src.max_pages, a.B), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
 
 hipError_t launch_quantize_expanded(const QuantizeArgs& a, hipStream_t s) {
   quantize_expanded_kernel<128, 64><<<dim3(a.src.max_pages, a.B), 256, 0, s>>>(a);

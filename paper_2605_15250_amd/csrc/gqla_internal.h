@@ -130,6 +130,8 @@ hipError_t launch_expand_fp8(const ExpandArgs&, void* ws /* as above */, hipStre
 hipError_t launch_expand_tail_fp8(const ExpandArgs&, void* ws /* as above */, hipStream_t);  // `expanded` is an 8-bit cache
 hipError_t launch_append_latent(const AppendArgs&, hipStream_t);
 hipError_t launch_quantize_expanded(const QuantizeArgs&, hipStream_t);
+hipError_t launch_quantize_latent(const QuantizeArgs&, hipStream_t);  // src: 16-bit latent cache, dst: 8-bit latent cache; k_inv_scale
+hipError_t launch_decode_absorb_fp8(const DecodeArgs&, float c_scale, hipStream_t);  // the cache is an 8-bit latent cache
 hipError_t launch_compress_f32(const CompressArgs&, hipStream_t);
 hipError_t launch_compress_bf16(const CompressArgs&, hipStream_t);
 hipError_t launch_rope_step(const RopeArgs&, bool bf16, hipStream_t);

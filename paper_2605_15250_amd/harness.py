@@ -70,6 +70,7 @@ class Decoder:
         self.latent_pool = None
         self.expanded_pool = None
         self.expanded_fp8_pool = None
+        self.latent_fp8_pool = None
         self.ws_e = None                                        # scratch of the expand call
         self.ws_o = None                                        # scratch of the output projection
 
@@ -199,6 +200,31 @@ class Decoder:
         if lse is None:
             lse = torch.empty((c.B, c.s_q, heads), dtype=torch.float32, device="cuda")
         B.gqla_decode_gqa_fp8(self.shape_gqa, self.plan_g, q_c, q_r, self.expanded_fp8_cache(), k_scale, v_scale, out, lse, self.ws_g)
+        return out, lse
+
+    # -- 8-bit latent cache --------------------------------------------------------------------------------
+    def latent_fp8_page_bytes(self):
+        c = self.cfg
+        return c.page_size * B.gqla_latent_fp8_bytes_per_token(c.r_kv, c.d_r)
+
+    def alloc_latent_fp8(self, fill=0xAA):
+        self.latent_fp8_pool = torch.full((self.num_pages * self.latent_fp8_page_bytes(),), fill, dtype=torch.uint8, device="cuda")
+        return self.latent_fp8_pool
+
+    def latent_fp8_cache(self):
+        return B.make_cache(self.latent_fp8_pool, self.d_lens, self.d_table, self.cfg.page_size, self.max_pages, self.num_pages, 0)
+
+    def quantize_latent(self, c_scale):
+        B.gqla_quantize_latent(self.shape, self.latent_cache(), self.latent_fp8_cache(), c_scale)
+        return self.latent_fp8_pool
+
+    def decode_absorb_fp8(self, q_hat, q_r, c_scale, w_uv, out=None, lse=None):
+        c = self.cfg
+        if out is None:
+            out = torch.empty((c.B, c.s_q, c.h_q, c.dv), dtype=torch_dtype(c.dtype), device="cuda")
+        if lse is None:
+            lse = torch.empty((c.B, c.s_q, c.h_q), dtype=torch.float32, device="cuda")
+        B.gqla_decode_absorb_fp8(self.shape, self.plan_a, q_hat, q_r, self.latent_fp8_cache(), c_scale, w_uv, out, lse, self.ws_a)
         return out, lse
 
     def decode_gqa(self, q_c, q_r, out=None, lse=None):

@@ -179,6 +179,26 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_DTYPE, B.gqla_expand_cache_fp8, f32, B.make_cache(A, A, None, 8, 4, 8, 0), A, A, 0, 2,
                 B.make_cache(A, A, None, 8, 4, 8, 2), 1.0, 1.0, A, 1 << 24, stream=0)
         assert B.gqla_expanded_fp8_bytes_per_token(8, 128, 64) == 2176 and B.gqla_expanded_fp8_bytes_per_token(4, 128, 64) == 1152
+        # the 8-bit latent cache: the same rules
+        lat8 = B.make_cache(A, A, None, 64, 4, 8, 0)
+        _expect(B.GQLA_ERR_DTYPE, B.gqla_quantize_latent, f32, B.make_cache(A, A, None, 8, 4, 8, 0), B.make_cache(A, A, None, 8, 4, 8, 0), 1.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_latent, ok, lat, lat8, 0.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_latent, ok, lat, lat8, float("nan"), stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_quantize_latent, ok, lat, B.make_cache(A, A, None, 128, 4, 8, 0), 1.0, stream=0)
+        _expect(B.GQLA_ERR_PAGE, B.gqla_quantize_latent, ok, lat, B.make_cache(A, A, None, 64, 4, 7, 0), 1.0, stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_quantize_latent, ok, B.make_cache(A, None, None, 64, 4, 8, 0), lat8, 1.0, stream=0)
+        _expect(B.GQLA_ERR_ALIGN, B.gqla_quantize_latent, ok, lat, B.make_cache(A + 8, A, None, 64, 4, 8, 0), 1.0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_decode_absorb_fp8, ok, plan_a, A, A, lat8, -1.0, A, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_decode_absorb_fp8, ok, plan_a, A, A, lat8, float("inf"), A, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_PLAN, B.gqla_decode_absorb_fp8, ok, plan_g, A, A, lat8, 1.0, A, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_decode_absorb_fp8, ok, plan_a, A, A, lat8, 1.0, A, A, None, A, big, stream=0)
+        _expect(B.GQLA_ERR_SEQLEN, B.gqla_decode_absorb_fp8, ok, plan_a, A, A, B.make_cache(A, A, None, 64, 2, 8, 0), 1.0, A, A, None, A, big, stream=0)
+        f32_plan = B.gqla_plan_create(f32, lens, 8, 256, B.GQLA_PATH_ABSORB)
+        try:
+            _expect(B.GQLA_ERR_DTYPE, B.gqla_decode_absorb_fp8, f32, f32_plan, A, A, B.make_cache(A, A, None, 8, 32, 64, 0), 1.0, A, A, None, A, big, stream=0)
+        finally:
+            B.gqla_plan_destroy(f32_plan)
+        assert B.gqla_latent_fp8_bytes_per_token(512, 64) == 640
     finally:
         B.gqla_plan_destroy(plan_a)
         B.gqla_plan_destroy(plan_g)
