@@ -11,8 +11,10 @@ against a second implementation.
 Latent page  (P tokens):   row-major  [P][r_kv + d_R]  =  c_kv | k_R   per token.
 Expanded page (P tokens, g_c groups), three planes of 8-element vectors:
     K_C : [g_c][d_h/8][P][8]     8 consecutive dims of one token are contiguous
-    V   : [g_c][P/8][d_h][8]     8 consecutive tokens of one dim are contiguous
+    V   : [g_c][P/8][d_v][8]     8 consecutive tokens of one dim are contiguous
     k_R : [d_R/8][P][8]
+d_v is the per-head value dim (d_h^V of Sec. 3.2.2); it defaults to d_h, and a token then takes the 2 g d_h + d_R
+elements of Sec. 4.2.2, otherwise g (d_h + d_v) + d_R.
 """
 from __future__ import annotations
 
@@ -24,8 +26,8 @@ def latent_elems_per_token(r_kv, d_r):
     return r_kv + d_r
 
 
-def expanded_elems_per_token(g, d_h, d_r):
-    return 2 * g * d_h + d_r
+def expanded_elems_per_token(g, d_h, d_r, d_v=None):
+    return g * (d_h + (d_h if d_v is None else d_v)) + d_r
 
 
 def pages_needed(L, P):
@@ -49,22 +51,25 @@ def latent_offset(page, slot, col, P, r_kv, d_r):
     return (page * P + slot) * (r_kv + d_r) + col
 
 
-def expanded_page_elems(P, g_c, d_h, d_r):
-    return P * (2 * g_c * d_h + d_r)
+def expanded_page_elems(P, g_c, d_h, d_r, d_v=None):
+    return P * expanded_elems_per_token(g_c, d_h, d_r, d_v)
 
 
-def expanded_k_offset(page, j, slot, d, P, g_c, d_h, d_r):
-    base = page * expanded_page_elems(P, g_c, d_h, d_r)
+def expanded_k_offset(page, j, slot, d, P, g_c, d_h, d_r, d_v=None):
+    base = page * expanded_page_elems(P, g_c, d_h, d_r, d_v)
     return base + ((j * (d_h // 8) + d // 8) * P + slot) * 8 + d % 8
 
 
-def expanded_v_offset(page, j, slot, d, P, g_c, d_h, d_r):
-    base = page * expanded_page_elems(P, g_c, d_h, d_r) + g_c * P * d_h
-    return base + ((j * (P // 8) + slot // 8) * d_h + d) * 8 + slot % 8
+def expanded_v_offset(page, j, slot, d, P, g_c, d_h, d_r, d_v=None):
+    """d in [0, d_v)."""
+    dv = d_h if d_v is None else d_v
+    base = page * expanded_page_elems(P, g_c, d_h, d_r, d_v) + g_c * P * d_h
+    return base + ((j * (P // 8) + slot // 8) * dv + d) * 8 + slot % 8
 
 
-def expanded_kr_offset(page, slot, d, P, g_c, d_h, d_r):
-    base = page * expanded_page_elems(P, g_c, d_h, d_r) + 2 * g_c * P * d_h
+def expanded_kr_offset(page, slot, d, P, g_c, d_h, d_r, d_v=None):
+    dv = d_h if d_v is None else d_v
+    base = page * expanded_page_elems(P, g_c, d_h, d_r, d_v) + g_c * P * (d_h + dv)
     return base + ((d // 8) * P + slot) * 8 + d % 8
 
 
@@ -80,11 +85,12 @@ def pack_latent_pool(seq_rows, table, num_pages, P, width, fill=np.nan):
 
 
 def pack_expanded_pool(KC_seqs, V_seqs, kR_seqs, table, num_pages, P, fill=np.nan):
-    """KC_seqs[b], V_seqs[b] = [L_b, g_c, d_h]; kR_seqs[b] = [L_b, d_r].
+    """KC_seqs[b] = [L_b, g_c, d_h], V_seqs[b] = [L_b, g_c, d_v]; kR_seqs[b] = [L_b, d_r].
     Returns a flat fp32 pool of num_pages * expanded_page_elems elements; unused slots = fill."""
     L0, g_c, d_h = KC_seqs[0].shape
+    d_v = V_seqs[0].shape[2]
     d_r = kR_seqs[0].shape[1]
-    pe = expanded_page_elems(P, g_c, d_h, d_r)
+    pe = expanded_page_elems(P, g_c, d_h, d_r, d_v)
     pool = np.full((num_pages * pe,), fill, dtype=np.float32)
     for b in range(len(KC_seqs)):
         L = KC_seqs[b].shape[0]
@@ -93,34 +99,37 @@ def pack_expanded_pool(KC_seqs, V_seqs, kR_seqs, table, num_pages, P, fill=np.na
         slot = (t % P).astype(np.int64)
         base = page * pe
         d = np.arange(d_h, dtype=np.int64)
+        e = np.arange(d_v, dtype=np.int64)
         for j in range(g_c):
             ko = base[:, None] + ((j * (d_h // 8) + d[None, :] // 8) * P + slot[:, None]) * 8 + d[None, :] % 8
             pool[ko] = KC_seqs[b][:, j, :]
             vo = (base[:, None] + g_c * P * d_h
-                  + ((j * (P // 8) + slot[:, None] // 8) * d_h + d[None, :]) * 8 + slot[:, None] % 8)
+                  + ((j * (P // 8) + slot[:, None] // 8) * d_v + e[None, :]) * 8 + slot[:, None] % 8)
             pool[vo] = V_seqs[b][:, j, :]
         dr = np.arange(d_r, dtype=np.int64)
-        ro = base[:, None] + 2 * g_c * P * d_h + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8
+        ro = base[:, None] + g_c * P * (d_h + d_v) + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8
         pool[ro] = kR_seqs[b]
     return pool
 
 
-def unpack_expanded_seq(pool, page_row, L, P, g_c, d_h, d_r):
-    """Inverse of pack_expanded_pool for one sequence: (KC [L,g_c,d_h], V [L,g_c,d_h], kR [L,d_r])."""
-    pe = expanded_page_elems(P, g_c, d_h, d_r)
+def unpack_expanded_seq(pool, page_row, L, P, g_c, d_h, d_r, d_v=None):
+    """Inverse of pack_expanded_pool for one sequence: (KC [L,g_c,d_h], V [L,g_c,d_v], kR [L,d_r])."""
+    d_v = d_h if d_v is None else d_v
+    pe = expanded_page_elems(P, g_c, d_h, d_r, d_v)
     t = np.arange(int(L))
     page = np.asarray(page_row)[t // P].astype(np.int64)
     slot = (t % P).astype(np.int64)
     base = page * pe
     d = np.arange(d_h, dtype=np.int64)
+    e = np.arange(d_v, dtype=np.int64)
     KC = np.empty((int(L), g_c, d_h), pool.dtype)
-    V = np.empty((int(L), g_c, d_h), pool.dtype)
+    V = np.empty((int(L), g_c, d_v), pool.dtype)
     for j in range(g_c):
         KC[:, j, :] = pool[base[:, None] + ((j * (d_h // 8) + d[None, :] // 8) * P + slot[:, None]) * 8 + d[None, :] % 8]
         V[:, j, :] = pool[base[:, None] + g_c * P * d_h
-                          + ((j * (P // 8) + slot[:, None] // 8) * d_h + d[None, :]) * 8 + slot[:, None] % 8]
+                          + ((j * (P // 8) + slot[:, None] // 8) * d_v + e[None, :]) * 8 + slot[:, None] % 8]
     dr = np.arange(d_r, dtype=np.int64)
-    kR = pool[base[:, None] + 2 * g_c * P * d_h + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8]
+    kR = pool[base[:, None] + g_c * P * (d_h + d_v) + ((dr[None, :] // 8) * P + slot[:, None]) * 8 + dr[None, :] % 8]
     return KC, V, kR
 
 

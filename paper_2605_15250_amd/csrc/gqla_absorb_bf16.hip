@@ -1442,8 +1442,6 @@ hipError_t launch_decode_absorb_bf16(const DecodeArgs& a, hipStream_t s) {
   // with so few chunks the chip is nowhere near its memory rate).
   const int chunks_padded = (a.n_chunks + 7) / 8 * 8;
   if (a.M <= 32 || chunks_padded * ((a.M + 31) / 32) <= a.num_cus) return launch_decode_absorb_split<4>(a, s);
-  static const bool old_kernel = getenv("GQLA_ABSORB_OLD") != nullptr;  // TEMPORARY: A/B switch while the new kernel is measured
-  if (old_kernel) return launch_decode_absorb_split<1>(a, s);
   // whole blocks of 128 rows (h_q s_q a multiple of 128): the pipelined kernel with shared probabilities; other row
   // counts above 32: one wave per 32 rows, each with its own probabilities
   return a.M % kRowsPerBlock == 0 ? launch_decode_absorb_shared(a, s) : launch_decode_absorb_split<1>(a, s);

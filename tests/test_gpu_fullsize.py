@@ -222,6 +222,50 @@ def test_c2_absorb_sq1():
         case.close()
 
 
+def test_c2_fp8_latent_at_full_size():
+    """configs[2] over the 8-bit latent cache (Sec. 2 / Sec. 5.1 (i): quantised caches; format of this build): the
+    quantising cache switch on the GPU holds the oracle's codes bit for bit on sampled sequences, and the decode is
+    checked on sampled (sequence, group) slices against the oracle's MQA-absorb decode (Sec. 3.1) on the dequantised
+    latent, consuming the q_hat bits the GPU consumes."""
+    from oracle import fp8_cache as F8
+    cfg = S.CONFIGS["C2"]
+    case = FullCase(cfg)
+    dec = case.dec
+    c_scale = 2.0 ** -6      # standard-normal latent: |c| / scale stays below 448
+    try:
+        G = cfg.h_q // cfg.g
+        dec.alloc_latent_fp8(fill=0xAA)
+        dec.quantize_latent(c_scale)
+        q_hat = dec.absorb_query(case.d(case.q_c), case.d_w_uk)
+        out8, lse8 = dec.decode_absorb_fp8(q_hat, case.d(case.q_r), c_scale, case.d_w_uv)
+        torch.cuda.synchronize()
+        o8, l8 = out8.float().cpu().numpy(), lse8.cpu().numpy()
+        qh = q_hat.float().cpu().numpy()
+        assert np.isfinite(o8).all() and np.isfinite(l8).all()
+        pool = dec.latent_fp8_pool.cpu().numpy()
+        P, pb = cfg.page_size, F8.latent_fp8_page_bytes(cfg.page_size, cfg.r_kv, cfg.d_r)
+        for b in case.sample_sequences(4):
+            c, kR = case.rows(b)
+            codes = F8.quantize_tensor(c, c_scale)
+            # the GPU's codes and k_R bits of this sequence, page by page
+            L = int(case.lens[b])
+            kr_bits = (np.ascontiguousarray(kR, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+            for p in range((L + P - 1) // P):
+                n = min(P, L - p * P)
+                base = int(case.table[b][p]) * pb
+                assert np.array_equal(pool[base: base + n * cfg.r_kv].reshape(n, cfg.r_kv), codes[p * P: p * P + n]), (b, p)
+                got_kr = pool[base + P * cfg.r_kv: base + P * cfg.r_kv + n * cfg.d_r * 2].view(np.uint16).reshape(n, cfg.d_r)
+                assert np.array_equal(got_kr, kr_bits[p * P: p * P + n]), (b, p)
+            c_deq = F8.dequantize_e4m3(codes) * c_scale
+            for j in (0, 3, 7):
+                hs = slice(j * G, (j + 1) * G)
+                ref_o, ref_l = O.decode_absorb(qh[b][:, hs], case.q_r[b][:, hs], c_deq, kR, case.w_uv[j:j + 1])
+                check("absorb over the 8-bit latent  b=%d L=%d group %d" % (b, L, j), o8[b][:, hs], ref_o)
+                assert float(np.max(np.abs(l8[b][:, hs] - ref_l))) <= 2e-2
+    finally:
+        case.close()
+
+
 def test_c3_single_group_slice():
     """One GPU's share of 8-way head-axis tensor parallelism: group 3 only, 320 cached elements per token."""
     cfg = S.CONFIGS["C3"]

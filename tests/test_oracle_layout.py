@@ -59,6 +59,55 @@ def test_packers_restate_scalar_offsets():
     assert np.isnan(pool).sum() == 5 * Lay.expanded_page_elems(P, g_c, d_h, d_r) - sum(lens) * (2 * g_c * d_h + d_r)
 
 
+@pytest.mark.parametrize("P,g_c,d_h,d_v,d_r", [(16, 2, 16, 24, 8), (64, 4, 192, 256, 64), (8, 3, 24, 8, 16)])
+def test_expanded_offsets_with_a_value_dim_of_its_own(P, g_c, d_h, d_v, d_r):
+    """d_h^V != d_h (Sec. 3.2.2): a token takes g (d_h + d_v) + d_R elements, the three planes still tile the page
+    exactly once, V vectors still hold 8 consecutive tokens of one dim, and d_v = d_h gives the equal-dims offsets."""
+    pe = Lay.expanded_page_elems(P, g_c, d_h, d_r, d_v)
+    assert pe == P * (g_c * (d_h + d_v) + d_r)
+    page = 2
+    seen = np.zeros(pe, dtype=np.int32)
+    for s in range(P):
+        for j in range(g_c):
+            for d in range(d_h):
+                seen[Lay.expanded_k_offset(page, j, s, d, P, g_c, d_h, d_r, d_v) - page * pe] += 1
+            for d in range(d_v):
+                seen[Lay.expanded_v_offset(page, j, s, d, P, g_c, d_h, d_r, d_v) - page * pe] += 1
+        for d in range(d_r):
+            seen[Lay.expanded_kr_offset(page, s, d, P, g_c, d_h, d_r, d_v) - page * pe] += 1
+    assert (seen == 1).all()
+    for s in range(7):
+        assert (Lay.expanded_v_offset(1, g_c - 1, s + 1, d_v - 1, P, g_c, d_h, d_r, d_v)
+                == Lay.expanded_v_offset(1, g_c - 1, s, d_v - 1, P, g_c, d_h, d_r, d_v) + 1)
+    # the planes come in the order K, V, k_R: the first V element sits right behind the last K element
+    assert Lay.expanded_v_offset(0, 0, 0, 0, P, g_c, d_h, d_r, d_v) == g_c * P * d_h
+    assert Lay.expanded_kr_offset(0, 0, 0, P, g_c, d_h, d_r, d_v) == g_c * P * (d_h + d_v)
+    for args in ((1, 1, 3, 5), (0, 0, 7, 0)):
+        assert Lay.expanded_v_offset(*args, P, g_c, d_h, d_r, d_h) == Lay.expanded_v_offset(*args, P, g_c, d_h, d_r)
+        assert Lay.expanded_k_offset(*args, P, g_c, d_h, d_r, d_h) == Lay.expanded_k_offset(*args, P, g_c, d_h, d_r)
+    # packer and unpacker restate the scalar offsets
+    r = np.random.default_rng(1)
+    lens = [P + 3, 2]
+    table = np.array([[1, 3], [0, -1]], dtype=np.int32)
+    KC = [r.standard_normal((L, g_c, d_h)).astype(np.float32) for L in lens]
+    V = [r.standard_normal((L, g_c, d_v)).astype(np.float32) for L in lens]
+    kR = [r.standard_normal((L, d_r)).astype(np.float32) for L in lens]
+    pool = Lay.pack_expanded_pool(KC, V, kR, table, 4, P)
+    assert pool.size == 4 * pe and np.isnan(pool).sum() == 4 * pe - sum(lens) * (g_c * (d_h + d_v) + d_r)
+    for b, L in enumerate(lens):
+        for t in (0, L - 1):
+            pg, slot = Lay.phys_token(table[b], t, P)
+            for j in (0, g_c - 1):
+                for d in range(d_h):
+                    assert pool[Lay.expanded_k_offset(pg, j, slot, d, P, g_c, d_h, d_r, d_v)] == KC[b][t, j, d]
+                for d in range(d_v):
+                    assert pool[Lay.expanded_v_offset(pg, j, slot, d, P, g_c, d_h, d_r, d_v)] == V[b][t, j, d]
+            for d in range(d_r):
+                assert pool[Lay.expanded_kr_offset(pg, slot, d, P, g_c, d_h, d_r, d_v)] == kR[b][t, d]
+        k2, v2, r2 = Lay.unpack_expanded_seq(pool, table[b], L, P, g_c, d_h, d_r, d_v)
+        assert np.array_equal(k2, KC[b]) and np.array_equal(v2, V[b]) and np.array_equal(r2, kR[b])
+
+
 def test_latent_offsets_and_phys_token():
     P, r_kv, d_r = 64, 512, 64
     assert Lay.latent_offset(0, 0, 0, P, r_kv, d_r) == 0
