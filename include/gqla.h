@@ -29,22 +29,24 @@
  *   - dtype GQLA_BF16: caches, queries, weights, q_hat and out are bf16; all accumulation, softmax
  *     and the log-sum-exps are fp32 (split partials: fp32 on the GQA path, bf16 in latent space on the absorb
  *     path); QK^T and PV run on bf16 MFMA.  Shape limits of the MFMA
- *     kernels: d_h = 128, d_r = 64, r_kv = 512, page_size a multiple of 64 (<= 1024).
+ *     kernels: (d_h, d_v) = (128, 128) or (192, 256) wherever an expanded cache is involved (see gqla_shape.d_v for
+ *     the absorb path), d_r = 64, r_kv = 512, page_size a multiple of 64 (<= 1024).
  *     dtype GQLA_F32: everything fp32 on the vector ALU; d_h, d_v, d_r, r_kv, page_size multiples of 8, and
  *     d_h, d_v, r_kv at most 512 (GQLA_ERR_SHAPE beyond).
  *
  * Tensor layouts (row-major, last index fastest)
  *   q_c   [B][s_q][h_q][d_h]      q_r  [B][s_q][h_q][d_r]     q_hat [B][s_q][h_q][r_kv]
- *   w_uk, w_uv  [g][r_kv][d_h]    (the transpose of the paper's d_h x r_kv head slice)
- *   out   [B][s_q][h_q][d_h]      lse  [B][s_q][h_q]  (fp32, natural log of the softmax denominator)
+ *   w_uk  [g][r_kv][d_h]   w_uv  [g][r_kv][d_v]   (the transpose of the paper's d_h x r_kv head slice)
+ *   out   [B][s_q][h_q][d_v]      lse  [B][s_q][h_q]  (fp32, natural log of the softmax denominator)
+ *   (d_v = d_h unless the shape names a value dim of its own, d_h^V of Sec. 3.2.2)
  *
  * Cache pools (gqla_cache.pool): pages of page_size (P) tokens, back to back.
  *   latent page    [P][r_kv + d_r]           per token: c_kv | k_R           (Sec. 4.2.1: r_kv + d_r elements)
- *   expanded page, g_c groups (Sec. 4.2.2: 2 g d_h + d_r elements per token), three planes of
- *   8-element vectors so that every 16-byte vector is already an MFMA operand fragment:
+ *   expanded page, g_c groups (Sec. 4.2.2: 2 g d_h + d_r elements per token; g (d_h + d_v) + d_r with a value dim
+ *   of its own), three planes of 8-element vectors so that every 16-byte vector is already an MFMA operand fragment:
  *       K_C : [g_c][d_h/8][P][8]     element (j, slot s, dim d) at ((j*(d_h/8) + d/8)*P + s)*8 + d%8
- *       V   : [g_c][P/8][d_h][8]     element (j, s, d) at g_c*P*d_h + ((j*(P/8) + s/8)*d_h + d)*8 + s%8
- *       k_R : [d_r/8][P][8]          element (s, d)    at 2*g_c*P*d_h + ((d/8)*P + s)*8 + d%8
+ *       V   : [g_c][P/8][d_v][8]     element (j, s, d) at g_c*P*d_h + ((j*(P/8) + s/8)*d_v + d)*8 + s%8
+ *       k_R : [d_r/8][P][8]          element (s, d)    at g_c*P*(d_h + d_v) + ((d/8)*P + s)*8 + d%8
  *   Logical token t of sequence b lives in page  page_table[b*max_pages + t/P]  (or b*max_pages + t/P
  *   when page_table is NULL) at slot t % P.  Slots at or beyond L_b are never used by a decode call
  *   (whatever bits they hold) and never written by gqla_expand_cache.
@@ -86,12 +88,13 @@ typedef struct {
   int32_t dtype;   /*     gqla_dtype                                         */
   float scale;     /*     softmax scale; 0 selects 1/sqrt(d_h + d_r) (Sec. 3.1) */
   int32_t d_v;     /*     per-head value dim d_h^V; 0 selects d_h.  A value dim of its own (the MLA checkpoints of
-                          Sec. 3.2.2: d_h = 192, d_h^V = 256) exists on the absorb path only: gqla_plan_create
-                          (GQLA_PATH_ABSORB), gqla_absorb_query, gqla_decode_absorb (w_uv [g][r_kv][d_v], out
-                          [B][s_q][h_q][d_v]), gqla_rope_step, gqla_append_latent, gqla_output_projection (w_o
-                          [d_model][h_q * d_v]) and gqla_estimate_paths accept it; every call that touches an expanded
-                          cache returns GQLA_ERR_SHAPE.  GQLA_BF16 supports d_h in {128, 192}, d_v in {128, 256},
-                          r_kv = 512, d_r = 64 (expanded cache: d_h = d_v = 128). */
+                          Sec. 3.2.2: d_h = 192, d_h^V = 256): w_uv is [g][r_kv][d_v], out [B][s_q][h_q][d_v], w_o
+                          [d_model][h_q * d_v], the expanded cache's V plane has d_v dims.  GQLA_BF16: the absorb path
+                          (gqla_absorb_query, gqla_decode_absorb and its 8-bit variant) takes d_h in {128, 192} and d_v
+                          in {128, 256}; everything over a 16-bit expanded cache (gqla_expand_cache and its tail
+                          variants, gqla_decode_gqa, gqla_compress_cache, plans for GQLA_PATH_GQA) takes (d_h, d_v) =
+                          (128, 128) or (192, 256); the 8-bit expanded cache and gqla_select_path take (128, 128) only.
+                          Other combinations: GQLA_ERR_SHAPE.  r_kv = 512, d_r = 64. */
 } gqla_shape;
 
 typedef struct {
@@ -170,7 +173,8 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
 gqla_status gqla_expand_cache(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk,
                               const void* w_uv, int32_t group_begin, int32_t group_count,
                               const gqla_cache* expanded, void* ws, size_t ws_bytes, void* stream);
-/* Bytes of scratch gqla_expand_cache needs for a slice of group_count groups (0 for GQLA_F32 or a bad shape). */
+/* Bytes of scratch gqla_expand_cache needs for a slice of group_count groups: group_count * r_kv * (d_h + d_v) * 2
+ * (0 for GQLA_F32 or a bad shape). */
 size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count);
 
 /* ---- the per-step cache updates around the two decode paths (Sec. 3.1: each step caches the new token's c_kv and
@@ -197,7 +201,7 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
  * slice's weights in matrix-core order) lives in a fixed 2 MiB device array inside the library instead of a
  * caller-supplied workspace, and the call allocates and frees nothing.  Every GPU the process uses holds its own copy of
  * that array until the process ends.  Limit: gqla_expand_workspace_bytes(shape, group_count) must not exceed
- * gqla_expand_cache_tail_static_max_workspace() (2 MiB: up to 8 groups at r_kv = 512, d_h = 128 in bf16);
+ * gqla_expand_cache_tail_static_max_workspace() (2 MiB: up to 8 groups at r_kv = 512, d_h = d_v = 128 in bf16, up to 4 at d_h = 192, d_v = 256);
  * GQLA_ERR_WORKSPACE beyond that, before anything is launched.  All calls on one GPU share the array: two such calls
  * whose kernels can overlap (different streams without an ordering between them) race on it; calls on one stream, or
  * ordered by events, are safe.  The array keeps the previous call's content; each call overwrites the part it uses
@@ -321,6 +325,12 @@ int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page
 int64_t gqla_expanded_k_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_v_offset(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
 int64_t gqla_expanded_kr_offset(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_r);
+/* The same for an expanded cache whose value dim differs from its key dim (d_h^V of Sec. 3.2.2; d in [0, d_v) for the V
+ * plane); with d_v = d_h they return what the functions above return. */
+int64_t gqla_expanded_elems_per_token_dv(int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r);
+int64_t gqla_expanded_k_offset_dv(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r);
+int64_t gqla_expanded_v_offset_dv(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r);
+int64_t gqla_expanded_kr_offset_dv(int64_t page, int32_t slot, int32_t d, int32_t page_size, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r);
 
 /* Path selection: one set of weights serves both paths and the serving runtime picks, per device, the one its
  * hardware runs faster (Abstract); the two-roof time model that decides it is Sec. 4.2.3.  The paper's Roofline

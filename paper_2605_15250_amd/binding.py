@@ -31,6 +31,7 @@ EXPORTS = [
     "gqla_output_projection_workspace_bytes",
     "gqla_decode_gqa", "gqla_latent_elems_per_token", "gqla_expanded_elems_per_token", "gqla_latent_offset",
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
+    "gqla_expanded_elems_per_token_dv", "gqla_expanded_k_offset_dv", "gqla_expanded_v_offset_dv", "gqla_expanded_kr_offset_dv",
     "gqla_time_next_decode_kernel", "gqla_expand_cache_tail_static", "gqla_expand_cache_tail_static_max_workspace",
 ]
 
@@ -152,6 +153,13 @@ def lib():
             getattr(L, name).restype = i64
         L.gqla_expanded_kr_offset.argtypes = [i64, i32, i32, i32, i32, i32, i32]
         L.gqla_expanded_kr_offset.restype = i64
+        L.gqla_expanded_elems_per_token_dv.argtypes = [i32, i32, i32, i32]
+        L.gqla_expanded_elems_per_token_dv.restype = i64
+        for name in ("gqla_expanded_k_offset_dv", "gqla_expanded_v_offset_dv"):
+            getattr(L, name).argtypes = [i64, i32, i32, i32, i32, i32, i32, i32, i32]
+            getattr(L, name).restype = i64
+        L.gqla_expanded_kr_offset_dv.argtypes = [i64, i32, i32, i32, i32, i32, i32, i32]
+        L.gqla_expanded_kr_offset_dv.restype = i64
         L.gqla_time_next_decode_kernel.argtypes = [vp, vp]
         L.gqla_time_next_decode_kernel.restype = i32
         L.gqla_status_string.argtypes = [i32]
@@ -421,3 +429,19 @@ def gqla_expanded_v_offset(page, j, slot, d, page_size, groups, d_h, d_r) -> int
 
 def gqla_expanded_kr_offset(page, slot, d, page_size, groups, d_h, d_r) -> int:
     return lib().gqla_expanded_kr_offset(page, slot, d, page_size, groups, d_h, d_r)
+
+
+def gqla_expanded_elems_per_token_dv(groups, d_h, d_v, d_r) -> int:
+    return lib().gqla_expanded_elems_per_token_dv(groups, d_h, d_v, d_r)
+
+
+def gqla_expanded_k_offset_dv(page, j, slot, d, page_size, groups, d_h, d_v, d_r) -> int:
+    return lib().gqla_expanded_k_offset_dv(page, j, slot, d, page_size, groups, d_h, d_v, d_r)
+
+
+def gqla_expanded_v_offset_dv(page, j, slot, d, page_size, groups, d_h, d_v, d_r) -> int:
+    return lib().gqla_expanded_v_offset_dv(page, j, slot, d, page_size, groups, d_h, d_v, d_r)
+
+
+def gqla_expanded_kr_offset_dv(page, slot, d, page_size, groups, d_h, d_v, d_r) -> int:
+    return lib().gqla_expanded_kr_offset_dv(page, slot, d, page_size, groups, d_h, d_v, d_r)

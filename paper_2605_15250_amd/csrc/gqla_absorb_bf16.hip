@@ -42,17 +42,6 @@ namespace gqla {
 
 namespace {
 
-// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), straight-line code from the start
-// (register arrays indexed by the counter are then promoted to registers even when the body is large)
-template <int... I, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
-}
-
 __device__ __forceinline__ float max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));

@@ -34,8 +34,19 @@ gqla_status check_shape(const gqla_shape* s) {
   return GQLA_OK;
 }
 
-// The expanded cache and everything that reads or writes it (GQA path, cache switches, 8-bit cache) is built for equal
-// key and value dims (and, in bf16, for d_h = 128); a value dim of its own exists on the absorb path only.
+// The 16-bit expanded cache and what reads or writes it (GQA path, the cache switches in both directions): in bf16 the
+// kernels exist for (d_h, d_v) = (128, 128) and (192, 256) (the shape of Sec. 3.2.2); fp32 takes any dims.
+gqla_status check_shape_expanded(const gqla_shape* s) {
+  const gqla_status st = check_shape(s);
+  if (st != GQLA_OK) return st;
+  if (s->dtype == GQLA_BF16) {
+    const int32_t d_v = value_dim(s);
+    if (!((s->d_h == 128 && d_v == 128) || (s->d_h == 192 && d_v == 256))) return GQLA_ERR_SHAPE;
+  }
+  return GQLA_OK;
+}
+
+// The 8-bit expanded cache (and the calibrated path choice) is built for equal key and value dims of 128.
 gqla_status check_shape_equal_dims(const gqla_shape* s) {
   const gqla_status st = check_shape(s);
   if (st != GQLA_OK) return st;
@@ -115,7 +126,7 @@ WsLayout make_layout(const gqla_plan& p) {
   w.first_slot_off = align_up(n * sizeof(ChunkEntry), 16);
   w.part_o_off = align_up(w.first_slot_off + (p.shape.batch + 1) * sizeof(int32_t), 256);
   size_t po;
-  if (p.path == GQLA_PATH_GQA) po = n * M * p.shape.d_h * 4;
+  if (p.path == GQLA_PATH_GQA) po = n * M * value_dim(&p.shape) * 4;
   else po = n * M * p.shape.r_kv * (p.shape.dtype == GQLA_BF16 ? 2 : 4);
   w.part_lse_off = align_up(w.part_o_off + po, 256);
   w.total = align_up(w.part_lse_off + n * M * 4, 256);
@@ -125,7 +136,7 @@ WsLayout make_layout(const gqla_plan& p) {
 gqla_status check_decode_common(const gqla_shape* shape, const gqla_plan* plan, int32_t path, const gqla_cache* cache,
                                 const void* qa, const void* qr, const void* out, const float* lse, const void* ws,
                                 size_t ws_bytes) {
-  gqla_status st = path == GQLA_PATH_GQA ? check_shape_equal_dims(shape) : check_shape(shape);
+  gqla_status st = path == GQLA_PATH_GQA ? check_shape_expanded(shape) : check_shape(shape);
   if (st != GQLA_OK) return st;
   if (!plan || !qa || !qr || !out || !ws) return GQLA_ERR_NULL;
   if (!same_shape(plan->shape, *shape) || plan->path != path) return GQLA_ERR_PLAN;
@@ -177,6 +188,7 @@ DecodeArgs decode_args(const gqla_shape* s, const gqla_plan* plan, const void* q
   a.g = s->g;
   a.G = s->h_q / s->g;
   a.d_h = s->d_h;
+  a.d_v = value_dim(s);
   a.r_kv = s->r_kv;
   a.d_r = s->d_r;
   a.s_q = s->s_q;
@@ -217,7 +229,7 @@ gqla_status gqla_plan_create(const gqla_shape* shape, const int32_t* seq_lens_ho
   if (st != GQLA_OK) return st;
   if (!seq_lens_host && shape->batch > 0) return GQLA_ERR_NULL;
   if (path != GQLA_PATH_ABSORB && path != GQLA_PATH_GQA) return GQLA_ERR_PLAN;
-  if (path == GQLA_PATH_GQA && check_shape_equal_dims(shape) != GQLA_OK) return GQLA_ERR_SHAPE;
+  if (path == GQLA_PATH_GQA && check_shape_expanded(shape) != GQLA_OK) return GQLA_ERR_SHAPE;
   if (num_cus <= 0 || chunk_pages_override < 0) return GQLA_ERR_SHAPE;
   st = check_page_size(shape, page_size);
   if (st != GQLA_OK) return st;
@@ -355,8 +367,8 @@ gqla_status gqla_decode_absorb(const gqla_shape* shape, const gqla_plan* plan, c
 }
 
 size_t gqla_expand_workspace_bytes(const gqla_shape* shape, int32_t group_count) {
-  if (!shape || check_shape_equal_dims(shape) != GQLA_OK || shape->dtype != GQLA_BF16 || group_count <= 0) return 0;
-  return (size_t)2 * group_count * shape->r_kv * shape->d_h * 2;  // both weight slices in fragment order, bf16
+  if (!shape || check_shape_expanded(shape) != GQLA_OK || shape->dtype != GQLA_BF16 || group_count <= 0) return 0;
+  return (size_t)group_count * shape->r_kv * (shape->d_h + value_dim(shape)) * 2;  // both weight slices in fragment order, bf16
 }
 
 namespace {
@@ -364,7 +376,7 @@ namespace {
 gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
                         int32_t group_begin, int32_t group_count, const gqla_cache* expanded, int32_t tail, void* ws,
                         size_t ws_bytes, void* stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f) {
-  gqla_status st = check_shape_equal_dims(shape);
+  gqla_status st = fp8 ? check_shape_equal_dims(shape) : check_shape_expanded(shape);
   if (st != GQLA_OK) return st;
   if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
   if (!aligned16(w_uk) || !aligned16(w_uv) || !aligned16(latent->pool) || !aligned16(expanded->pool)) return GQLA_ERR_ALIGN;
@@ -391,6 +403,7 @@ gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const
   a.B = shape->batch;
   a.g = shape->g;
   a.d_h = shape->d_h;
+  a.d_v = value_dim(shape);
   a.r_kv = shape->r_kv;
   a.d_r = shape->d_r;
   a.group_begin = group_begin;
@@ -457,7 +470,7 @@ gqla_status gqla_expand_cache_tail_static(const gqla_shape* shape, const gqla_ca
                                           const void* w_uv, int32_t group_begin, int32_t group_count,
                                           const gqla_cache* expanded, int32_t tail_tokens, void* stream) {
   if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
-  const gqla_status st = check_shape_equal_dims(shape);
+  const gqla_status st = check_shape_expanded(shape);
   if (st != GQLA_OK) return st;
   if (shape->dtype != GQLA_BF16)  // the fp32 kernels use no scratch at all
     return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, nullptr, 0, stream);
@@ -519,7 +532,8 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   if (shape->batch == 0) return GQLA_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const DecodeArgs a = decode_args(shape, plan, q_c, q_r, expanded, ws);
-  const CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
+  CombineArgs c = combine_args(shape, plan, ws, nullptr, out, lse);
+  c.d_h = value_dim(shape);  // partials and outputs are value dims
   const KernelTimer timer(s);
   hipError_t e = timer.begin();
   if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
@@ -646,7 +660,7 @@ gqla_status gqla_left_inverse(const gqla_shape* shape, const float* w_uk_host, f
 
 gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expanded, const void* w_inv,
                                 const gqla_cache* latent, void* stream) {
-  gqla_status st = check_shape_equal_dims(shape);
+  gqla_status st = check_shape_expanded(shape);
   if (st != GQLA_OK) return st;
   if (!expanded || !latent || !w_inv || !expanded->pool || !latent->pool || !expanded->seq_lens) return GQLA_ERR_NULL;
   if (!aligned16(w_inv) || !aligned16(expanded->pool) || !aligned16(latent->pool)) return GQLA_ERR_ALIGN;
@@ -667,6 +681,7 @@ gqla_status gqla_compress_cache(const gqla_shape* shape, const gqla_cache* expan
   a.B = shape->batch;
   a.g = shape->g;
   a.d_h = shape->d_h;
+  a.d_v = value_dim(shape);
   a.r_kv = shape->r_kv;
   a.d_r = shape->d_r;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -781,6 +796,20 @@ int64_t gqla_latent_fp8_bytes_per_token(int32_t r_kv, int32_t d_r) { return (int
 int64_t gqla_expanded_fp8_bytes_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + 2ll * d_r; }
 int64_t gqla_latent_elems_per_token(int32_t r_kv, int32_t d_r) { return (int64_t)r_kv + d_r; }
 int64_t gqla_expanded_elems_per_token(int32_t groups, int32_t d_h, int32_t d_r) { return 2ll * groups * d_h + d_r; }
+int64_t gqla_expanded_elems_per_token_dv(int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r) {
+  return (int64_t)groups * ((int64_t)d_h + d_v) + d_r;
+}
+int64_t gqla_expanded_k_offset_dv(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r) {
+  return page * P * gqla_expanded_elems_per_token_dv(groups, d_h, d_v, d_r) + (((int64_t)j * (d_h / 8) + d / 8) * P + slot) * 8 + d % 8;
+}
+int64_t gqla_expanded_v_offset_dv(int64_t page, int32_t j, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r) {
+  return page * P * gqla_expanded_elems_per_token_dv(groups, d_h, d_v, d_r) + (int64_t)groups * P * d_h +
+         (((int64_t)j * (P / 8) + slot / 8) * d_v + d) * 8 + slot % 8;
+}
+int64_t gqla_expanded_kr_offset_dv(int64_t page, int32_t slot, int32_t d, int32_t P, int32_t groups, int32_t d_h, int32_t d_v, int32_t d_r) {
+  return page * P * gqla_expanded_elems_per_token_dv(groups, d_h, d_v, d_r) + (int64_t)groups * P * ((int64_t)d_h + d_v) +
+         ((int64_t)(d / 8) * P + slot) * 8 + d % 8;
+}
 int64_t gqla_latent_offset(int64_t page, int32_t slot, int32_t col, int32_t page_size, int32_t r_kv, int32_t d_r) {
   return (page * page_size + slot) * ((int64_t)r_kv + d_r) + col;
 }

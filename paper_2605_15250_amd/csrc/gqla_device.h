@@ -8,6 +8,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "gqla_internal.h"
 
 // Names of all 256 accumulation registers, for the clobber list of kernels that address them by name in inline
@@ -20,6 +23,17 @@
       GQLA_A10(21), GQLA_A10(22), GQLA_A10(23), GQLA_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
 
 namespace gqla {
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), straight-line code from the start
+// (register arrays indexed by the counter are then promoted to registers even when the body is large)
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;

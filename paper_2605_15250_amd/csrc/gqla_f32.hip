@@ -43,12 +43,12 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
   const int t = rho / a.h_q, i = rho % a.h_q, j = i / a.G;
   const int P = a.cache.page_size;
   const int dk = kAbsorb ? a.r_kv : a.d_h;  // content part of the key
-  const int dv = kAbsorb ? a.r_kv : a.d_h;  // value dims
+  const int dv = kAbsorb ? a.r_kv : a.d_v;  // value dims
   const float* qa = (const float*)a.q_a + ((int64_t)(ce.b * a.s_q + t) * a.h_q + i) * dk;
   const float* qr = (const float*)a.q_r + ((int64_t)(ce.b * a.s_q + t) * a.h_q + i) * a.d_r;
   const float* pool = (const float*)a.cache.pool;
   const int gc = a.cache.groups;
-  const int64_t page_elems = kAbsorb ? (int64_t)P * (a.r_kv + a.d_r) : (int64_t)P * (2 * gc * a.d_h + a.d_r);
+  const int64_t page_elems = kAbsorb ? (int64_t)P * (a.r_kv + a.d_r) : (int64_t)P * (gc * (a.d_h + a.d_v) + a.d_r);
   const int vis_end = min(ce.tok_end, ce.L - a.s_q + t + 1);
 
   float m_run = GQLA_NEG_INF, l_run = 0.f;
@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
       } else {
         for (int d = 0; d < a.d_h; ++d)
           acc += qa[d] * base[((int64_t)(j * (a.d_h / 8) + d / 8) * P + slot) * 8 + d % 8];
-        const float* rb = base + (int64_t)2 * gc * P * a.d_h;
+        const float* rb = base + (int64_t)gc * P * (a.d_h + a.d_v);
         for (int d = 0; d < a.d_r; ++d) acc += qr[d] * rb[((int64_t)(d / 8) * P + slot) * 8 + d % 8];
       }
       z = acc * a.scale_log2e;
@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
         if (d < dv) {
           float v;
           if (kAbsorb) v = base[(int64_t)slots * (a.r_kv + a.d_r) + d];
-          else v = base[(int64_t)gc * P * a.d_h + ((int64_t)(j * (P / 8) + slots / 8) * a.d_h + d) * 8 + slots % 8];
+          else v = base[(int64_t)gc * P * a.d_h + ((int64_t)(j * (P / 8) + slots / 8) * a.d_v + d) * 8 + slots % 8];
           o[u] += ps * v;
         }
       }
@@ -212,21 +212,23 @@ __global__ void expand_f32_kernel(ExpandArgs a) {
   const int W = a.r_kv + a.d_r;
   const int gc = a.group_count;
   const float* in = (const float*)a.latent.pool + (int64_t)pg_in * P * W;
-  float* out = (float*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * a.d_h + a.d_r);
-  const int per_tok = 2 * gc * a.d_h + a.d_r;
+  float* out = (float*)a.expanded.pool + (int64_t)pg_out * P * (gc * (a.d_h + a.d_v) + a.d_r);
+  const int nk = gc * a.d_h, per_tok = gc * (a.d_h + a.d_v) + a.d_r;  // K elements, all elements of a token
   for (int idx = threadIdx.x; idx < valid * per_tok; idx += blockDim.x) {
     const int slot = idx / per_tok, e = idx % per_tok;
     const float* c = in + (int64_t)slot * W;
-    if (e < 2 * gc * a.d_h) {
-      const int kind = e / (gc * a.d_h), jj = (e / a.d_h) % gc, d = e % a.d_h;
-      const float* w = (const float*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * a.r_kv * a.d_h;
+    if (e < per_tok - a.d_r) {
+      const int kind = e >= nk;                       // 0: a K_C element, 1: a V element
+      const int dim = kind ? a.d_v : a.d_h;           // columns of this kind's weight
+      const int x = kind ? e - nk : e, jj = x / dim, d = x % dim;
+      const float* w = (const float*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * a.r_kv * dim;
       float acc = 0.f;
-      for (int r = 0; r < a.r_kv; ++r) acc += w[(int64_t)r * a.d_h + d] * c[r];
+      for (int r = 0; r < a.r_kv; ++r) acc += w[(int64_t)r * dim + d] * c[r];
       if (kind == 0) out[((int64_t)(jj * (a.d_h / 8) + d / 8) * P + slot) * 8 + d % 8] = acc;
-      else out[(int64_t)gc * P * a.d_h + ((int64_t)(jj * (P / 8) + slot / 8) * a.d_h + d) * 8 + slot % 8] = acc;
+      else out[(int64_t)gc * P * a.d_h + ((int64_t)(jj * (P / 8) + slot / 8) * a.d_v + d) * 8 + slot % 8] = acc;
     } else {
-      const int d = e - 2 * gc * a.d_h;
-      out[(int64_t)2 * gc * P * a.d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8] = c[a.r_kv + d];
+      const int d = e - (per_tok - a.d_r);
+      out[(int64_t)gc * P * (a.d_h + a.d_v) + ((int64_t)(d / 8) * P + slot) * 8 + d % 8] = c[a.r_kv + d];
     }
   }
 }
@@ -245,19 +247,21 @@ __global__ void expand_tail_f32_kernel(ExpandArgs a) {
   const int gc = a.group_count;
   const int slot = pos % P;
   const float* c = (const float*)a.latent.pool + ((int64_t)pg_in * P + slot) * W;
-  float* out = (float*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * a.d_h + a.d_r);
-  const int per_tok = 2 * gc * a.d_h + a.d_r;
+  float* out = (float*)a.expanded.pool + (int64_t)pg_out * P * (gc * (a.d_h + a.d_v) + a.d_r);
+  const int nk = gc * a.d_h, per_tok = gc * (a.d_h + a.d_v) + a.d_r;  // K elements, all elements of a token
   for (int e = threadIdx.x; e < per_tok; e += blockDim.x) {
-    if (e < 2 * gc * a.d_h) {
-      const int kind = e / (gc * a.d_h), jj = (e / a.d_h) % gc, d = e % a.d_h;
-      const float* w = (const float*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * a.r_kv * a.d_h;
+    if (e < per_tok - a.d_r) {
+      const int kind = e >= nk;                       // 0: a K_C element, 1: a V element
+      const int dim = kind ? a.d_v : a.d_h;           // columns of this kind's weight
+      const int x = kind ? e - nk : e, jj = x / dim, d = x % dim;
+      const float* w = (const float*)(kind ? a.w_uv : a.w_uk) + (int64_t)(a.group_begin + jj) * a.r_kv * dim;
       float acc = 0.f;
-      for (int r = 0; r < a.r_kv; ++r) acc += w[(int64_t)r * a.d_h + d] * c[r];
+      for (int r = 0; r < a.r_kv; ++r) acc += w[(int64_t)r * dim + d] * c[r];
       if (kind == 0) out[((int64_t)(jj * (a.d_h / 8) + d / 8) * P + slot) * 8 + d % 8] = acc;
-      else out[(int64_t)gc * P * a.d_h + ((int64_t)(jj * (P / 8) + slot / 8) * a.d_h + d) * 8 + slot % 8] = acc;
+      else out[(int64_t)gc * P * a.d_h + ((int64_t)(jj * (P / 8) + slot / 8) * a.d_v + d) * 8 + slot % 8] = acc;
     } else {
-      const int d = e - 2 * gc * a.d_h;
-      out[(int64_t)2 * gc * P * a.d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8] = c[a.r_kv + d];
+      const int d = e - (per_tok - a.d_r);
+      out[(int64_t)gc * P * (a.d_h + a.d_v) + ((int64_t)(d / 8) * P + slot) * 8 + d % 8] = c[a.r_kv + d];
     }
   }
 }
@@ -272,7 +276,7 @@ __global__ void compress_f32_kernel(CompressArgs a) {
   if (pg_in < 0 || pg_out < 0) return;
   const int valid = min(P, L - p * P);
   const int g = a.g, W = a.r_kv + a.d_r, K = g * a.d_h;
-  const float* in = (const float*)a.expanded.pool + (int64_t)pg_in * P * (2 * g * a.d_h + a.d_r);
+  const float* in = (const float*)a.expanded.pool + (int64_t)pg_in * P * (g * (a.d_h + a.d_v) + a.d_r);
   float* out = (float*)a.latent.pool + (int64_t)pg_out * P * W;
   for (int idx = threadIdx.x; idx < valid * W; idx += blockDim.x) {
     const int slot = idx / W, e = idx % W;
@@ -287,7 +291,7 @@ __global__ void compress_f32_kernel(CompressArgs a) {
       v = acc;
     } else {
       const int d = e - a.r_kv;
-      v = in[(int64_t)2 * g * P * a.d_h + ((int64_t)(d / 8) * P + slot) * 8 + d % 8];
+      v = in[(int64_t)g * P * (a.d_h + a.d_v) + ((int64_t)(d / 8) * P + slot) * 8 + d % 8];
     }
     out[(int64_t)slot * W + e] = v;
   }

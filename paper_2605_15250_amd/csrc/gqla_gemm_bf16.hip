@@ -70,24 +70,29 @@ __device__ __forceinline__ void mfma_results_ready(f32x16& c0, f32x16& c1, f32x1
 }
 
 // ---- cache expansion -----------------------------------------------------------------------------------------
-// Step 1 (tiny): the weights of the expanded groups are repacked once per call into MFMA fragment order,
-//   packed[(jj*2 + kind)*2 + mtp][ks][e][lane][8]  with  lane (m = l % 32, h = l / 32), element i  =
-//   W_kind[group_begin + jj][r = 16*ks + 8*h + i][d = 64*mtp + 32*e + m],
+// Step 1 (tiny): the weights of the expanded groups are repacked once per call into MFMA fragment order.  A "stage"
+// is one 64-column block of one group's W_UK or W_UV; a group has DH/64 key stages followed by DV/64 value stages
+// (DH = DV = 128: two and two; the shape of Sec. 3.2.2, DH = 192 and DV = 256: three and four):
+//   packed[jj * (DH + DV)/64 + sub][ks][e][lane][8]  with  lane (m = l % 32, h = l / 32), element i  =
+//   W_kind[group_begin + jj][r = 16*ks + 8*h + i][d = 64*mtp + 32*e + m],   (kind, mtp) = stage_kind<DH>(sub)
 // i.e. each 1 KB block is one A fragment of W^T (or, with the same register contents, one B fragment of W), and each
-// (matrix, 64-column half) is one contiguous 64 KB "stage".
+// stage is one contiguous 64 KB.
 // One workgroup per (stage, 4 k-steps): a [64 latent dims][64 columns] tile of W goes through LDS, read with whole
 // 16-byte vectors along the rows and written as whole fragments.
-template <int DH, int RKV>
+template <int DH, int DV, int RKV>
 __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __bf16* packed) {
   constexpr int KS = RKV / 16;
+  constexpr int NSK = DH / 64, NSUB = (DH + DV) / 64;
   __shared__ __attribute__((aligned(16))) __bf16 tile[64][64 + 8];  // rows padded by one vector: column reads spread over the banks
-  const int stage = blockIdx.x;  // (jj*2 + kind)*2 + mtp
+  const int stage = blockIdx.x;  // jj * NSUB + sub
   const int kq = blockIdx.y;     // k-steps 4*kq .. 4*kq + 3
-  const int mtp = stage & 1, kind = (stage >> 1) & 1, jj = stage >> 2;
-  const __bf16* w = (const __bf16*)(kind ? a.w_uv : a.w_uk) + ((int64_t)(a.group_begin + jj) * RKV + 64 * kq) * DH + 64 * mtp;
+  const int jj = stage / NSUB, sub = stage % NSUB;
+  const int kind = sub >= NSK, mtp = kind ? sub - NSK : sub;
+  const int dim = kind ? DV : DH;  // columns of this kind's weight
+  const __bf16* w = (const __bf16*)(kind ? a.w_uv : a.w_uk) + ((int64_t)(a.group_begin + jj) * RKV + 64 * kq) * dim + 64 * mtp;
   for (int v = threadIdx.x; v < 512; v += 256) {
     const int r = v >> 3, c = (v & 7) * 8;
-    *(u32x4*)&tile[r][c] = *(const u32x4*)(w + (int64_t)r * DH + c);
+    *(u32x4*)&tile[r][c] = *(const u32x4*)(w + (int64_t)r * dim + c);
   }
   __syncthreads();
   __bf16* out = packed + (int64_t)stage * KS * 2 * 512 + (int64_t)(4 * kq) * 2 * 512;
@@ -112,13 +117,18 @@ __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __
 // The two output orientations put 4 consecutive dims (K plane) or 4 consecutive tokens (V plane) of the expanded
 // page's 8-element vectors in one lane.  A stage's results are stored while the next stage is being multiplied, so
 // that the end-of-stage wait (which also covers stores on this hardware) finds them long gone.
-template <int DH, int RKV, int DR, bool FP8>
+// With an odd number of stages per group (DH = 192, DV = 256: seven) the two result sets would meet at the group
+// boundary, so there the group's last stage stores its results at once instead of in the next stage's shadow.
+template <int DH, int DV, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
   constexpr int STAGE_BYTES = KS * 2 * 1024;  // 64 KB
   constexpr int DEPTH = 2;                    // weight fragments are fetched this many k-steps ahead
-  static_assert(DH == 128, "two 64-column stages per weight matrix");
+  constexpr int NSK = DH / 64, NSUB = (DH + DV) / 64;  // key stages, all stages of a group
+  constexpr bool ODD = (NSUB & 1) != 0;
+  static_assert(DH % 64 == 0 && DV % 64 == 0, "64-column stages");
+  static_assert(!FP8 || (DH == 128 && DV == 128), "the 8-bit page format is written for equal dims of 128");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -145,7 +155,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   const __bf16* in_page = (const __bf16*)a.latent.pool + (int64_t)(wave_ok ? pg_in : 0) * P * W;
   // FP8: `expanded` is an 8-bit cache (E4M3 code planes and a 16-bit k_R plane, see the header): 2 gc DH + 2 DR bytes per token
   constexpr int EB = FP8 ? 1 : 2;  // bytes per K_C / V element
-  char* const page_bytes = (char*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (2 * gc * DH * EB + 2 * DR);
+  char* const page_bytes = (char*)a.expanded.pool + (int64_t)(wave_ok ? pg_out : 0) * P * (gc * (DH + DV) * EB + 2 * DR);
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const bool tok_ok = wave_ok && (tokw + 32 * nt + n < L);
@@ -158,7 +168,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 #pragma unroll
       for (int cb = h; cb < DR / 8; cb += 2) {
         const u32x4 v = *(const u32x4*)(in_row + RKV + cb * 8);
-        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (int64_t)2 * gc * DH * P * EB + ((int64_t)cb * P + slot0 + 32 * nt + n) * 16));
+        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (int64_t)gc * (DH + DV) * P * EB + ((int64_t)cb * P + slot0 + 32 * nt + n) * 16));
       }
     }
   }
@@ -177,9 +187,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   // results of the previous stage ([token tile][32-column half]), kept until the next stage's arithmetic is under way
   f32x16 accs[2][2][2];  // [stage parity][token tile][32-column half]: one set accumulates while the other is stored
   // stores address the page through one uniform base and 32-bit offsets (a page is at most a few MB)
-  const uint32_t plane = (uint32_t)DH * P;                            // elements of one group's K (or V) plane
+  const uint32_t plane_k = (uint32_t)DH * P, plane_v = (uint32_t)DV * P;          // elements of one group's K and V plane
   const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + (uint32_t)h * P * 8;        // K plane: token slot0 + n, 8-dim block + h
-  const uint32_t v_lane = (uint32_t)((slot0 >> 3) + h) * DH * 8 + n * 8;          // V plane: dim n, 8-token block slot0/8 + h
+  const uint32_t v_lane = (uint32_t)((slot0 >> 3) + h) * DV * 8 + n * 8;          // V plane: dim n, 8-token block slot0/8 + h
   const bool wave_full = tokw + 64 <= L;                                          // no token of this wave lies beyond L_b
   // One 16-byte store per lane: piece (nt, e, qp) of the previous stage's results; kind, mtp and the piece are compile-time.
   // A lane holds rows 4h..4h+3 of each 8-row block of its column; the two half-waves trade so that lane (n, h) ends up
@@ -187,9 +197,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   // 8-bit destination: one 16-byte store per lane and (nt, e): the 32 results of the lane's column as the two code
   // vectors of the page layout (a vector holds 8-row blocks h' and 2 + h' of the 32 rows, each block 4 rows from either
   // half-wave); every result is rounded to bf16 first, so that the codes are those of expanding and then converting.
-  auto store_prev8 = [&](int kind, int mtp, int jj, int nt, int e) {
+  auto store_prev8 = [&](int par, int kind, int mtp, int jj, int nt, int e) {
     if (jj < 0 || !wave_ok) return;
-    const f32x16& acc = accs[(kind * 2 + mtp) & 1][nt][e];
+    const f32x16& acc = accs[par][nt][e];
     const float inv = kind == 0 ? a.k_inv_scale : a.v_inv_scale;
     uint32_t code[4];  // code[q] = rows 8q + 4h + 0..3
 #pragma unroll
@@ -224,9 +234,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       }
     }
   };
-  auto store_prev = [&](int kind, int mtp, int jj, int nt, int e, int qp) {
+  auto store_prev = [&](int par, int kind, int mtp, int jj, int nt, int e, int qp) {
     if (jj < 0 || !wave_ok) return;
-    const f32x16& acc = accs[(kind * 2 + mtp) & 1][nt][e];
+    const f32x16& acc = accs[par][nt][e];
     const int q0 = 2 * qp;
     const uint32_t x0 = pack_bf16(acc[4 * q0], acc[4 * q0 + 1]), x1 = pack_bf16(acc[4 * q0 + 2], acc[4 * q0 + 3]);
     const uint32_t y0 = pack_bf16(acc[4 * q0 + 4], acc[4 * q0 + 5]), y1 = pack_bf16(acc[4 * q0 + 6], acc[4 * q0 + 7]);
@@ -237,12 +247,12 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
     if (kind == 0) {
       // lane = token; the vector is dims 64*mtp + 32*e + 8*(2*qp + h) + 0..7 of the K plane
       if (wave_full || tokw + 32 * nt + n < L) {
-        const uint32_t off = (uint32_t)jj * plane + (uint32_t)(8 * mtp + 4 * e + q0) * P * 8 + 32 * nt * 8 + k_lane;
+        const uint32_t off = (uint32_t)jj * plane_k + (uint32_t)(8 * mtp + 4 * e + q0) * P * 8 + 32 * nt * 8 + k_lane;
         __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (size_t)off * 2));
       }
     } else {
       // lane = dim 64*mtp + 32*e + n; the vector is tokens 32*nt + 8*(2*qp + h) + 0..7 of the V plane
-      const uint32_t off = (uint32_t)(gc + jj) * plane + (uint32_t)(4 * nt + q0) * DH * 8 + (2 * mtp + e) * 32 * 8 + v_lane;
+      const uint32_t off = (uint32_t)gc * plane_k + (uint32_t)jj * plane_v + (uint32_t)(4 * nt + q0) * DV * 8 + (2 * mtp + e) * 32 * 8 + v_lane;
       __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
       const int tk = tokw + 32 * nt + 8 * (q0 + h);  // first of 8 tokens
       if (wave_full || tk + 7 < L) {
@@ -255,16 +265,22 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
     }
   };
 
-  const int n_stages = gc * 4;
+  const int n_stages = gc * NSUB;
   stage_in(0, smem);
   wait_all_memory();
   __syncthreads();
   for (int jj = 0; jj < gc; ++jj) {
-#pragma unroll
-    for (int sub = 0; sub < 4; ++sub) {  // sub = kind*2 + mtp, compile time: fixes the MFMA operand order
-      const int stage = jj * 4 + sub;
+    static_for<NSUB>([&](auto SUB) __attribute__((always_inline)) {  // compile time: fixes the kind (MFMA operand order) and the result set
+      constexpr int sub = decltype(SUB)::value;
+      const int stage = jj * NSUB + sub;
       const char* buf = smem + (stage & 1) * STAGE_BYTES + lane * 16;
       f32x16 (&acc)[2][2] = accs[sub & 1];
+      // the stage before this one, whose results leave in this stage's shadow (none at the start of a group when the
+      // group's last stage has stored its own)
+      constexpr int kPrevNone = -1;
+      constexpr int psub = sub > 0 ? sub - 1 : (ODD ? kPrevNone : NSUB - 1);
+      constexpr int pkind = psub >= NSK, pmtp = pkind ? psub - NSK : psub, ppar = psub & 1;
+      const int pjj = psub == kPrevNone ? -1 : (sub == 0 ? jj - 1 : jj);
       if (wave_ok) {
         bf16x8 w[DEPTH + 1][2];
 #pragma unroll
@@ -285,7 +301,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
               const bf16x8 wf = w[ks % (DEPTH + 1)][e];
-              if ((sub >> 1) == 0) {
+              if (sub < NSK) {
                 if (ks == 0) mfma_va_first(acc[nt][e], wf, xf[nt][ks]);
                 else mfma_va(acc[nt][e], wf, xf[nt][ks]);
               } else {
@@ -297,25 +313,31 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
           // the previous stage's results leave one store at a time, in the shadow of this stage's MFMAs
           if constexpr (FP8) {
             if ((ks & 3) == 3 && ks <= 15)  // four pieces (nt, e)
-              store_prev8(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj, (ks >> 2) >> 1, (ks >> 2) & 1);
+              store_prev8(ppar, pkind, pmtp, pjj, (ks >> 2) >> 1, (ks >> 2) & 1);
           } else if (ks >= 1 && ks <= 15 && (ks & 1)) {
-            store_prev(((sub + 3) & 3) >> 1, (sub + 3) & 1, sub == 0 ? jj - 1 : jj, (ks >> 1) >> 2, ((ks >> 1) >> 1) & 1, (ks >> 1) & 1);
+            store_prev(ppar, pkind, pmtp, pjj, (ks >> 1) >> 2, ((ks >> 1) >> 1) & 1, (ks >> 1) & 1);
           }
         }
         mfma_results_ready(acc[0][0], acc[0][1], acc[1][0], acc[1][1]);
+        if constexpr (ODD && !FP8) {
+          if (sub == NSUB - 1) {
+#pragma unroll
+            for (int piece = 0; piece < 8; ++piece) store_prev(sub & 1, 1, sub - NSK, jj, piece >> 2, (piece >> 1) & 1, piece & 1);
+          }
+        }
       } else if (stage + 1 < n_stages) {
         stage_in(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES);  // a wave without tokens still stages its share
       }
       wait_all_memory();
       __syncthreads();  // next stage has landed; everyone is done with this stage's buffer
-    }
+    });
   }
   if constexpr (FP8) {
 #pragma unroll
-    for (int piece = 0; piece < 4; ++piece) store_prev8(1, 1, gc - 1, piece >> 1, piece & 1);
-  } else {
+    for (int piece = 0; piece < 4; ++piece) store_prev8((NSUB - 1) & 1, 1, NSUB - 1 - NSK, gc - 1, piece >> 1, piece & 1);
+  } else if constexpr (!ODD) {
 #pragma unroll
-    for (int piece = 0; piece < 8; ++piece) store_prev(1, 1, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
+    for (int piece = 0; piece < 8; ++piece) store_prev((NSUB - 1) & 1, 1, NSUB - 1 - NSK, gc - 1, piece >> 2, (piece >> 1) & 1, piece & 1);
   }
 }
 
@@ -332,14 +354,17 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 // FP8 = true: `expanded` is an 8-bit cache (E4M3 code planes, see the header); every result is first rounded to bf16,
 // the value the 16-bit cache would hold, and then quantised, so that the codes equal those of expanding into a 16-bit
 // cache and converting it.
-template <int DH, int RKV, int DR, bool FP8>
+template <int DH, int DV, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
   constexpr int KS = RKV / 16;
+  constexpr int NSK = DH / 64, NSUB = (DH + DV) / 64;
+  static_assert(!FP8 || (DH == 128 && DV == 128), "the 8-bit page format is written for equal dims of 128");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, h = lane >> 5;
-  const int stage = blockIdx.x;  // (jj*2 + kind)*2 + mtp
-  const int mtp = stage & 1, kind = (stage >> 1) & 1, jj = stage >> 2;
+  const int stage = blockIdx.x;  // jj * NSUB + sub
+  const int jj = stage / NSUB, sub = stage % NSUB;
+  const int kind = sub >= NSK, mtp = kind ? sub - NSK : sub;
   const int e = wave & 1;
   const int idx = blockIdx.y * 64 + (wave >> 1) * 32 + n;  // this lane's token in the list
   const int P = a.latent.page_size;
@@ -395,7 +420,7 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
     }
     return;
   }
-  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)pg_out * P * (2 * gc * DH + DR);
+  __bf16* out_page = (__bf16*)a.expanded.pool + (int64_t)pg_out * P * (gc * (DH + DV) + DR);
   if (kind == 0) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -403,12 +428,12 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
       *(u32x2*)(out_page + ((int64_t)(jj * (DH / 8) + d0 / 8 + q) * P + slot) * 8 + 4 * h) = v;
     }
   } else {
-    __bf16* vp = out_page + (int64_t)gc * P * DH + ((int64_t)(jj * (P / 8) + slot / 8) * DH) * 8 + slot % 8;
+    __bf16* vp = out_page + (int64_t)gc * P * DH + ((int64_t)(jj * (P / 8) + slot / 8) * DV) * 8 + slot % 8;
 #pragma unroll
     for (int i = 0; i < 16; ++i) vp[(int64_t)(d0 + 8 * (i >> 2) + 4 * h + (i & 3)) * 8] = (__bf16)acc[i];
   }
   if (stage == 0 && e == 0) {  // k_R of this token: dims 8*c .. 8*c + 7 for c = h, h + 2, ...
-    __bf16* rp = out_page + (int64_t)2 * gc * P * DH;
+    __bf16* rp = out_page + (int64_t)gc * P * (DH + DV);
 #pragma unroll
     for (int c = h; c < DR / 8; c += 2) *(u32x4*)(rp + ((int64_t)c * P + slot) * 8) = *(const u32x4*)(row + RKV + c * 8);
   }
@@ -430,7 +455,7 @@ constexpr int compress_lds_bytes() {
   return 3 * (kCompressKS / 8) * ((RKV + 4) + kCompressTok) * 16;
 }
 
-template <int DH, int RKV, int DR>
+template <int DH, int DV, int RKV, int DR>
 __global__ void __launch_bounds__(512) compress_bf16_kernel(CompressArgs a) {
   static_assert(RKV == 512 && DH % kCompressKS == 0, "wave tiling below assumes 4 blocks of 128 latent dims");
   constexpr int NC = kCompressKS / 8;                 // vector planes per stage
@@ -449,7 +474,7 @@ __global__ void __launch_bounds__(512) compress_bf16_kernel(CompressArgs a) {
   const int P = a.expanded.page_size;
   const int g = a.g;
   const int K = g * DH;
-  const int64_t in_page_elems = (int64_t)P * (2 * g * DH + DR);
+  const int64_t in_page_elems = (int64_t)P * (g * (DH + DV) + DR);
 
   // staging role of this thread: one K vector per stage (token kt of the tile, plane kc) and four A^+ vectors
   const int kt = tid & (kCompressTok - 1), kc = tid >> 7;
@@ -555,7 +580,7 @@ __global__ void __launch_bounds__(512) compress_bf16_kernel(CompressArgs a) {
         *(u32x2*)(row + 128 * rw + 32 * rt + 8 * q + 4 * h) = v;
       }
     if (rw == 0) {  // k_R: dims 8c .. 8c + 7 for c = h, h + 2, ...
-      const __bf16* rp = in_page + (int64_t)2 * g * P * DH;
+      const __bf16* rp = in_page + (int64_t)g * P * (DH + DV);
 #pragma unroll
       for (int c = h; c < DR / 8; c += 2) *(u32x4*)(row + RKV + c * 8) = *(const u32x4*)(rp + ((int64_t)c * P + slot) * 8);
     }
@@ -564,14 +589,19 @@ __global__ void __launch_bounds__(512) compress_bf16_kernel(CompressArgs a) {
 
 }  // namespace
 
-hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
+template <int DH, int DV>
+static hipError_t launch_compress_dims(const CompressArgs& a, hipStream_t s) {
   constexpr int lds = compress_lds_bytes<512>();
   static const hipError_t attr =
-      hipFuncSetAttribute((const void*)compress_bf16_kernel<128, 512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      hipFuncSetAttribute((const void*)compress_bf16_kernel<DH, DV, 512, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (attr != hipSuccess) return attr;
   const int64_t max_tokens = (int64_t)a.expanded.max_pages * a.expanded.page_size;
-  compress_bf16_kernel<128, 512, 64><<<dim3((unsigned)((max_tokens + kCompressTok - 1) / kCompressTok), a.B), 512, lds, s>>>(a);
+  compress_bf16_kernel<DH, DV, 512, 64><<<dim3((unsigned)((max_tokens + kCompressTok - 1) / kCompressTok), a.B), 512, lds, s>>>(a);
   return hipGetLastError();
+}
+
+hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
+  return a.d_h == 192 ? launch_compress_dims<192, 256>(a, s) : launch_compress_dims<128, 128>(a, s);
 }
 
 hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
@@ -582,40 +612,42 @@ hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int DH, int DV, bool FP8>
+static hipError_t launch_expand_tail_dims(const ExpandArgs& a, void* ws, hipStream_t s) {
+  constexpr int NSUB = (DH + DV) / 64;
+  const int tokens = a.B * a.tail;
+  pack_weights_bf16_kernel<DH, DV, 512><<<dim3(a.group_count * NSUB, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_tail_bf16_kernel<DH, DV, 512, 64, FP8><<<dim3(a.group_count * NSUB, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
+  return hipGetLastError();
+}
+
 hipError_t launch_expand_tail_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
-  const int tokens = a.B * a.tail;
-  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  expand_tail_bf16_kernel<128, 512, 64, false><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
-  return hipGetLastError();
+  return a.d_h == 192 ? launch_expand_tail_dims<192, 256, false>(a, ws, s) : launch_expand_tail_dims<128, 128, false>(a, ws, s);
 }
 
-hipError_t launch_expand_tail_fp8(const ExpandArgs& a, void* ws, hipStream_t s) {
-  const int tokens = a.B * a.tail;
-  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  expand_tail_bf16_kernel<128, 512, 64, true><<<dim3(a.group_count * 4, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
-  return hipGetLastError();
-}
+hipError_t launch_expand_tail_fp8(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_tail_dims<128, 128, true>(a, ws, s); }
 
-template <bool FP8>
+template <int DH, int DV, bool FP8>
 static hipError_t launch_expand_one_shot(const ExpandArgs& a, void* ws, hipStream_t s) {
   constexpr int kLds = 2 * (512 / 16) * 2 * 1024;
+  constexpr int NSUB = (DH + DV) / 64;
   // once per process (function-local statics are initialised under a lock); an error is reported by every call
   static const hipError_t attr =
-      hipFuncSetAttribute((const void*)expand_bf16_kernel<128, 512, 64, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+      hipFuncSetAttribute((const void*)expand_bf16_kernel<DH, DV, 512, 64, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
   if (attr != hipSuccess) return attr;
   const int64_t max_tokens = (int64_t)a.latent.max_pages * a.latent.page_size;
   dim3 grid((unsigned)((max_tokens + 255) / 256), a.B);
-  pack_weights_bf16_kernel<128, 512><<<dim3(a.group_count * 4, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
+  pack_weights_bf16_kernel<DH, DV, 512><<<dim3(a.group_count * NSUB, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  expand_bf16_kernel<128, 512, 64, FP8><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);
+  expand_bf16_kernel<DH, DV, 512, 64, FP8><<<grid, 256, kLds, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }
-hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_one_shot<false>(a, ws, s); }
-hipError_t launch_expand_fp8(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_one_shot<true>(a, ws, s); }
+hipError_t launch_expand_bf16(const ExpandArgs& a, void* ws, hipStream_t s) {
+  return a.d_h == 192 ? launch_expand_one_shot<192, 256, false>(a, ws, s) : launch_expand_one_shot<128, 128, false>(a, ws, s);
+}
+hipError_t launch_expand_fp8(const ExpandArgs& a, void* ws, hipStream_t s) { return launch_expand_one_shot<128, 128, true>(a, ws, s); }
 
 }  // namespace gqla

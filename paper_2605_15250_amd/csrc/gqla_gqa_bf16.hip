@@ -30,12 +30,16 @@ __device__ __forceinline__ bf16x8 widen_e4m3(uint32_t w0, uint32_t w1) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int DH, int DR, bool FP8>
-__global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg,
-                                                              float k_scale, float v_scale) {
+// DH: key dims per head, DV: value dims per head (d_h^V of Sec. 3.2.2).  MAXT: threads per workgroup at most -- 512
+// (two waves per SIMD, 256 registers each) for equal dims of 128; the (192, 256) shape keeps 128 more accumulators and
+// 28 cache vectors in flight per wave, needs the whole register file of a SIMD and runs with 256.
+template <int DH, int DV, int DR, bool FP8, int MAXT>
+__global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg,
+                                                               float k_scale, float v_scale) {
   constexpr int KS_C = DH / 16;  // k-steps over the content dims
   constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
-  constexpr int MT = DH / 32;    // 32-dim tiles of the output
+  constexpr int MT = DV / 32;    // 32-dim tiles of the output
+  static_assert(!FP8 || DH == DV, "the 8-bit page format is written for equal dims");
   const int lane = threadIdx.x & 63;
   const int wpb = __builtin_amdgcn_readfirstlane(blockDim.x >> 6);  // waves per workgroup: 8, or the number of groups when that is 2 or 4
   const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));  // wave-uniform: keep it scalar
@@ -69,8 +73,8 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   const int P = a.cache.page_size;
   const int gc = a.cache.groups;
   constexpr int EB = FP8 ? 1 : 2;                                             // bytes per K_C / V element
-  const int64_t page_bytes = (int64_t)P * (2 * gc * DH * EB + DR * 2);
-  const int64_t kr_plane = (int64_t)2 * gc * DH * P * EB;                      // byte offset of the k_R plane in a page
+  const int64_t page_bytes = (int64_t)P * (gc * (DH + DV) * EB + DR * 2);
+  const int64_t kr_plane = (int64_t)gc * (DH + DV) * P * EB;                   // byte offset of the k_R plane in a page
   const char* pool = (const char*)a.cache.pool;
 
   bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
@@ -113,7 +117,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   };
   auto load_v = [&](int tok, int32_t pg) {
     v_ok = pg >= 0;
-    const char* base = pool + (int64_t)(v_ok ? pg : 0) * page_bytes + ((int64_t)gc * DH * P + (int64_t)j * DH * P) * EB;
+    const char* base = pool + (int64_t)(v_ok ? pg : 0) * page_bytes + ((int64_t)gc * DH * P + (int64_t)j * DV * P) * EB;
     if constexpr (FP8) {
       const int T = (tok % P) / 32;  // 32-token tile of the page: [T][dim][half] vectors
 #pragma unroll
@@ -125,7 +129,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
-          vf[mt][kk] = __builtin_nontemporal_load((const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DH + mt * 32 + n) * 16));
+          vf[mt][kk] = __builtin_nontemporal_load((const bf16x8*)(base + ((int64_t)(tb + 2 * kk) * DV + mt * 32 + n) * 16));
     }
   };
 
@@ -184,9 +188,10 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
       // this tile's k_R was requested before the cache loads that followed it (loads complete in issue order): the
       // tile's key and value vectors, 16-byte loads each -- KS_C + 2*MT of them in 16 bits, half as many as codes
       constexpr int kLoadsBehindKr = FP8 ? KS_C / 2 + MT : KS_C + 2 * MT;
-      static_assert(kLoadsBehindKr == (FP8 ? 8 : 16), "the wait below is written for these counts");
-      if constexpr (FP8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      static_assert(kLoadsBehindKr == 8 || kLoadsBehindKr == 16 || kLoadsBehindKr == 28, "the wait below is written for these counts");
+      if constexpr (kLoadsBehindKr == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else if constexpr (kLoadsBehindKr == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(28)" ::: "memory");
       __syncthreads();
       const char* kr = kr_lds[((tok - ce.tok_begin) >> 5) & 1] + lane * 16;
 #pragma unroll
@@ -279,7 +284,7 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
   if (!row_ok) return;
   const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * (FP8 ? v_scale : 1.f);
   const int64_t prow = (int64_t)chunk * a.M + (int64_t)t * a.h_q + head;
-  float* po = (float*)a.part_o + prow * DH;
+  float* po = (float*)a.part_o + prow * DV;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -292,31 +297,37 @@ __global__ void __launch_bounds__(512) decode_gqa_bf16_kernel(DecodeArgs a, int 
 
 }  // namespace
 
-static void gqa_launch_shape(const DecodeArgs& a, int& row_blocks, int& n_items, bool& team, int& wpb, int& blocks) {
+static void gqa_launch_shape(const DecodeArgs& a, int max_wpb, int& row_blocks, int& n_items, bool& team, int& wpb, int& blocks) {
   row_blocks = (a.G * a.s_q + 31) / 32;
   n_items = a.n_chunks * row_blocks * a.g;
   // all waves of a workgroup are groups of one (chunk, row block) when the group count is a multiple of the waves per
   // workgroup: then they share the tile's k_R through LDS (and run in step, one barrier per tile)
-  // With 2 or 4 groups the workgroup also takes all row blocks of the chunk when that keeps it within 8 waves: they
+  // With 2 or 4 groups the workgroup also takes all row blocks of the chunk when that keeps it within its waves: they
   // stream the same cache vectors in step, so all but the first request for a line is served by the cache hierarchy.
-  team = a.g % 8 == 0 || a.g == 4 || a.g == 2;
-  wpb = (a.g == 4 || a.g == 2) ? (a.g * row_blocks <= 8 ? a.g * row_blocks : a.g) : 8;
+  const bool few = (a.g == 4 || a.g == 2) && a.g <= max_wpb;
+  team = a.g % max_wpb == 0 || few;
+  wpb = few ? (a.g * row_blocks <= max_wpb ? a.g * row_blocks : a.g) : max_wpb;
   blocks = (n_items + wpb - 1) / wpb;
 }
 
 hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
   int row_blocks, n_items, wpb, blocks;
   bool team;
-  gqa_launch_shape(a, row_blocks, n_items, team, wpb, blocks);
-  decode_gqa_bf16_kernel<128, 64, false><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+  if (a.d_h == 192) {  // (d_h, d_v) = (192, 256): four waves per workgroup
+    gqa_launch_shape(a, 4, row_blocks, n_items, team, wpb, blocks);
+    decode_gqa_bf16_kernel<192, 256, 64, false, 256><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+    return hipGetLastError();
+  }
+  gqa_launch_shape(a, 8, row_blocks, n_items, team, wpb, blocks);
+  decode_gqa_bf16_kernel<128, 128, 64, false, 512><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_gqa_fp8(const DecodeArgs& a, float k_scale, float v_scale, hipStream_t s) {
   int row_blocks, n_items, wpb, blocks;
   bool team;
-  gqa_launch_shape(a, row_blocks, n_items, team, wpb, blocks);
-  decode_gqa_bf16_kernel<128, 64, true><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
+  gqa_launch_shape(a, 8, row_blocks, n_items, team, wpb, blocks);
+  decode_gqa_bf16_kernel<128, 128, 64, true, 512><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
   return hipGetLastError();
 }
 

@@ -31,9 +31,9 @@ struct DecodeArgs {
   CacheView cache;
   const ChunkEntry* chunks;
   int32_t n_chunks;
-  void* part_o;      // GQA: fp32 [chunks][M][d_h];  absorb bf16: bf16 [chunks][M][r_kv];  absorb f32: fp32 [chunks][M][r_kv]
+  void* part_o;      // GQA: fp32 [chunks][M][d_v];  absorb bf16: bf16 [chunks][M][r_kv];  absorb f32: fp32 [chunks][M][r_kv]
   float* part_lse;   // fp32 [chunks][M], natural log
-  int32_t B, h_q, g, G, d_h, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i
+  int32_t B, h_q, g, G, d_h, d_v, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i; d_v: value dim (GQA path)
   int32_t num_cus;                               // compute units the plan was made for (launch-shape choices only)
   float scale_log2e;                             // softmax scale times log2(e)
 };
@@ -55,7 +55,7 @@ struct ExpandArgs {
   const int32_t* seq_lens;
   const void* w_uk;
   const void* w_uv;
-  int32_t B, g, d_h, r_kv, d_r, group_begin, group_count;
+  int32_t B, g, d_h, d_v, r_kv, d_r, group_begin, group_count;  // d_h: key dim (columns of W_UK), d_v: value dim (columns of W_UV)
   int32_t tail;  // tail variants only: positions L_b - tail .. L_b - 1 of every sequence
   float k_inv_scale, v_inv_scale;  // 8-bit tail variant only: 1 / scale of the two code planes
 };
@@ -65,7 +65,7 @@ struct CompressArgs {
   CacheView latent;
   const int32_t* seq_lens;
   const void* w_inv;   // [r_kv][g*d_h], the cache's element type
-  int32_t B, g, d_h, r_kv, d_r;
+  int32_t B, g, d_h, d_v, r_kv, d_r;
 };
 
 struct QuantizeArgs {

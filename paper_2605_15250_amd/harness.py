@@ -52,11 +52,12 @@ class Decoder:
         self.groups = cfg.g if groups is None else groups       # groups held by the expanded cache (TP slice if < g)
         self.group_begin = group_begin
         self.shape = B.make_shape(cfg.B, cfg.h_q, cfg.g, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q, lib_dtype(cfg.dtype), 0.0, cfg.d_v)
-        self.absorb_only = cfg.dv != cfg.d_h                    # a value dim of its own exists on the absorb path only
+        # the library has bf16 kernels over the expanded cache for (d_h, d_v) = (128, 128) and (192, 256) only
+        self.absorb_only = cfg.dtype == "bf16" and (cfg.d_h, cfg.dv) not in ((128, 128), (192, 256))
         G = cfg.h_q // cfg.g
         # shape seen by the GQA decode: for a slice, only the heads and groups of the slice
         self.shape_gqa = B.make_shape(cfg.B, G * self.groups, self.groups, cfg.d_h, cfg.r_kv, cfg.d_r, cfg.s_q,
-                                      lib_dtype(cfg.dtype), 0.0)
+                                      lib_dtype(cfg.dtype), 0.0, cfg.d_v)
         self.d_lens = torch.from_numpy(self.lens).cuda()
         self.d_table = torch.from_numpy(self.table).cuda() if use_page_table else None
         self.plan_a = B.gqla_plan_create(self.shape, self.lens, cfg.page_size, num_cus, B.GQLA_PATH_ABSORB, chunk_pages_absorb)
@@ -90,7 +91,7 @@ class Decoder:
 
     def expanded_page_elems(self):
         c = self.cfg
-        return c.page_size * (2 * self.groups * c.d_h + c.d_r)
+        return c.page_size * (self.groups * (c.d_h + c.dv) + c.d_r)
 
     def alloc_expanded(self, fill=float("nan")):
         self.expanded_pool = torch.full((self.num_pages * self.expanded_page_elems(),), fill,
@@ -232,7 +233,7 @@ class Decoder:
         c = self.cfg
         hq = (c.h_q // c.g) * self.groups
         if out is None:
-            out = torch.empty((c.B, c.s_q, hq, c.d_h), dtype=torch_dtype(c.dtype), device="cuda")
+            out = torch.empty((c.B, c.s_q, hq, c.dv), dtype=torch_dtype(c.dtype), device="cuda")
         if lse is None:
             lse = torch.empty((c.B, c.s_q, hq), dtype=torch.float32, device="cuda")
         B.gqla_decode_gqa(self.shape_gqa, self.plan_g, q_c, q_r, self.expanded_cache(), out, lse, self.ws_g)

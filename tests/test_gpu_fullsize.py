@@ -88,7 +88,7 @@ def oracle_group(case, b, j, path):
     qc, qr = case.q_c[b][:, hs], case.q_r[b][:, hs]
     wk, wv = case.w_uk[j:j + 1], case.w_uv[j:j + 1]
     if path == "absorb":
-        return O.decode_absorb(O.absorb_query(qc, wk), qr, c, kR, wv)
+        return O.decode_absorb(O.absorb_query(qc, wk), qr, c, kR, wv, d_h=cfg.d_h)
     KC, V = O.expand_latent(c, wk, wv)
     return O.decode_gqa(qc, qr, KC, V, kR)
 
@@ -218,6 +218,16 @@ def test_c2_absorb_sq1():
             for j in (2, 7):
                 ref_o, _ = oracle_group(case, b, j, "absorb")
                 check("absorb  b=%d group %d" % (b, j), oa[b][:, j * G:(j + 1) * G], ref_o)
+    finally:
+        case.close()
+
+
+def test_c2_size_with_the_value_dim_of_the_mla_checkpoints():
+    """B = 64, L = 8192 with (d_h, d_v) = (192, 256) (Sec. 3.2.2): the two GPU paths agree with each other on every
+    output (Sec. 3.1: one attention output, two routes), and with the oracle on sampled (sequence, group) slices."""
+    case = FullCase(S.CONFIGS["C2"].with_(d_h=192, d_v=256, seed=4192))
+    try:
+        run_both_paths(case, groups_to_check=[0, 5])
     finally:
         case.close()
 

@@ -111,12 +111,12 @@ def run_gqa_path(case, seqs=None):
     for b in seqs:
         KC, V = O.expand_latent(case.c(b), case.w_uk[j0:j0 + gc], case.w_uv[j0:j0 + gc])
         exp_ref[b] = (KC, V)
-        k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], case.lens[b], cfg.page_size, gc, cfg.d_h, cfg.d_r)
+        k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], case.lens[b], cfg.page_size, gc, cfg.d_h, cfg.d_r, cfg.dv)
         check("expand K_C seq %d" % b, k2, KC, cfg.dtype)
         check("expand V seq %d" % b, v2, V, cfg.dtype)
         assert np.array_equal(r2, case.kR(b)), "k_R must be copied bit for bit"
     # slots no token owns were never written: still NaN, and their count is exact
-    per_tok = 2 * gc * cfg.d_h + cfg.d_r
+    per_tok = gc * (cfg.d_h + cfg.dv) + cfg.d_r
     assert int(np.isnan(pool_h).sum()) == pool_h.size - int(case.lens.sum()) * per_tok
     # a6 in isolation: both sides consume the oracle's expansion rounded to the storage type
     q_c_s = np.ascontiguousarray(case.q_c[:, :, heads, :])
@@ -356,5 +356,77 @@ def test_absorb_path_with_a_value_dim_of_its_own(key, h_q, g, d_h, d_v, s_q, len
         torch.cuda.synchronize()
         ref = np.stack([O.output_projection(S.quantize(out[b], cfg.dtype), w_o) for b in range(cfg.B)])
         check("W^O over h_q * d_v columns", host(y), ref, cfg.dtype)
+    finally:
+        case.close()
+
+
+@pytest.mark.parametrize("key,h_q,g,d_h,d_v,s_q,lens,paged,cp", [
+    ("C2", 20, 4, 192, 256, 1, [300, 4000, 64], True, (0, 0)),    # the MLA checkpoint shape of Sec. 3.2.2, g = 4 (G = 5)
+    ("C2", 20, 5, 192, 256, 2, [129, 1000], True, (0, 1)),        # g = 5 (G = 4, no k_R sharing between waves), two step tokens
+    ("C2", 128, 8, 192, 256, 2, [700, 65, 2], False, (0, 0)),     # 8 groups of 16 heads, contiguous pages, L == s_q
+    ("C2", 32, 2, 192, 256, 1, [513], True, (0, 2)),              # 2 groups of 16 heads
+    ("C0", 8, 2, 16, 24, 2, [40, 7, 2], True, (0, 0)),            # fp32 kernels, value dim larger than the key dim
+    ("C0", 6, 3, 24, 8, 1, [33], True, (0, 0)),                   # fp32 kernels, value dim smaller than the key dim
+])
+def test_both_paths_with_a_value_dim_of_its_own(key, h_q, g, d_h, d_v, s_q, lens, paged, cp):
+    """d_h^V != d_h (Sec. 3.2.2) through the expanded cache: the one-shot expansion (K plane with d_h dims, V plane with
+    d_v dims), the GQA-path decode over it, the absorb path on the same weights, each against the oracle, and the
+    paper's statement that the two paths give the same attention output (Sec. 3.1) between the two GPU paths."""
+    cfg = S.CONFIGS[key].with_(B=len(lens), h_q=h_q, g=g, d_h=d_h, d_v=d_v, s_q=s_q, L=0, paged=paged,
+                               page_size=64 if key != "C0" else 8, seed=7007 + d_h + d_v + h_q)
+    case = Case(cfg, lens=lens, use_page_table=paged, chunk_pages=cp)
+    try:
+        out_a = run_absorb_path(case)
+        out_g = run_gqa_path(case)
+        assert out_a.shape == out_g.shape == (cfg.B, s_q, h_q, d_v)
+        check("absorb path vs gqa path", out_a, out_g, cfg.dtype)
+    finally:
+        case.close()
+
+
+@pytest.mark.parametrize("h_q,g,lens", [(20, 4, [200, 2, 65, 1000]), (128, 8, [300, 64])])
+def test_step_updates_with_a_value_dim_of_its_own(h_q, g, lens):
+    """(d_h, d_v) = (192, 256): the step's positions expanded by the tail variant hold bit for bit what the one-shot
+    expansion writes there, nothing else is written, and the reverse cache switch recovers the latent."""
+    from paper_2605_15250_amd import binding as B_
+    cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, d_h=192, d_v=256, s_q=2, L=0, paged=True, seed=7100 + h_q)
+    case = Case(cfg, lens=lens)
+    dec = case.dec
+    try:
+        dec.alloc_expanded(fill=0.0)
+        dec.expand(case.d_w_uk, case.d_w_uv)
+        torch.cuda.synchronize()
+        one_shot = dec.expanded_pool.clone()
+        dec.alloc_expanded()                          # NaN everywhere
+        dec.expand_tail(case.d_w_uk, case.d_w_uv, cfg.s_q)
+        torch.cuda.synchronize()
+        got = dec.expanded_pool
+        written = ~torch.isnan(got.float())
+        per_tok = cfg.g * (cfg.d_h + cfg.dv) + cfg.d_r
+        assert int(written.sum()) == cfg.B * cfg.s_q * per_tok
+        assert torch.equal(got[written].view(torch.int16), one_shot[written].view(torch.int16))
+        pool_h = host(got)
+        for b in range(cfg.B):
+            L = int(case.lens[b])
+            k2, v2, r2 = Lay.unpack_expanded_seq(pool_h, case.table[b], L, cfg.page_size, cfg.g, cfg.d_h, cfg.d_r, cfg.dv)
+            assert np.isfinite(k2[L - cfg.s_q:]).all() and np.isfinite(v2[L - cfg.s_q:]).all() and np.isfinite(r2[L - cfg.s_q:]).all()
+            assert np.isnan(k2[:L - cfg.s_q]).all() and np.isnan(v2[:L - cfg.s_q]).all()
+        # reverse switch: latent from the expanded keys through the left inverse of the stacked key up-projection
+        dec.expanded_pool = one_shot
+        w_inv = B_.gqla_left_inverse(dec.shape, case.w_uk)
+        truth = dec.latent_pool
+        dec.latent_pool = torch.zeros_like(truth)
+        dec.compress(case.to_device(S.quantize(w_inv, cfg.dtype), cfg.dtype))
+        torch.cuda.synchronize()
+        W = cfg.r_kv + cfg.d_r
+        rec_h, tru_h = host(dec.latent_pool).reshape(-1, W), host(truth).reshape(-1, W)
+        for b in range(cfg.B):
+            t = np.arange(int(case.lens[b]))
+            rows = case.table[b][t // cfg.page_size].astype(np.int64) * cfg.page_size + t % cfg.page_size
+            assert np.array_equal(rec_h[rows, cfg.r_kv:], tru_h[rows, cfg.r_kv:]), "k_R is copied"
+            r = rel_l2(rec_h[rows, :cfg.r_kv], tru_h[rows, :cfg.r_kv])
+            print("recovered latent, sequence %d: rel_l2 %.3e" % (b, r), flush=True)
+            assert r <= 2e-2      # what the 16-bit roundings of the keys and of the left inverse cost
+        dec.latent_pool = truth
     finally:
         case.close()

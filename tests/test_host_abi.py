@@ -338,32 +338,68 @@ def test_step_ops_validate_on_the_host():
     B.gqla_output_projection(B.make_shape(0, 32, 8, 128, 512, 64, 2, B.GQLA_BF16), 4096, A, A, A, None, 0, stream=0)
 
 
-def test_value_dim_is_accepted_on_the_absorb_path_only():
-    """gqla_shape.d_v: 0 means d_h; bf16 takes d_h in {128, 192} and d_v in {128, 256}; every entry point that touches
-    an expanded cache refuses a value dim that differs from the key dim (and bf16 key dims other than 128)."""
+def test_value_dim_of_its_own_is_accepted_where_the_kernels_exist():
+    """gqla_shape.d_v: 0 means d_h; on the absorb path bf16 takes d_h in {128, 192} and d_v in {128, 256}; what reads or
+    writes a 16-bit expanded cache takes (d_h, d_v) = (128, 128) or (192, 256); the 8-bit expanded cache and the
+    calibrated path choice take (128, 128) only."""
     A = 0x10000
     glm = B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 256)
     lens = [300, 4000]
     p = B.gqla_plan_create(glm, lens, 64, 256, B.GQLA_PATH_ABSORB)
+    pg = B.gqla_plan_create(glm, lens, 64, 256, B.GQLA_PATH_GQA)
     try:
-        assert B.gqla_plan_num_chunks(p) > 0
+        assert B.gqla_plan_num_chunks(p) > 0 and B.gqla_plan_num_chunks(pg) > 0
         # a plan made for another value dim does not fit
         other = B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 128)
         lat = B.make_cache(A, A, None, 64, 63, 126, 0)
         _expect(B.GQLA_ERR_PLAN, B.gqla_decode_absorb, other, p, A, A, lat, A, A, None, A, 1 << 30, stream=0)
+        # the GQA plan's workspace holds partials of d_v floats per row
+        n = B.gqla_plan_num_chunks(pg)
+        assert B.gqla_plan_workspace_bytes(pg) >= n * 20 * 256 * 4
+        # the 8-bit expanded cache has no kernels for this shape
+        exp8 = B.make_cache(A, A, None, 64, 63, 126, 4)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_decode_gqa_fp8, glm, pg, A, A, exp8, 1.0, 1.0, A, None, A, 1 << 30, stream=0)
     finally:
         B.gqla_plan_destroy(p)
-    _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, glm, lens, 64, 256, B.GQLA_PATH_GQA)
+        B.gqla_plan_destroy(pg)
     _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 160, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, B.GQLA_PATH_ABSORB)
     _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 128, 512, 64, 1, B.GQLA_BF16, 0.0, 192), lens, 64, 256, B.GQLA_PATH_ABSORB)
     _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, B.make_shape(2, 20, 4, 192, 512, 64, 1, B.GQLA_BF16), lens, 64, 256, B.GQLA_PATH_ABSORB)  # d_v = d_h = 192
+    # mixed pairs exist on the absorb path only
+    for d_h, d_v in ((128, 256), (192, 128)):
+        mixed = B.make_shape(2, 32, 8, d_h, 512, 64, 1, B.GQLA_BF16, 0.0, d_v)
+        pm = B.gqla_plan_create(mixed, lens, 64, 256, B.GQLA_PATH_ABSORB)
+        B.gqla_plan_destroy(pm)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_plan_create, mixed, lens, 64, 256, B.GQLA_PATH_GQA)
+        assert B.gqla_expand_workspace_bytes(mixed, 8) == 0
     lat = B.make_cache(A, A, None, 64, 4, 8, 0)
     full = B.make_cache(A, A, None, 64, 4, 8, 4)
-    _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache, glm, lat, A, A, 0, 4, full, A, 1 << 24, stream=0)
+    assert B.gqla_expand_workspace_bytes(glm, 4) == 4 * 512 * (192 + 256) * 2
+    _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache, glm, lat, A, A, 0, 4, full, A, 4 * 512 * (192 + 256) * 2 - 1, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache, glm, lat, A, A, 2, 3, B.make_cache(A, A, None, 64, 4, 8, 3), A, 1 << 24, stream=0)
     _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_fp8, glm, lat, A, A, 0, 4, full, 1.0, 1.0, A, 1 << 24, stream=0)
-    _expect(B.GQLA_ERR_SHAPE, B.gqla_compress_cache, glm, full, A, lat, stream=0)
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_fp8, glm, lat, A, A, 0, 4, full, 1, 1.0, 1.0, A, 1 << 24, stream=0)
     _expect(B.GQLA_ERR_SHAPE, B.gqla_quantize_expanded, glm, full, full, 1.0, 1.0, stream=0)
-    assert B.gqla_expand_workspace_bytes(glm, 4) == 0
+    # the variant with its scratch inside the library holds 4 groups of this shape, not 5
+    glm5 = B.make_shape(2, 20, 5, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 256)
+    _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_static, glm5, lat, A, A, 0, 5, B.make_cache(A, A, None, 64, 4, 8, 5), 1, stream=0)
+    # compress needs g d_h >= r_kv: 2 groups of 192 are too few
+    _expect(B.GQLA_ERR_SHAPE, B.gqla_compress_cache, B.make_shape(2, 20, 2, 192, 512, 64, 1, B.GQLA_BF16, 0.0, 256),
+            B.make_cache(A, A, None, 64, 4, 8, 2), A, lat, stream=0)
+    # sizes and offsets with a value dim of its own, against the oracle's layout
+    from oracle import layout as Lay
+    P, gc, d_h, d_v, d_r = 64, 4, 192, 256, 64
+    assert B.gqla_expanded_elems_per_token_dv(gc, d_h, d_v, d_r) == Lay.expanded_elems_per_token(gc, d_h, d_r, d_v) == 4 * 448 + 64
+    assert B.gqla_expanded_elems_per_token_dv(8, 128, 128, 64) == B.gqla_expanded_elems_per_token(8, 128, 64)
+    for page, j, slot in ((0, 0, 0), (3, 2, 17), (1, 3, 63)):
+        for d in (0, 7, 8, 191):
+            assert B.gqla_expanded_k_offset_dv(page, j, slot, d, P, gc, d_h, d_v, d_r) == Lay.expanded_k_offset(page, j, slot, d, P, gc, d_h, d_r, d_v)
+        for d in (0, 5, 192, 255):
+            assert B.gqla_expanded_v_offset_dv(page, j, slot, d, P, gc, d_h, d_v, d_r) == Lay.expanded_v_offset(page, j, slot, d, P, gc, d_h, d_r, d_v)
+        for d in (0, 9, 63):
+            assert B.gqla_expanded_kr_offset_dv(page, slot, d, P, gc, d_h, d_v, d_r) == Lay.expanded_kr_offset(page, slot, d, P, gc, d_h, d_r, d_v)
+        assert B.gqla_expanded_v_offset_dv(page, j, slot, 100, P, gc, 128, 128, d_r) == B.gqla_expanded_v_offset(page, j, slot, 100, P, gc, 128, d_r)
+        assert B.gqla_expanded_kr_offset_dv(page, slot, 9, P, gc, 128, 128, d_r) == B.gqla_expanded_kr_offset(page, slot, 9, P, gc, 128, d_r)
     # W^O takes h_q * d_v columns: 20 * 256 = 5120 = 20 phases of 256
     # 32 column tiles -> 16 ranges wanted -> 2 phases each -> 10 ranges
     assert B.gqla_output_projection_workspace_bytes(glm, 4096) == 10 * 2 * 4096 * 4
