@@ -49,11 +49,17 @@ def _compile(src: str, extra) -> str:
 # there), the expansion loads them asynchronously from inline assembly (a compiler-made copy before the wait would copy
 # stale data).  The compiler touches accumulation registers itself (v_accvgpr_write / _read / _mov outside the assembly
 # blocks) only when it runs out of ordinary registers: the build checks the generated assembly and refuses such a
-# kernel instead of shipping silent corruption.  The same kernels fetch page-table entries with a scalar load written
-# in inline assembly and wait for it by hand much later: a compiler-made copy of that register ahead of the wait reads
-# it while the load is pending, and the check refuses that too.
+# kernel instead of shipping silent corruption.
 NAMED_AGPR_SOURCES = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "decode_absorb_shared_bf16_kernel", "decode_absorb_fp8_kernel"],
                       "gqla_gemm_bf16.hip": ["expand_bf16_kernel"]}
+
+
+# Kernels that fetch page-table entries with a scalar load written in inline assembly and wait for it by hand much
+# later: a compiler-made copy of that register ahead of the wait would read it while the load is pending (the compiler
+# cannot see the load, so nothing protects such a read).  The build scans the generated assembly for any read of the
+# register between the load and the next wait for scalar memory and refuses the kernel.
+HAND_SCALAR_LOAD_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "decode_absorb_shared_bf16_kernel"],
+                            "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"]}
 
 
 # Kernels whose loops wait on hand-counted numbers of outstanding vector-memory instructions (s_waitcnt vmcnt(N) written
@@ -65,6 +71,25 @@ COUNTED_WAIT_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "d
                         "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"]}
 
 
+def _reads_register(instr: str, reg: str) -> bool:
+    """Does this instruction read scalar register `reg`?  The first operand is the destination, except for compares,
+    branches and stores, which only read."""
+    parts = instr.split(None, 1)
+    if len(parts) < 2:
+        return False
+    ops = [o.strip() for o in parts[1].split(",")]
+    if not parts[0].startswith(("s_cmp", "s_bitcmp", "v_cmp", "s_cbranch", "global_store", "ds_write", "buffer_store", "s_store")):
+        ops = ops[1:]
+    num = int(reg[1:])
+    for o in ops:
+        if re.fullmatch(r"%s" % reg, o):
+            return True
+        m = re.fullmatch(r"s\[(\d+):(\d+)\]", o)     # a register range that contains it
+        if m and int(m.group(1)) <= num <= int(m.group(2)):
+            return True
+    return False
+
+
 def _check_device_code(src: str, extra) -> None:
     """One device-only compile to assembly with the resource report: no compiler-made accumulation-register traffic in
     the kernels of NAMED_AGPR_SOURCES, no spills and no scratch in those of COUNTED_WAIT_KERNELS."""
@@ -74,7 +99,9 @@ def _check_device_code(src: str, extra) -> None:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stderr))
-    kernels = NAMED_AGPR_SOURCES.get(src, [])
+    agpr_kernels = NAMED_AGPR_SOURCES.get(src, [])
+    sload_kernels = HAND_SCALAR_LOAD_KERNELS.get(src, [])
+    kernels = sorted(set(agpr_kernels) | set(sload_kernels))
     current, in_asm, seen_labels = None, False, set()
     pending = None   # scalar register that a hand-written s_load_dword has in flight (until the hand-written wait)
     with open(asm_path) as fh:
@@ -91,16 +118,17 @@ def _check_device_code(src: str, extra) -> None:
                 in_asm = True
             elif ";;#ASMEND" in t:
                 in_asm = False
-            elif current and not in_asm and t.startswith("v_accvgpr_"):
+            elif current in agpr_kernels and not in_asm and t.startswith("v_accvgpr_"):
                 raise RuntimeError("%s: the compiler uses accumulation registers of its own in %s (%s); "
                                    "lower the kernel's VGPR pressure" % (src, current, t))
-            elif current and in_asm and t.startswith("s_load_dword "):
+            elif current in sload_kernels and in_asm and t.startswith("s_load_dword "):
                 pending = t.split()[1].rstrip(",")
             elif current and pending and t.startswith("s_waitcnt") and "lgkmcnt(0)" in t:   # hand-written or the compiler's
                 pending = None
-            elif current and pending and not in_asm and not t.startswith((";", ".")) and re.search(r"\b%s\b" % pending, t):
+            elif current and pending and not in_asm and not t.startswith((";", ".")) and _reads_register(t, pending):
                 # (in the order of the listing, which is the order of execution on the paths where this can happen:
-                # the load and its wait sit in one loop body)
+                # the load and its wait sit in one loop body; a write to the register belongs to the branch that
+                # computes the value without a load)
                 raise RuntimeError("%s: %s reads %s while the scalar load issued by hand is still in flight (%s): the "
                                    "compiler cannot see that load, so no wait protects this read" % (src, current, pending, t))
     missing = [k for k in kernels if k not in seen_labels]
