@@ -15,6 +15,8 @@ namespace gqla {
 
 namespace {
 
+constexpr float kRescaleThreshold = 8.f;  // log2 units
+
 // FP8 = true: K_C and V are E4M3 codes (16-byte vectors holding one lane's elements of two consecutive k-steps, see
 // the header's format), widened to bf16 in registers right before their MFMAs; the scales enter once per tile (K: on
 // the content part of the logits, before the RoPE part is added) and once per chunk (V: on the normalised output).
@@ -33,7 +35,12 @@ __device__ __forceinline__ bf16x8 widen_e4m3(uint32_t w0, uint32_t w1) {
 // DH: key dims per head, DV: value dims per head (d_h^V of Sec. 3.2.2).  MAXT: threads per workgroup at most -- 512
 // (two waves per SIMD, 256 registers each) for equal dims of 128; the (192, 256) shape keeps 128 more accumulators and
 // 28 cache vectors in flight per wave, needs the whole register file of a SIMD and runs with 256.
-template <int DH, int DV, int DR, bool FP8, int MAXT>
+// RB: 32-row blocks per wave.  A group with more than 32 query rows (G s_q = 64: 32 heads per group with one
+// multi-token-prediction head) gives RB = 2: one wave multiplies every loaded cache vector into both blocks' S^T and
+// O^T, so that the vector crosses the vector-memory path once (two waves with 32 rows each would both load it; such a
+// wave also needs a SIMD's whole register file: MAXT = 256).  Its query fragments (96 registers' worth, the same for
+// every tile) live in LDS instead, 24 KB per wave, and are read back one 16-byte vector per MFMA.
+template <int DH, int DV, int DR, bool FP8, int MAXT, int RB>
 __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg,
                                                                float k_scale, float v_scale) {
   constexpr int KS_C = DH / 16;  // k-steps over the content dims
@@ -50,25 +57,45 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
   const ChunkEntry ce = a.chunks[chunk];
   const int n = lane & 31, h = lane >> 5;
 
-  // query row of this lane: rho in [0, G*s_q), rho = t*G + head-in-group
-  const int rho = rb * 32 + n;
-  const bool row_ok = rho < a.G * a.s_q;
-  const int t = row_ok ? rho / a.G : 0;
-  const int head = j * a.G + (row_ok ? rho % a.G : 0);
-  const int64_t qrow = (int64_t)(ce.b * a.s_q + t) * a.h_q + head;
-  const int vis_end = row_ok ? min(ce.tok_end, ce.L - a.s_q + t + 1) : 0;  // tokens this row may see in the chunk
-  const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);             // below this every real row sees every token
-
-  bf16x8 qc[KS_C], qr[KS_R];
-  {
+  // query rows of this lane, one per row block x: rho in [0, G*s_q), rho = t*G + head-in-group
+  constexpr bool QLDS = RB > 1;  // query fragments in LDS (dynamic shared memory: RB * (KS_C + KS_R) KB per wave)
+  extern __shared__ __attribute__((aligned(16))) char q_lds_all[];
+  char* const q_lds = q_lds_all + (threadIdx.x >> 6) * (RB * (KS_C + KS_R) * 1024) + lane * 16;
+  bool row_ok[RB];
+  int t_of[RB], head_of[RB], vis_end[RB];
+  bf16x8 qc[QLDS ? 1 : RB][QLDS ? 1 : KS_C], qr[QLDS ? 1 : RB][QLDS ? 1 : KS_R];
+#pragma unroll
+  for (int x = 0; x < RB; ++x) {
+    const int rho = (rb * RB + x) * 32 + n;
+    row_ok[x] = rho < a.G * a.s_q;
+    t_of[x] = row_ok[x] ? rho / a.G : 0;
+    head_of[x] = j * a.G + (row_ok[x] ? rho % a.G : 0);
+    vis_end[x] = row_ok[x] ? min(ce.tok_end, ce.L - a.s_q + t_of[x] + 1) : 0;  // tokens this row may see in the chunk
+    const int64_t qrow = (int64_t)(ce.b * a.s_q + t_of[x]) * a.h_q + head_of[x];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     const __bf16* pc = (const __bf16*)a.q_a + qrow * DH + h * 8;
     const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
+    if constexpr (QLDS) {  // (each lane reads back only what it wrote itself: no barrier needed)
 #pragma unroll
-    for (int ks = 0; ks < KS_C; ++ks) qc[ks] = row_ok ? *(const bf16x8*)(pc + ks * 16) : zero;
+      for (int ks = 0; ks < KS_C; ++ks) *(bf16x8*)(q_lds + (x * (KS_C + KS_R) + ks) * 1024) = row_ok[x] ? *(const bf16x8*)(pc + ks * 16) : zero;
 #pragma unroll
-    for (int ks = 0; ks < KS_R; ++ks) qr[ks] = row_ok ? *(const bf16x8*)(pr + ks * 16) : zero;
+      for (int ks = 0; ks < KS_R; ++ks) *(bf16x8*)(q_lds + (x * (KS_C + KS_R) + KS_C + ks) * 1024) = row_ok[x] ? *(const bf16x8*)(pr + ks * 16) : zero;
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS_C; ++ks) qc[x][ks] = row_ok[x] ? *(const bf16x8*)(pc + ks * 16) : zero;
+#pragma unroll
+      for (int ks = 0; ks < KS_R; ++ks) qr[x][ks] = row_ok[x] ? *(const bf16x8*)(pr + ks * 16) : zero;
+    }
   }
+  auto q_content = [&](int x, int ks) __attribute__((always_inline)) -> bf16x8 {
+    if constexpr (QLDS) return *(const bf16x8*)(q_lds + (x * (KS_C + KS_R) + ks) * 1024);
+    else return qc[x][ks];
+  };
+  auto q_rope = [&](int x, int ks) __attribute__((always_inline)) -> bf16x8 {
+    if constexpr (QLDS) return *(const bf16x8*)(q_lds + (x * (KS_C + KS_R) + KS_C + ks) * 1024);
+    else return qr[x][ks];
+  };
+  const int unmasked_end = min(ce.tok_end, ce.L - a.s_q + 1);             // below this every real row sees every token
 
   const int P = a.cache.page_size;
   const int gc = a.cache.groups;
@@ -79,6 +106,7 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
 
   bf16x8 kf[KS_C], rf[KS_R], vf[MT][2];
   u32x4 kf8[FP8 ? KS_C / 2 : 1], vf8[FP8 ? MT : 1];                           // raw code vectors (FP8 only)
+
   bool k_ok = true, v_ok = true;
 
   // The shared RoPE key of a tile is the same for every group.  When all waves of a workgroup are groups of one
@@ -133,12 +161,17 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
     }
   };
 
-  f32x16 o[MT];
+  f32x16 o[RB][MT];
+  float m_run[RB], l_run[RB];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int x = 0; x < RB; ++x) {
+    m_run[x] = GQLA_NEG_INF;
+    l_run[x] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) o[mt][i] = 0.f;
-  float m_run = GQLA_NEG_INF, l_run = 0.f;
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[x][mt][i] = 0.f;
+  }
 
   // Page ids travel through the scalar cache, looked up one tile ahead of the loads that need them: a vector load of
   // the table entry would have to be waited for with vmcnt(0), i.e. behind every cache load still in flight.
@@ -160,9 +193,11 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
   load_v(ce.tok_begin, pg_next);
   if (ce.tok_begin + 32 < ce.tok_end) lookup_start(ce.tok_begin + 32, pg_raw);
   for (int tok = ce.tok_begin; tok < ce.tok_end; tok += 32) {
-    f32x16 s;
+    f32x16 s[RB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    for (int x = 0; x < RB; ++x)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[x][i] = 0.f;
     if constexpr (FP8) {
 #pragma unroll
       for (int kp = 0; kp < KS_C / 2; ++kp) {
@@ -178,11 +213,16 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
       }
     }
     const bool tile_v_ok = v_ok;  // v_ok is overwritten by the next tile's request below (FP8)
+
 #pragma unroll
-    for (int ks = 0; ks < KS_C; ++ks) s = mfma32(kf[ks], qc[ks], s);
+    for (int ks = 0; ks < KS_C; ++ks)
+#pragma unroll
+      for (int x = 0; x < RB; ++x) s[x] = mfma32(kf[ks], q_content(x, ks), s[x]);
     if constexpr (FP8) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] *= k_scale;
+      for (int x = 0; x < RB; ++x)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[x][i] *= k_scale;
     }
     if (share_kr) {
       // this tile's k_R was requested before the cache loads that followed it (loads complete in issue order): the
@@ -198,7 +238,9 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
       for (int ks = 0; ks < KS_R; ++ks) rf[ks] = *(const bf16x8*)(kr + ks * 1024);
     }
 #pragma unroll
-    for (int ks = 0; ks < KS_R; ++ks) s = mfma32(rf[ks], qr[ks], s);
+    for (int ks = 0; ks < KS_R; ++ks)
+#pragma unroll
+      for (int x = 0; x < RB; ++x) s[x] = mfma32(rf[ks], q_rope(x, ks), s[x]);
     const bool tile_k_ok = k_ok;
     const bool has_next = tok + 32 < ce.tok_end;
     if (has_next) {
@@ -211,53 +253,63 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
     }
 
     // online softmax, base-2 domain; register i of lane (n, h) is token tok + 8*(i/4) + 4*h + i%4
-    float sv[16];
+    bf16x8 pf[RB][2];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sv[i] = s[i] * a.scale_log2e;
-    const bool need_mask = (tok + 32 > unmasked_end) || !tile_k_ok || !row_ok;
-    if (need_mask) {
-      const int lim = tile_k_ok ? vis_end : 0;
+    for (int x = 0; x < RB; ++x) {
+      float sv[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int tk = tok + 8 * (i >> 2) + 4 * h + (i & 3);
-        if (tk >= lim) sv[i] = GQLA_NEG_INF;
+      for (int i = 0; i < 16; ++i) sv[i] = s[x][i] * a.scale_log2e;
+      const bool need_mask = (tok + 32 > unmasked_end) || !tile_k_ok || !row_ok[x];
+      if (need_mask) {
+        const int lim = tile_k_ok ? vis_end[x] : 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int tk = tok + 8 * (i >> 2) + 4 * h + (i & 3);
+          if (tk >= lim) sv[i] = GQLA_NEG_INF;
+        }
       }
-    }
-    float tmax = sv[0];
+      float tmax = sv[0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sv[i]);
-    tmax = pair_max(tmax);
-    const float m_new = fmaxf(m_run, tmax);
-    const float m_use = (m_new == GQLA_NEG_INF) ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_use);
-    m_run = m_new;
-    float psum = 0.f;
+      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sv[i]);
+      tmax = pair_max(tmax);
+      // m_run is the reference of the exponentials, not the exact running maximum: it moves only when some row's
+      // maximum has outgrown it by kRescaleThreshold (log2 units; the probabilities then stay below 2^threshold, far
+      // inside the range of bf16 and fp32), so that far into a long context the update of O^T and l is skipped
+      if (__builtin_amdgcn_ballot_w64(tmax > m_run[x] + kRescaleThreshold) != 0) {
+        const float m_new = fmaxf(m_run[x], tmax);
+        const float alpha = fast_exp2(m_run[x] - ((m_new == GQLA_NEG_INF) ? 0.f : m_new));
+        m_run[x] = m_new;
+        l_run[x] *= alpha;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      sv[i] = fast_exp2(sv[i] - m_use);
-      psum += sv[i];
-    }
-    l_run = l_run * alpha + psum;  // per-lane partial sum; the two half-waves are added at the end
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+          for (int i = 0; i < 16; ++i) o[x][mt][i] *= alpha;
+      }
+      const float m_use = (m_run[x] == GQLA_NEG_INF) ? 0.f : m_run[x];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[mt][i] *= alpha;
+      for (int i = 0; i < 16; ++i) sv[i] = fast_exp2(sv[i] - m_use);
 
-    // P^T fragments: k-step kk covers tokens tok + 16*kk .. +15, lane half h needs tokens 8h .. 8h+7 of them
-    bf16x8 pf[2];
+      // P^T fragments: k-step kk covers tokens tok + 16*kk .. +15, lane half h needs tokens 8h .. 8h+7 of them.
+      // The denominator sums the probabilities as the matrix cores see them (rounded to bf16): numerator and
+      // denominator then weigh every token alike, whatever the reference of the exponentials is.
+      float psum = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const uint32_t x0 = pack_bf16(sv[8 * kk + 0], sv[8 * kk + 1]), x1 = pack_bf16(sv[8 * kk + 2], sv[8 * kk + 3]);
-      const uint32_t y0 = pack_bf16(sv[8 * kk + 4], sv[8 * kk + 5]), y1 = pack_bf16(sv[8 * kk + 6], sv[8 * kk + 7]);
-      u32x4 w;
-      uint32_t r0, r1;
-      half_swap(x0, y0, r0, r1);
-      w[0] = r0;
-      w[2] = r1;
-      half_swap(x1, y1, r0, r1);
-      w[1] = r0;
-      w[3] = r1;
-      pf[kk] = __builtin_bit_cast(bf16x8, w);
+      for (int kk = 0; kk < 2; ++kk) {
+        const uint32_t x0 = pack_bf16(sv[8 * kk + 0], sv[8 * kk + 1]), x1 = pack_bf16(sv[8 * kk + 2], sv[8 * kk + 3]);
+        const uint32_t y0 = pack_bf16(sv[8 * kk + 4], sv[8 * kk + 5]), y1 = pack_bf16(sv[8 * kk + 6], sv[8 * kk + 7]);
+#pragma unroll
+        for (uint32_t wd : {x0, x1, y0, y1}) psum += __builtin_bit_cast(float, wd << 16) + __builtin_bit_cast(float, wd & 0xffff0000u);
+        u32x4 w;
+        uint32_t r0, r1;
+        half_swap(x0, y0, r0, r1);
+        w[0] = r0;
+        w[2] = r1;
+        half_swap(x1, y1, r0, r1);
+        w[1] = r0;
+        w[3] = r1;
+        pf[x][kk] = __builtin_bit_cast(bf16x8, w);
+      }
+      l_run[x] += psum;  // per-lane partial sum; the two half-waves are added at the end
     }
 
     // values of tokens outside the chunk may hold any bits (NaN included): zero them so that 0 * v stays 0
@@ -274,31 +326,38 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) o[mt] = mfma32(vf[mt][kk], pf[kk], o[mt]);
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int x = 0; x < RB; ++x) o[x][mt] = mfma32(vf[mt][kk], pf[x][kk], o[x][mt]);
     if constexpr (!FP8) {
       if (has_next) load_v(tok + 32, pg_next);
     }
   }
 
-  const float l_tot = pair_sum(l_run);
-  if (!row_ok) return;
-  const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * (FP8 ? v_scale : 1.f);
-  const int64_t prow = (int64_t)chunk * a.M + (int64_t)t * a.h_q + head;
-  float* po = (float*)a.part_o + prow * DV;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int x = 0; x < RB; ++x) {
+    const float l_tot = pair_sum(l_run[x]);
+    if (!row_ok[x]) continue;
+    const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * (FP8 ? v_scale : 1.f);
+    const int64_t prow = (int64_t)chunk * a.M + (int64_t)t_of[x] * a.h_q + head_of[x];
+    float* po = (float*)a.part_o + prow * DV;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      f32x4 v = {o[mt][4 * q] * inv, o[mt][4 * q + 1] * inv, o[mt][4 * q + 2] * inv, o[mt][4 * q + 3] * inv};
-      *(f32x4*)(po + mt * 32 + 8 * q + 4 * h) = v;
-    }
-  if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_run + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v = {o[x][mt][4 * q] * inv, o[x][mt][4 * q + 1] * inv, o[x][mt][4 * q + 2] * inv, o[x][mt][4 * q + 3] * inv};
+        *(f32x4*)(po + mt * 32 + 8 * q + 4 * h) = v;
+      }
+    if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_run[x] + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+  }
 }
 
 }  // namespace
 
-static void gqa_launch_shape(const DecodeArgs& a, int max_wpb, int& row_blocks, int& n_items, bool& team, int& wpb, int& blocks) {
-  row_blocks = (a.G * a.s_q + 31) / 32;
+// rows_per_wave: 32, or 64 when a wave takes two row blocks
+static void gqa_launch_shape(const DecodeArgs& a, int max_wpb, int rows_per_wave, int& row_blocks, int& n_items, bool& team, int& wpb,
+                             int& blocks) {
+  row_blocks = (a.G * a.s_q + rows_per_wave - 1) / rows_per_wave;
   n_items = a.n_chunks * row_blocks * a.g;
   // all waves of a workgroup are groups of one (chunk, row block) when the group count is a multiple of the waves per
   // workgroup: then they share the tile's k_R through LDS (and run in step, one barrier per tile)
@@ -310,25 +369,38 @@ static void gqa_launch_shape(const DecodeArgs& a, int max_wpb, int& row_blocks, 
   blocks = (n_items + wpb - 1) / wpb;
 }
 
-hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
+template <bool FP8>
+static hipError_t launch_decode_gqa_128(const DecodeArgs& a, float k_scale, float v_scale, hipStream_t s) {
   int row_blocks, n_items, wpb, blocks;
   bool team;
-  if (a.d_h == 192) {  // (d_h, d_v) = (192, 256): four waves per workgroup
-    gqa_launch_shape(a, 4, row_blocks, n_items, team, wpb, blocks);
-    decode_gqa_bf16_kernel<192, 256, 64, false, 256><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+  if (a.G * a.s_q > 32) {  // more than one row block per group: two per wave, four waves per workgroup
+    gqa_launch_shape(a, 4, 64, row_blocks, n_items, team, wpb, blocks);
+    constexpr int kQBytesPerWave = 2 * (128 / 16 + 64 / 16) * 1024;  // both row blocks' query fragments
+    static const hipError_t attr = hipFuncSetAttribute((const void*)decode_gqa_bf16_kernel<128, 128, 64, FP8, 256, 2>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kQBytesPerWave);
+    if (attr != hipSuccess) return attr;
+    decode_gqa_bf16_kernel<128, 128, 64, FP8, 256, 2><<<blocks, 64 * wpb, wpb * kQBytesPerWave, s>>>(a, n_items, row_blocks, team ? 1 : 0,
+                                                                                                    k_scale, v_scale);
     return hipGetLastError();
   }
-  gqa_launch_shape(a, 8, row_blocks, n_items, team, wpb, blocks);
-  decode_gqa_bf16_kernel<128, 128, 64, false, 512><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+  gqa_launch_shape(a, 8, 32, row_blocks, n_items, team, wpb, blocks);
+  decode_gqa_bf16_kernel<128, 128, 64, FP8, 512, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
   return hipGetLastError();
 }
 
+hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
+  if (a.d_h == 192) {  // (d_h, d_v) = (192, 256): four waves per workgroup, one row block each
+    int row_blocks, n_items, wpb, blocks;
+    bool team;
+    gqa_launch_shape(a, 4, 32, row_blocks, n_items, team, wpb, blocks);
+    decode_gqa_bf16_kernel<192, 256, 64, false, 256, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+    return hipGetLastError();
+  }
+  return launch_decode_gqa_128<false>(a, 1.f, 1.f, s);
+}
+
 hipError_t launch_decode_gqa_fp8(const DecodeArgs& a, float k_scale, float v_scale, hipStream_t s) {
-  int row_blocks, n_items, wpb, blocks;
-  bool team;
-  gqa_launch_shape(a, 8, row_blocks, n_items, team, wpb, blocks);
-  decode_gqa_bf16_kernel<128, 128, 64, true, 512><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
-  return hipGetLastError();
+  return launch_decode_gqa_128<true>(a, k_scale, v_scale, s);
 }
 
 }  // namespace gqla

@@ -200,6 +200,8 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (8, 8, 1, [130, 64], False, (0, 0)),                 # G = 1 (multi-head limit of the grouping): 8 rows
     (128, 4, 2, [700, 65], True, (0, 0)),                # (g, s_q) = (4, 2) at 128 heads: G = 32, 64 rows per group
     (128, 4, 1, [321], False, (0, 0)),                   # (g, s_q) = (4, 1), the 2176-byte-per-token operating point
+    (64, 1, 1, [300, 70], True, (0, 0)),                 # one group of 64 heads: a GQA wave takes both 32-row blocks, no k_R sharing
+    (96, 2, 2, [513, 64, 2], True, (0, 1)),              # 96 rows per group: two waves of two row blocks, the last block all padding
 ])
 @pytest.mark.parametrize("num_cus", [256, 2])   # planned for the whole chip, or for a sliver of it: with few chunks and
                                                 # many compute units the absorb decode gives every 32 query rows a
