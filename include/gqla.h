@@ -114,12 +114,16 @@ typedef struct {
  * Rule (all integer, reproduced bit for bit by the tests' independent implementation):
  *   npages_b = ceil(L_b / P);   slots = number of chunks the device works on at once:
  *       absorb: max(1, num_cus / ceil(h_q*s_q / 128))          gqa: max(1, num_cus*8 / (g * ceil(G*s_q / 32)))
+ *       (gqa with a token team -- g = 1 and h_q*s_q <= 32, where the eight waves of a workgroup share one chunk:
+ *       max(1, num_cus))
  *   chunk_pages = the cp in 1..max_b npages_b minimising, with n(cp) = sum_b ceil(npages_b/cp) chunks,
  *           w(cp) * ceil(n(cp) / slots) * (cp + ovh)  +  merge * ceil(max_b npages_b / cp),
- *       in eightieths of the time one page takes: ovh = 4 (absorb) or 2 (gqa) pages of per-chunk fixed cost;
+ *       in eightieths of the time one page takes: ovh = 4 (absorb) or 2 (gqa; 16 with a token team) pages of
+ *       per-chunk fixed cost;
  *       merge = 16 (absorb) or 5 (gqa) per chunk partial that the combine merges for the longest sequence;
  *       w(cp) = 80, except on the absorb path when the decode launch gives every 32 query rows a workgroup of their
  *       own and a page costs less: w(cp) = 53 if h_q*s_q <= 32 or 8*ceil(n(cp)/8) * ceil(h_q*s_q/32) <= num_cus;
+ *       w(cp) = 10 on the gqa path with a token team;
  *       ties go to the larger cp;
  *   sequence b gets n_b = ceil(npages_b / chunk_pages) chunks of ceil(npages_b / n_b) pages (last one shorter);
  *   chunk k of b covers tokens [k*per_b*P, min((k+1)*per_b*P, L_b)) and owns partial slot first_slot[b] + k.

@@ -138,19 +138,29 @@ PATH_ABSORB = 0
 PATH_GQA = 1
 
 
+def gqa_token_team(h_q, g, s_q):
+    """GQA path with one group of at most 32 query rows: the eight waves of a workgroup share one chunk."""
+    return g == 1 and h_q * s_q <= 32
+
+
 def plan_slots(num_cus, path, h_q, g, s_q):
     """How many chunks the device works on at once under the documented launch shapes:
     absorb  one 4-wave workgroup per CU covers 128 query rows  -> num_cus / ceil(h_q*s_q / 128)
-    gqa     8 waves per CU, one wave per (chunk, group, 32-row block) -> num_cus*8 / (g * ceil(G*s_q / 32))"""
+    gqa     8 waves per CU, one wave per (chunk, group, 32-row block) -> num_cus*8 / (g * ceil(G*s_q / 32)),
+            or one workgroup per chunk -> num_cus with a token team"""
     if path == PATH_ABSORB:
         rb = -(-(h_q * s_q) // 128)
         return max(1, num_cus // rb)
+    if gqa_token_team(h_q, g, s_q):
+        return max(1, num_cus)
     rb = -(-((h_q // g) * s_q) // 32)
     return max(1, (num_cus * 8) // (g * rb))
 
 
-def plan_overhead_pages(path):
-    return 4 if path == PATH_ABSORB else 2
+def plan_overhead_pages(path, h_q=0, g=0, s_q=0):
+    if path == PATH_ABSORB:
+        return 4
+    return 16 if gqa_token_team(h_q, g, s_q) else 2
 
 
 def plan_merge_cost(path):
@@ -158,12 +168,13 @@ def plan_merge_cost(path):
     return 16 if path == PATH_ABSORB else 5
 
 
-def plan_page_weight(path, n_chunks, num_cus, h_q, s_q):
+def plan_page_weight(path, n_chunks, num_cus, h_q, s_q, g=0):
     """Eightieths of the reference page time that one page costs a workgroup: 80, or 53 on the absorb path when the
     launch gives every 32 query rows a workgroup of their own -- at most 32 rows per sequence, or so few chunks
-    (counted in eights) that one workgroup per chunk and 32 rows still fits the device in one round."""
+    (counted in eights) that one workgroup per chunk and 32 rows still fits the device in one round; 10 on the GQA
+    path with a token team (eight waves share the chunk's pages)."""
     if path != PATH_ABSORB:
-        return 80
+        return 10 if gqa_token_team(h_q, g, s_q) else 80
     M = h_q * s_q
     padded = -(-n_chunks // 8) * 8
     return 53 if (M <= 32 or padded * (-(-M // 32)) <= num_cus) else 80
@@ -175,13 +186,13 @@ def plan_chunk_pages(lens, P, num_cus, path, h_q, g, s_q):
     n_chunks(cp) = sum_b ceil(npages_b / cp); ties go to the larger cp."""
     npages = [pages_needed(L, P) for L in lens]
     slots = plan_slots(num_cus, path, h_q, g, s_q)
-    ovh = plan_overhead_pages(path)
+    ovh = plan_overhead_pages(path, h_q, g, s_q)
     longest = max(npages)
     best_cp, best_cost = 1, None
     for cp in range(1, longest + 1):
         n_chunks = sum(-(-n // cp) for n in npages)
         rounds = -(-n_chunks // slots)
-        cost = (plan_page_weight(path, n_chunks, num_cus, h_q, s_q) * rounds * (cp + ovh)
+        cost = (plan_page_weight(path, n_chunks, num_cus, h_q, s_q, g) * rounds * (cp + ovh)
                 + plan_merge_cost(path) * (-(-longest // cp)))
         if best_cost is None or cost <= best_cost:
             best_cp, best_cost = cp, cost

@@ -82,12 +82,18 @@ gqla_status check_cache(const gqla_shape* s, const gqla_cache* c, int32_t page_s
   return GQLA_OK;
 }
 
+// GQA path, one group with at most 32 query rows (one rank's share of head-axis tensor parallelism): a chunk would
+// be a single wave's work; instead the eight waves of a workgroup take every eighth tile of one chunk each and merge
+// their partials before anything is written.
+bool gqa_token_team(const gqla_shape& s) { return s.g == 1 && (int64_t)s.h_q * s.s_q <= 32; }
+
 int32_t plan_slots(const gqla_shape& s, int32_t num_cus, int32_t path) {
   if (path == GQLA_PATH_ABSORB) {
     const int32_t rb = (int32_t)ceil_div((int64_t)s.h_q * s.s_q, 128);
     return std::max(1, num_cus / rb);
   }
   const int32_t rb = (int32_t)ceil_div((int64_t)(s.h_q / s.g) * s.s_q, 32);
+  if (gqa_token_team(s)) return std::max(1, num_cus);  // the eight waves of a workgroup share one chunk
   return std::max<int64_t>(1, (int64_t)num_cus * 8 / ((int64_t)s.g * rb));
 }
 
@@ -95,12 +101,14 @@ int32_t plan_slots(const gqla_shape& s, int32_t num_cus, int32_t path) {
 // 128-row absorb workgroup (or a GQA wave) spends on one page: rounds of chunks on the device, each a chunk plus its
 // fixed cost, then the combine, whose time is set by the longest chain of chunk partials it merges for one sequence.
 // On the absorb path a page costs 53 instead of 80 when the launch gives every 32 query rows a workgroup of their own
-// (at most 32 rows per sequence, or so few chunks that all those workgroups run at once).
+// (at most 32 rows per sequence, or so few chunks that all those workgroups run at once).  On the GQA path with a token
+// team a page costs the workgroup an eighth (10), and the fixed cost counts eight times as many pages (16).
 int32_t choose_chunk_pages(const std::vector<int32_t>& npages, const gqla_shape& s, int32_t num_cus, int32_t path) {
   int32_t max_np = 1;
   for (int32_t v : npages) max_np = std::max(max_np, v);
   const int64_t slots = plan_slots(s, num_cus, path);
-  const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : 2;
+  const bool team = path == GQLA_PATH_GQA && gqa_token_team(s);
+  const int64_t ovh = path == GQLA_PATH_ABSORB ? 4 : (team ? 16 : 2);
   const int64_t merge = path == GQLA_PATH_ABSORB ? 16 : 5;
   const int64_t M = (int64_t)s.h_q * s.s_q;
   int64_t best = -1;
@@ -109,7 +117,8 @@ int32_t choose_chunk_pages(const std::vector<int32_t>& npages, const gqla_shape&
     int64_t n = 0;
     for (int32_t v : npages) n += ceil_div(v, c);
     const bool shared_rows = path == GQLA_PATH_ABSORB && (M <= 32 || ceil_div(n, 8) * 8 * ceil_div(M, 32) <= num_cus);
-    const int64_t cost = (shared_rows ? 53 : 80) * ceil_div(n, slots) * (c + ovh) + merge * ceil_div(max_np, c);
+    const int64_t weight = team ? 10 : (shared_rows ? 53 : 80);
+    const int64_t cost = weight * ceil_div(n, slots) * (c + ovh) + merge * ceil_div(max_np, c);
     if (best < 0 || cost <= best) {
       best = cost;
       cp = c;

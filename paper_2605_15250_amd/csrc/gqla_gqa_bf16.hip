@@ -40,17 +40,25 @@ __device__ __forceinline__ bf16x8 widen_e4m3(uint32_t w0, uint32_t w1) {
 // O^T, so that the vector crosses the vector-memory path once (two waves with 32 rows each would both load it; such a
 // wave also needs a SIMD's whole register file: MAXT = 256).  Its query fragments (96 registers' worth, the same for
 // every tile) live in LDS instead, 24 KB per wave, and are read back one 16-byte vector per MFMA.
+// tt (kernel argument): token team.  1: a wave works through its chunk alone.  8 (one group with at most 32 query rows,
+// RB = 1): the eight waves of a workgroup share one chunk, wave w taking tiles w, w + 8, ...; their eight partial
+// states (m, l, O^T) are merged through LDS, so that one partial per chunk reaches memory instead of eight.
 template <int DH, int DV, int DR, bool FP8, int MAXT, int RB>
 __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int n_items, int row_blocks, int share_kr_arg,
-                                                               float k_scale, float v_scale) {
+                                                               int tt_arg, float k_scale, float v_scale) {
   constexpr int KS_C = DH / 16;  // k-steps over the content dims
   constexpr int KS_R = DR / 16;  // k-steps over the RoPE dims
   constexpr int MT = DV / 32;    // 32-dim tiles of the output
   static_assert(!FP8 || DH == DV, "the 8-bit page format is written for equal dims");
+  constexpr bool CAN_TEAM = RB == 1 && MT == 4;  // the merge below is written (and its LDS sized) for 64 accumulators per lane
+  const int tt = CAN_TEAM ? tt_arg : 1;
   const int lane = threadIdx.x & 63;
   const int wpb = __builtin_amdgcn_readfirstlane(blockDim.x >> 6);  // waves per workgroup: 8, or the number of groups when that is 2 or 4
-  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));  // wave-uniform: keep it scalar
-  if (item >= n_items) return;
+  const int wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * (wpb / tt) + wave_in_wg / tt);  // wave-uniform: keep it scalar
+  const int tw = wave_in_wg % tt;   // position in the token team
+  const int tstep = 32 * tt;        // tokens from one tile of this wave to its next
+  if (item >= n_items) return;      // (a whole token team leaves together)
   const int j = item % a.g;
   const int rb = (item / a.g) % row_blocks;
   const int chunk = item / (a.g * row_blocks);
@@ -59,8 +67,8 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
 
   // query rows of this lane, one per row block x: rho in [0, G*s_q), rho = t*G + head-in-group
   constexpr bool QLDS = RB > 1;  // query fragments in LDS (dynamic shared memory: RB * (KS_C + KS_R) KB per wave)
-  extern __shared__ __attribute__((aligned(16))) char q_lds_all[];
-  char* const q_lds = q_lds_all + (threadIdx.x >> 6) * (RB * (KS_C + KS_R) * 1024) + lane * 16;
+  extern __shared__ __attribute__((aligned(16))) char dyn_lds[];  // RB > 1: query fragments; tt > 1: the merge buffers
+  char* const q_lds = dyn_lds + (threadIdx.x >> 6) * (RB * (KS_C + KS_R) * 1024) + lane * 16;
   bool row_ok[RB];
   int t_of[RB], head_of[RB], vis_end[RB];
   bf16x8 qc[QLDS ? 1 : RB][QLDS ? 1 : KS_C], qr[QLDS ? 1 : RB][QLDS ? 1 : KS_R];
@@ -185,14 +193,18 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
     if (table_row) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(raw));
   };
   int32_t pg_raw = 0;
-  lookup_start(ce.tok_begin, pg_raw);
-  lookup_done(pg_raw);
-  int32_t pg_next = checked(pg_raw);
-  if (share_kr) stage_kr(ce.tok_begin, pg_next, 0);
-  load_k(ce.tok_begin, pg_next);
-  load_v(ce.tok_begin, pg_next);
-  if (ce.tok_begin + 32 < ce.tok_end) lookup_start(ce.tok_begin + 32, pg_raw);
-  for (int tok = ce.tok_begin; tok < ce.tok_end; tok += 32) {
+  int32_t pg_next = -1;
+  const int tok0 = ce.tok_begin + 32 * tw;  // this wave's first tile (a short chunk may leave some of a team without any)
+  if (tok0 < ce.tok_end) {
+    lookup_start(tok0, pg_raw);
+    lookup_done(pg_raw);
+    pg_next = checked(pg_raw);
+    if (share_kr) stage_kr(tok0, pg_next, 0);
+    load_k(tok0, pg_next);
+    load_v(tok0, pg_next);
+    if (tok0 + tstep < ce.tok_end) lookup_start(tok0 + tstep, pg_raw);
+  }
+  for (int tok = tok0; tok < ce.tok_end; tok += tstep) {
     f32x16 s[RB];
 #pragma unroll
     for (int x = 0; x < RB; ++x)
@@ -242,14 +254,14 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
 #pragma unroll
       for (int x = 0; x < RB; ++x) s[x] = mfma32(rf[ks], q_rope(x, ks), s[x]);
     const bool tile_k_ok = k_ok;
-    const bool has_next = tok + 32 < ce.tok_end;
+    const bool has_next = tok + tstep < ce.tok_end;
     if (has_next) {
       lookup_done(pg_raw);
       pg_next = checked(pg_raw);
-      if (share_kr) stage_kr(tok + 32, pg_next, (((tok - ce.tok_begin) >> 5) + 1) & 1);
-      load_k(tok + 32, pg_next);
-      if constexpr (FP8) load_v(tok + 32, pg_next);
-      if (tok + 64 < ce.tok_end) lookup_start(tok + 64, pg_raw);
+      if (share_kr) stage_kr(tok + tstep, pg_next, (((tok - ce.tok_begin) >> 5) + 1) & 1);  // (shared k_R: tt = 1)
+      load_k(tok + tstep, pg_next);
+      if constexpr (FP8) load_v(tok + tstep, pg_next);
+      if (tok + 2 * tstep < ce.tok_end) lookup_start(tok + 2 * tstep, pg_raw);
     }
 
     // online softmax, base-2 domain; register i of lane (n, h) is token tok + 8*(i/4) + 4*h + i%4
@@ -330,7 +342,60 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
 #pragma unroll
         for (int x = 0; x < RB; ++x) o[x][mt] = mfma32(vf[mt][kk], pf[x][kk], o[x][mt]);
     if constexpr (!FP8) {
-      if (has_next) load_v(tok + 32, pg_next);
+      if (has_next) load_v(tok + tstep, pg_next);
+    }
+  }
+
+  if constexpr (CAN_TEAM) {
+    if (tt > 1) {
+      // ---- merge of the team's partial states (tt = 8 waves; row = lane % 32) ----
+      // dyn_lds: O^T of every wave as [wave][quad q = 4 mt + i/4][lane][4] fp32 (16 KB per wave, MT = 4), then m and l
+      // per (wave, row).  Wave w sums quads 2w, 2w + 1 of all eight waves in a fixed order and writes them.
+      constexpr int kQuads = MT * 4;
+      float* const o_lds = (float*)dyn_lds;
+      float* const ml_lds = o_lds + 8 * kQuads * 64 * 4;
+      const float l_mine = pair_sum(l_run[0]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *(f32x4*)(o_lds + ((tw * kQuads + 4 * mt + q) * 64 + lane) * 4) =
+              f32x4{o[0][mt][4 * q], o[0][mt][4 * q + 1], o[0][mt][4 * q + 2], o[0][mt][4 * q + 3]};
+      if (h == 0) {
+        ml_lds[tw * 32 + n] = m_run[0];
+        ml_lds[256 + tw * 32 + n] = l_mine;
+      }
+      __syncthreads();
+      float m_all = GQLA_NEG_INF;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) m_all = fmaxf(m_all, ml_lds[w * 32 + n]);
+      const float m_use = (m_all == GQLA_NEG_INF) ? 0.f : m_all;
+      float c[8], l_all = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) {
+        c[w] = fast_exp2(ml_lds[w * 32 + n] - m_use);  // 0 for a wave that saw no visible token
+        l_all += c[w] * ml_lds[256 + w * 32 + n];
+      }
+      const bool ok = row_ok[0];
+      const float inv = (l_all > 0.f ? 1.f / l_all : 0.f) * (FP8 ? v_scale : 1.f);
+      const int64_t prow = (int64_t)chunk * a.M + (int64_t)t_of[0] * a.h_q + head_of[0];
+      float* po = (float*)a.part_o + prow * DV;
+      constexpr int kQuadsPerWave = kQuads / 8;
+      static_assert(kQuads % 8 == 0, "every wave of the team sums the same number of quads");
+#pragma unroll
+      for (int qq = 0; qq < kQuadsPerWave; ++qq) {
+        const int quad = tw * kQuadsPerWave + qq;  // = 4 mt + q
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+          const f32x4 v = *(const f32x4*)(o_lds + ((w * kQuads + quad) * 64 + lane) * 4);
+          if (c[w] > 0.f) acc += c[w] * v;  // (a wave without tiles holds zeros; one whose rows were all masked may hold anything times 0)
+        }
+        acc *= inv;
+        if (ok) *(f32x4*)(po + (quad >> 2) * 32 + 8 * (quad & 3) + 4 * h) = acc;
+      }
+      if (ok && tw == 0 && h == 0) a.part_lse[prow] = l_all > 0.f ? (m_all + fast_log2(l_all)) * kLn2 : GQLA_NEG_INF;
+      return;
     }
   }
 
@@ -380,11 +445,19 @@ static hipError_t launch_decode_gqa_128(const DecodeArgs& a, float k_scale, floa
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kQBytesPerWave);
     if (attr != hipSuccess) return attr;
     decode_gqa_bf16_kernel<128, 128, 64, FP8, 256, 2><<<blocks, 64 * wpb, wpb * kQBytesPerWave, s>>>(a, n_items, row_blocks, team ? 1 : 0,
-                                                                                                    k_scale, v_scale);
+                                                                                                    1, k_scale, v_scale);
+    return hipGetLastError();
+  }
+  if (a.g == 1) {  // one group with at most 32 query rows: a token team of eight waves per chunk (the plan cuts chunks for that)
+    constexpr int kMergeBytes = 8 * (128 / 32) * 4 * 64 * 16 + 2 * 8 * 32 * 4;  // eight O^T of 16 KB, then m and l per (wave, row)
+    static const hipError_t attr = hipFuncSetAttribute((const void*)decode_gqa_bf16_kernel<128, 128, 64, FP8, 512, 1>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMergeBytes);
+    if (attr != hipSuccess) return attr;
+    decode_gqa_bf16_kernel<128, 128, 64, FP8, 512, 1><<<a.n_chunks, 512, kMergeBytes, s>>>(a, a.n_chunks, 1, 0, 8, k_scale, v_scale);
     return hipGetLastError();
   }
   gqa_launch_shape(a, 8, 32, row_blocks, n_items, team, wpb, blocks);
-  decode_gqa_bf16_kernel<128, 128, 64, FP8, 512, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, k_scale, v_scale);
+  decode_gqa_bf16_kernel<128, 128, 64, FP8, 512, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1, k_scale, v_scale);
   return hipGetLastError();
 }
 
@@ -393,7 +466,7 @@ hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
     int row_blocks, n_items, wpb, blocks;
     bool team;
     gqa_launch_shape(a, 4, 32, row_blocks, n_items, team, wpb, blocks);
-    decode_gqa_bf16_kernel<192, 256, 64, false, 256, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1.f, 1.f);
+    decode_gqa_bf16_kernel<192, 256, 64, false, 256, 1><<<blocks, 64 * wpb, 0, s>>>(a, n_items, row_blocks, team ? 1 : 0, 1, 1.f, 1.f);
     return hipGetLastError();
   }
   return launch_decode_gqa_128<false>(a, 1.f, 1.f, s);

@@ -24,6 +24,7 @@ def _bf16_bits(x):
     (32, 8, 1, [513, 40], False, (0.37, 2.5)),             # scales that are not powers of two
     (64, 4, 1, [700], True, (0.02, 0.01)),                 # small scales: part of the values saturate at 448
     (128, 4, 2, [300, 65], True, (0.5, 2.0)),              # 64 rows per group: a wave takes both 32-row blocks
+    (16, 1, 2, [300, 33, 2], True, (1.0, 0.5)),            # one group, 32 rows: eight waves share a chunk and merge their partials
 ])
 def test_fp8_cache_quantise_and_decode(h_q, g, s_q, lens, paged, scales):
     cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=h_q, g=g, s_q=s_q, L=0, paged=paged, seed=880 + h_q)

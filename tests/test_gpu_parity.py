@@ -202,6 +202,10 @@ def test_fp32_small_shapes(s_q, lens, paged, cp):
     (128, 4, 1, [321], False, (0, 0)),                   # (g, s_q) = (4, 1), the 2176-byte-per-token operating point
     (64, 1, 1, [300, 70], True, (0, 0)),                 # one group of 64 heads: a GQA wave takes both 32-row blocks, no k_R sharing
     (96, 2, 2, [513, 64, 2], True, (0, 1)),              # 96 rows per group: two waves of two row blocks, the last block all padding
+    (16, 1, 2, [700, 2, 65, 300], True, (0, 0)),         # one group, 32 rows: the eight waves of a GQA workgroup share a chunk's tiles;
+                                                         # chunks of 1 and 3 tiles leave most of the team without any
+    (32, 1, 1, [1029, 40], False, (0, 3)),               # the same with 32 heads, forced 3-page chunks (6 tiles for 8 waves)
+    (8, 1, 1, [130, 5000], True, (0, 0)),                # 8 rows (24 lanes of padding), one long sequence
 ])
 @pytest.mark.parametrize("num_cus", [256, 2])   # planned for the whole chip, or for a sliver of it: with few chunks and
                                                 # many compute units the absorb decode gives every 32 query rows a
