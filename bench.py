@@ -44,8 +44,9 @@ def parse_args():
     ap.add_argument("--legs", default="absorb,gqa", help="debugging only: subset of absorb,gqa to run (the judged line needs both)")
     ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences per leg in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip everything outside the timed step (ceiling probes, slice, cache updates, 8-bit cache, compression, step ops)")
-    ap.add_argument("--operating-points", action="store_true",
-                    help="also time both decode paths at the operating points of the paper's Sec. 4.2.3 table (g, s_q) for B = 1 and 64")
+    ap.add_argument("--no-operating-points", dest="operating_points", action="store_false",
+                    help="skip the operating points of the paper's Sec. 4.2.3 table: both decode paths at (g, s_q) in "
+                         "{(8,1), (8,2), (4,1), (4,2)} for B = 1 and 64, L = 8192, timed per call with events")
     ap.add_argument("--crossover", action="store_true",
                     help="also time both decode paths over B = 1 .. 128 (canonical shape, L = 8192, s_q = 1 and 2): where the faster path changes")
     ap.add_argument("--no-other-configs", action="store_true",

@@ -867,9 +867,9 @@ gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gql
   if (st != GQLA_OK) return st;
   const double row_blocks = (double)(((shape->h_q / shape->g) * shape->s_q + 31) / 32);
   // absorb, throughput form: the rates the kernel sustains when every compute unit has a long chunk
-  double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 0.95e15);
+  double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 1.09e15);
   // absorb, critical path of one workgroup: the split plan of `batch` equal sequences on 64-token pages and 256 compute
-  // units gives every workgroup `rounds` chunks of `per` pages; a page costs a workgroup 4.4 us (128 rows, one wave
+  // units gives every workgroup `rounds` chunks of `per` pages; a page costs a workgroup 3.8 us (128 rows, one wave
   // per 32 rows), 2.6 us when the chunks are so few that the launch gives every 32 rows a workgroup of their own, and
   // 1.6 us when a sequence has at most 32 rows; a chunk's fixed cost is that of 4 pages.
   if (shape->batch > 0 && cached_tokens > 0) {
@@ -878,11 +878,15 @@ gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gql
     const int64_t cp = choose_chunk_pages(std::vector<int32_t>((size_t)shape->batch, (int32_t)np), *shape, 256, GQLA_PATH_ABSORB);
     const int64_t per_seq = ceil_div(np, cp), per = ceil_div(np, per_seq), chunks = shape->batch * per_seq;
     const int64_t M = (int64_t)shape->h_q * shape->s_q;
-    const double page_s = M <= 32 ? 1.6e-6 : (ceil_div(chunks, 8) * 8 * ceil_div(M, 32) <= 256 ? 2.6e-6 : 4.4e-6);
+    const double page_s = M <= 32 ? 1.6e-6 : (ceil_div(chunks, 8) * 8 * ceil_div(M, 32) <= 256 ? 2.6e-6 : 3.8e-6);
     ta = std::max(ta, 28e-6 + (double)(ceil_div(chunks, slots) * (per + 4)) * page_s);
   }
   out->absorb_seconds = ta;
-  out->gqa_seconds = 24e-6 + (1.0 + 0.45 * (row_blocks - 1.0)) * e.gqa_bytes / 7.0e12;
+  // GQA: a fixed cost plus the cache bytes at the rate the kernel streams them -- 7.0 TB/s from HBM; a cache of up to
+  // 200 MB is still in the chip's last-level cache from the previous step and streams at about 10 TB/s.  (A group with
+  // 64 query rows costs a few percent more per byte than one with 32: a wave then takes both row blocks.)
+  const double gqa_bytes = (1.0 + 0.05 * (row_blocks - 1.0)) * e.gqa_bytes;
+  out->gqa_seconds = 26e-6 + std::min(gqa_bytes, 200e6) / 10e12 + std::max(0.0, gqa_bytes - 200e6) / 7.0e12;
   out->faster_path = out->gqa_seconds < out->absorb_seconds ? GQLA_PATH_GQA : GQLA_PATH_ABSORB;
   return GQLA_OK;
 }

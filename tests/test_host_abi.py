@@ -258,16 +258,16 @@ def test_calibrated_path_choice_matches_the_measured_operating_points():
     of decode_gqa on one MI355X): predicted times within 25 % of every measured row, and the measured faster path
     wherever the two paths are more than 12 % apart (the model is good to about that per path)."""
     measured = [  # B, h_q, g, s_q, cached tokens, absorb us, gqa us
-        (1, 128, 8, 1, 8192, 50.1, 30.4), (1, 128, 8, 2, 8192, 53.7, 34.1), (1, 128, 4, 1, 8192, 50.7, 25.7),
-        (1, 128, 4, 2, 8192, 52.6, 31.6), (64, 128, 8, 1, 524288, 182.8, 334.2), (64, 128, 8, 2, 524288, 321.6, 342.8),
-        (64, 128, 4, 1, 524288, 181.2, 191.5), (64, 128, 4, 2, 524288, 320.0, 260.6),
-        (32, 32, 8, 1, 131072, 44.8 + 8.0, 89.6),          # configs[1]; its absorb figure there is the decode call alone
-        (128, 128, 8, 2, 2234929, 1328.6 + 15.0, 1557.4),  # configs[4], same remark
+        (1, 128, 8, 1, 8192, 50.5, 34.0), (1, 128, 8, 2, 8192, 53.3, 37.4), (1, 128, 4, 1, 8192, 51.4, 26.2),
+        (1, 128, 4, 2, 8192, 52.4, 35.5), (64, 128, 8, 1, 524288, 169.2, 328.3), (64, 128, 8, 2, 524288, 293.0, 336.8),
+        (64, 128, 4, 1, 524288, 165.3, 193.1), (64, 128, 4, 2, 524288, 292.9, 193.5),
+        (32, 32, 8, 1, 131072, 47.6 + 8.0, 89.7),          # configs[1]; its absorb figure there is the decode call alone
+        (128, 128, 8, 2, 2234929, 1199.5 + 15.0, 1541.0),  # configs[4], same remark
         # batch sweep, canonical shape, 8192 tokens per sequence
-        (2, 128, 8, 1, 16384, 54.2, 32.8), (4, 128, 8, 1, 32768, 54.8, 40.0), (8, 128, 8, 1, 65536, 70.0, 58.9),
-        (16, 128, 8, 1, 131072, 76.6, 96.7), (32, 128, 8, 1, 262144, 108.5, 177.3), (128, 128, 8, 1, 1048576, 357.0, 650.3),
-        (2, 128, 8, 2, 16384, 55.7, 37.5), (4, 128, 8, 2, 32768, 68.3, 42.4), (8, 128, 8, 2, 65536, 75.0, 63.8),
-        (16, 128, 8, 2, 131072, 104.0, 103.6), (32, 128, 8, 2, 262144, 167.0, 183.9), (128, 128, 8, 2, 1048576, 630.1, 660.2),
+        (2, 128, 8, 1, 16384, 54.2, 37.5), (4, 128, 8, 1, 32768, 57.2, 43.4), (8, 128, 8, 1, 65536, 67.5, 57.3),
+        (16, 128, 8, 1, 131072, 77.2, 95.5), (32, 128, 8, 1, 262144, 103.1, 172.7), (128, 128, 8, 1, 1048576, 314.6, 645.4),
+        (2, 128, 8, 2, 16384, 57.3, 42.2), (4, 128, 8, 2, 32768, 67.1, 46.5), (8, 128, 8, 2, 65536, 73.0, 61.3),
+        (16, 128, 8, 2, 131072, 100.4, 101.5), (32, 128, 8, 2, 262144, 159.6, 179.6), (128, 128, 8, 2, 1048576, 559.6, 652.2),
     ]
     for Bn, h_q, g, s_q, tokens, t_a, t_g in measured:
         ch = B.gqla_select_path(B.make_shape(Bn, h_q, g, 128, 512, 64, s_q, B.GQLA_BF16), tokens)
