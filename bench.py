@@ -11,7 +11,8 @@ cache switch gqla_expand_cache (Sec. 3.1: done once at deployment) is timed in t
 `roofline` is the split-L decode kernel that is further from its target (kernel time from events the library records
 around that kernel, see gqla_time_next_decode_kernel); `rooflines` has both decode kernels and the expansion.  Also in
 the line: the other workload shapes (configs[1] with rotating cache buffers so that it is not served from the
-last-level cache, configs[4] ragged and paged), the oracle's CPU rate on a bounded sample, and timings of the calls
+last-level cache, configs[4] ragged and paged), both paths at the operating points of the paper's Sec. 4.2.3 table,
+the oracle's CPU rate on a bounded sample, and timings of the calls
 around the path (measured ceilings of the chip, the single-group slice, the 8-bit caches, the reverse cache switch, the
 rotary step and W^O, each path's whole decode step as one HIP graph, the absorb step with a value dim of its own)."""
 from __future__ import annotations
