@@ -236,7 +236,7 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
  * gqla_output_projection computes y_t = W^O [o_{t,1}; ...; o_{t,h_q}] (last line of the GQA-path and of the MQA-absorb
  * equation): o is a decode call's output [B][s_q][h_q][d_h], w_o is [d_model][h_q * d_h] row-major (the paper's
  * W^O in R^{D x h_q d_h}), y is [B][s_q][d_model]; all device memory of the shape's element type, fp32 accumulation.
- * With GQLA_BF16, d_model must be a multiple of 128 and h_q * d_h of 256 (GQLA_ERR_SHAPE otherwise), and the call may
+ * With GQLA_BF16, d_model must be a multiple of 128 and h_q * d_h of 256, at most 2^24 (GQLA_ERR_SHAPE otherwise), and the call may
  * need device scratch: ws of at least gqla_output_projection_workspace_bytes(shape, d_model) bytes, 16-byte aligned
  * (fp32 partial sums over ranges of the contraction, added in a fixed order; GQLA_ERR_NULL / GQLA_ERR_WORKSPACE when
  * it is needed and missing or too small).  GQLA_F32 needs none.  Both calls only enqueue work on `stream`. */

@@ -68,7 +68,8 @@ HAND_SCALAR_LOAD_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel"
 # spill or scratch use in them.
 COUNTED_WAIT_KERNELS = {"gqla_absorb_bf16.hip": ["decode_absorb_bf16_kernel", "decode_absorb_shared_bf16_kernel"],
                         "gqla_gemm_bf16.hip": ["expand_bf16_kernel"],
-                        "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"]}
+                        "gqla_gqa_bf16.hip": ["decode_gqa_bf16_kernel"],
+                        "gqla_step_ops.hip": ["out_proj_bf16_kernel"]}
 
 
 def _reads_register(instr: str, reg: str) -> bool:

@@ -577,7 +577,7 @@ gqla_status gqla_rope_step(const gqla_shape* shape, const int32_t* seq_lens, flo
 size_t gqla_output_projection_workspace_bytes(const gqla_shape* shape, int32_t d_model) {
   if (check_shape(shape) != GQLA_OK || d_model <= 0 || shape->dtype != GQLA_BF16) return 0;
   const int64_t M = (int64_t)shape->batch * shape->s_q, K = (int64_t)shape->h_q * value_dim(shape);
-  if (M == 0 || d_model % 128 || K % 256) return 0;
+  if (M == 0 || d_model % 128 || K % 256 || K > (1 << 24)) return 0;
   int krange = 0;
   const int ksplit = out_proj_split((int)M, (int)K, d_model, &krange);
   return ksplit > 1 ? (size_t)ksplit * M * d_model * sizeof(float) : 0;
@@ -605,7 +605,7 @@ gqla_status gqla_output_projection(const gqla_shape* shape, int32_t d_model, con
   a.krange = (int32_t)K;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (shape->dtype != GQLA_BF16) return launch_out_proj_f32(a, s) == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
-  if (d_model % 128 || K % 256) return GQLA_ERR_SHAPE;
+  if (d_model % 128 || K % 256 || K > (1 << 24)) return GQLA_ERR_SHAPE;   // the kernel's row offsets inside a tile are 32-bit
   a.ksplit = out_proj_split(a.M, a.K, a.D, &a.krange);
   if (a.ksplit > 1) {
     if (!ws) return GQLA_ERR_NULL;

@@ -53,17 +53,20 @@ def test_rope_step_matches_the_oracle(key, lens, s_q, base):
     assert torch.equal(d_q2, d_q) and torch.equal(d_rows2, d_rows)
 
 
-@pytest.mark.parametrize("key,Bsz,s_q,d_model", [
-    ("C1", 5, 2, 256),          # 10 rows: one ragged row tile, 16 k-ranges
-    ("C1", 70, 2, 128),         # 140 rows: two row blocks, the second ragged
-    ("C3", 3, 1, 384),          # h_q = 128: K = 16384
-    ("C1", 64, 1, 4096),        # the bench shape of configs[1]
-    ("C0", 3, 2, 24),           # fp32 kernel
+@pytest.mark.parametrize("key,Bsz,s_q,d_model,h_q", [
+    ("C1", 5, 2, 256, 32),      # 10 rows: one ragged row tile, 16 k-ranges
+    ("C1", 70, 2, 128, 32),     # 140 rows: two row blocks, the second ragged
+    ("C3", 3, 1, 384, 128),     # K = 16384
+    ("C1", 64, 1, 4096, 32),    # the bench shape of configs[1]
+    ("C1", 40, 2, 384, 24),     # K = 3072: 36 workgroups, not a multiple of the eight dies they are dealt over
+    ("C1", 150, 2, 256, 32),    # 300 rows: three row blocks, the last ragged
+    ("C1", 20, 2, 4096, 40),    # K = 5120: seven k-ranges, the last one shorter
+    ("C0", 3, 2, 24, 8),        # fp32 kernel
 ])
-def test_output_projection_matches_the_oracle(key, Bsz, s_q, d_model):
+def test_output_projection_matches_the_oracle(key, Bsz, s_q, d_model, h_q):
     from paper_2605_15250_amd import binding as B
     from paper_2605_15250_amd.harness import Decoder, to_device
-    cfg = S.CONFIGS[key].with_(B=Bsz, s_q=s_q, L=64, seed=1414)
+    cfg = S.CONFIGS[key].with_(B=Bsz, s_q=s_q, L=64, seed=1414, h_q=h_q)
     lens = S.seq_lens(cfg)
     table, npg = S.page_table(cfg, lens)
     dec = Decoder(cfg, lens, table, npg)

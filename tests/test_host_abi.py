@@ -316,15 +316,15 @@ def test_step_ops_validate_on_the_host():
     _expect(B.GQLA_ERR_SHAPE, B.gqla_output_projection, ok, 4000, A, A, A, A, 1 << 30, stream=0)          # not a multiple of 128
     _expect(B.GQLA_ERR_SHAPE, B.gqla_output_projection, B.make_shape(2, 1, 1, 128, 512, 64, 2, B.GQLA_BF16), 4096, A, A, A, A, 1 << 30, stream=0)  # K = 128
     need = B.gqla_output_projection_workspace_bytes(ok, 4096)
-    # 32 column tiles x 1 row block -> 16 k-ranges of one 256-element phase each
-    assert need == 16 * 4 * 4096 * 4
+    # 32 column tiles x 1 row block -> 256 // 32 = 8 k-ranges of two 256-element pieces each
+    assert need == 8 * 4 * 4096 * 4
     _expect(B.GQLA_ERR_NULL, B.gqla_output_projection, ok, 4096, A, A, A, None, 0, stream=0)
     _expect(B.GQLA_ERR_WORKSPACE, B.gqla_output_projection, ok, 4096, A, A, A, A, need - 1, stream=0)
     assert B.gqla_output_projection_workspace_bytes(ok, 4000) == 0
     assert B.gqla_output_projection_workspace_bytes(B.make_shape(2, 8, 2, 16, 32, 8, 1, B.GQLA_F32), 24) == 0
-    # 7168 columns (56 tiles), K = 16384 (64 phases): 512 // 56 = 9 ranges wanted -> 8 phases each -> 8 ranges
+    # 7168 columns (56 tiles), K = 16384 (64 pieces): 256 // 56 = 4 ranges of 16 pieces
     big = B.make_shape(64, 128, 8, 128, 512, 64, 1, B.GQLA_BF16)
-    assert B.gqla_output_projection_workspace_bytes(big, 7168) == 8 * 64 * 7168 * 4
+    assert B.gqla_output_projection_workspace_bytes(big, 7168) == 4 * 64 * 7168 * 4
     # compress: needs all groups, matching geometry, g d_h >= r_kv
     full = B.make_cache(A, A, None, 64, 4, 8, 8)
     lat = B.make_cache(A, A, None, 64, 4, 8, 0)
@@ -400,6 +400,6 @@ def test_value_dim_of_its_own_is_accepted_where_the_kernels_exist():
             assert B.gqla_expanded_kr_offset_dv(page, slot, d, P, gc, d_h, d_v, d_r) == Lay.expanded_kr_offset(page, slot, d, P, gc, d_h, d_r, d_v)
         assert B.gqla_expanded_v_offset_dv(page, j, slot, 100, P, gc, 128, 128, d_r) == B.gqla_expanded_v_offset(page, j, slot, 100, P, gc, 128, d_r)
         assert B.gqla_expanded_kr_offset_dv(page, slot, 9, P, gc, 128, 128, d_r) == B.gqla_expanded_kr_offset(page, slot, 9, P, gc, 128, d_r)
-    # W^O takes h_q * d_v columns: 20 * 256 = 5120 = 20 phases of 256
-    # 32 column tiles -> 16 ranges wanted -> 2 phases each -> 10 ranges
-    assert B.gqla_output_projection_workspace_bytes(glm, 4096) == 10 * 2 * 4096 * 4
+    # W^O takes h_q * d_v columns: 20 * 256 = 5120 = 20 pieces of 256
+    # 32 column tiles -> 8 ranges wanted -> 3 pieces each -> 7 ranges (the last of 2 pieces)
+    assert B.gqla_output_projection_workspace_bytes(glm, 4096) == 7 * 2 * 4096 * 4
