@@ -328,7 +328,16 @@ def main():
             w_o = to_device(S.output_weights(c_, d_model), c_.dtype)
             y = torch.empty((c_.B, c_.s_q, d_model), dtype=torch.bfloat16, device="cuda")
             o_in = leg["out"]
-            t_o = timed_steady(lambda: d_.output_projection(o_in, w_o, y), 20)
+            # three weight matrices in turn, as the layers of a model would bring them: one matrix alone (235 MB at 128
+            # heads) would be served in part by the 256 MB last-level cache from one timed call to the next
+            w_turn = [w_o, torch.roll(w_o, 1, 0), torch.roll(w_o, 2, 0)]
+            turn = [0]
+
+            def out_proj_call():
+                turn[0] = (turn[0] + 1) % 3
+                d_.output_projection(o_in, w_turn[turn[0]], y)
+            t_o = timed_steady(out_proj_call, 21)
+            del w_turn
             q_tmp = leg["d_q_r"].clone()
             rows_tmp = torch.zeros((c_.B, c_.s_q, c_.r_kv + c_.d_r), dtype=torch.bfloat16, device="cuda")
             t_r = timed_steady(lambda: d_.rope_step(10000.0, q_tmp, rows_tmp), 20)

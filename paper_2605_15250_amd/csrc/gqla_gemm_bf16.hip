@@ -119,6 +119,11 @@ __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __
 // that the end-of-stage wait (which also covers stores on this hardware) finds them long gone.
 // With an odd number of stages per group (DH = 192, DV = 256: seven) the two result sets would meet at the group
 // boundary, so there the group's last stage stores its results at once instead of in the next stage's shadow.
+#ifdef EXP_PROBE_PLAIN_STORE
+#define EXP_STORE(v, p) (*(p) = (v))
+#else
+#define EXP_STORE(v, p) __builtin_nontemporal_store(v, p)
+#endif
 template <int DH, int DV, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
@@ -175,10 +180,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
 
   // LDS-DMA of one stage: 64 instructions of 1 KB, 16 per wave, linear (the packed layout is already fragment order)
   auto stage_in_step = [&](int stage, char* buf, int u) {  // u = 0..15
-    const char* src = (const char*)packed + (int64_t)stage * STAGE_BYTES;
-    const int blk = wave * 16 + u;
-    const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(buf + blk * 1024);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(lane * 16), "s"(src + blk * 1024) : "memory");
+    const char* src = (const char*)packed + (int64_t)stage * STAGE_BYTES + wave * (16 * 1024);
+    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)(buf + wave * (16 * 1024)));
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(lane * 16), "s"(src + u * 1024), "n"(u * 1024) : "memory", "scc");  // the add writes SCC
   };
   auto stage_in = [&](int stage, char* buf) {
 #pragma unroll
@@ -186,6 +190,10 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
   };
   // results of the previous stage ([token tile][32-column half]), kept until the next stage's arithmetic is under way
   f32x16 accs[2][2][2];  // [stage parity][token tile][32-column half]: one set accumulates while the other is stored
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) accs[i >> 2][(i >> 1) & 1][i & 1][k] = 0.f;
   // stores address the page through one uniform base and 32-bit offsets (a page is at most a few MB)
   const uint32_t plane_k = (uint32_t)DH * P, plane_v = (uint32_t)DV * P;          // elements of one group's K and V plane
   const uint32_t k_lane = (uint32_t)(slot0 + n) * 8 + (uint32_t)h * P * 8;        // K plane: token slot0 + n, 8-dim block + h
@@ -234,8 +242,9 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       }
     }
   };
-  auto store_prev = [&](int par, int kind, int mtp, int jj, int nt, int e, int qp) {
-    if (jj < 0 || !wave_ok) return;
+  // The two halves of a store are separate so that each fits in the shadow of one matrix instruction: pack_prev rounds
+  // and trades (6 vector instructions), emit_prev forms the address and stores.
+  auto pack_prev = [&](int par, int nt, int e, int qp) -> u32x4 {
     const f32x16& acc = accs[par][nt][e];
     const int q0 = 2 * qp;
     const uint32_t x0 = pack_bf16(acc[4 * q0], acc[4 * q0 + 1]), x1 = pack_bf16(acc[4 * q0 + 2], acc[4 * q0 + 3]);
@@ -243,12 +252,16 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
     uint32_t r0, r1, r2, r3;
     half_swap(x0, y0, r0, r2);
     half_swap(x1, y1, r1, r3);
-    const u32x4 v = {r0, r1, r2, r3};
+    return u32x4{r0, r1, r2, r3};
+  };
+  auto emit_prev = [&](const u32x4 v, int kind, int mtp, int jj, int nt, int e, int qp) {
+    if (jj < 0 || !wave_ok) return;
+    const int q0 = 2 * qp;
     if (kind == 0) {
       // lane = token; the vector is dims 64*mtp + 32*e + 8*(2*qp + h) + 0..7 of the K plane
       if (wave_full || tokw + 32 * nt + n < L) {
         const uint32_t off = (uint32_t)jj * plane_k + (uint32_t)(8 * mtp + 4 * e + q0) * P * 8 + 32 * nt * 8 + k_lane;
-        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (size_t)off * 2));
+        EXP_STORE(v, (u32x4*)(page_bytes + (size_t)off * 2));
       }
     } else {
       // lane = dim 64*mtp + 32*e + n; the vector is tokens 32*nt + 8*(2*qp + h) + 0..7 of the V plane
@@ -256,13 +269,17 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
       const int tk = tokw + 32 * nt + 8 * (q0 + h);  // first of 8 tokens
       if (wave_full || tk + 7 < L) {
-        __builtin_nontemporal_store(v, (u32x4*)dst);
+        EXP_STORE(v, (u32x4*)dst);
       } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           if (tk + i < L) ((uint16_t*)dst)[i] = (uint16_t)(v[i >> 1] >> (16 * (i & 1)));
       }
     }
+  };
+  auto store_prev = [&](int par, int kind, int mtp, int jj, int nt, int e, int qp) {
+    if (jj < 0 || !wave_ok) return;
+    emit_prev(pack_prev(par, nt, e, qp), kind, mtp, jj, nt, e, qp);
   };
 
   const int n_stages = gc * NSUB;
@@ -288,34 +305,48 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
           w[ks][0] = *(const bf16x8*)(buf + (2 * ks) * 1024);
           w[ks][1] = *(const bf16x8*)(buf + (2 * ks + 1) * 1024);
         }
+        // A wave issues in order and is alone on its SIMD: whatever stands between two matrix instructions delays the
+        // second one unless it fits into the 32 cycles the first one occupies the pipe.  The other work of a k-step is
+        // therefore dealt out one small piece per gap: the two fragment reads for two k-steps ahead, the k-step's share
+        // of the next stage's staging, and half of a store of the previous stage's results (pack in the odd k-steps,
+        // address and store in the even ones that follow).
+        u32x4 packed_piece = {0u, 0u, 0u, 0u};
+        auto mm = [&](int ks, int nt, int e) __attribute__((always_inline)) {
+          const bf16x8 wf = w[ks % (DEPTH + 1)][e];
+          if (sub < NSK) {
+            if (ks == 0) mfma_va_first(acc[nt][e], wf, xf[nt][ks]);
+            else mfma_va(acc[nt][e], wf, xf[nt][ks]);
+          } else {
+            if (ks == 0) mfma_av_first(acc[nt][e], xf[nt][ks], wf);
+            else mfma_av(acc[nt][e], xf[nt][ks], wf);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        };
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          if (ks + DEPTH < KS) {
-            w[(ks + DEPTH) % (DEPTH + 1)][0] = *(const bf16x8*)(buf + (2 * (ks + DEPTH)) * 1024);
-            w[(ks + DEPTH) % (DEPTH + 1)][1] = *(const bf16x8*)(buf + (2 * (ks + DEPTH) + 1) * 1024);
-          }
-          if (ks < 16 && stage + 1 < n_stages) stage_in_step(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES, ks);
           __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              const bf16x8 wf = w[ks % (DEPTH + 1)][e];
-              if (sub < NSK) {
-                if (ks == 0) mfma_va_first(acc[nt][e], wf, xf[nt][ks]);
-                else mfma_va(acc[nt][e], wf, xf[nt][ks]);
-              } else {
-                if (ks == 0) mfma_av_first(acc[nt][e], xf[nt][ks], wf);
-                else mfma_av(acc[nt][e], xf[nt][ks], wf);
-              }
-            }
+          mm(ks, 0, 0);
+          if (ks + DEPTH < KS) w[(ks + DEPTH) % (DEPTH + 1)][0] = *(const bf16x8*)(buf + (2 * (ks + DEPTH)) * 1024);
           __builtin_amdgcn_sched_barrier(0);
-          // the previous stage's results leave one store at a time, in the shadow of this stage's MFMAs
+          mm(ks, 0, 1);
+          if (ks + DEPTH < KS) w[(ks + DEPTH) % (DEPTH + 1)][1] = *(const bf16x8*)(buf + (2 * (ks + DEPTH) + 1) * 1024);
+          __builtin_amdgcn_sched_barrier(0);
+          mm(ks, 1, 0);
+          // (after the last stage this stages that stage once more, into the buffer nobody reads any more: no branch)
+          if (ks < 16) stage_in_step(min(stage + 1, n_stages - 1), smem + ((stage + 1) & 1) * STAGE_BYTES, ks);
+          __builtin_amdgcn_sched_barrier(0);
+          mm(ks, 1, 1);
+          // the previous stage's results leave in the shadow of this stage's MFMAs
           if constexpr (FP8) {
             if ((ks & 3) == 3 && ks <= 15)  // four pieces (nt, e)
               store_prev8(ppar, pkind, pmtp, pjj, (ks >> 2) >> 1, (ks >> 2) & 1);
-          } else if (ks >= 1 && ks <= 15 && (ks & 1)) {
-            store_prev(ppar, pkind, pmtp, pjj, (ks >> 1) >> 2, ((ks >> 1) >> 1) & 1, (ks >> 1) & 1);
+          } else if (psub != kPrevNone && ks >= 1 && ks <= 16) {
+            const int piece = (ks - 1) >> 1;  // packed at k-step 2 piece + 1, stored at 2 piece + 2
+            if (ks & 1) {
+              packed_piece = pack_prev(ppar, piece >> 2, (piece >> 1) & 1, piece & 1);  // (before the first stage: zeros, never stored)
+            } else {
+              emit_prev(packed_piece, pkind, pmtp, pjj, piece >> 2, (piece >> 1) & 1, piece & 1);
+            }
           }
         }
         mfma_results_ready(acc[0][0], acc[0][1], acc[1][0], acc[1][1]);
@@ -325,8 +356,8 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
             for (int piece = 0; piece < 8; ++piece) store_prev(sub & 1, 1, sub - NSK, jj, piece >> 2, (piece >> 1) & 1, piece & 1);
           }
         }
-      } else if (stage + 1 < n_stages) {
-        stage_in(stage + 1, smem + ((stage + 1) & 1) * STAGE_BYTES);  // a wave without tokens still stages its share
+      } else {
+        stage_in(min(stage + 1, n_stages - 1), smem + ((stage + 1) & 1) * STAGE_BYTES);  // a wave without tokens still stages its share
       }
       wait_all_memory();
       __syncthreads();  // next stage has landed; everyone is done with this stage's buffer
