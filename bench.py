@@ -487,11 +487,12 @@ def main():
         crossover = [] if args.crossover else None
         todo = []
         if args.operating_points:       # the paper's table (Sec. 4.2.3), at B = 1 and 64
-            todo += [(points, Bn, g_k, sq_k) for Bn in (1, 64) for g_k, sq_k in ((8, 1), (8, 2), (4, 1), (4, 2))]
+            todo += [(points, Bn, 128, g_k, sq_k) for Bn in (1, 64) for g_k, sq_k in ((8, 1), (8, 2), (4, 1), (4, 2))]
+            todo += [(points, 64, 64, 8, sq_k) for sq_k in (1, 2)]     # h_q = 64 (Sec. 4.2: recent open models; every intensity halves)
         if args.crossover:              # where the faster path changes with the batch, canonical shape
-            todo += [(crossover, Bn, 8, sq_k) for sq_k in (1, 2) for Bn in (1, 2, 4, 8, 16, 32, 64, 128)]
-        for sink_list, Bn, g_k, sq_k in todo:
-            c = S.CONFIGS["C2"].with_(B=Bn, g=g_k, s_q=sq_k)
+            todo += [(crossover, Bn, 128, 8, sq_k) for sq_k in (1, 2) for Bn in (1, 2, 4, 8, 16, 32, 64, 128)]
+        for sink_list, Bn, hq_k, g_k, sq_k in todo:
+            c = S.CONFIGS["C2"].with_(B=Bn, h_q=hq_k, g=g_k, s_q=sq_k)
             lens_k = S.seq_lens(c)
             table_k, np_k = S.page_table(c, lens_k)
             dk = Decoder(c, lens_k, table_k, np_k, use_page_table=False)
@@ -512,7 +513,7 @@ def main():
             t_g = timed3(lambda: dk.decode_gqa(d_qc, d_qr, o_k, l_k), 20)
             Ls = int(lens_k.sum())
             est = B.gqla_estimate_paths(B.make_shape(c.B, c.h_q, c.g, c.d_h, c.r_kv, c.d_r, c.s_q, B.GQLA_BF16), Ls, rates[0], rates[1])
-            sink_list.append({"batch": Bn, "context": c.L, "g": g_k, "s_q": sq_k,
+            sink_list.append({"batch": Bn, "context": c.L, "h_q": hq_k, "g": g_k, "s_q": sq_k,
                            "absorb_bytes_per_token": 2 * (c.r_kv + c.d_r), "gqa_bytes_per_token": 2 * (2 * c.g * c.d_h + c.d_r),
                            "absorb_intensity": est["absorb_intensity"], "gqa_intensity": est["gqa_intensity"],
                            "absorb_us": t_a * 1e6, "gqa_us": t_g * 1e6,

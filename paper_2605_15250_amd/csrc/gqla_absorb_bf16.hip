@@ -491,7 +491,9 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
   if (!row_ok) return;
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const int64_t prow = (int64_t)chunk * a.M + rho;
-  __bf16* po = (__bf16*)a.part_o + prow * RKV;
+  // this lane holds dims 4 h .. 4 h + 3 of vector 4 (part DTW + dt) + q of its row: with consecutive rows in consecutive
+  // lanes a store instruction writes 512 contiguous bytes
+  __bf16* po = (__bf16*)a.part_o + part_vec_index(chunk, rho, a.M, RKV / 8, 0) * 8 + 4 * h;
 #pragma unroll
   for (int dt = 0; dt < DTW; ++dt) {
     float x[16];
@@ -499,7 +501,7 @@ __global__ void __launch_bounds__(256) decode_absorb_bf16_kernel(DecodeArgs a, i
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
-      *(u32x2*)(po + (part * DTW + dt) * 32 + 8 * q + 4 * h) = v;
+      *(u32x2*)(po + ((part * DTW + dt) * 4 + q) * (32 * 8)) = v;
     }
   }
   if (h == 0 && part == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
@@ -929,7 +931,8 @@ __global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeAr
   for (int rb = 0; rb < 4; ++rb) {
     const int row = row0 + rb * 32 + n;
     const float inv = inv_l[rb * 32 + n];
-    __bf16* po = (__bf16*)a.part_o + ((int64_t)chunk * a.M + row) * RKV + wave * 128;
+    // dims 4 h .. 4 h + 3 of vector 16 wave + 4 d + q of the lane's row: 512 contiguous bytes per store instruction
+    __bf16* po = (__bf16*)a.part_o + part_vec_index(chunk, row, a.M, RKV / 8, 16 * wave) * 8 + 4 * h;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       float x[16];
@@ -937,7 +940,7 @@ __global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeAr
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
-        *(u32x2*)(po + d * 32 + 8 * q + 4 * h) = v;
+        *(u32x2*)(po + (4 * d + q) * (32 * 8)) = v;
       }
     }
   }
@@ -1254,7 +1257,9 @@ __global__ void __launch_bounds__(256) decode_absorb_fp8_kernel(DecodeArgs a, in
   if (!row_ok) return;
   const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * c_scale;  // o_hat = scale * sum_s p_s value(code_s)
   const int64_t prow = (int64_t)chunk * a.M + rho;
-  __bf16* po = (__bf16*)a.part_o + prow * RKV;
+  // this lane holds dims 4 h .. 4 h + 3 of vector 4 (part DTW + dt) + q of its row: with consecutive rows in consecutive
+  // lanes a store instruction writes 512 contiguous bytes
+  __bf16* po = (__bf16*)a.part_o + part_vec_index(chunk, rho, a.M, RKV / 8, 0) * 8 + 4 * h;
 #pragma unroll
   for (int dt = 0; dt < DTW; ++dt) {
     float x[16];
@@ -1262,7 +1267,7 @@ __global__ void __launch_bounds__(256) decode_absorb_fp8_kernel(DecodeArgs a, in
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       u32x2 v = {pack_bf16(x[4 * q] * inv, x[4 * q + 1] * inv), pack_bf16(x[4 * q + 2] * inv, x[4 * q + 3] * inv)};
-      *(u32x2*)(po + (part * DTW + dt) * 32 + 8 * q + 4 * h) = v;
+      *(u32x2*)(po + ((part * DTW + dt) * 4 + q) * (32 * 8)) = v;
     }
   }
   if (h == 0 && part == 0) a.part_lse[prow] = l_tot > 0.f ? (m_ref + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
@@ -1309,7 +1314,9 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
   for (int ksl = 0; ksl < KSW; ++ksl)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[ksl][e] = 0.f;
-  const __bf16* po = (const __bf16*)a.part_o + (int64_t)rho * RKV + (KSW * wave) * 16 + h * 8;
+  // vector 2 (KSW wave + ksl) + h of the lane's row, chunk 0 (see part_vec_index: consecutive rows are 16 bytes apart)
+  const __bf16* po = (const __bf16*)a.part_o + part_vec_index(0, rho, a.M, RKV / 8, 2 * KSW * wave + h) * 8;
+  const int64_t chunk_stride = (int64_t)((a.M + 31) / 32) * 32 * RKV;   // elements from one chunk's partials to the next
   for (int sb = s0; sb < s1; sb += kNB) {
     float l[kNB];
     u32x4 v[kNB][KSW];
@@ -1318,7 +1325,7 @@ __global__ void __launch_bounds__(256) combine_project_bf16_kernel(CombineArgs a
       const int sc = min(sb + k, s1 - 1);  // clamped: a chunk beyond the range is loaded again and given weight 0
       l[k] = a.part_lse[(int64_t)sc * a.M + rho];
 #pragma unroll
-      for (int ksl = 0; ksl < KSW; ++ksl) v[k][ksl] = *(const u32x4*)(po + (int64_t)sc * a.M * RKV + ksl * 16);
+      for (int ksl = 0; ksl < KSW; ++ksl) v[k][ksl] = *(const u32x4*)(po + sc * chunk_stride + ksl * (2 * 32 * 8));
     }
     float m_new = m;
 #pragma unroll

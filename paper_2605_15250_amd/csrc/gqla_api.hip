@@ -136,7 +136,8 @@ WsLayout make_layout(const gqla_plan& p) {
   w.part_o_off = align_up(w.first_slot_off + (p.shape.batch + 1) * sizeof(int32_t), 256);
   size_t po;
   if (p.path == GQLA_PATH_GQA) po = n * M * value_dim(&p.shape) * 4;
-  else po = n * M * p.shape.r_kv * (p.shape.dtype == GQLA_BF16 ? 2 : 4);
+  else if (p.shape.dtype == GQLA_BF16) po = n * ((M + 31) / 32 * 32) * p.shape.r_kv * 2;   // whole blocks of 32 rows (part_vec_index)
+  else po = n * M * p.shape.r_kv * 4;
   w.part_lse_off = align_up(w.part_o_off + po, 256);
   w.total = align_up(w.part_lse_off + n * M * 4, 256);
   return w;

@@ -35,6 +35,14 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
+// Chunk partials of the 16-bit MQA-absorb decode: 8-dim vectors (16 bytes) ordered [chunk][block of 32 rows][r_kv / 8][row
+// in the block].  The decode kernels' lanes (row n, four of a vector's dims per half-wave) and the combine kernel's lanes
+// (row n, vector h of a k-step) then both touch contiguous memory with consecutive n.  Index of vector `vec` of row `rho`.
+__device__ __forceinline__ int64_t part_vec_index(int64_t chunk, int rho, int M, int vecs_per_row, int vec) {
+  const int row_blocks = (M + 31) >> 5;
+  return (((chunk * row_blocks + (rho >> 5)) * vecs_per_row + vec) << 5) + (rho & 31);
+}
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

@@ -31,7 +31,7 @@ struct DecodeArgs {
   CacheView cache;
   const ChunkEntry* chunks;
   int32_t n_chunks;
-  void* part_o;      // GQA: fp32 [chunks][M][d_v];  absorb bf16: bf16 [chunks][M][r_kv];  absorb f32: fp32 [chunks][M][r_kv]
+  void* part_o;      // GQA: fp32 [chunks][M][d_v];  absorb bf16: bf16 vectors [chunks][M / 32][r_kv / 8][32][8] (part_vec_index);  absorb f32: fp32 [chunks][M][r_kv]
   float* part_lse;   // fp32 [chunks][M], natural log
   int32_t B, h_q, g, G, d_h, d_v, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i; d_v: value dim (GQA path)
   int32_t num_cus;                               // compute units the plan was made for (launch-shape choices only)
