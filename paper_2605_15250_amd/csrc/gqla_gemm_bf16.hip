@@ -119,11 +119,6 @@ __global__ void __launch_bounds__(256) pack_weights_bf16_kernel(ExpandArgs a, __
 // that the end-of-stage wait (which also covers stores on this hardware) finds them long gone.
 // With an odd number of stages per group (DH = 192, DV = 256: seven) the two result sets would meet at the group
 // boundary, so there the group's last stage stores its results at once instead of in the next stage's shadow.
-#ifdef EXP_PROBE_PLAIN_STORE
-#define EXP_STORE(v, p) (*(p) = (v))
-#else
-#define EXP_STORE(v, p) __builtin_nontemporal_store(v, p)
-#endif
 template <int DH, int DV, int RKV, int DR, bool FP8>
 __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __bf16* packed) {
   constexpr int W = RKV + DR;
@@ -261,7 +256,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       // lane = token; the vector is dims 64*mtp + 32*e + 8*(2*qp + h) + 0..7 of the K plane
       if (wave_full || tokw + 32 * nt + n < L) {
         const uint32_t off = (uint32_t)jj * plane_k + (uint32_t)(8 * mtp + 4 * e + q0) * P * 8 + 32 * nt * 8 + k_lane;
-        EXP_STORE(v, (u32x4*)(page_bytes + (size_t)off * 2));
+        __builtin_nontemporal_store(v, (u32x4*)(page_bytes + (size_t)off * 2));
       }
     } else {
       // lane = dim 64*mtp + 32*e + n; the vector is tokens 32*nt + 8*(2*qp + h) + 0..7 of the V plane
@@ -269,7 +264,7 @@ __global__ void __launch_bounds__(256) expand_bf16_kernel(ExpandArgs a, const __
       __bf16* dst = (__bf16*)(page_bytes + (size_t)off * 2);
       const int tk = tokw + 32 * nt + 8 * (q0 + h);  // first of 8 tokens
       if (wave_full || tk + 7 < L) {
-        EXP_STORE(v, (u32x4*)dst);
+        __builtin_nontemporal_store(v, (u32x4*)dst);
       } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
