@@ -412,12 +412,21 @@ __global__ void __launch_bounds__(256) expand_tail_bf16_kernel(ExpandArgs a, con
   // a lane without a token reads row 0 of page 0 (valid memory); its MFMA column is never stored
   const __bf16* row = (const __bf16*)a.latent.pool + ((int64_t)(ok ? pg_in : 0) * P + slot) * W;
   const __bf16* wf = packed + (int64_t)stage * KS * 2 * 512 + e * 512 + lane * 8;
-  f32x16 acc;
+  // Every load of the contraction is in flight before the first MFMA (the call is a chain of short kernels: what it costs
+  // is memory latency, paid once this way): the latent fragments go straight into accumulation registers, as in the
+  // one-shot kernel, which leaves the ordinary registers to the 32 weight fragments.  One accumulation chain in k order,
+  // the one-shot kernel's order: the two produce the same bits.
+  bf16x8 xf[KS], wv[KS];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll 8
-  for (int ks = 0; ks < KS; ++ks)
-    acc = mfma32(*(const bf16x8*)(wf + (int64_t)ks * 1024), *(const bf16x8*)(row + ks * 16 + h * 8), acc);
+  for (int ks = 0; ks < KS; ++ks) asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(xf[ks]) : "v"(row + ks * 16 + h * 8));
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) wv[ks] = *(const bf16x8*)(wf + (int64_t)ks * 1024);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  f32x16 acc;
+  mfma_va_first(acc, wv[0], xf[0]);
+#pragma unroll
+  for (int ks = 1; ks < KS; ++ks) mfma_va(acc, wv[ks], xf[ks]);
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc));  // the last MFMA's passes, before anything else reads the results
   if (!ok) return;
   const int d0 = 64 * mtp + 32 * e;  // register i holds dim d0 + 8*(i/4) + 4*h + i%4 of this lane's token
   if constexpr (FP8) {
