@@ -8,8 +8,10 @@ d_R=64), B=64 sequences of L=8192 cached tokens, on seeded synthetic data alread
                          (the step's rows into the latent cache, their K_C / V / k_R into the expanded cache, grouped decode)
 Prints ONE JSON line.  `value` = decoded step tokens per second of that step (B*1 + B*2 tokens per step).  The one-shot
 cache switch gqla_expand_cache (Sec. 3.1: done once at deployment) is timed in the same run, outside `value`.
-`roofline` is the split-L decode kernel that is further from its target (kernel time from events the library records
-around that kernel, see gqla_time_next_decode_kernel); `rooflines` has both decode kernels and the expansion.  Also in
+`roofline` is the split-L decode kernel that is further from its target, the absorb decode (kernel time from events
+the library records around that kernel inside the timed steps, see gqla_time_next_decode_kernel); `rooflines` has both
+decode kernels and the expansion; the per-call times and the GQA kernel's come from passes of the same steps right
+behind the timed one (each event is a packet in the stream and would be charged to `value`).  Also in
 the line: the other workload shapes (configs[1] with rotating cache buffers so that it is not served from the
 last-level cache, configs[4] ragged and paged), both paths at the operating points of the paper's Sec. 4.2.3 table,
 the oracle's CPU rate on a bounded sample, and timings of the calls
@@ -112,7 +114,7 @@ def main():
                        for b in range(cg.B)]).cuda()
     step_rows = Gq["dec"].latent_pool.view(-1, Wl)[pos.view(-1)].view(cg.B, cg.s_q, Wl).contiguous()
 
-    def step(events=None, kev=None):
+    def step(events=None, kev_a=None, kev_g=None):
         def rec(i):
             if events is not None:
                 events[i].record()
@@ -121,8 +123,8 @@ def main():
             A["dec"].absorb_query(A["d_q_c"], A["d_w_uk"], A["q_hat"])
         rec(1)
         if "absorb" in run_legs:
-            if kev is not None:
-                B.gqla_time_next_decode_kernel(kev[0], kev[1])
+            if kev_a is not None:
+                B.gqla_time_next_decode_kernel(kev_a[0], kev_a[1])
             A["dec"].decode_absorb(A["q_hat"], A["d_q_r"], A["d_w_uv"], A["out"], A["lse"])
         rec(2)
         if "gqa" in run_legs:
@@ -132,8 +134,8 @@ def main():
             Gq["dec"].expand_tail(Gq["d_w_uk"], Gq["d_w_uv"], cg.s_q)
         rec(4)
         if "gqa" in run_legs:
-            if kev is not None:
-                B.gqla_time_next_decode_kernel(kev[2], kev[3])
+            if kev_g is not None:
+                B.gqla_time_next_decode_kernel(kev_g[0], kev_g[1])
             Gq["dec"].decode_gqa(Gq["d_q_c"], Gq["d_q_r"], Gq["out"], Gq["lse"])
         rec(5)
 
@@ -156,12 +158,22 @@ def main():
         for e in row:
             e.record()
     torch.cuda.synchronize()
+    # The timed region carries only the events the top-level roofline needs (the library records them around the absorb
+    # decode kernel on this stream).  Every recorded event is a packet of its own in the stream (measured: the six
+    # between the calls and the two pairs around the decode kernels took 4 % off `value`), so the per-call breakdown
+    # and the second decode kernel's duration come from two more passes of the same steps right behind the timed one.
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(ev[k], kev[k])
+        step(None, kev[k][0:2], None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    for k in range(args.steps):
+        step(ev[k], None, None)
+    torch.cuda.synchronize()
+    for k in range(args.steps):
+        step(None, None, kev[k][2:4])
+    torch.cuda.synchronize()
     call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)])) for i, n in enumerate(names)}
     kernel_ms = {}
     if "absorb" in run_legs:
