@@ -49,6 +49,62 @@ __global__ void __launch_bounds__(256) absorb_query_bf16_kernel(AbsorbQueryArgs 
     }
 }
 
+// The same product for d_h = 128 with both sides of the kernel coalesced (the call is a short kernel in front of every
+// absorb decode, and what it costs is how many memory lines its instructions touch): one workgroup per (group j, 32 query
+// rows of the group), wave w taking latent dims 128 w .. 128 w + 127.  W_UK[j] (512 rows of 256 bytes, contiguous) is
+// staged in LDS with LDS-DMA, 1 KB of consecutive memory per instruction, and read back as conflict-free A fragments; the
+// results go back through LDS (a wave's 32 x 128 tile, rows padded to 272 bytes) so that a store instruction writes four
+// rows of 256 contiguous bytes instead of 8-byte pieces of 32 rows.  Same MFMAs in the same order as the kernel above.
+template <int RKV>
+__global__ void __launch_bounds__(256) absorb_query_staged_bf16_kernel(AbsorbQueryArgs a, int rows_per_group) {
+  constexpr int DH = 128, KS = DH / 16;
+  constexpr int PITCH = 272;                      // bytes per row of the output tile in LDS
+  static_assert(RKV == 512, "four waves x 128 latent dims");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int64_t qrow_of[32];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const int j = blockIdx.z;
+  stage_panels_full<RKV, DH / 64, 4, DH * 2>(smem, (const char*)a.w_uk + (int64_t)j * RKV * DH * 2, wave, lane);
+  const int x = blockIdx.x * 32 + n;       // x = row * G + head-in-group, row = b * s_q + t
+  const bool row_ok = x < rows_per_group;
+  const int64_t qrow = row_ok ? (int64_t)(x / a.G) * a.h_q + j * a.G + x % a.G : -1;
+  if (wave == 0 && h == 0) qrow_of[n] = qrow;
+  bf16x8 qf[KS];
+  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = row_ok ? *(const bf16x8*)((const __bf16*)a.q_c + qrow * DH + ks * 16 + h * 8) : zero;
+  wait_all_memory();
+  __syncthreads();  // W_UK[j] staged
+  f32x16 acc[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma32(row_frag<RKV>(smem, 128 * wave + 32 * mt + n, 2 * ks + h), qf[ks], acc[mt]);
+  }
+  __syncthreads();  // every wave is done reading the staged weights: the space becomes the output tiles
+  char* tile = smem + wave * (32 * PITCH);
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const u32x2 v = {pack_bf16(acc[mt][4 * q], acc[mt][4 * q + 1]), pack_bf16(acc[mt][4 * q + 2], acc[mt][4 * q + 3])};
+      *(u32x2*)(tile + n * PITCH + (mt * 32 + 8 * q + 4 * h) * 2) = v;
+    }
+  // (only this wave reads its tile: the compiler's wait for the LDS writes is all the ordering needed)
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const int r = 4 * p + (lane >> 4), c = lane & 15;
+    const int64_t orow = qrow_of[r];
+    const u32x4 v = *(const u32x4*)(tile + r * PITCH + c * 16);
+    if (orow >= 0) *(u32x4*)((__bf16*)a.q_hat + orow * RKV + wave * 128 + c * 8) = v;
+  }
+}
+
 // MFMAs written out so that the latent fragments can live in the accumulation registers (the compiler's own selection
 // keeps A and B operands in ordinary registers only): c (+)= A * B with one operand in an AGPR quad.  The *_first forms
 // start a sum from zero.  Dependent MFMAs on one accumulator interlock in hardware; before any other instruction reads
@@ -642,8 +698,15 @@ hipError_t launch_compress_bf16(const CompressArgs& a, hipStream_t s) {
 hipError_t launch_absorb_query_bf16(const AbsorbQueryArgs& a, hipStream_t s) {
   const int rows_per_group = a.rows * a.G;
   dim3 grid((rows_per_group + 31) / 32, (512 / 128 + 3) / 4, a.g);
-  if (a.d_h == 192) absorb_query_bf16_kernel<192, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
-  else absorb_query_bf16_kernel<128, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
+  if (a.d_h == 192) {
+    absorb_query_bf16_kernel<192, 512><<<grid, 256, 0, s>>>(a, rows_per_group);
+    return hipGetLastError();
+  }
+  constexpr int kLds = 512 * 128 * 2;   // W_UK[j]
+  static const hipError_t attr =
+      hipFuncSetAttribute((const void*)absorb_query_staged_bf16_kernel<512>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (attr != hipSuccess) return attr;
+  absorb_query_staged_bf16_kernel<512><<<dim3(grid.x, 1, a.g), 256, kLds, s>>>(a, rows_per_group);
   return hipGetLastError();
 }
 
