@@ -357,11 +357,11 @@ gqla_status gqla_estimate_paths(const gqla_shape* shape, int64_t cached_tokens, 
  * two-roof form with the rates the kernels sustain instead of the chip's peaks and a fixed cost per call, and, for
  * the absorb path, the critical path of one workgroup when the batch is too small to fill the chip.  All constants are
  * measurements of this build (the operating-point, batch-sweep and all-config tables under profiles/):
- *   absorb (query absorption + decode):  28 us + max(bytes / 5.5 TB/s, flops / 1.09 PFLOP/s, rounds * (per + 4) * page)
+ *   absorb (query absorption + decode):  24 us + max(bytes / 5.5 TB/s, flops / 1.09 PFLOP/s, rounds * (per + 4) * page)
  *          where the split-plan rule of gqla_plan_create, applied to `batch` sequences of cached_tokens / batch tokens
  *          on 64-token pages and 256 compute units, gives every workgroup `rounds` chunks of `per` pages, and a page
  *          costs a workgroup 3.8 us (1.6 us when h_q s_q <= 32; 2.6 us when 8 * ceil(chunks / 8) * ceil(h_q s_q / 32) <= 256,
- *          where the launch gives every 32 rows their own workgroup)
+ *          where the launch gives every 32 rows their own workgroup; else 3.0 us when h_q s_q <= 64)
  *   gqa    (decode on the expanded cache): 26 us + min(f bytes, 200 MB) / 10 TB/s + max(0, f bytes - 200 MB) / 7.0 TB/s,
  *          f = 1 + 0.05 * (ceil(G s_q / 32) - 1): a cache of up to 200 MB is still in the chip's last-level cache from
  *          the step before; a group with 64 query rows costs a few percent more per byte (a wave takes both row blocks)

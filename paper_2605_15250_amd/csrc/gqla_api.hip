@@ -868,19 +868,20 @@ gqla_status gqla_select_path(const gqla_shape* shape, int64_t cached_tokens, gql
   if (st != GQLA_OK) return st;
   const double row_blocks = (double)(((shape->h_q / shape->g) * shape->s_q + 31) / 32);
   // absorb, throughput form: the rates the kernel sustains when every compute unit has a long chunk
-  double ta = 28e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 1.09e15);
+  double ta = 24e-6 + std::max(e.absorb_bytes / 5.5e12, e.absorb_flops / 1.09e15);
   // absorb, critical path of one workgroup: the split plan of `batch` equal sequences on 64-token pages and 256 compute
   // units gives every workgroup `rounds` chunks of `per` pages; a page costs a workgroup 3.8 us (128 rows, one wave
-  // per 32 rows), 2.6 us when the chunks are so few that the launch gives every 32 rows a workgroup of their own, and
-  // 1.6 us when a sequence has at most 32 rows; a chunk's fixed cost is that of 4 pages.
+  // per 32 rows), 3.0 us with 64 rows (two of the four waves have rows), 2.6 us when the chunks are so few that the
+  // launch gives every 32 rows a workgroup of their own, and 1.6 us when a sequence has at most 32 rows; a chunk's
+  // fixed cost is that of 4 pages.
   if (shape->batch > 0 && cached_tokens > 0) {
     const int64_t np = ceil_div(ceil_div(cached_tokens, shape->batch), 64);
     const int64_t slots = plan_slots(*shape, 256, GQLA_PATH_ABSORB);
     const int64_t cp = choose_chunk_pages(std::vector<int32_t>((size_t)shape->batch, (int32_t)np), *shape, 256, GQLA_PATH_ABSORB);
     const int64_t per_seq = ceil_div(np, cp), per = ceil_div(np, per_seq), chunks = shape->batch * per_seq;
     const int64_t M = (int64_t)shape->h_q * shape->s_q;
-    const double page_s = M <= 32 ? 1.6e-6 : (ceil_div(chunks, 8) * 8 * ceil_div(M, 32) <= 256 ? 2.6e-6 : 3.8e-6);
-    ta = std::max(ta, 28e-6 + (double)(ceil_div(chunks, slots) * (per + 4)) * page_s);
+    const double page_s = M <= 32 ? 1.6e-6 : (ceil_div(chunks, 8) * 8 * ceil_div(M, 32) <= 256 ? 2.6e-6 : (M <= 64 ? 3.0e-6 : 3.8e-6));
+    ta = std::max(ta, 24e-6 + (double)(ceil_div(chunks, slots) * (per + 4)) * page_s);
   }
   out->absorb_seconds = ta;
   // GQA: a fixed cost plus the cache bytes at the rate the kernel streams them -- 7.0 TB/s from HBM; a cache of up to

@@ -258,16 +258,17 @@ def test_calibrated_path_choice_matches_the_measured_operating_points():
     of decode_gqa on one MI355X): predicted times within 25 % of every measured row, and the measured faster path
     wherever the two paths are more than 12 % apart (the model is good to about that per path)."""
     measured = [  # B, h_q, g, s_q, cached tokens, absorb us, gqa us
-        (1, 128, 8, 1, 8192, 50.5, 34.0), (1, 128, 8, 2, 8192, 53.3, 37.4), (1, 128, 4, 1, 8192, 51.4, 26.2),
-        (1, 128, 4, 2, 8192, 52.4, 35.5), (64, 128, 8, 1, 524288, 169.2, 328.3), (64, 128, 8, 2, 524288, 293.0, 336.8),
-        (64, 128, 4, 1, 524288, 165.3, 193.1), (64, 128, 4, 2, 524288, 292.9, 193.5),
-        (32, 32, 8, 1, 131072, 47.6 + 8.0, 89.7),          # configs[1]; its absorb figure there is the decode call alone
-        (128, 128, 8, 2, 2234929, 1199.5 + 15.0, 1541.0),  # configs[4], same remark
+        (1, 128, 8, 1, 8192, 46.0, 33.7), (1, 128, 8, 2, 8192, 51.4, 37.7), (1, 128, 4, 1, 8192, 46.6, 25.7),
+        (1, 128, 4, 2, 8192, 50.1, 35.8), (64, 128, 8, 1, 524288, 165.1, 327.2), (64, 128, 8, 2, 524288, 292.4, 337.0),
+        (64, 128, 4, 1, 524288, 168.4, 189.0), (64, 128, 4, 2, 524288, 290.2, 190.7),
+        (64, 64, 8, 1, 524288, 134.2, 324.6), (64, 64, 8, 2, 524288, 165.1, 326.5),   # 64 heads
+        (32, 32, 8, 1, 131072, 46.1 + 7.5, 89.7),          # configs[1]; its absorb figure there is the decode call alone
+        (128, 128, 8, 2, 2234929, 1208.2 + 12.0, 1536.2),  # configs[4], same remark
         # batch sweep, canonical shape, 8192 tokens per sequence
-        (2, 128, 8, 1, 16384, 54.2, 37.5), (4, 128, 8, 1, 32768, 57.2, 43.4), (8, 128, 8, 1, 65536, 67.5, 57.3),
-        (16, 128, 8, 1, 131072, 77.2, 95.5), (32, 128, 8, 1, 262144, 103.1, 172.7), (128, 128, 8, 1, 1048576, 314.6, 645.4),
-        (2, 128, 8, 2, 16384, 57.3, 42.2), (4, 128, 8, 2, 32768, 67.1, 46.5), (8, 128, 8, 2, 65536, 73.0, 61.3),
-        (16, 128, 8, 2, 131072, 100.4, 101.5), (32, 128, 8, 2, 262144, 159.6, 179.6), (128, 128, 8, 2, 1048576, 559.6, 652.2),
+        (2, 128, 8, 1, 16384, 51.7, 36.7), (4, 128, 8, 1, 32768, 55.1, 42.2), (8, 128, 8, 1, 65536, 57.3, 58.3),
+        (16, 128, 8, 1, 131072, 68.4, 94.8), (32, 128, 8, 1, 262144, 96.1, 171.7), (128, 128, 8, 1, 1048576, 310.0, 643.7),
+        (2, 128, 8, 2, 16384, 52.8, 41.6), (4, 128, 8, 2, 32768, 56.4, 46.0), (8, 128, 8, 2, 65536, 64.9, 62.8),
+        (16, 128, 8, 2, 131072, 91.5, 102.2), (32, 128, 8, 2, 262144, 153.1, 178.2), (128, 128, 8, 2, 1048576, 567.4, 644.7),
     ]
     for Bn, h_q, g, s_q, tokens, t_a, t_g in measured:
         ch = B.gqla_select_path(B.make_shape(Bn, h_q, g, 128, 512, 64, s_q, B.GQLA_BF16), tokens)
