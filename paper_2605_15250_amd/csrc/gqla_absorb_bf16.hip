@@ -613,8 +613,18 @@ __global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeAr
   const uint32_t stage_off = stage_lane_offset<kTile, NP, 4, ROWB>(wave, lane);
 
   GQLA_STAMP(4);
-  acc_zero();
   float m_ref = GQLA_NEG_INF, l_run = 0.f;
+
+  // the queries are requested first: their addresses need only the chunk entry, and they are the bulk of what a
+  // workgroup waits for before its first MFMA; the page ids (a dependent scalar load) arrive in their shadow
+  bf16x8 qf[KS];
+  {
+    const int64_t qrow = (int64_t)ce.b * a.M + rho;
+    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8;
+    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(ks < RKV / 16 ? ph + ks * 16 : pr + (ks - RKV / 16) * 16);
+  }
 
   const int n_tiles = (ce.tok_end - ce.tok_begin + kTile - 1) / kTile;
   // page ids of tiles it .. it+3; iteration `it` stages tile it+2 (the first three are staged up front), the table entry
@@ -646,19 +656,14 @@ __global__ void __launch_bounds__(256) decode_absorb_shared_bf16_kernel(DecodeAr
   int st_slot = (3 * kTile) % P;                                     // slot of tile it+3 in its page
   int lk_slot = (4 * kTile) % P, lk_p = p_first + (4 * kTile) / P;   // tile it+4
 
-  // Start-up: all workgroups begin at once, so the first requests of the whole chip queue at the memory system (the
-  // queries alone are 147 KB per workgroup, 38 MB over the chip: about 12 k cycles before the first MFMA, and the same
-  // when they are staged through LDS in whole lines -- it is their volume, not the shape of the loads).  The queries
-  // go first, then tile 0; tiles 1 and 2 are requested once those have landed, while tile 0 is being multiplied.
-  bf16x8 qf[KS];
-  {
-    const int64_t qrow = (int64_t)ce.b * a.M + rho;
-    const __bf16* ph = (const __bf16*)a.q_a + qrow * RKV + h * 8;
-    const __bf16* pr = (const __bf16*)a.q_r + qrow * DR + h * 8;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(ks < RKV / 16 ? ph + ks * 16 : pr + (ks - RKV / 16) * 16);
-  }
+  // Start-up: all workgroups begin at once, on cold address translations, and each walks a chain of dependent first
+  // touches (chunk entry, page table, queries and tile 0): about 15 k cycles pass before the first MFMA, 7 % of the
+  // kernel at the canonical shape, the same whether the queries (147 KB per workgroup, 38 MB over the chip) are loaded
+  // as fragments or staged through LDS in whole lines, and the same with the chunks of a sequence on one die -- it is
+  // neither the shape of the loads nor their volume.  The queries go first (above), then tile 0; tiles 1 and 2 are
+  // requested once those have landed, while tile 0 is being multiplied.
   stage_panels_full<kTile, NP, 4, ROWB, true>(smem, tile_src(pg0, 0), wave, lane);
+  acc_zero();  // 256 register writes, in the shadow of the requests above
   // The query loads complete here, before the loop (the compiler's wait for them also covers the request for tile 0
   // above); inside the loop only hand-counted waits remain.
 #pragma unroll
