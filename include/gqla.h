@@ -200,6 +200,21 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
                                    const gqla_cache* expanded, int32_t tail_tokens, void* ws, size_t ws_bytes,
                                    void* stream);
 
+/* The step's expansion with the weights repacked ahead of time.  gqla_expand_cache and gqla_expand_cache_tail first
+ * reorder the slice's W_UK, W_UV into the operand order of the matrix instructions, in the caller's scratch; a serving
+ * loop, whose weights do not change, does that once: gqla_pack_expand_weights writes the reordered copy of groups
+ * group_begin .. group_begin + group_count - 1 into `packed` (device memory, 16-byte aligned, at least
+ * gqla_expand_workspace_bytes(shape, group_count) bytes; the layout is the library's own and holds for this build and
+ * this shape only), and gqla_expand_cache_tail_packed is gqla_expand_cache_tail reading that copy -- same results bit
+ * for bit, one kernel less per step.  GQLA_BF16 only (GQLA_ERR_DTYPE otherwise: the fp32 kernels read the weights as they
+ * are); `packed` must stay untouched between the two calls; other arguments, geometry rules and errors as for
+ * gqla_expand_cache_tail (GQLA_ERR_WORKSPACE when packed_bytes is too small).  Both calls only enqueue work on `stream`. */
+gqla_status gqla_pack_expand_weights(const gqla_shape* shape, const void* w_uk, const void* w_uv, int32_t group_begin,
+                                     int32_t group_count, void* packed, size_t packed_bytes, void* stream);
+gqla_status gqla_expand_cache_tail_packed(const gqla_shape* shape, const gqla_cache* latent, const void* packed,
+                                          size_t packed_bytes, int32_t group_count, const gqla_cache* expanded,
+                                          int32_t tail_tokens, void* stream);
+
 /* gqla_expand_cache_tail for callers that cannot allocate device memory at all (code recorded into a HIP graph, tight
  * serving loops, harnesses that forbid hipMalloc): same operation, same results bit for bit, but the scratch (the
  * slice's weights in matrix-core order) lives in a fixed 2 MiB device array inside the library instead of a

@@ -33,6 +33,7 @@ EXPORTS = [
     "gqla_expanded_k_offset", "gqla_expanded_v_offset", "gqla_expanded_kr_offset", "gqla_status_string",
     "gqla_expanded_elems_per_token_dv", "gqla_expanded_k_offset_dv", "gqla_expanded_v_offset_dv", "gqla_expanded_kr_offset_dv",
     "gqla_time_next_decode_kernel", "gqla_expand_cache_tail_static", "gqla_expand_cache_tail_static_max_workspace",
+    "gqla_pack_expand_weights", "gqla_expand_cache_tail_packed",
 ]
 
 
@@ -96,6 +97,10 @@ def lib():
         L.gqla_expand_cache.restype = i32
         L.gqla_expand_cache_tail.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, vp, C.c_size_t, vp]
         L.gqla_expand_cache_tail.restype = i32
+        L.gqla_pack_expand_weights.argtypes = [sp, vp, vp, i32, i32, vp, C.c_size_t, vp]
+        L.gqla_pack_expand_weights.restype = i32
+        L.gqla_expand_cache_tail_packed.argtypes = [sp, cp, vp, C.c_size_t, i32, cp, i32, vp]
+        L.gqla_expand_cache_tail_packed.restype = i32
         L.gqla_expand_cache_tail_static.argtypes = [sp, cp, vp, vp, i32, i32, cp, i32, vp]
         L.gqla_expand_cache_tail_static.restype = i32
         L.gqla_expand_cache_tail_static_max_workspace.argtypes = []
@@ -307,6 +312,21 @@ def gqla_expand_cache_tail(shape, latent: gqla_cache, w_uk, w_uv, group_begin, g
     _check(lib().gqla_expand_cache_tail(C.byref(shape), C.byref(latent), _ptr(w_uk), _ptr(w_uv), group_begin, group_count,
                                         C.byref(expanded), tail_tokens, _ptr(ws), ws_bytes, _stream(stream)),
            "gqla_expand_cache_tail")
+
+
+def gqla_pack_expand_weights(shape, w_uk, w_uv, group_begin, group_count, packed, packed_bytes=None, stream=None):
+    if packed_bytes is None:
+        packed_bytes = packed.numel() * packed.element_size() if packed is not None and hasattr(packed, "numel") else 0
+    _check(lib().gqla_pack_expand_weights(C.byref(shape), _ptr(w_uk), _ptr(w_uv), group_begin, group_count, _ptr(packed),
+                                          packed_bytes, _stream(stream)), "gqla_pack_expand_weights")
+
+
+def gqla_expand_cache_tail_packed(shape, latent: gqla_cache, packed, group_count, expanded: gqla_cache, tail_tokens,
+                                  packed_bytes=None, stream=None):
+    if packed_bytes is None:
+        packed_bytes = packed.numel() * packed.element_size() if packed is not None and hasattr(packed, "numel") else 0
+    _check(lib().gqla_expand_cache_tail_packed(C.byref(shape), C.byref(latent), _ptr(packed), packed_bytes, group_count,
+                                               C.byref(expanded), tail_tokens, _stream(stream)), "gqla_expand_cache_tail_packed")
 
 
 def gqla_expand_cache_tail_static(shape, latent: gqla_cache, w_uk, w_uv, group_begin, group_count, expanded: gqla_cache,

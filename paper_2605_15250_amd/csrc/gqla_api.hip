@@ -385,10 +385,12 @@ namespace {
 // tail = 0: every token of every sequence; tail > 0: the last `tail` positions only
 gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const void* w_uk, const void* w_uv,
                         int32_t group_begin, int32_t group_count, const gqla_cache* expanded, int32_t tail, void* ws,
-                        size_t ws_bytes, void* stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f) {
+                        size_t ws_bytes, void* stream, bool fp8 = false, float k_scale = 1.f, float v_scale = 1.f,
+                        bool weights_packed = false) {
   gqla_status st = fp8 ? check_shape_equal_dims(shape) : check_shape_expanded(shape);
   if (st != GQLA_OK) return st;
-  if (!latent || !expanded || !w_uk || !w_uv || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
+  if (!latent || !expanded || !latent->pool || !expanded->pool || !latent->seq_lens) return GQLA_ERR_NULL;
+  if (!weights_packed && (!w_uk || !w_uv)) return GQLA_ERR_NULL;
   if (!aligned16(w_uk) || !aligned16(w_uv) || !aligned16(latent->pool) || !aligned16(expanded->pool)) return GQLA_ERR_ALIGN;
   if (group_begin < 0 || group_count <= 0 || group_begin + group_count > shape->g || expanded->groups != group_count)
     return GQLA_ERR_SHAPE;
@@ -419,6 +421,7 @@ gqla_status expand_impl(const gqla_shape* shape, const gqla_cache* latent, const
   a.group_begin = group_begin;
   a.group_count = group_count;
   a.tail = tail;
+  a.weights = weights_packed ? 2 : 0;
   a.k_inv_scale = 1.0f / k_scale;
   a.v_inv_scale = 1.0f / v_scale;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -441,6 +444,43 @@ gqla_status gqla_expand_cache_tail(const gqla_shape* shape, const gqla_cache* la
                                    int32_t tail_tokens, void* ws, size_t ws_bytes, void* stream) {
   if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
   return expand_impl(shape, latent, w_uk, w_uv, group_begin, group_count, expanded, tail_tokens, ws, ws_bytes, stream);
+}
+
+// ---- the weights of a group slice repacked once, the step's expansion from the repacked copy ---------------------------------
+gqla_status gqla_pack_expand_weights(const gqla_shape* shape, const void* w_uk, const void* w_uv, int32_t group_begin,
+                                     int32_t group_count, void* packed, size_t packed_bytes, void* stream) {
+  gqla_status st = check_shape_expanded(shape);
+  if (st != GQLA_OK) return st;
+  if (shape->dtype != GQLA_BF16) return GQLA_ERR_DTYPE;  // the fp32 kernels read the weights as they are
+  if (!w_uk || !w_uv || !packed) return GQLA_ERR_NULL;
+  if (!aligned16(w_uk) || !aligned16(w_uv) || !aligned16(packed)) return GQLA_ERR_ALIGN;
+  if (group_begin < 0 || group_count <= 0 || group_begin + group_count > shape->g) return GQLA_ERR_SHAPE;
+  if (packed_bytes < gqla_expand_workspace_bytes(shape, group_count)) return GQLA_ERR_WORKSPACE;
+  ExpandArgs a = {};
+  a.w_uk = w_uk;
+  a.w_uv = w_uv;
+  a.B = 0;
+  a.g = shape->g;
+  a.d_h = shape->d_h;
+  a.d_v = value_dim(shape);
+  a.r_kv = shape->r_kv;
+  a.d_r = shape->d_r;
+  a.group_begin = group_begin;
+  a.group_count = group_count;
+  a.tail = 1;
+  a.weights = 1;
+  const hipError_t e = launch_expand_tail_bf16(a, packed, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
+}
+
+gqla_status gqla_expand_cache_tail_packed(const gqla_shape* shape, const gqla_cache* latent, const void* packed,
+                                          size_t packed_bytes, int32_t group_count, const gqla_cache* expanded,
+                                          int32_t tail_tokens, void* stream) {
+  if (shape && shape->dtype != GQLA_BF16) return check_shape(shape) == GQLA_OK ? GQLA_ERR_DTYPE : check_shape(shape);
+  if (latent && (tail_tokens < 1 || tail_tokens > latent->page_size)) return GQLA_ERR_SHAPE;
+  // (the slice's first group does not matter any more: the repacked copy holds the slice's groups from 0)
+  return expand_impl(shape, latent, nullptr, nullptr, 0, group_count, expanded, tail_tokens, const_cast<void*>(packed), packed_bytes,
+                     stream, false, 1.f, 1.f, true);
 }
 
 // ---- the variant for callers that cannot allocate: scratch in a file-scope device array ---------------------------------

@@ -714,9 +714,11 @@ template <int DH, int DV, bool FP8>
 static hipError_t launch_expand_tail_dims(const ExpandArgs& a, void* ws, hipStream_t s) {
   constexpr int NSUB = (DH + DV) / 64;
   const int tokens = a.B * a.tail;
-  pack_weights_bf16_kernel<DH, DV, 512><<<dim3(a.group_count * NSUB, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (a.weights != 2) {
+    pack_weights_bf16_kernel<DH, DV, 512><<<dim3(a.group_count * NSUB, 512 / 64), 256, 0, s>>>(a, (__bf16*)ws);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.weights == 1) return e;
+  }
   expand_tail_bf16_kernel<DH, DV, 512, 64, FP8><<<dim3(a.group_count * NSUB, (tokens + 63) / 64), 256, 0, s>>>(a, (const __bf16*)ws);
   return hipGetLastError();
 }

@@ -57,6 +57,7 @@ struct ExpandArgs {
   const void* w_uv;
   int32_t B, g, d_h, d_v, r_kv, d_r, group_begin, group_count;  // d_h: key dim (columns of W_UK), d_v: value dim (columns of W_UV)
   int32_t tail;  // tail variants only: positions L_b - tail .. L_b - 1 of every sequence
+  int32_t weights;  // bf16 tail launcher: 0 = repack the weights into ws, then expand; 1 = repack only; 2 = ws already holds them
   float k_inv_scale, v_inv_scale;  // 8-bit tail variant only: 1 / scale of the two code planes
 };
 

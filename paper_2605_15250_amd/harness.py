@@ -133,6 +133,17 @@ class Decoder:
                                  self.expanded_cache(), tail_tokens, self.ws_e)
         return self.expanded_pool
 
+    def pack_expand_weights(self, w_uk, w_uv):
+        """The slice's weights in the expansion kernels' operand order, kept for expand_tail_packed."""
+        nbytes = B.gqla_expand_workspace_bytes(self.shape, self.groups)
+        self.packed_w = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+        B.gqla_pack_expand_weights(self.shape, w_uk, w_uv, self.group_begin, self.groups, self.packed_w)
+        return self.packed_w
+
+    def expand_tail_packed(self, tail_tokens):
+        B.gqla_expand_cache_tail_packed(self.shape, self.latent_cache(), self.packed_w, self.groups, self.expanded_cache(), tail_tokens)
+        return self.expanded_pool
+
     def append_latent(self, rows):
         """rows: [B, s_q, r_kv + d_r] contiguous, the cache's element type."""
         B.gqla_append_latent(self.shape, rows, self.latent_cache())

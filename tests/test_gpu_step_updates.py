@@ -109,6 +109,51 @@ def test_tail_expand_of_a_group_slice():
         case.close()
 
 
+@pytest.mark.parametrize("dims,groups,group_begin,lens,tail", [
+    ((128, 128), 8, 0, [200, 3, 70, 2, 1000], 2),
+    ((128, 128), 2, 5, [200, 3, 70, 2], 3),           # a group slice: the packed copy holds the slice's groups from 0
+    ((192, 256), 4, 0, [130, 64, 1], 1),              # the MLA checkpoint's dims (Sec. 3.2.2)
+])
+def test_tail_expand_from_packed_weights_is_bit_identical(dims, groups, group_begin, lens, tail):
+    """gqla_pack_expand_weights once, then gqla_expand_cache_tail_packed (a serving loop's form of the step's expansion):
+    the same bits as gqla_expand_cache_tail, which repacks on every call, and nothing else written; the packed copy
+    serves a second call, on other lengths, unchanged."""
+    from paper_2605_15250_amd import binding as B
+    d_h, d_v = dims
+    if dims == (128, 128):
+        cfg = S.CONFIGS["C3"].with_(B=len(lens), L=0, paged=True, seed=2718)
+    else:
+        cfg = S.CONFIGS["C2"].with_(B=len(lens), h_q=20, g=4, d_h=d_h, d_v=d_v, s_q=1, L=0, paged=True, seed=2719)
+    case = Case(cfg, lens=lens, groups=groups, group_begin=group_begin)
+    dec = case.dec
+    try:
+        dec.alloc_expanded()
+        dec.expand_tail(case.d_w_uk, case.d_w_uv, tail)
+        torch.cuda.synchronize()
+        want = dec.expanded_pool.clone()
+        packed = dec.pack_expand_weights(case.d_w_uk, case.d_w_uv)
+        snapshot = packed.clone()
+        for _ in range(2):
+            dec.alloc_expanded()
+            dec.expand_tail_packed(tail)
+            torch.cuda.synchronize()
+            assert torch.equal(dec.expanded_pool.view(torch.uint8), want.view(torch.uint8)), "packed and unpacked tail expansion differ"
+        assert torch.equal(packed, snapshot), "the packed weights are read-only for the expansion"
+        # the packed copy does not depend on the cache: one token fewer per sequence, same copy
+        shorter = np.maximum(np.asarray(lens) - 1, 0).astype(np.int32)
+        dec.d_lens.copy_(torch.from_numpy(shorter))
+        dec.alloc_expanded()
+        dec.expand_tail(case.d_w_uk, case.d_w_uv, tail)
+        torch.cuda.synchronize()
+        want2 = dec.expanded_pool.clone()
+        dec.alloc_expanded()
+        dec.expand_tail_packed(tail)
+        torch.cuda.synchronize()
+        assert torch.equal(dec.expanded_pool.view(torch.uint8), want2.view(torch.uint8))
+    finally:
+        case.close()
+
+
 @pytest.mark.parametrize("key,lens,page_size", [
     ("C3", [300, 2, 129, 1000], 64),
     ("C3", [257, 128, 70], 128),             # 128-token pages: a workgroup's two 64-token halves share a page

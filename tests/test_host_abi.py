@@ -147,6 +147,24 @@ def test_argument_validation_happens_on_the_host():
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 65, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail, ok, lat, A, A, 6, 3, B.make_cache(A, A, None, 64, 4, 8, 3), 1, A, 1 << 24, stream=0)
         _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail, ok, lat, A, A, 0, 8, full, 2, None, 0, stream=0)
+        # the weights repacked ahead of time: bf16 only, the slice inside the shape's groups, scratch large enough
+        need8 = B.gqla_expand_workspace_bytes(ok, 8)
+        _expect(B.GQLA_ERR_NULL, B.gqla_pack_expand_weights, ok, None, A, 0, 8, A, need8, stream=0)
+        _expect(B.GQLA_ERR_NULL, B.gqla_pack_expand_weights, ok, A, A, 0, 8, None, need8, stream=0)
+        _expect(B.GQLA_ERR_ALIGN, B.gqla_pack_expand_weights, ok, A, A + 8, 0, 8, A, need8, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_pack_expand_weights, ok, A, A, 6, 3, A, need8, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_pack_expand_weights, ok, A, A, 0, 0, A, need8, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_pack_expand_weights, ok, A, A, 0, 8, A, need8 - 1, stream=0)
+        f32 = B.make_shape(2, 8, 2, 16, 32, 8, 1, B.GQLA_F32)
+        _expect(B.GQLA_ERR_DTYPE, B.gqla_pack_expand_weights, f32, A, A, 0, 2, A, 1 << 20, stream=0)
+        _expect(B.GQLA_ERR_DTYPE, B.gqla_expand_cache_tail_packed, f32, B.make_cache(A, A, None, 8, 4, 8, 0), A, 2,
+                B.make_cache(A, A, None, 8, 4, 8, 2), 1, packed_bytes=1 << 20, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_packed, ok, lat, A, 8, full, 1, packed_bytes=need8 - 1, stream=0)
+        _expect(B.GQLA_ERR_WORKSPACE, B.gqla_expand_cache_tail_packed, ok, lat, None, 8, full, 1, packed_bytes=0, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_packed, ok, lat, A, 8, full, 0, packed_bytes=need8, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_packed, ok, lat, A, 8, full, 65, packed_bytes=need8, stream=0)
+        _expect(B.GQLA_ERR_SHAPE, B.gqla_expand_cache_tail_packed, ok, lat, A, 3, full, 1, packed_bytes=need8, stream=0)   # the cache holds 8 groups
+        _expect(B.GQLA_ERR_NULL, B.gqla_expand_cache_tail_packed, ok, B.make_cache(None, A, None, 64, 4, 8, 0), A, 8, full, 1, packed_bytes=need8, stream=0)
         # the variant with the scratch inside the library: the size limit and the shape checks come before anything
         # touches a device
         assert B.gqla_expand_cache_tail_static_max_workspace() == 2 << 20
