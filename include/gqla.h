@@ -140,9 +140,10 @@ int32_t gqla_plan_chunk_pages(const gqla_plan* plan);
 /* Copies up to *n chunk triples (b, tok_begin, tok_end) in slot order to triples (host int32[3 * *n]) and the
  * per-sequence first slots to first_slot (host int32[batch], may be NULL); sets *n to the chunk count. */
 gqla_status gqla_plan_export(const gqla_plan* plan, int32_t* triples, int32_t* first_slot, int32_t* n);
-/* Bytes of device workspace a decode call with this plan needs: the chunk table, then the partial outputs
- * (GQA path: fp32 [chunks][s_q*h_q][d_h]; absorb path: [chunks][s_q*h_q][r_kv], bf16 for GQLA_BF16, fp32 for
- * GQLA_F32) and the fp32 partial log-sum-exps [chunks][s_q*h_q]. */
+/* Bytes of device workspace a decode call with this plan needs: the chunk table, then the partial outputs (GQA path:
+ * d_v fp32 values per chunk and row; absorb path: r_kv values, bf16 for GQLA_BF16 and fp32 for GQLA_F32; with
+ * GQLA_BF16 the rows are rounded up to whole blocks of 32 and the order is the library's own) and the fp32 partial
+ * log-sum-exps [chunks][s_q*h_q]. */
 size_t gqla_plan_workspace_bytes(const gqla_plan* plan);
 /* Enqueues the copy of the plan's chunk table into the head of ws (device, 16-byte aligned, at least
  * gqla_plan_workspace_bytes).  Must precede, in stream order, every decode call that uses (plan, ws).  The plan

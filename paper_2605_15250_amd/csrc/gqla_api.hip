@@ -135,7 +135,7 @@ WsLayout make_layout(const gqla_plan& p) {
   w.first_slot_off = align_up(n * sizeof(ChunkEntry), 16);
   w.part_o_off = align_up(w.first_slot_off + (p.shape.batch + 1) * sizeof(int32_t), 256);
   size_t po;
-  if (p.path == GQLA_PATH_GQA) po = n * M * value_dim(&p.shape) * 4;
+  if (p.path == GQLA_PATH_GQA) po = n * (p.shape.dtype == GQLA_BF16 ? (M + 31) / 32 * 32 : M) * value_dim(&p.shape) * 4;   // bf16 kernels: whole blocks of 32 rows
   else if (p.shape.dtype == GQLA_BF16) po = n * ((M + 31) / 32 * 32) * p.shape.r_kv * 2;   // whole blocks of 32 rows (part_vec_index)
   else po = n * M * p.shape.r_kv * 4;
   w.part_lse_off = align_up(w.part_o_off + po, 256);
@@ -588,7 +588,7 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   hipError_t e = timer.begin();
   if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
   if (e == hipSuccess) e = timer.end();
-  if (e == hipSuccess) e = launch_combine_f32(c, shape->dtype == GQLA_BF16, s);
+  if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_combine_gqa_bf16(c, s) : launch_combine_f32(c, false, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 
@@ -786,7 +786,7 @@ gqla_status gqla_decode_gqa_fp8(const gqla_shape* shape, const gqla_plan* plan, 
   hipError_t e = timer.begin();
   if (e == hipSuccess) e = launch_decode_gqa_fp8(a, k_scale, v_scale, s);
   if (e == hipSuccess) e = timer.end();
-  if (e == hipSuccess) e = launch_combine_f32(c, true, s);
+  if (e == hipSuccess) e = launch_combine_gqa_bf16(c, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 

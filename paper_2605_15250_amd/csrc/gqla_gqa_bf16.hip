@@ -378,8 +378,11 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
       }
       const bool ok = row_ok[0];
       const float inv = (l_all > 0.f ? 1.f / l_all : 0.f) * (FP8 ? v_scale : 1.f);
-      const int64_t prow = (int64_t)chunk * a.M + (int64_t)t_of[0] * a.h_q + head_of[0];
-      float* po = (float*)a.part_o + prow * DV;
+      const int rho = t_of[0] * a.h_q + head_of[0];
+      const int64_t prow = (int64_t)chunk * a.M + rho;
+      // chunk partial in fp32, 4-dim vectors ordered [chunk][32-row block][d_v / 4][row] (part_vec_index): this lane
+      // holds vector 2 quad + h of its row
+      float* po = (float*)a.part_o + part_vec_index(chunk, rho, a.M, DV / 4, h) * 4;
       constexpr int kQuadsPerWave = kQuads / 8;
       static_assert(kQuads % 8 == 0, "every wave of the team sums the same number of quads");
 #pragma unroll
@@ -392,7 +395,7 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
           if (c[w] > 0.f) acc += c[w] * v;  // (a wave without tiles holds zeros; one whose rows were all masked may hold anything times 0)
         }
         acc *= inv;
-        if (ok) *(f32x4*)(po + (quad >> 2) * 32 + 8 * (quad & 3) + 4 * h) = acc;
+        if (ok) *(f32x4*)(po + 2 * quad * (32 * 4)) = acc;
       }
       if (ok && tw == 0 && h == 0) a.part_lse[prow] = l_all > 0.f ? (m_all + fast_log2(l_all)) * kLn2 : GQLA_NEG_INF;
       return;
@@ -404,16 +407,92 @@ __global__ void __launch_bounds__(MAXT) decode_gqa_bf16_kernel(DecodeArgs a, int
     const float l_tot = pair_sum(l_run[x]);
     if (!row_ok[x]) continue;
     const float inv = (l_tot > 0.f ? 1.f / l_tot : 0.f) * (FP8 ? v_scale : 1.f);
-    const int64_t prow = (int64_t)chunk * a.M + (int64_t)t_of[x] * a.h_q + head_of[x];
-    float* po = (float*)a.part_o + prow * DV;
+    const int rho = t_of[x] * a.h_q + head_of[x];
+    const int64_t prow = (int64_t)chunk * a.M + rho;
+    // chunk partial in fp32, 4-dim vectors ordered [chunk][32-row block][d_v / 4][row] (part_vec_index): consecutive rows
+    // sit in consecutive lanes, so a store instruction writes runs of contiguous 16-byte vectors instead of 32-byte pieces
+    // of 32 rows; all waves of the launch reach this point together, and nothing hides what these stores cost.  (16-bit
+    // partials would halve them, but cost the path its margin on outputs of magnitude 4 to 8, where half a bf16 step
+    // of the final rounding alone is 1.6e-2 of the 2e-2 allowed.)
+    float* po = (float*)a.part_o + part_vec_index(chunk, rho, a.M, DV / 4, h) * 4;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 v = {o[x][mt][4 * q] * inv, o[x][mt][4 * q + 1] * inv, o[x][mt][4 * q + 2] * inv, o[x][mt][4 * q + 3] * inv};
-        *(f32x4*)(po + mt * 32 + 8 * q + 4 * h) = v;
-      }
+      for (int q = 0; q < 4; ++q)
+        *(f32x4*)(po + (8 * mt + 2 * q) * (32 * 4)) =
+            f32x4{o[x][mt][4 * q] * inv, o[x][mt][4 * q + 1] * inv, o[x][mt][4 * q + 2] * inv, o[x][mt][4 * q + 3] * inv};
     if (h == 0) a.part_lse[prow] = l_tot > 0.f ? (m_run[x] + fast_log2(l_tot)) * kLn2 : GQLA_NEG_INF;
+  }
+}
+
+
+// ---- log-sum-exp merge of the chunk partials (not in the paper: the split over the context is this library's) ----------
+// One workgroup per (sequence, block of 32 rows); thread (row n = tid % 32, vector slot tid / 32) merges vectors
+// slot, slot + 8, ... of its row (4 floats each), so that the loads of a wave are 32 consecutive 16-byte vectors.
+// Chunks are merged kNB at a time (their loads in flight together) with a running maximum, as in an online softmax.  The
+// merged block goes through LDS (32 rows, padded) and leaves as whole rows: 16 lanes x 16 bytes per row of 128 value dims.
+template <int DV>
+__global__ void __launch_bounds__(256) combine_gqa_bf16_kernel(CombineArgs a) {
+  constexpr int kNB = 4;
+  constexpr int NV = DV / 4;                 // 4-float vectors per row
+  constexpr int PITCH = DV * 2 + 16;         // bytes per row of the block in LDS
+  __shared__ __attribute__((aligned(16))) char tile[32 * PITCH];
+  const int blocks_per_seq = (a.M + 31) / 32;
+  const int b = blockIdx.x / blocks_per_seq, rb = blockIdx.x % blocks_per_seq;
+  const int n = threadIdx.x & 31, slot = threadIdx.x >> 5;
+  const int rho = rb * 32 + n;
+  const bool row_ok = rho < a.M;
+  const int rc = row_ok ? rho : 0;
+  const int s0 = a.first_slot[b], s1 = a.first_slot[b + 1];
+  const f32x4* po = (const f32x4*)a.part_o + part_vec_index(0, rc, a.M, NV, slot);
+  const int64_t chunk_stride = (int64_t)blocks_per_seq * NV * 32;   // vectors from one chunk's partials to the next
+  float m = GQLA_NEG_INF, den = 0.f;
+  f32x4 acc[NV / 8];
+#pragma unroll
+  for (int v = 0; v < NV / 8; ++v) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int sb = s0; sb < s1; sb += kNB) {
+    float l[kNB];
+    f32x4 x[kNB][NV / 8];
+#pragma unroll
+    for (int k = 0; k < kNB; ++k) {
+      const int sc = min(sb + k, s1 - 1);  // clamped: a chunk beyond the range is loaded again and given weight 0
+      l[k] = a.part_lse[(int64_t)sc * a.M + rc];
+#pragma unroll
+      for (int v = 0; v < NV / 8; ++v) x[k][v] = po[sc * chunk_stride + v * (8 * 32)];
+    }
+    float m_new = m;
+#pragma unroll
+    for (int k = 0; k < kNB; ++k) {
+      if (sb + k >= s1) l[k] = GQLA_NEG_INF;
+      m_new = fmaxf(m_new, l[k]);
+    }
+    const float m_use = (m_new == GQLA_NEG_INF) ? 0.f : m_new;
+    const float rescale = __expf(m - m_use);  // 0 on the first batch (m = -inf), where den and acc are 0 anyway
+    den *= rescale;
+#pragma unroll
+    for (int v = 0; v < NV / 8; ++v) acc[v] *= rescale;
+    m = m_new;
+#pragma unroll
+    for (int k = 0; k < kNB; ++k) {
+      const float w = __expf(l[k] - m_use);
+      den += w;
+      if (w > 0.f) {  // a chunk without visible tokens may hold anything
+#pragma unroll
+        for (int v = 0; v < NV / 8; ++v) acc[v] += w * x[k][v];
+      }
+    }
+  }
+  const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+  for (int v = 0; v < NV / 8; ++v)
+    *(u32x2*)(tile + n * PITCH + (slot + 8 * v) * 8) = u32x2{pack_bf16(acc[v][0] * inv, acc[v][1] * inv), pack_bf16(acc[v][2] * inv, acc[v][3] * inv)};
+  if (a.lse && row_ok && slot == 0) a.lse[(int64_t)b * a.M + rho] = m + __logf(den);
+  __syncthreads();
+  constexpr int LPR = DV / 8;                // lanes per row on the way out (16 bytes each)
+  for (int idx = threadIdx.x; idx < 32 * LPR; idx += 256) {
+    const int r = idx / LPR, c = idx % LPR;
+    if (rb * 32 + r < a.M)
+      *(u32x4*)((__bf16*)a.out + ((int64_t)b * a.M + rb * 32 + r) * DV + c * 8) = *(const u32x4*)(tile + r * PITCH + c * 16);
   }
 }
 
@@ -474,6 +553,13 @@ hipError_t launch_decode_gqa_bf16(const DecodeArgs& a, hipStream_t s) {
 
 hipError_t launch_decode_gqa_fp8(const DecodeArgs& a, float k_scale, float v_scale, hipStream_t s) {
   return launch_decode_gqa_128<true>(a, k_scale, v_scale, s);
+}
+
+hipError_t launch_combine_gqa_bf16(const CombineArgs& a, hipStream_t s) {
+  const unsigned blocks = (unsigned)(a.B * ((a.M + 31) / 32));
+  if (a.d_h == 256) combine_gqa_bf16_kernel<256><<<blocks, 256, 0, s>>>(a);   // a.d_h: value dims here
+  else combine_gqa_bf16_kernel<128><<<blocks, 256, 0, s>>>(a);
+  return hipGetLastError();
 }
 
 }  // namespace gqla

@@ -31,7 +31,7 @@ struct DecodeArgs {
   CacheView cache;
   const ChunkEntry* chunks;
   int32_t n_chunks;
-  void* part_o;      // GQA: fp32 [chunks][M][d_v];  absorb bf16: bf16 vectors [chunks][M / 32][r_kv / 8][32][8] (part_vec_index);  absorb f32: fp32 [chunks][M][r_kv]
+  void* part_o;      // GQA fp32: fp32 [chunks][M][d_v];  GQA bf16 / 8-bit: fp32 vectors [chunks][M / 32][d_v / 4][32][4] (part_vec_index);  absorb bf16: bf16 vectors [chunks][M / 32][r_kv / 8][32][8] (part_vec_index);  absorb f32: fp32 [chunks][M][r_kv]
   float* part_lse;   // fp32 [chunks][M], natural log
   int32_t B, h_q, g, G, d_h, d_v, r_kv, d_r, s_q, M;  // M = s_q * h_q rows per sequence, row = t*h_q + i; d_v: value dim (GQA path)
   int32_t num_cus;                               // compute units the plan was made for (launch-shape choices only)
@@ -120,7 +120,8 @@ hipError_t launch_decode_gqa_f32(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_gqa_bf16(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_absorb_f32(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_absorb_bf16(const DecodeArgs&, hipStream_t);
-hipError_t launch_combine_f32(const CombineArgs&, bool out_bf16, hipStream_t);           // partials in d_h space
+hipError_t launch_combine_f32(const CombineArgs&, bool out_bf16, hipStream_t);           // fp32 partials in d_h space, [chunks][M][d_v]
+hipError_t launch_combine_gqa_bf16(const CombineArgs&, hipStream_t);                     // fp32 partials in d_h space, vector order (part_vec_index), bf16 out
 hipError_t launch_combine_project_f32(const CombineArgs&, hipStream_t);                  // fp32 latent partials, fp32 out
 hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);                 // bf16 latent partials, bf16 out
 hipError_t launch_expand_f32(const ExpandArgs&, hipStream_t);
