@@ -588,7 +588,7 @@ gqla_status gqla_decode_gqa(const gqla_shape* shape, const gqla_plan* plan, cons
   hipError_t e = timer.begin();
   if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_decode_gqa_bf16(a, s) : launch_decode_gqa_f32(a, s);
   if (e == hipSuccess) e = timer.end();
-  if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_combine_gqa_bf16(c, s) : launch_combine_f32(c, false, s);
+  if (e == hipSuccess) e = shape->dtype == GQLA_BF16 ? launch_combine_gqa_bf16(c, s) : launch_combine_f32(c, s);
   return e == hipSuccess ? GQLA_OK : GQLA_ERR_DEVICE;
 }
 

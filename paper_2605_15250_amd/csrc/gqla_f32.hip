@@ -118,7 +118,6 @@ __global__ void __launch_bounds__(64) decode_f32_kernel(DecodeArgs a) {
 // step.  One pass over the chunks, kNB at a time so that their loads are in flight together; the running maximum
 // moves as in an online softmax (three passes with one dependent load per chunk each would cost three memory
 // latencies per chunk).
-template <typename OutT>
 __global__ void __launch_bounds__(256) combine_kernel(CombineArgs a) {
   constexpr int kNB = 4;
   const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);  // row = b * M + rho
@@ -159,13 +158,7 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineArgs a) {
       }
     }
     acc *= 1.f / den;
-    OutT* out = (OutT*)a.out + row * a.d_h + d;
-    if constexpr (sizeof(OutT) == 4) {
-      *(f32x4*)out = acc;
-    } else {
-      u32x2 pk = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
-      *(u32x2*)out = pk;
-    }
+    *(f32x4*)((float*)a.out + row * a.d_h + d) = acc;
   }
   if (a.lse && (threadIdx.x & 31) == 0) a.lse[row] = m + __logf(den);
 }
@@ -337,10 +330,9 @@ hipError_t launch_decode_absorb_f32(const DecodeArgs& a, hipStream_t s) {
   decode_f32_kernel<true><<<dim3(a.n_chunks, a.M), 64, 0, s>>>(a);
   return hipGetLastError();
 }
-hipError_t launch_combine_f32(const CombineArgs& a, bool out_bf16, hipStream_t s) {
+hipError_t launch_combine_f32(const CombineArgs& a, hipStream_t s) {
   const unsigned blocks = (unsigned)(((int64_t)a.B * a.M + 7) / 8);
-  if (out_bf16) combine_kernel<__bf16><<<blocks, 256, 0, s>>>(a);
-  else combine_kernel<float><<<blocks, 256, 0, s>>>(a);
+  combine_kernel<<<blocks, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 hipError_t launch_combine_project_f32(const CombineArgs& a, hipStream_t s) {

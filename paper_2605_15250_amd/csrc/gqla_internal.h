@@ -120,7 +120,7 @@ hipError_t launch_decode_gqa_f32(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_gqa_bf16(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_absorb_f32(const DecodeArgs&, hipStream_t);
 hipError_t launch_decode_absorb_bf16(const DecodeArgs&, hipStream_t);
-hipError_t launch_combine_f32(const CombineArgs&, bool out_bf16, hipStream_t);           // fp32 partials in d_h space, [chunks][M][d_v]
+hipError_t launch_combine_f32(const CombineArgs&, hipStream_t);                          // fp32 partials in d_h space, [chunks][M][d_v]
 hipError_t launch_combine_gqa_bf16(const CombineArgs&, hipStream_t);                     // fp32 partials in d_h space, vector order (part_vec_index), bf16 out
 hipError_t launch_combine_project_f32(const CombineArgs&, hipStream_t);                  // fp32 latent partials, fp32 out
 hipError_t launch_combine_project_bf16(const CombineArgs&, hipStream_t);                 // bf16 latent partials, bf16 out
