@@ -657,7 +657,7 @@ def main():
         path_model["gqa_leg_s_q2"]["measured_gqa_us"] = call_ms["decode_gqa"] * 1e3
 
     wl = ("canonical (h_q=128,g=8,d_h=128,r_kv=512,d_R=64) B=%d L=%d: configs[2] absorb decode s_q=1 + configs[3] GQA decode s_q=2 "
-          "(append + tail expansion + decode; the one-shot expansion is timed beside the step, in calls_ms and rooflines)" % (ca.B, ca.L))
+          "(append + tail expansion from weights repacked once + decode; the one-shot expansion is timed beside the step, in calls_ms and rooflines)" % (ca.B, ca.L))
     line = {
         "metric": "decode attn tokens/s + % roofline (MFMA absorb, HBM GB/s GQA) on 1 MI355X",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
