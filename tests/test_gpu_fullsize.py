@@ -179,6 +179,20 @@ def test_c3_step_updates_and_fp8_cache_at_full_size():
         dec.expand_tail(case.d_w_uk, case.d_w_uv, cfg.s_q)
         torch.cuda.synchronize()
         assert torch.equal(dec.expanded_pool.view(torch.int16), one_shot.view(torch.int16)), "tail expansion vs one-shot expansion"
+        # the same from weights repacked ahead of time (what the benchmark step calls): into a zeroed pool, against what
+        # the call that repacks per step writes into a zeroed pool
+        dec.expanded_pool.zero_()
+        dec.expand_tail(case.d_w_uk, case.d_w_uv, cfg.s_q)
+        torch.cuda.synchronize()
+        tail_only = dec.expanded_pool.clone()
+        assert int((tail_only.view(torch.int16) != 0).sum()) > cfg.B * cfg.s_q * (2 * cfg.g * cfg.d_h) // 2
+        dec.pack_expand_weights(case.d_w_uk, case.d_w_uv)
+        dec.expanded_pool.zero_()
+        dec.expand_tail_packed(cfg.s_q)
+        torch.cuda.synchronize()
+        assert torch.equal(dec.expanded_pool.view(torch.int16), tail_only.view(torch.int16)), "packed vs unpacked tail expansion"
+        del tail_only
+        dec.expanded_pool = one_shot
         # 8-bit cache
         dec.alloc_expanded_fp8(fill=0)
         dec.quantize_expanded(1.0, 1.0)
